@@ -1,0 +1,189 @@
+"""TEST INFRASTRUCTURE - NOT PART OF THE PRODUCT PATH.
+
+Python face of the dense-matrix CPU oracle (``spinner_oracle.c``) for the
+structured spinner ``y = H D3 H D2 H D1 x`` and the three downstream steps the
+paper attaches to it.  Only ``tests/``, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this module; it imports nothing from the HIP
+package and shares no code with it.
+
+What each function follows:
+
+* ``spinner``            - Section 1 / Section 3 (the HD3HD2HD1 member of the
+  family; H is the L2-normalised Hadamard matrix, D_i diagonal).
+* ``epilogue_none``      - Section 3.2: an m x n spinner is the first m rows of
+  the n x n one; ``scale`` is the caller's extra factor (sqrt(n) in Lemma 1,
+  sqrt(n/m) for a norm-preserving embedding).
+* ``epilogue_cossin``    - Section 5 (kernel approximation): features
+  ``s(Ax) = exp(-i A x / sigma)`` scaled by ``1/sqrt(d')``; written in its real
+  form ``(1/sqrt(m)) [cos w ; sin w]`` whose dot product is the Hermitian
+  product of the complex features.
+* ``epilogue_hash``      - Section 4, Theorem 4 and its proof: the hash of a
+  vector is the signed canonical direction closest to its projection, i.e.
+  ``argmax_i |y_i|`` together with the sign of that coordinate.
+
+Readings where the paper is silent: Sylvester row order; bucket ``i`` for
+``+e_i`` and ``i + n`` for ``-e_i``; lowest index wins exact ties; a zero
+coordinate counts as positive; features are concatenated (cos block, then sin
+block), not interleaved.
+
+Parity status: every function here is pinned by the CPU tests (``tests/
+test_oracle_*.py``) against closed forms, library constructions of the Hadamard
+matrix, invariants and brute force; nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spinner_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_spinner.so")
+_lib = None
+
+# n above which the dense n x n Hadamard matrix is not materialised and the
+# two explicit Kronecker factors are used instead.
+DENSE_MAX_N = 1 << 14
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP over vectors). Returns the .so path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_hadamard_sign.restype = ctypes.c_int
+        lib.oracle_hadamard_sign.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.oracle_hadamard_dense.restype = None
+        lib.oracle_hadamard_dense.argtypes = [ctypes.c_int, ctypes.c_void_p]
+        lib.oracle_max_threads.restype = ctypes.c_int
+        lib.oracle_hadamard_apply.restype = ctypes.c_int
+        lib.oracle_hadamard_apply.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_long,
+                                              ctypes.c_int, ctypes.c_void_p]
+        lib.oracle_spinner.restype = ctypes.c_int
+        lib.oracle_spinner.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_long,
+                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def _is_pow2(v: int) -> bool:
+    return v > 0 and (v & (v - 1)) == 0
+
+
+def default_kron_a(n: int) -> int:
+    """0 (dense H_n) up to DENSE_MAX_N, else the larger factor of a balanced split."""
+    if n <= DENSE_MAX_N:
+        return 0
+    log2n = n.bit_length() - 1
+    return 1 << ((log2n + 1) // 2)
+
+
+def hadamard_sign(i: int, j: int) -> int:
+    return int(_load().oracle_hadamard_sign(i, j))
+
+
+def hadamard_dense(n: int) -> np.ndarray:
+    """Unnormalised Sylvester Hadamard matrix, int8 [n][n]."""
+    assert _is_pow2(n)
+    H = np.empty((n, n), dtype=np.int8)
+    _load().oracle_hadamard_dense(n, H.ctypes.data)
+    return H
+
+
+def hadamard_apply(t: np.ndarray, kron_a: int = 0) -> np.ndarray:
+    """(H_n / sqrt(n)) t for each row of fp64 ``t`` [batch][n] (dense or Kronecker route)."""
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    squeeze = t.ndim == 1
+    if squeeze:
+        t = t[None, :]
+    batch, n = t.shape
+    out = np.empty_like(t)
+    rc = _load().oracle_hadamard_apply(t.ctypes.data, n, batch, kron_a, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_hadamard_apply: bad arguments")
+    return out[0] if squeeze else out
+
+
+def spinner(x: np.ndarray, d1: np.ndarray, d2: np.ndarray, d3: np.ndarray,
+            kron_a: int | None = None, nthreads: int = 0) -> np.ndarray:
+    """y = H D3 H D2 H D1 x in fp64 for each row of fp32 ``x`` [batch][n]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    squeeze = x.ndim == 1
+    if squeeze:
+        x = x[None, :]
+    batch, n = x.shape
+    ds = [np.ascontiguousarray(d, dtype=np.float32) for d in (d1, d2, d3)]
+    for d in ds:
+        if d.shape != (n,):
+            raise ValueError("diagonal must have shape (n,)")
+    if kron_a is None:
+        kron_a = default_kron_a(n)
+    y = np.empty((batch, n), dtype=np.float64)
+    rc = _load().oracle_spinner(x.ctypes.data, n, batch, ds[0].ctypes.data, ds[1].ctypes.data,
+                                ds[2].ctypes.data, kron_a, nthreads, y.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_spinner: bad arguments or out of memory")
+    return y[0] if squeeze else y
+
+
+def epilogue_none(y: np.ndarray, m: int, scale: float) -> np.ndarray:
+    """First m coordinates of ``scale * y`` (Section 3.2: first m rows of the spinner)."""
+    return float(scale) * y[..., :m]
+
+
+def epilogue_cossin(y: np.ndarray, m: int, scale: float) -> np.ndarray:
+    """(1/sqrt(m)) [cos(w_0..w_{m-1}), sin(w_0..w_{m-1})] with w = scale * y (Section 5)."""
+    w = float(scale) * y[..., :m]
+    return np.concatenate([np.cos(w), np.sin(w)], axis=-1) / np.sqrt(float(m))
+
+
+def epilogue_hash(y: np.ndarray) -> np.ndarray:
+    """Cross-polytope bucket per row: i* = argmax |y_i| (lowest index on ties),
+    bucket = i* if y_{i*} >= 0 else i* + n (Section 4, Theorem 4)."""
+    n = y.shape[-1]
+    istar = np.argmax(np.abs(y), axis=-1)            # numpy returns the first maximum
+    ystar = np.take_along_axis(y, istar[..., None], axis=-1)[..., 0]
+    return (istar + n * (ystar < 0)).astype(np.int32)
+
+
+def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,
+          kron_a: int | None = None, nthreads: int = 0) -> np.ndarray:
+    """Whole path for one diagonal triple: spinner then the named epilogue, fp64."""
+    y = spinner(x, d1, d2, d3, kron_a=kron_a, nthreads=nthreads)
+    if epilogue == "none":
+        return epilogue_none(y, m, scale)
+    if epilogue == "cossin":
+        return epilogue_cossin(y, m, scale)
+    raise ValueError("unknown epilogue %r" % (epilogue,))
+
+
+def hash(x, diag_sets: np.ndarray, nthreads: int = 0, return_y: bool = False):
+    """Buckets for L independently drawn triples (Section 3.2: independently
+    constructed blocks).  diag_sets: fp32 [L][3][n].  Returns int32 [batch][L]
+    (and the fp64 projections [L][batch][n] when ``return_y``)."""
+    diag_sets = np.ascontiguousarray(diag_sets, dtype=np.float32)
+    L = diag_sets.shape[0]
+    cols, ys = [], []
+    for l in range(L):
+        y = spinner(x, diag_sets[l, 0], diag_sets[l, 1], diag_sets[l, 2], nthreads=nthreads)
+        cols.append(epilogue_hash(y))
+        if return_y:
+            ys.append(y)
+    idx = np.stack(cols, axis=-1).astype(np.int32)
+    return (idx, np.stack(ys, axis=0)) if return_y else idx
