@@ -1,0 +1,134 @@
+/*
+ * spinner.h - C ABI of the MI355X (gfx950) structured-spinner library.
+ *
+ * The library computes, for a batch of fp32 vectors, the structured projection
+ *
+ *        y = H D3 H D2 H D1 x
+ *
+ * of "Structured Spinners" (Section 1; Section 3, Lemma 1), where H is the
+ * L2-normalised Hadamard matrix in Sylvester (natural) order, entry (i,j) =
+ * (-1)^popcount(i & j) / sqrt(n), and D1, D2, D3 are diagonal matrices given by
+ * their fp32 diagonals (+-1 in the random setting, arbitrary in the adaptive
+ * one, Gaussian D3 for the H D_g H D2 H D1 member).  H is never materialised:
+ * each H is a fast Walsh-Hadamard transform that runs entirely on the GPU.
+ * The projection is fused with the step that consumes it (Section 1:
+ * "projections are often passed to a possibly highly nonlinear function").
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers unless stated otherwise, must be
+ *     16-byte aligned, and are owned by the caller.  The library never
+ *     allocates, frees or synchronises; all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).  Buffers
+ *     must stay alive until the stream has run the call.
+ *   - Vectors are row-major and contiguous: x is fp32 [batch][n].
+ *   - n must be a power of two in [2^4, 2^24].  Zero-padding other sizes is
+ *     the caller's job.
+ *   - Return value: SPINNER_OK (0) or a negative SPINNER_ERR_* code.  All
+ *     validation happens before the first launch; a failed call enqueues
+ *     nothing.  batch == 0 is a successful no-op.
+ */
+#ifndef SPINNER_H
+#define SPINNER_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SPINNER_OK               =  0,
+    SPINNER_ERR_BAD_N        = -1,  /* n not a power of two or outside [2^4, 2^24]          */
+    SPINNER_ERR_BAD_M        = -2,  /* m < 1 or m > n                                       */
+    SPINNER_ERR_NULL_PTR     = -3,  /* a required pointer is NULL                           */
+    SPINNER_ERR_BAD_EPILOGUE = -4,  /* epilogue is not one of spinner_epilogue_t            */
+    SPINNER_ERR_BAD_BATCH    = -5,  /* batch < 0, or batch * n does not fit the index range */
+    SPINNER_ERR_WORKSPACE    = -6,  /* workspace required (see spinner_workspace_bytes) but NULL */
+    SPINNER_ERR_HIP          = -7,  /* a kernel launch failed; see spinner_strerror         */
+    SPINNER_ERR_BAD_L        = -8,  /* L < 1                                                */
+    SPINNER_ERR_ALIGNMENT    = -9,  /* a data pointer is not 16-byte aligned                */
+    SPINNER_ERR_UNSUPPORTED  = -10  /* combination not built (e.g. hashing with n > 2^14)   */
+};
+
+typedef enum {
+    /* out[batch][m]  = scale * (first m coordinates of y).
+     * Section 3.2: an m x n spinner is the first m rows of the n x n one.      */
+    SPINNER_EPI_NONE = 0,
+    /* out[batch][2m] = (1/sqrt(m)) [cos(w_0..w_{m-1}), sin(w_0..w_{m-1})],
+     * w = scale * y.  Section 5 (kernel approximation): random Fourier features
+     * s(Ax) = exp(-i A x / sigma) scaled by 1/sqrt(d'), in real form; with
+     * A = sqrt(n) H D3 H D2 H D1 pass scale = sqrt(n) / sigma.                  */
+    SPINNER_EPI_COSSIN = 1
+} spinner_epilogue_t;
+
+/*
+ * Apply one spinner (one triple of diagonals) to a batch and run an epilogue.
+ *
+ *   x         in   device fp32 [batch][n]; never written
+ *   n         in   vector length, power of two in [2^4, 2^24]
+ *   batch     in   number of vectors, >= 0
+ *   d1,d2,d3  in   device fp32 [n] each: the diagonals of D1, D2, D3
+ *   m         in   number of leading coordinates kept, 1 <= m <= n
+ *   epilogue  in   spinner_epilogue_t
+ *   scale     in   caller's factor on top of the normalised transform
+ *                  (1 for the plain spinner, sqrt(n/m) for a norm-preserving
+ *                  reduction, sqrt(n)/sigma for Gaussian-kernel features)
+ *   out       out  device fp32 [batch][m] (NONE) or [batch][2m] (COSSIN).
+ *                  May alias x only when n <= 2^14, m == n and epilogue is NONE.
+ *   workspace      device scratch of spinner_workspace_bytes(...) bytes, or
+ *                  NULL when that is 0
+ *   stream         hipStream_t
+ *
+ * n <= 2^14: one fused kernel (all three sign-flip + transform rounds on chip).
+ * n  > 2^14: four passes over HBM using the Kronecker structure
+ *            H_{ab} = H_a (x) H_b of the Sylvester matrix; intermediate passes
+ *            run in place in `out` when m == n, else in `workspace`.
+ */
+int spinner_apply(const float *x, int n, long batch,
+                  const float *d1, const float *d2, const float *d3,
+                  int m, int epilogue, float scale,
+                  float *out, void *workspace, void *stream);
+
+/*
+ * Cross-polytope LSH (Section 4, Theorem 4): for each vector and each of L
+ * independently drawn diagonal triples (Section 3.2: independently constructed
+ * blocks), the hash is the signed canonical direction closest to the
+ * projection: i* = argmax_i |y_i| (lowest index on exact ties), bucket = i* if
+ * y_{i*} >= 0 else i* + n.  x is read once for all L triples.
+ *
+ *   x          in   device fp32 [batch][n]
+ *   L          in   number of triples, >= 1
+ *   diag_sets  in   device fp32 [L][3][n], order d1, d2, d3 within a triple
+ *   out_idx    out  device int32 [batch][L], values in [0, 2n)
+ *
+ * Supported for n <= 2^14 (SPINNER_ERR_UNSUPPORTED above that).
+ */
+int spinner_hash(const float *x, int n, long batch, int L,
+                 const float *diag_sets, int *out_idx, void *stream);
+
+/*
+ * Bytes of device scratch spinner_apply needs for these arguments: 0 when
+ * n <= 2^14 or when m == n with epilogue NONE; otherwise batch * n * 4.
+ * Returns 0 for invalid arguments (spinner_apply reports those).
+ */
+size_t spinner_workspace_bytes(int n, long batch, int m, int epilogue);
+
+/* Static, NUL-terminated description of a status code (host memory). */
+const char *spinner_strerror(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int spinner_version(void);
+
+/*
+ * Measurement aid, not part of the method: dst[i] = src[i] for count fp32
+ * elements with the same 16-byte-per-lane access shape the spinner kernels
+ * use.  It gives the achievable read+write HBM rate on the machine at hand
+ * and calibrates hardware byte counters against a transfer of known size.
+ * count must be a multiple of 4; pointers 16-byte aligned.
+ */
+int spinner_stream_copy(const float *src, float *dst, size_t count, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPINNER_H */

@@ -1,0 +1,184 @@
+// C ABI of the structured-spinner library: argument validation and dispatch.
+// The declarations, their meaning and the passages of the paper they follow
+// are in include/spinner.h.
+#include "spinner.h"
+
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "launch.hpp"
+
+namespace spinner {
+// ------------------------------------------------------------------ plain copy (measurement aid)
+__global__ void __launch_bounds__(256) stream_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                          size_t count4)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < count4; i += stride) dst[i] = src[i];
+}
+
+}  // namespace spinner
+
+namespace {
+
+thread_local char g_hip_msg[256] = "HIP error";
+
+int hip_fail(hipError_t e)
+{
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error: %s", hipGetErrorString(e));
+    return SPINNER_ERR_HIP;
+}
+
+bool pow2_in_range(int n, int* log2n)
+{
+    if (n < 16 || n > (1 << 24) || (n & (n - 1))) return false;
+    int l = 0;
+    while ((1 << l) < n) ++l;
+    *log2n = l;
+    return true;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int kFusedMaxLog = 14;
+
+}  // namespace
+
+extern "C" {
+
+int spinner_version(void) { return 100; }
+
+const char* spinner_strerror(int status)
+{
+    switch (status) {
+    case SPINNER_OK: return "success";
+    case SPINNER_ERR_BAD_N: return "n must be a power of two in [2^4, 2^24]";
+    case SPINNER_ERR_BAD_M: return "m must satisfy 1 <= m <= n";
+    case SPINNER_ERR_NULL_PTR: return "a required pointer is NULL";
+    case SPINNER_ERR_BAD_EPILOGUE: return "unknown epilogue";
+    case SPINNER_ERR_BAD_BATCH: return "batch is negative or too large";
+    case SPINNER_ERR_WORKSPACE: return "workspace required but NULL";
+    case SPINNER_ERR_HIP: return g_hip_msg;
+    case SPINNER_ERR_BAD_L: return "L must be >= 1";
+    case SPINNER_ERR_ALIGNMENT: return "data pointers must be 16-byte aligned";
+    case SPINNER_ERR_UNSUPPORTED: return "combination not supported";
+    default: return "unknown status";
+    }
+}
+
+size_t spinner_workspace_bytes(int n, long batch, int m, int epilogue)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || batch <= 0 || m < 1 || m > n) return 0;
+    if (log2n <= kFusedMaxLog) return 0;
+    if (m == n && epilogue == SPINNER_EPI_NONE) return 0;
+    return (size_t)batch * (size_t)n * sizeof(float);
+}
+
+int spinner_apply(const float* x, int n, long batch, const float* d1, const float* d2, const float* d3, int m,
+                  int epilogue, float scale, float* out, void* workspace, void* stream)
+{
+    using namespace spinner;
+    int log2n;
+    if (!pow2_in_range(n, &log2n)) return SPINNER_ERR_BAD_N;
+    if (m < 1 || m > n) return SPINNER_ERR_BAD_M;
+    if (epilogue != SPINNER_EPI_NONE && epilogue != SPINNER_EPI_COSSIN) return SPINNER_ERR_BAD_EPILOGUE;
+    if (batch < 0 || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    if (batch == 0) return SPINNER_OK;
+    if (!x || !d1 || !d2 || !d3 || !out) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(x) || !aligned16(d1) || !aligned16(d2) || !aligned16(d3) || !aligned16(out))
+        return SPINNER_ERR_ALIGNMENT;
+    const size_t ws = spinner_workspace_bytes(n, batch, m, epilogue);
+    if (ws && !workspace) return SPINNER_ERR_WORKSPACE;
+    if (ws && !aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int epi = epilogue == SPINNER_EPI_COSSIN ? EPI_STORE_COSSIN : EPI_STORE_NONE;
+    const long long out_stride = epilogue == SPINNER_EPI_COSSIN ? 2LL * m : (long long)m;
+    // n^{-3/2} * scale, formed in double and rounded once
+    const float factor = (float)((double)scale / ((double)n * sqrt((double)n)));
+    const float inv_sqrt_m = (float)(1.0 / sqrt((double)m));
+
+    TileParams p;
+    memset(&p, 0, sizeof(p));
+    p.batch = batch;
+    p.m = m;
+    p.inv_sqrt_m = inv_sqrt_m;
+
+    if (log2n <= kFusedMaxLog) {
+        const long long blocks_needed = batch;   // upper bound on workgroups
+        if (blocks_needed > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
+        p.x = x; p.out = out;
+        p.d[0] = d1; p.d[1] = d2; p.d[2] = d3;
+        p.in_stride = n; p.out_stride = out_stride;
+        p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0;
+        p.factor = factor;
+        const hipError_t e = epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, p, batch, s)
+                                                      : launch_fused_none(log2n, p, batch, s);
+        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+    }
+
+    // four passes; rows are contiguous runs of 2^nr elements, there are 2^kColRowsLog of them
+    const int nr = log2n - kColRowsLog;
+    float* buf = ws ? static_cast<float*>(workspace) : out;
+    const long long row_tiles = (long long)batch << kColRowsLog;
+    const long long col_tiles = (long long)batch << (nr - kColContigLog);
+    if (row_tiles > 0x7fffffffLL * 4 || col_tiles > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
+
+    hipError_t e;
+    // P1: D1, rows : x -> buf
+    p.x = x; p.out = buf; p.d[0] = d1; p.d[1] = nullptr; p.d[2] = nullptr;
+    p.in_stride = n; p.out_stride = n; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
+    p.m = n; p.factor = 1.0f;
+    if ((e = launch_row_first(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
+    // P2: cols, D2, cols : buf -> buf
+    p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
+    p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
+    if ((e = launch_col_middle(p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+    // P3: rows, D3, rows : buf -> buf
+    p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
+    if ((e = launch_row_middle(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
+    // P4: cols, epilogue : buf -> out
+    p.out = out; p.d[1] = nullptr; p.out_stride = out_stride;
+    p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
+    p.m = m; p.factor = factor;
+    if ((e = launch_col_last(epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+    return SPINNER_OK;
+}
+
+int spinner_hash(const float* x, int n, long batch, int L, const float* diag_sets, int* out_idx, void* stream)
+{
+    using namespace spinner;
+    int log2n;
+    if (!pow2_in_range(n, &log2n)) return SPINNER_ERR_BAD_N;
+    if (L < 1) return SPINNER_ERR_BAD_L;
+    if (batch < 0 || (double)batch * (double)n > 9.0e15 || batch > 0x7fffffffL) return SPINNER_ERR_BAD_BATCH;
+    if (batch == 0) return SPINNER_OK;
+    if (!x || !diag_sets || !out_idx) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(x) || !aligned16(diag_sets)) return SPINNER_ERR_ALIGNMENT;
+    if (log2n > kFusedMaxLog) return SPINNER_ERR_UNSUPPORTED;
+    HashParams p;
+    p.x = x; p.diag_sets = diag_sets; p.out_idx = out_idx; p.batch = batch; p.L = L;
+    const hipError_t e = launch_hash(log2n, p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_stream_copy(const float* src, float* dst, size_t count, void* stream)
+{
+    if (!src || !dst) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(src) || !aligned16(dst) || (count & 3)) return SPINNER_ERR_ALIGNMENT;
+    if (count == 0) return SPINNER_OK;
+    const size_t count4 = count / 4;
+    size_t blocks = (count4 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;   // grid-stride: 32 workgroups per CU
+    hipLaunchKernelGGL(spinner::stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const float4*>(src),
+                       reinterpret_cast<float4*>(dst), count4);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,13 @@
+// Fused three-round kernels, first-m-rows epilogue, n = 2^4 .. 2^14.
+#include "launch.hpp"
+namespace spinner {
+#define CASE(NT) case NT: return launch_tile<NT, NT, 3, true, EPI_STORE_NONE>(p, tiles, s);
+hipError_t launch_fused_none(int log2n, const TileParams& p, long long tiles, hipStream_t s)
+{
+    switch (log2n) {
+        CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14)
+    default: return hipErrorInvalidValue;
+    }
+}
+#undef CASE
+}  // namespace spinner

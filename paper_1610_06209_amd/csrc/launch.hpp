@@ -1,0 +1,33 @@
+// Host-side launch helpers shared by the translation units that instantiate
+// the kernels (split only to compile them in parallel).
+#pragma once
+#include "spinner_kernels.hpp"
+
+namespace spinner {
+
+template <int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
+inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
+{
+    using G = TileGeom<NT>;
+    const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((spinner_tile_kernel<NT, C, NSTEPS, FIRST_DIAG, EPI>), dim3((unsigned)blocks), dim3(G::THREADS),
+                       0, stream, p);
+    return hipGetLastError();
+}
+
+// implemented in fused_none.hip / fused_cossin.hip / multipass.hip / hash.hip
+hipError_t launch_fused_none(int log2n, const TileParams& p, long long tiles, hipStream_t s);
+hipError_t launch_fused_cossin(int log2n, const TileParams& p, long long tiles, hipStream_t s);
+hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
+hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
+hipError_t launch_col_middle(const TileParams& p, long long tiles, hipStream_t s);           // cols, D2, cols
+hipError_t launch_col_last(int epi, const TileParams& p, long long tiles, hipStream_t s);    // cols, epilogue
+hipError_t launch_hash(int log2n, const HashParams& p, hipStream_t s);
+
+constexpr int kColTileLog = 14;   // column tile: 2^10 rows x 2^4 contiguous columns
+constexpr int kColContigLog = 4;
+constexpr int kColRowsLog = kColTileLog - kColContigLog;
+
+}  // namespace spinner

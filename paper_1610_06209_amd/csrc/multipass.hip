@@ -1,0 +1,36 @@
+// Passes of the four-pass schedule for n > 2^14.  The vector is viewed as a
+// 2^10 x 2^(N-10) row-major matrix; H_n = H_rows (x) H_cols acts as a transform
+// along rows (contiguous tiles) and along columns (tiles of 2^10 rows x 16
+// columns).  Row and column transforms commute and a diagonal is elementwise, so
+//   P1: D1, rows   P2: cols, D2, cols   P3: rows, D3, rows   P4: cols, epilogue
+// equals H D3 H D2 H D1 with four trips through HBM instead of six.
+#include "launch.hpp"
+namespace spinner {
+#define ROWCASE(NT, STEPS, FD) case NT: return launch_tile<NT, NT, STEPS, FD, EPI_STORE_NONE>(p, tiles, s);
+hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s)
+{
+    switch (nt) {
+        ROWCASE(5, 1, true) ROWCASE(6, 1, true) ROWCASE(7, 1, true) ROWCASE(8, 1, true) ROWCASE(9, 1, true)
+        ROWCASE(10, 1, true) ROWCASE(11, 1, true) ROWCASE(12, 1, true) ROWCASE(13, 1, true) ROWCASE(14, 1, true)
+    default: return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s)
+{
+    switch (nt) {
+        ROWCASE(5, 2, false) ROWCASE(6, 2, false) ROWCASE(7, 2, false) ROWCASE(8, 2, false) ROWCASE(9, 2, false)
+        ROWCASE(10, 2, false) ROWCASE(11, 2, false) ROWCASE(12, 2, false) ROWCASE(13, 2, false) ROWCASE(14, 2, false)
+    default: return hipErrorInvalidValue;
+    }
+}
+#undef ROWCASE
+hipError_t launch_col_middle(const TileParams& p, long long tiles, hipStream_t s)
+{
+    return launch_tile<kColTileLog, kColContigLog, 2, false, EPI_STORE_NONE>(p, tiles, s);
+}
+hipError_t launch_col_last(int epi, const TileParams& p, long long tiles, hipStream_t s)
+{
+    if (epi == EPI_STORE_COSSIN) return launch_tile<kColTileLog, kColContigLog, 1, false, EPI_STORE_COSSIN>(p, tiles, s);
+    return launch_tile<kColTileLog, kColContigLog, 1, false, EPI_STORE_NONE>(p, tiles, s);
+}
+}  // namespace spinner

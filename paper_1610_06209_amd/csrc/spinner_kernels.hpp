@@ -1,0 +1,467 @@
+// Device code of the structured spinner y = H D3 H D2 H D1 x for gfx950 (wave64).
+//
+// One "tile" is 2^NT fp32 elements that live on chip for a whole kernel: a
+// complete vector when n <= 2^14 (all three rounds fused, Section 1 / Section 3
+// of the paper define the product), or a row / column block of the Kronecker
+// view H_{ab} = H_a (x) H_b when n is larger.  Every thread keeps R = 2^r
+// elements in registers.  A Walsh-Hadamard transform is a butterfly stage per
+// index bit and the stages commute, so each index bit is handled where it is
+// cheapest:
+//   * bits held by the register index  : plain add/sub between two registers;
+//   * bits held by the lane id         : exchange with lane^mask (DPP, LDS
+//                                        crossbar swizzle, bpermute) + one FMA;
+//   * bits held by the wave id (NT>12) : an LDS transpose swaps them with
+//                                        register bits, then register stages.
+// The lane id always holds index bits 2..7, so every global and LDS access is a
+// 16-byte-per-lane, fully coalesced access, and diagonals are read with the
+// same addresses as the data.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+namespace spinner {
+
+// ------------------------------------------------------------------ helpers
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// Value of `v` held by lane (id ^ MASK); MASK is a single bit.
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v)
+{
+    const int s = __builtin_bit_cast(int, v);
+    int t;
+    if constexpr (MASK == 1)        // quad_perm:[1,0,3,2]
+        t = __builtin_amdgcn_update_dpp(s, s, 0xB1, 0xF, 0xF, false);
+    else if constexpr (MASK == 2)   // quad_perm:[2,3,0,1]
+        t = __builtin_amdgcn_update_dpp(s, s, 0x4E, 0xF, 0xF, false);
+    else if constexpr (MASK == 8)   // row_ror:8 (rotation by half a 16-lane row)
+        t = __builtin_amdgcn_update_dpp(s, s, 0x128, 0xF, 0xF, false);
+    else if constexpr (MASK == 4)   // swizzle, bit mode: and=0x1f or=0 xor=4
+        t = __builtin_amdgcn_ds_swizzle(s, (4 << 10) | 0x1F);
+    else if constexpr (MASK == 16)  // swizzle, bit mode: xor=16
+        t = __builtin_amdgcn_ds_swizzle(s, (16 << 10) | 0x1F);
+    else {                          // MASK == 32: crosses the 32-lane halves
+        static_assert(MASK == 32, "single lane bit expected");
+        const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        t = __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, s);
+    }
+    return __builtin_bit_cast(float, t);
+}
+
+template <int MASK>
+__device__ __forceinline__ int lane_xor_i(int v)
+{
+    return __builtin_bit_cast(int, lane_xor<MASK>(__builtin_bit_cast(float, v)));
+}
+
+// ------------------------------------------------------------------ geometry
+// Which index bit each register / lane / wave bit holds.  Two layouts:
+//   layout 0 ("top"): registers hold bits {0,1} and the top r-2 bits
+//   layout 1 ("mid"): registers hold bits {0,1} and the r-2 bits just above the
+//                     lane bits (only used when a tile spans several waves)
+// Lanes hold bits 2 .. 2+LB-1 in both layouts.
+template <int NT>
+struct TileGeom {
+    static_assert(NT >= 4 && NT <= 14, "tile of 2^4 .. 2^14 elements");
+    static constexpr int r = NT >= 8 ? 6 : NT - 2;
+    static constexpr int R = 1 << r;
+    static constexpr int LB = (NT - r) < 6 ? (NT - r) : 6;   // lane bits per tile
+    static constexpr int WB = NT - r - LB;                   // wave bits per tile
+    static constexpr int TPW = 64 >> LB;                     // tiles per wave
+    static constexpr int WAVES = WB ? (1 << WB) : 4;         // waves per workgroup
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int TILES_PER_WG = WB ? 1 : 4 * TPW;
+
+    static constexpr int reg_pos(int lay, int q) { return q < 2 ? q : (lay == 0 ? NT - r + q : LB + q); }
+    static constexpr int lane_pos(int b) { return 2 + b; }
+    static constexpr int wave_pos(int lay, int b) { return lay == 0 ? 2 + LB + b : LB + r + b; }
+    static constexpr int reg_index(int lay, int j)
+    {
+        int e = 0;
+        for (int q = 0; q < r; ++q)
+            if ((j >> q) & 1) e |= 1 << reg_pos(lay, q);
+        return e;
+    }
+    static constexpr bool is_wave_pos(int lay, int pos)
+    {
+        for (int b = 0; b < WB; ++b)
+            if (wave_pos(lay, b) == pos) return true;
+        return false;
+    }
+    // layout in force after `steps` complete (diag, transform) steps
+    static constexpr int layout_after(int steps) { return WB ? (steps & 1) : 0; }
+};
+
+struct TileParams {
+    const float* x;           // input, row stride in_stride
+    float* out;               // output, row stride out_stride
+    const float* d[3];        // diagonals used by step 0, 1, 2 (unused entries may be null)
+    long long batch;
+    long long in_stride;
+    long long out_stride;
+    int tiles_per_vec_log;    // log2(tiles per vector)
+    int tb;                   // tile number -> first element: q << tb
+    int sl;                   // log2(row stride) of a column tile (ignored for contiguous tiles)
+    int m;                    // coordinates kept by the epilogue
+    float factor;             // n^{-3/2} * scale (or 1 for an intermediate pass)
+    float inv_sqrt_m;         // COSSIN only
+};
+
+enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1 };
+
+// Position of tile element e inside its vector, relative to the tile's base:
+// the low C bits are contiguous, the rest walks rows of 2^sl elements.
+template <int NT, int C>
+__device__ __forceinline__ long long tile_offset(int e, int sl)
+{
+    if constexpr (C >= NT) {
+        return e;
+    } else {
+        return (long long)(e & ((1 << C) - 1)) + ((long long)(e >> C) << sl);
+    }
+}
+
+// ------------------------------------------------------------------ per-thread state
+template <int NT>
+struct ThreadCtx {
+    int lit;        // lane within tile
+    int wv;         // wave bits of the tile index held by this thread
+    float sg[6];    // +1 / -1 by lane bit: sign of the own value in a lane butterfly
+    __device__ __forceinline__ int base_index(int lay) const
+    {
+        using G = TileGeom<NT>;
+        int e = lit << 2;
+        for (int b = 0; b < G::WB; ++b)
+            e |= ((wv >> b) & 1) << G::wave_pos(lay, b);
+        return e;
+    }
+};
+
+// ------------------------------------------------------------------ butterflies
+template <int Q, int R>
+__device__ __forceinline__ void reg_stage(float (&v)[R])
+{
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        if (!(j & (1 << Q))) {
+            const float a = v[j], b = v[j | (1 << Q)];
+            v[j] = a + b;
+            v[j | (1 << Q)] = a - b;
+        }
+    }
+}
+
+template <int B, int R>
+__device__ __forceinline__ void lane_stage(float (&v)[R], float sign_own)
+{
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+        v[j] = __builtin_fmaf(v[j], sign_own, lane_xor<(1 << B)>(v[j]));
+}
+
+// All stages of one transform that the current layout can do without moving
+// data between waves: register bits and lane bits at index positions >= CB.
+// SKIP_WAVE_OWNED: skip register bits that the *other* layout's waves hold
+// (those are finished after the transpose instead, so do not do them twice).
+template <int NT, int CB, int LAY>
+__device__ __forceinline__ void local_stages(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c)
+{
+    using G = TileGeom<NT>;
+    static_for<0, G::r>([&](auto q) {
+        if constexpr (G::reg_pos(LAY, q.value) >= CB) reg_stage<q.value>(v);
+    });
+    static_for<0, G::LB>([&](auto b) {
+        if constexpr (G::lane_pos(b.value) >= CB) lane_stage<b.value>(v, c.sg[b.value]);
+    });
+}
+
+// Register stages, in layout LAY, for exactly those index bits that layout
+// 1-LAY keeps in the wave id (the part of a transform left after a transpose).
+template <int NT, int CB, int LAY>
+__device__ __forceinline__ void wave_owned_stages(float (&v)[TileGeom<NT>::R])
+{
+    using G = TileGeom<NT>;
+    static_for<0, G::r>([&](auto q) {
+        constexpr int pos = G::reg_pos(LAY, q.value);
+        if constexpr (pos >= CB && G::is_wave_pos(1 - LAY, pos)) reg_stage<q.value>(v);
+    });
+}
+
+// In layout LAY, register bits that are *not* wave-owned in the other layout
+// would be transformed twice per step if local_stages ran in both layouts; the
+// step below therefore runs local_stages only in the layout the step starts in.
+
+// ------------------------------------------------------------------ LDS transpose between layouts
+template <int NT, int FROM, bool SYNC_BEFORE>
+__device__ __forceinline__ void transpose(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c, float4* lds)
+{
+    using G = TileGeom<NT>;
+    constexpr int TO = 1 - FROM;
+    if constexpr (SYNC_BEFORE) __syncthreads();     // earlier readers of lds are done
+    const int ef = c.base_index(FROM);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const int e = ef | G::reg_index(FROM, jh * 4);
+        lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
+    }
+    __syncthreads();
+    const int et = c.base_index(TO);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const int e = et | G::reg_index(TO, jh * 4);
+        const float4 t = lds[e >> 2];
+        v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+    }
+}
+
+// ------------------------------------------------------------------ diagonal product
+template <int NT, int C, int LAY>
+__device__ __forceinline__ void diag_multiply(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c,
+                                              const float* dtile, int sl)
+{
+    using G = TileGeom<NT>;
+    const float* base = dtile + tile_offset<NT, C>(c.base_index(LAY), sl);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const float4 t = *reinterpret_cast<const float4*>(base + tile_offset<NT, C>(G::reg_index(LAY, jh * 4), sl));
+        v[jh * 4] *= t.x; v[jh * 4 + 1] *= t.y; v[jh * 4 + 2] *= t.z; v[jh * 4 + 3] *= t.w;
+    }
+}
+
+// One (diagonal, transform) step starting in layout LAY; ends in
+// TileGeom::layout_after.  NTRANS counts transposes done so far in the kernel.
+template <int NT, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE>
+__device__ __forceinline__ void spinner_step(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c,
+                                             const float* dtile, int sl, float4* lds)
+{
+    using G = TileGeom<NT>;
+    if constexpr (HAS_DIAG) diag_multiply<NT, C, LAY>(v, c, dtile, sl);
+    local_stages<NT, CB, LAY>(v, c);
+    if constexpr (G::WB > 0) {
+        transpose<NT, LAY, !FIRST_TRANSPOSE>(v, c, lds);
+        wave_owned_stages<NT, CB, 1 - LAY>(v);
+    }
+}
+
+// ------------------------------------------------------------------ accurate sincos for |w| up to a few thousand
+__device__ __forceinline__ void sincos_reduced(float w, float& s, float& c)
+{
+    sincosf(w, &s, &c);
+}
+
+// ------------------------------------------------------------------ the tile kernel
+// NT      log2(tile elements)
+// C       log2(contiguous run) - NT for a contiguous tile, 4 for a column tile
+// NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
+// FIRST_DIAG  whether step 0 multiplies by p.d[0] first
+// EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
+template <int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
+__global__ void __launch_bounds__(TileGeom<NT>::THREADS)
+spinner_tile_kernel(TileParams p)
+{
+    using G = TileGeom<NT>;
+    constexpr int R = G::R;
+    constexpr int CB = C >= NT ? 0 : C;          // index bits below CB are not transformed
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    ThreadCtx<NT> c;
+    long long tile;
+    if constexpr (G::WB > 0) {
+        tile = blockIdx.x;
+        c.lit = lane;
+        c.wv = wave;
+    } else {
+        tile = ((long long)blockIdx.x * 4 + wave) * G::TPW + (lane >> G::LB);
+        c.lit = lane & ((1 << G::LB) - 1);
+        c.wv = 0;
+    }
+#pragma unroll
+    for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
+
+    const long long total = p.batch << p.tiles_per_vec_log;
+    const bool active = tile < total;
+    long long vec = 0, q = 0;
+    if (active) {
+        if (p.tiles_per_vec_log == 0) { vec = tile; }
+        else { q = tile / p.batch; vec = tile - q * p.batch; }   // neighbours share the diagonal block
+    }
+    const long long tile_first = q << p.tb;      // first element of the tile inside its vector
+
+    __shared__ float4 lds_store[G::WB > 0 ? (1 << NT) / 4 : 1];
+    float4* lds = lds_store;
+
+    float v[R];
+    {
+        const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(0), p.sl);
+#pragma unroll
+        for (int jh = 0; jh < R / 4; ++jh) {
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (active) t = *reinterpret_cast<const float4*>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
+            v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+        }
+    }
+
+    // steps (layout alternates only when a tile spans several waves)
+    spinner_step<NT, C, CB, G::layout_after(0), FIRST_DIAG, true>(v, c, p.d[0] + tile_first, p.sl, lds);
+    if constexpr (NSTEPS > 1)
+        spinner_step<NT, C, CB, G::layout_after(1), true, false>(v, c, p.d[1] + tile_first, p.sl, lds);
+    if constexpr (NSTEPS > 2)
+        spinner_step<NT, C, CB, G::layout_after(2), true, false>(v, c, p.d[2] + tile_first, p.sl, lds);
+
+    constexpr int LAYF = G::layout_after(NSTEPS);
+    const int ebase = c.base_index(LAYF);
+    if (!active) return;
+    const long long m = p.m;
+    if constexpr (EPI == EPI_STORE_NONE) {
+        float* dst = p.out + vec * p.out_stride;
+#pragma unroll
+        for (int jh = 0; jh < R / 4; ++jh) {
+            const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
+            const float a0 = v[jh * 4] * p.factor, a1 = v[jh * 4 + 1] * p.factor;
+            const float a2 = v[jh * 4 + 2] * p.factor, a3 = v[jh * 4 + 3] * p.factor;
+            if (i + 3 < m && (p.out_stride & 3) == 0) {
+                *reinterpret_cast<float4*>(dst + i) = make_float4(a0, a1, a2, a3);
+            } else {
+                if (i < m) dst[i] = a0;
+                if (i + 1 < m) dst[i + 1] = a1;
+                if (i + 2 < m) dst[i + 2] = a2;
+                if (i + 3 < m) dst[i + 3] = a3;
+            }
+        }
+    } else {
+        float* dst = p.out + vec * p.out_stride;       // out_stride == 2m
+#pragma unroll
+        for (int jh = 0; jh < R / 4; ++jh) {
+            const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
+            float sn[4], cs[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                sincos_reduced(v[jh * 4 + k] * p.factor, sn[k], cs[k]);
+                sn[k] *= p.inv_sqrt_m;
+                cs[k] *= p.inv_sqrt_m;
+            }
+            if (i + 3 < m && (m & 3) == 0) {
+                *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+                *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (i + k < m) { dst[i + k] = cs[k]; dst[m + i + k] = sn[k]; }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ cross-polytope hash kernel
+// One contiguous tile = one whole vector (n = 2^NT).  x stays in registers while
+// L diagonal triples are applied one after the other.
+struct HashParams {
+    const float* x;
+    const float* diag_sets;   // [L][3][n]
+    int* out_idx;             // [batch][L]
+    long long batch;
+    int L;
+};
+
+template <int NT>
+__global__ void __launch_bounds__(TileGeom<NT>::THREADS)
+spinner_hash_kernel(HashParams p)
+{
+    using G = TileGeom<NT>;
+    constexpr int R = G::R;
+    constexpr int n = 1 << NT;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    ThreadCtx<NT> c;
+    long long vec;
+    if constexpr (G::WB > 0) {
+        vec = blockIdx.x;
+        c.lit = lane;
+        c.wv = wave;
+    } else {
+        vec = ((long long)blockIdx.x * 4 + wave) * G::TPW + (lane >> G::LB);
+        c.lit = lane & ((1 << G::LB) - 1);
+        c.wv = 0;
+    }
+#pragma unroll
+    for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
+    const bool active = vec < p.batch;
+
+    __shared__ float4 lds_store[G::WB > 0 ? (1 << NT) / 4 : 1];
+    __shared__ float red_val[G::WB > 0 ? G::WAVES : 1];
+    __shared__ int red_idx[G::WB > 0 ? G::WAVES : 1];
+    float4* lds = lds_store;
+
+    float x0[R];
+    {
+        const float* src = p.x + (active ? vec : 0) * (long long)n + c.base_index(0);
+#pragma unroll
+        for (int jh = 0; jh < R / 4; ++jh) {
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (active) t = *reinterpret_cast<const float4*>(src + G::reg_index(0, jh * 4));
+            x0[jh * 4] = t.x; x0[jh * 4 + 1] = t.y; x0[jh * 4 + 2] = t.z; x0[jh * 4 + 3] = t.w;
+        }
+    }
+
+    for (int l = 0; l < p.L; ++l) {
+        const float* d = p.diag_sets + (long long)l * 3 * n;
+        float v[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) v[j] = x0[j];
+        // a fresh triple starts in layout 0 again, so re-sync before reusing the LDS
+        if constexpr (G::WB > 0) __syncthreads();
+        spinner_step<NT, NT, 0, G::layout_after(0), true, true>(v, c, d, 0, lds);
+        spinner_step<NT, NT, 0, G::layout_after(1), true, false>(v, c, d + n, 0, lds);
+        spinner_step<NT, NT, 0, G::layout_after(2), true, false>(v, c, d + 2 * n, 0, lds);
+
+        constexpr int LAYF = G::layout_after(3);
+        const int ebase = c.base_index(LAYF);
+        // per-thread candidate: visit registers in increasing index order, strict '>' keeps the lowest index
+        float best = v[0];
+        int best_i = ebase | G::reg_index(LAYF, 0);
+#pragma unroll
+        for (int j = 1; j < R; ++j) {
+            const bool take = __builtin_fabsf(v[j]) > __builtin_fabsf(best);
+            best = take ? v[j] : best;
+            best_i = take ? (ebase | G::reg_index(LAYF, j)) : best_i;
+        }
+        // across the lanes of the tile
+        static_for<0, G::LB>([&](auto b) {
+            const float ov = lane_xor<(1 << b.value)>(best);
+            const int oi = lane_xor_i<(1 << b.value)>(best_i);
+            const float fa = __builtin_fabsf(ov), fb = __builtin_fabsf(best);
+            const bool take = (fa > fb) || (fa == fb && oi < best_i);
+            best = take ? ov : best;
+            best_i = take ? oi : best_i;
+        });
+        if constexpr (G::WB > 0) {
+            if (lane == 0) { red_val[wave] = best; red_idx[wave] = best_i; }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                for (int w = 1; w < G::WAVES; ++w) {
+                    const float ov = red_val[w];
+                    const int oi = red_idx[w];
+                    const float fa = __builtin_fabsf(ov), fb = __builtin_fabsf(best);
+                    const bool take = (fa > fb) || (fa == fb && oi < best_i);
+                    best = take ? ov : best;
+                    best_i = take ? oi : best_i;
+                }
+                p.out_idx[vec * p.L + l] = best_i + ((best < 0.0f) ? n : 0);
+            }
+        } else {
+            if (active && c.lit == 0) p.out_idx[vec * p.L + l] = best_i + ((best < 0.0f) ? n : 0);
+        }
+    }
+}
+
+}  // namespace spinner

@@ -1,0 +1,40 @@
+"""Shared comparison rules for GPU-vs-oracle parity tests."""
+import numpy as np
+
+REL_L2_TOL = 1e-5          # per output vector, fp32 path vs fp64 oracle
+HASH_BAND = 1e-5           # relative band inside which near-ties may resolve either way
+
+
+def rel_l2_per_vector(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    got = got.astype(np.float64)
+    num = np.linalg.norm(got - want, axis=-1)
+    den = np.linalg.norm(want, axis=-1)
+    return num / np.where(den == 0, 1.0, den)
+
+
+def check_hash_against_projection(idx_gpu: np.ndarray, y: np.ndarray, band: float = HASH_BAND):
+    """idx_gpu int32 [batch][L]; y fp64 [L][batch][n] (the oracle's projections).
+
+    Exact agreement with the oracle bucket is required wherever the oracle's two
+    largest |y_i| differ by more than `band` relative; inside the band any index
+    whose |y_i| is within the band of the maximum is accepted, with its own sign.
+    Returns (number of exact matches, number accepted through the band)."""
+    L, batch, n = y.shape
+    exact = banded = 0
+    for l in range(L):
+        ay = np.abs(y[l])
+        istar = np.argmax(ay, axis=1)
+        top = ay[np.arange(batch), istar]
+        want = istar + n * (y[l][np.arange(batch), istar] < 0)
+        got = idx_gpu[:, l].astype(np.int64)
+        same = got == want
+        exact += int(same.sum())
+        for v in np.nonzero(~same)[0]:
+            g = int(got[v])
+            assert 0 <= g < 2 * n, (v, l, g)
+            i = g % n
+            # the GPU's choice must be a near-tie of the maximum and carry the right sign
+            assert ay[v, i] >= top[v] * (1.0 - band), (v, l, g, int(want[v]), ay[v, i], top[v])
+            assert (g >= n) == (y[l][v, i] < 0), (v, l, g)
+            banded += 1
+    return exact, banded

@@ -1,0 +1,101 @@
+"""Host-only checks of the C-ABI library: it loads, exports every entry point the
+header declares, and turns invalid arguments into status codes before any launch
+(no GPU work is issued by these tests)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spinner.h")
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_1610_06209_amd import binding
+
+    return binding
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spinner_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(b):
+    names = _declared_functions()
+    assert names == sorted(b.EXPORTS)
+    for name in names:
+        assert getattr(b.lib, name) is not None
+
+
+def test_version_and_messages(b):
+    assert b.spinner_version() >= 100
+    assert b.spinner_strerror(0) == "success"
+    for code in range(-10, 0):
+        msg = b.spinner_strerror(code)
+        assert msg and msg != "unknown status"
+    assert b.spinner_strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes(b):
+    assert b.spinner_workspace_bytes(1 << 14, 32768, 1024, "none") == 0
+    assert b.spinner_workspace_bytes(1 << 20, 256, 1 << 20, "none") == 0          # in place in out
+    assert b.spinner_workspace_bytes(1 << 20, 256, 1024, "none") == 256 * (1 << 20) * 4
+    assert b.spinner_workspace_bytes(1 << 20, 256, 1 << 20, "cossin") == 256 * (1 << 20) * 4
+    assert b.spinner_workspace_bytes(1000, 4, 10, "none") == 0                    # invalid -> 0
+
+
+def _apply(b, n=256, batch=4, m=256, epi=0, x=64, d1=64, d2=64, d3=64, out=64, ws=None):
+    return b.lib.spinner_apply(x, n, batch, d1, d2, d3, m, epi, ctypes.c_float(1.0), out, ws, None)
+
+
+def test_apply_rejects_bad_arguments_before_launch(b):
+    # pointers are fake but aligned; every call below must return before touching them
+    assert _apply(b, n=100) == b.SPINNER_ERR_BAD_N
+    assert _apply(b, n=8) == b.SPINNER_ERR_BAD_N
+    assert _apply(b, n=1 << 25) == b.SPINNER_ERR_BAD_N
+    assert _apply(b, n=0) == b.SPINNER_ERR_BAD_N
+    assert _apply(b, m=0) == b.SPINNER_ERR_BAD_M
+    assert _apply(b, m=257) == b.SPINNER_ERR_BAD_M
+    assert _apply(b, epi=2) == b.SPINNER_ERR_BAD_EPILOGUE
+    assert _apply(b, batch=-1) == b.SPINNER_ERR_BAD_BATCH
+    assert _apply(b, x=None) == b.SPINNER_ERR_NULL_PTR
+    assert _apply(b, d2=None) == b.SPINNER_ERR_NULL_PTR
+    assert _apply(b, out=None) == b.SPINNER_ERR_NULL_PTR
+    assert _apply(b, d3=8) == b.SPINNER_ERR_ALIGNMENT
+    assert _apply(b, out=68) == b.SPINNER_ERR_ALIGNMENT
+    assert _apply(b, n=1 << 20, m=1024) == b.SPINNER_ERR_WORKSPACE
+    assert _apply(b, batch=0, x=None, out=None) == b.SPINNER_OK                    # empty batch: no-op
+
+
+def test_hash_rejects_bad_arguments_before_launch(b):
+    h = b.lib.spinner_hash
+    assert h(64, 1000, 4, 2, 64, 64, None) == b.SPINNER_ERR_BAD_N
+    assert h(64, 1024, 4, 0, 64, 64, None) == b.SPINNER_ERR_BAD_L
+    assert h(64, 1024, -2, 2, 64, 64, None) == b.SPINNER_ERR_BAD_BATCH
+    assert h(None, 1024, 4, 2, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert h(64, 1024, 4, 2, 64, None, None) == b.SPINNER_ERR_NULL_PTR
+    assert h(4, 1024, 4, 2, 64, 64, None) == b.SPINNER_ERR_ALIGNMENT
+    assert h(64, 1 << 15, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert h(None, 1024, 0, 2, None, None, None) == b.SPINNER_OK
+
+
+def test_stream_copy_rejects_bad_arguments(b):
+    c = b.lib.spinner_stream_copy
+    assert c(None, 64, 16, None) == b.SPINNER_ERR_NULL_PTR
+    assert c(64, 68, 16, None) == b.SPINNER_ERR_ALIGNMENT
+    assert c(64, 64, 6, None) == b.SPINNER_ERR_ALIGNMENT
+    assert c(64, 64, 0, None) == b.SPINNER_OK
+
+
+def test_workloads_module_is_independent():
+    # the shared input recipes import neither side and carry none of the method's arithmetic
+    src = open(os.path.join(ROOT, "paper_1610_06209_amd", "workloads.py")).read()
+    code = "\n".join(l for l in src.splitlines() if not l.lstrip().startswith("#"))
+    for word in ("import oracle", "from oracle", "binding", "popcount", "argmax", "np.cos", "np.sin", "ctypes"):
+        assert word not in code.split('"""', 2)[2], word
+    osrc = open(os.path.join(ROOT, "oracle", "spinner_oracle.py")).read()
+    assert "paper_1610_06209_amd" not in osrc

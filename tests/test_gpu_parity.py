@@ -1,0 +1,234 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 dense
+oracle on the same seeded inputs, element by element.
+
+Tolerances (see tests/helpers.py): relative L2 error <= 1e-5 per output vector
+for fp32 outputs; hash buckets exact outside a 1e-5 relative near-tie band.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+from helpers import HASH_BAND, REL_L2_TOL, check_hash_against_projection, rel_l2_per_vector
+from paper_1610_06209_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1610_06209_amd import binding
+
+    class G:
+        pass
+
+    g = G()
+    g.torch = torch
+    g.b = binding
+    g.dev = torch.device("cuda:0")
+    return g
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print("\n[gpu-case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+
+
+def _rng_case(n, batch, seed, gaussian_d3=False):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((batch, n)).astype(np.float32)
+    d = (1.0 - 2.0 * rng.integers(0, 2, (3, n))).astype(np.float32)
+    if gaussian_d3:
+        d[2] = rng.standard_normal(n).astype(np.float32)
+    return x, d
+
+
+def _to(g, a):
+    return g.torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
+
+
+def _run_apply(g, x, d, m, epilogue, scale, **kw):
+    out = g.b.spinner_apply(_to(g, x), _to(g, d[0]), _to(g, d[1]), _to(g, d[2]), m, epilogue, scale, **kw)
+    g.torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+# ------------------------------------------------------------------ fused sizes, plain spinner
+@pytest.mark.parametrize("log2n", list(range(4, 15)))
+def test_plain_spinner_every_fused_size(gpu, oracle, log2n):
+    n = 1 << log2n
+    # ragged batch: not a multiple of the vectors a workgroup handles, several workgroups
+    batch = {4: 1000, 5: 777, 6: 333, 7: 200}.get(log2n, 37 if log2n < 12 else 9)
+    x, d = _rng_case(n, batch, 1000 + log2n, gaussian_d3=(log2n % 2 == 0))
+    got = _run_apply(gpu, x, d, n, "none", 1.0)
+    want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+    err = rel_l2_per_vector(got, want)
+    assert got.shape == (batch, n)
+    assert err.max() <= REL_L2_TOL, (log2n, err.max())
+
+
+def test_batch_of_one_and_exact_multiple(gpu, oracle):
+    for n, batch in ((256, 1), (256, 64), (1024, 16), (4096, 4)):
+        x, d = _rng_case(n, batch, n + batch)
+        got = _run_apply(gpu, x, d, n, "none", 1.0)
+        want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+        assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+
+
+def test_empty_batch_is_a_noop(gpu):
+    t = gpu.torch
+    x = t.empty((0, 256), dtype=t.float32, device=gpu.dev)
+    d = t.ones(256, dtype=t.float32, device=gpu.dev)
+    out = gpu.b.spinner_apply(x, d, d, d)
+    assert out.shape == (0, 256)
+    idx = gpu.b.spinner_hash(x, t.ones((2, 3, 256), dtype=t.float32, device=gpu.dev))
+    assert idx.shape == (0, 2)
+
+
+def test_identity_diagonals_and_special_inputs(gpu):
+    # D = I: y = H x.  x = ones -> sqrt(n) e_0 ; x = e_j -> column j of H (all +-1/sqrt(n)).
+    t = gpu.torch
+    for n in (64, 1024, 8192):
+        one = t.ones(n, dtype=t.float32, device=gpu.dev)
+        x = t.zeros((3, n), dtype=t.float32, device=gpu.dev)
+        x[0] = 1.0
+        x[1, 5] = 1.0
+        x[2, n - 1] = 2.0
+        y = gpu.b.spinner_apply(x, one, one, one).cpu().numpy().astype(np.float64)
+        want0 = np.zeros(n)
+        want0[0] = math.sqrt(n)
+        assert np.allclose(y[0], want0, atol=1e-4 * math.sqrt(n))
+        j = np.arange(n)
+        col5 = np.array([(-1.0) ** bin(i & 5).count("1") for i in j]) / math.sqrt(n)
+        assert np.allclose(y[1], col5, rtol=1e-6, atol=0)
+        coln = 2.0 * np.array([(-1.0) ** bin(i & (n - 1)).count("1") for i in j]) / math.sqrt(n)
+        assert np.allclose(y[2], coln, rtol=1e-6, atol=0)
+
+
+def test_in_place_and_non_default_stream(gpu, oracle):
+    t = gpu.torch
+    n, batch = 2048, 11
+    x, d = _rng_case(n, batch, 4242)
+    want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+    xd = _to(gpu, x)
+    dd = [_to(gpu, d[k]) for k in range(3)]
+    s = t.cuda.Stream()
+    s.wait_stream(t.cuda.current_stream())
+    with t.cuda.stream(s):
+        gpu.b.spinner_apply(xd, dd[0], dd[1], dd[2], out=xd)        # out aliases x
+    s.synchronize()
+    assert rel_l2_per_vector(xd.cpu().numpy(), want).max() <= REL_L2_TOL
+
+
+# ------------------------------------------------------------------ truncation
+@pytest.mark.parametrize("n,m,scale", [(256, 64, 2.0), (256, 5, 1.0), (1024, 1000, 0.5), (4096, 1, 1.0),
+                                       (16384, 1024, 4.0), (8192, 4100, 1.0), (64, 62, 3.0)])
+def test_first_m_rows(gpu, oracle, n, m, scale):
+    x, d = _rng_case(n, 7, n + m)
+    got = _run_apply(gpu, x, d, m, "none", scale)
+    want = oracle.apply(x, d[0], d[1], d[2], m, "none", scale)
+    assert got.shape == (7, m)
+    # relative to the norm of the kept coordinates; m = 1 compares one number
+    assert rel_l2_per_vector(got, want).max() <= (REL_L2_TOL if m > 8 else 2e-5)
+
+
+# ------------------------------------------------------------------ random features
+@pytest.mark.parametrize("n,m,scale", [(64, 64, 8.0), (1024, 1024, 32.0), (1024, 100, 3.0), (4096, 4096, 64.0),
+                                       (16384, 16384, 1.0)])
+def test_cos_sin_features(gpu, oracle, n, m, scale):
+    x, d = _rng_case(n, 6, 7 * n + m)
+    got = _run_apply(gpu, x, d, m, "cossin", scale)
+    want = oracle.apply(x, d[0], d[1], d[2], m, "cossin", scale)
+    assert got.shape == (6, 2 * m)
+    err = rel_l2_per_vector(got, want)
+    assert err.max() <= REL_L2_TOL, err.max()
+    assert np.allclose(np.linalg.norm(got.astype(np.float64), axis=1), 1.0, atol=1e-5)
+
+
+# ------------------------------------------------------------------ hash
+@pytest.mark.parametrize("log2n", list(range(4, 15)))
+def test_hash_every_size(gpu, oracle, log2n):
+    n = 1 << log2n
+    batch = 70 if log2n < 12 else 6
+    L = 3
+    w = W.Workload("h", "hash", n, batch, n, "hash", 1.0, L, "unit_normal", 500 + log2n, batch)
+    x = W.make_x_numpy(w)
+    ds = W.diag_sets(w)
+    got = gpu.b.spinner_hash(_to(gpu, x), _to(gpu, ds)).cpu().numpy()
+    assert got.shape == (batch, L) and got.dtype == np.int32
+    _, ys = oracle.hash(x, ds, return_y=True)
+    exact, banded = check_hash_against_projection(got, ys)
+    assert exact + banded == batch * L
+    assert banded <= 1
+
+
+def test_hash_rules_on_constructed_inputs(gpu):
+    # D = I, x = +-(column j of normalised H)  ->  bucket j / j + n ; zero vector -> bucket 0 ;
+    # exact tie -> lowest index.
+    t = gpu.torch
+    n = 1024
+    ones = t.ones((2, 3, n), dtype=t.float32, device=gpu.dev)
+    js = [0, 1, 77, 512, n - 1]
+    x = np.zeros((2 * len(js) + 2, n), dtype=np.float32)
+    for k, j in enumerate(js):
+        col = np.array([(-1.0) ** bin(i & j).count("1") for i in range(n)]) / 32.0     # sqrt(1024) = 32, exact
+        x[2 * k] = col
+        x[2 * k + 1] = -col
+    # x = e_0 + e_3 gives y = H x with |y_i| = 2/sqrt(n) on a quarter of the coordinates... use a
+    # cleaner tie: x = H(e_5 + e_9) so that y = e_5 + e_9 exactly (entries are multiples of 1/32)
+    c5 = np.array([(-1.0) ** bin(i & 5).count("1") for i in range(n)]) / 32.0
+    c9 = np.array([(-1.0) ** bin(i & 9).count("1") for i in range(n)]) / 32.0
+    x[-2] = c5 + c9
+    got = gpu.b.spinner_hash(_to(gpu, x), ones).cpu().numpy()
+    for k, j in enumerate(js):
+        assert got[2 * k].tolist() == [j, j]
+        assert got[2 * k + 1].tolist() == [j + n, j + n]
+    assert got[-2].tolist() == [5, 5]            # tie between 5 and 9 -> lowest index
+    assert got[-1].tolist() == [0, 0]            # all-zero vector
+
+
+def test_hash_antipodal_symmetry_full_gpu(gpu):
+    w = W.Workload("h", "hash", 512, 4096, 512, "hash", 1.0, 5, "unit_normal", 31, 0)
+    x = _to(gpu, W.make_x_numpy(w))
+    ds = _to(gpu, W.diag_sets(w))
+    h = gpu.b.spinner_hash(x, ds)
+    hn = gpu.b.spinner_hash(-x, ds)
+    assert bool(((h + w.n) % (2 * w.n) == hn).all())
+    assert int(h.min()) >= 0 and int(h.max()) < 2 * w.n
+
+
+# ------------------------------------------------------------------ n above the fused range (four passes)
+@pytest.mark.parametrize("log2n,batch", [(15, 3), (16, 2), (18, 2), (20, 2)])
+def test_multipass_plain(gpu, oracle, log2n, batch):
+    n = 1 << log2n
+    x, d = _rng_case(n, batch, 900 + log2n, gaussian_d3=(log2n == 16))
+    got = _run_apply(gpu, x, d, n, "none", 1.0)
+    want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+
+
+def test_multipass_truncated_and_features(gpu, oracle):
+    n = 1 << 15
+    x, d = _rng_case(n, 3, 77)
+    y = oracle.spinner(x, d[0], d[1], d[2])
+    got = _run_apply(gpu, x, d, 1024, "none", 4.0)
+    assert got.shape == (3, 1024)
+    assert rel_l2_per_vector(got, oracle.epilogue_none(y, 1024, 4.0)).max() <= REL_L2_TOL
+    got = _run_apply(gpu, x, d, 2048, "cossin", 2.0)
+    assert got.shape == (3, 4096)
+    assert rel_l2_per_vector(got, oracle.epilogue_cossin(y, 2048, 2.0)).max() <= REL_L2_TOL
+
+
+def test_stream_copy(gpu):
+    t = gpu.torch
+    src = t.randn(1 << 20, device=gpu.dev)
+    dst = t.zeros_like(src)
+    gpu.b.spinner_stream_copy(src, dst)
+    t.cuda.synchronize()
+    assert bool((src == dst).all())
