@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the structured-spinner hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quick]
+
+A "step" is one pass of the whole hot path (load, three sign-flip + transform
+rounds, epilogue, store) over one batch of the headline workload, i.e. one
+call of the C ABI.  Inputs are seeded, synthetic and already resident in HBM
+when the timed region starts.  Rank 0 prints ONE JSON line; the same line
+carries the per-size sweep (n = 2^10 .. 2^20) and the five configurations.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# fp32 VALU peak without packed math: 256 CUs x 64 lanes x 2.4 GHz operations per second
+VALU_PEAK_GOPS = 256 * 64 * 2.4
+
+# HBM bytes per launch read from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by what the same counter reads for spinner_stream_copy of known size); see
+# profiles/.  None where no counter run has been made for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_calls(torch, fn, steps, warmup):
+    """Returns (wall ms per step, HIP-event ms per step) for `steps` back-to-back calls."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def make_runner(torch, b, W, w, dev):
+    """Allocate inputs/outputs for workload w and return (callable, bytes info)."""
+    x = W.make_x_torch(w, dev)
+    ds = torch.from_numpy(W.diag_sets(w)).to(dev)
+    if w.kind == "hash":
+        out = torch.empty((w.batch, w.L), dtype=torch.int32, device=dev)
+
+        def fn():
+            b.spinner_hash(x, ds, out_idx=out)
+    else:
+        width = 2 * w.m if w.epilogue == "cossin" else w.m
+        out = torch.empty((w.batch, width), dtype=torch.float32, device=dev)
+        need = b.spinner_workspace_bytes(w.n, w.batch, w.m, w.epilogue)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
+        d1, d2, d3 = ds[0, 0], ds[0, 1], ds[0, 2]
+
+        def fn():
+            b.spinner_apply(x, d1, d2, d3, w.m, w.epilogue, w.scale, out=out, workspace=ws)
+    return fn, x
+
+
+def measure(torch, b, W, w, dev, steps, warmup):
+    fn, x = make_runner(torch, b, W, w, dev)
+    wall_ms, ev_ms = time_calls(torch, fn, steps, warmup)
+    alg = W.algorithmic_bytes_per_vector(w) * w.batch
+    ops = W.adds_per_vector(w) * w.batch
+    res = {
+        "workload": w.name, "n": w.n, "batch": w.batch, "m": w.m, "epilogue": w.epilogue, "L": w.L,
+        "ms_per_step": round(wall_ms, 5), "kernel_ms": round(ev_ms, 5),
+        "vectors_per_s": w.batch / (wall_ms * 1e-3),
+        "algorithmic_bytes": alg,
+        "achieved_GBs": alg / (ev_ms * 1e-3) / 1e9,
+        "hbm_frac": alg / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "butterfly_adds_Gops": ops / (ev_ms * 1e-3) / 1e9,
+        "valu_frac_adds_only": ops / (ev_ms * 1e-3) / 1e9 / VALU_PEAK_GOPS,
+    }
+    del fn, x
+    torch.cuda.empty_cache()
+    return res
+
+
+def copy_ceiling(torch, b, dev, steps, warmup):
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    _, ev_ms = time_calls(torch, lambda: b.spinner_stream_copy(src, dst), steps, warmup)
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2 * 4 * (1 << 28) / (ev_ms * 1e-3) / 1e9
+
+
+def cpu_baseline(W, w):
+    """The oracle as it stands, timed on the host cores on a bounded sample of workload w."""
+    import numpy as np
+
+    from oracle import spinner_oracle as oracle
+
+    oracle.build()
+    per_vec_macs = 3.0 * w.n * w.n * w.L if w.n <= (1 << 14) else 3.0 * 2.0 * math.sqrt(w.n) * w.n
+    sample = int(max(4, min(w.batch, 4096, 2.0e10 / per_vec_macs)))
+    ws = W.Workload(w.name, w.kind, w.n, sample, w.m, w.epilogue, w.scale, w.L, w.dist, w.seed, sample)
+    x = W.make_x_numpy(ws)
+    ds = W.diag_sets(ws)
+    oracle.hadamard_dense(16)          # load the library outside the timed region
+    t0 = time.perf_counter()
+    if w.kind == "hash":
+        oracle.hash(x, ds)
+    else:
+        oracle.apply(x, ds[0, 0], ds[0, 1], ds[0, 2], w.m, w.epilogue, w.scale)
+    dt = time.perf_counter() - t0
+    return {"value": sample / dt, "unit": "vectors/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": "%d vectors of %s (n=%d), dense O(n^2) fp64 oracle, %.2f s wall" % (sample, w.name, w.n, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="sweep_plain_n2p12",
+                    help="headline workload: sweep_plain_n2pK (K=10..20) or one of the cfg names")
+    ap.add_argument("--quick", action="store_true", help="headline only: no sweep, no configs, no CPU baseline")
+    ap.add_argument("--only", action="store_true", help="headline only, and a single JSON line without extras")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over the batch with no "
+              "collective; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_1610_06209_amd import binding as b
+    from paper_1610_06209_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def resolve(name):
+        if name in W.CONFIGS:
+            return W.CONFIGS[name]
+        if name.startswith("sweep_plain_n2p"):
+            return W.sweep_workload(int(name[len("sweep_plain_n2p"):]))
+        raise SystemExit("unknown workload %r" % name)
+
+    head = resolve(args.workload)
+    log("[bench] headline %s: n=%d batch=%d" % (head.name, head.n, head.batch))
+    hres = measure(torch, b, W, head, dev, args.steps, args.warmup)
+    log("[bench] %s: %.4f ms/step, %.3e vectors/s, %.0f GB/s (%.1f%% of 8 TB/s)" % (
+        head.name, hres["ms_per_step"], hres["vectors_per_s"], hres["achieved_GBs"], 100 * hres["hbm_frac"]))
+
+    extras = {}
+    if not (args.quick or args.only):
+        extras["copy_ceiling_GBs"] = round(copy_ceiling(torch, b, dev, 10, 3), 1)
+        log("[bench] plain copy kernel: %.0f GB/s" % extras["copy_ceiling_GBs"])
+        sweep = []
+        for k in range(10, 21):
+            w = W.sweep_workload(k)
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2))
+            sweep.append({"log2n": k, "batch": w.batch, "ms": round(r["kernel_ms"], 4),
+                          "vectors_per_s": round(r["vectors_per_s"], 1), "GBs": round(r["achieved_GBs"], 1),
+                          "hbm_frac": round(r["hbm_frac"], 4)})
+            log("[bench] sweep n=2^%d batch=%d: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)" % (
+                k, w.batch, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"]))
+        extras["sweep"] = sweep
+        cfgs = []
+        for name in W.CONFIG_ORDER:
+            w = W.CONFIGS[name]
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2))
+            cfgs.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
+                         "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
+                         "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
+            log("[bench] %s: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)  butterfly adds at %.1f%% of VALU peak" % (
+                name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
+                100 * r["valu_frac_adds_only"]))
+        extras["configs"] = cfgs
+
+    traffic = MEASURED_TRAFFIC_BYTES.get(head.name)
+    line = {
+        "metric": "HD3HD2HD1 vectors/s + achieved HBM GB/s vs peak, fp32, n=2^10..2^20",
+        "value": hres["vectors_per_s"],
+        "unit": "vectors/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": hres["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64" if head.epilogue == "cossin" and head.n <= (1 << 14) else "f32",
+        "data": "synthetic",
+        "config": {"workload": head.name, "n": head.n, "batch": head.batch, "m": head.m,
+                   "epilogue": head.epilogue, "L": head.L, "diagonals": "rademacher fp32"},
+        "roofline": {
+            "bound": "alu" if head.kind == "hash" else "hbm",
+            "achieved": hres["butterfly_adds_Gops"] / 1e3 if head.kind == "hash" else hres["achieved_GBs"],
+            "peak": VALU_PEAK_GOPS / 1e3 if head.kind == "hash" else HBM_PEAK_GBS,
+            "unit": "TFLOP/s" if head.kind == "hash" else "GB/s",
+            "frac": hres["valu_frac_adds_only"] if head.kind == "hash" else hres["hbm_frac"],
+            "traffic": traffic,
+            "kernel_ms": hres["kernel_ms"],
+            "algorithmic_bytes": hres["algorithmic_bytes"],
+        },
+    }
+    if not (args.quick or args.only):
+        line["cpu_baseline"] = cpu_baseline(W, head)
+        log("[bench] cpu oracle: %.1f vectors/s on %d cores (%s)" % (
+            line["cpu_baseline"]["value"], line["cpu_baseline"]["cores"], line["cpu_baseline"]["sample"]))
+    else:
+        line["cpu_baseline"] = None
+    line.update(extras)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

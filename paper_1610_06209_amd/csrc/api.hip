@@ -107,6 +107,7 @@ int spinner_apply(const float* x, int n, long batch, const float* d1, const floa
     p.batch = batch;
     p.m = m;
     p.inv_sqrt_m = inv_sqrt_m;
+    p.factor_rev = (double)scale / ((double)n * sqrt((double)n)) / 6.283185307179586476925286766559;
 
     if (log2n <= kFusedMaxLog) {
         const long long blocks_needed = batch;   // upper bound on workgroups

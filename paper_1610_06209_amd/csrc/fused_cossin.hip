@@ -1,7 +1,9 @@
 // Fused three-round kernels, cos/sin random-feature epilogue, n = 2^4 .. 2^14.
+// The butterflies run in fp64: with w = scale * y of magnitude ~10^2 the rounding
+// of 3 log2(n) fp32 stages alone would exceed a 1e-5 relative feature error.
 #include "launch.hpp"
 namespace spinner {
-#define CASE(NT) case NT: return launch_tile<NT, NT, 3, true, EPI_STORE_COSSIN>(p, tiles, s);
+#define CASE(NT) case NT: return launch_tile<double, NT, NT, 3, true, EPI_STORE_COSSIN>(p, tiles, s);
 hipError_t launch_fused_cossin(int log2n, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (log2n) {

@@ -1,7 +1,7 @@
 // Fused three-round kernels, first-m-rows epilogue, n = 2^4 .. 2^14.
 #include "launch.hpp"
 namespace spinner {
-#define CASE(NT) case NT: return launch_tile<NT, NT, 3, true, EPI_STORE_NONE>(p, tiles, s);
+#define CASE(NT) case NT: return launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE>(p, tiles, s);
 hipError_t launch_fused_none(int log2n, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (log2n) {

@@ -4,11 +4,11 @@ namespace spinner {
 template <int NT>
 static hipError_t launch_hash_nt(const HashParams& p, hipStream_t s)
 {
-    using G = TileGeom<NT>;
+    using G = TileGeom<NT, 6>;
     const long long blocks = (p.batch + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((spinner_hash_kernel<NT>), dim3((unsigned)blocks), dim3(G::THREADS), 0, s, p);
+    hipLaunchKernelGGL((spinner_hash_kernel<G>), dim3((unsigned)blocks), dim3(G::THREADS), 0, s, p);
     return hipGetLastError();
 }
 #define CASE(NT) case NT: return launch_hash_nt<NT>(p, s);

@@ -5,14 +5,18 @@
 
 namespace spinner {
 
-template <int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
+// fp64 butterflies keep 32 values per thread (64 registers), fp32 ones 64.
+template <typename T, int NT>
+using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : 6>;
+
+template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
-    using G = TileGeom<NT>;
+    using G = GeomFor<T, NT>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((spinner_tile_kernel<NT, C, NSTEPS, FIRST_DIAG, EPI>), dim3((unsigned)blocks), dim3(G::THREADS),
+    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI>), dim3((unsigned)blocks), dim3(G::THREADS),
                        0, stream, p);
     return hipGetLastError();
 }

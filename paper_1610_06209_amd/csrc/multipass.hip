@@ -6,7 +6,7 @@
 // equals H D3 H D2 H D1 with four trips through HBM instead of six.
 #include "launch.hpp"
 namespace spinner {
-#define ROWCASE(NT, STEPS, FD) case NT: return launch_tile<NT, NT, STEPS, FD, EPI_STORE_NONE>(p, tiles, s);
+#define ROWCASE(NT, STEPS, FD) case NT: return launch_tile<float, NT, NT, STEPS, FD, EPI_STORE_NONE>(p, tiles, s);
 hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (nt) {
@@ -26,11 +26,11 @@ hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipSt
 #undef ROWCASE
 hipError_t launch_col_middle(const TileParams& p, long long tiles, hipStream_t s)
 {
-    return launch_tile<kColTileLog, kColContigLog, 2, false, EPI_STORE_NONE>(p, tiles, s);
+    return launch_tile<float, kColTileLog, kColContigLog, 2, false, EPI_STORE_NONE>(p, tiles, s);
 }
 hipError_t launch_col_last(int epi, const TileParams& p, long long tiles, hipStream_t s)
 {
-    if (epi == EPI_STORE_COSSIN) return launch_tile<kColTileLog, kColContigLog, 1, false, EPI_STORE_COSSIN>(p, tiles, s);
-    return launch_tile<kColTileLog, kColContigLog, 1, false, EPI_STORE_NONE>(p, tiles, s);
+    if (epi == EPI_STORE_COSSIN) return launch_tile<float, kColTileLog, kColContigLog, 1, false, EPI_STORE_COSSIN>(p, tiles, s);
+    return launch_tile<float, kColTileLog, kColContigLog, 1, false, EPI_STORE_NONE>(p, tiles, s);
 }
 }  // namespace spinner

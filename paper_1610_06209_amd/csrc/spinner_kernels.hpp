@@ -62,16 +62,29 @@ __device__ __forceinline__ int lane_xor_i(int v)
     return __builtin_bit_cast(int, lane_xor<MASK>(__builtin_bit_cast(float, v)));
 }
 
+template <int MASK>
+__device__ __forceinline__ double lane_xor(double v)
+{
+    const int lo = lane_xor_i<MASK>(__double2loint(v));
+    const int hi = lane_xor_i<MASK>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ float fused_mul_add(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fused_mul_add(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
 // ------------------------------------------------------------------ geometry
 // Which index bit each register / lane / wave bit holds.  Two layouts:
 //   layout 0 ("top"): registers hold bits {0,1} and the top r-2 bits
 //   layout 1 ("mid"): registers hold bits {0,1} and the r-2 bits just above the
 //                     lane bits (only used when a tile spans several waves)
 // Lanes hold bits 2 .. 2+LB-1 in both layouts.
-template <int NT>
+template <int NT_, int RMAX = 6>
 struct TileGeom {
+    static constexpr int NT = NT_;
     static_assert(NT >= 4 && NT <= 14, "tile of 2^4 .. 2^14 elements");
-    static constexpr int r = NT >= 8 ? 6 : NT - 2;
+    static_assert(RMAX >= 4 && RMAX <= 7, "16 .. 128 elements per thread");
+    static constexpr int r = NT >= RMAX + 2 ? RMAX : NT - 2;
     static constexpr int R = 1 << r;
     static constexpr int LB = (NT - r) < 6 ? (NT - r) : 6;   // lane bits per tile
     static constexpr int WB = NT - r - LB;                   // wave bits per tile
@@ -112,6 +125,7 @@ struct TileParams {
     int sl;                   // log2(row stride) of a column tile (ignored for contiguous tiles)
     int m;                    // coordinates kept by the epilogue
     float factor;             // n^{-3/2} * scale (or 1 for an intermediate pass)
+    double factor_rev;        // factor / (2 pi), fp64: w in revolutions for the fp64 feature path
     float inv_sqrt_m;         // COSSIN only
 };
 
@@ -130,14 +144,13 @@ __device__ __forceinline__ long long tile_offset(int e, int sl)
 }
 
 // ------------------------------------------------------------------ per-thread state
-template <int NT>
+template <typename G>
 struct ThreadCtx {
     int lit;        // lane within tile
     int wv;         // wave bits of the tile index held by this thread
     float sg[6];    // +1 / -1 by lane bit: sign of the own value in a lane butterfly
     __device__ __forceinline__ int base_index(int lay) const
     {
-        using G = TileGeom<NT>;
         int e = lit << 2;
         for (int b = 0; b < G::WB; ++b)
             e |= ((wv >> b) & 1) << G::wave_pos(lay, b);
@@ -146,35 +159,34 @@ struct ThreadCtx {
 };
 
 // ------------------------------------------------------------------ butterflies
-template <int Q, int R>
-__device__ __forceinline__ void reg_stage(float (&v)[R])
+template <int Q, typename T, int R>
+__device__ __forceinline__ void reg_stage(T (&v)[R])
 {
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         if (!(j & (1 << Q))) {
-            const float a = v[j], b = v[j | (1 << Q)];
+            const T a = v[j], b = v[j | (1 << Q)];
             v[j] = a + b;
             v[j | (1 << Q)] = a - b;
         }
     }
 }
 
-template <int B, int R>
-__device__ __forceinline__ void lane_stage(float (&v)[R], float sign_own)
+template <int B, typename T, int R>
+__device__ __forceinline__ void lane_stage(T (&v)[R], float sign_own)
 {
 #pragma unroll
     for (int j = 0; j < R; ++j)
-        v[j] = __builtin_fmaf(v[j], sign_own, lane_xor<(1 << B)>(v[j]));
+        v[j] = fused_mul_add(v[j], (T)sign_own, lane_xor<(1 << B)>(v[j]));
 }
 
 // All stages of one transform that the current layout can do without moving
 // data between waves: register bits and lane bits at index positions >= CB.
 // SKIP_WAVE_OWNED: skip register bits that the *other* layout's waves hold
 // (those are finished after the transpose instead, so do not do them twice).
-template <int NT, int CB, int LAY>
-__device__ __forceinline__ void local_stages(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c)
+template <typename G, int CB, int LAY, typename T>
+__device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
-    using G = TileGeom<NT>;
     static_for<0, G::r>([&](auto q) {
         if constexpr (G::reg_pos(LAY, q.value) >= CB) reg_stage<q.value>(v);
     });
@@ -185,25 +197,22 @@ __device__ __forceinline__ void local_stages(float (&v)[TileGeom<NT>::R], const 
 
 // Register stages, in layout LAY, for exactly those index bits that layout
 // 1-LAY keeps in the wave id (the part of a transform left after a transpose).
-template <int NT, int CB, int LAY>
-__device__ __forceinline__ void wave_owned_stages(float (&v)[TileGeom<NT>::R])
+template <typename G, int CB, int LAY, typename T>
+__device__ __forceinline__ void wave_owned_stages(T (&v)[G::R])
 {
-    using G = TileGeom<NT>;
     static_for<0, G::r>([&](auto q) {
         constexpr int pos = G::reg_pos(LAY, q.value);
         if constexpr (pos >= CB && G::is_wave_pos(1 - LAY, pos)) reg_stage<q.value>(v);
     });
 }
 
-// In layout LAY, register bits that are *not* wave-owned in the other layout
-// would be transformed twice per step if local_stages ran in both layouts; the
-// step below therefore runs local_stages only in the layout the step starts in.
-
 // ------------------------------------------------------------------ LDS transpose between layouts
-template <int NT, int FROM, bool SYNC_BEFORE>
-__device__ __forceinline__ void transpose(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c, float4* lds)
+// Moves every element from its (wave, lane, register) place in layout FROM to
+// its place in the other layout.  Both sides access the LDS as 16 bytes per
+// lane with consecutive lanes on consecutive addresses (no bank conflicts).
+template <typename G, int FROM, bool SYNC_BEFORE>
+__device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& c, float4* lds)
 {
-    using G = TileGeom<NT>;
     constexpr int TO = 1 - FROM;
     if constexpr (SYNC_BEFORE) __syncthreads();     // earlier readers of lds are done
     const int ef = c.base_index(FROM);
@@ -222,58 +231,110 @@ __device__ __forceinline__ void transpose(float (&v)[TileGeom<NT>::R], const Thr
     }
 }
 
+// fp64 values cross in two trips (low words, then high words) so that the LDS
+// footprint stays 4 bytes per element.
+template <typename G, int FROM, bool SYNC_BEFORE>
+__device__ __forceinline__ void transpose(double (&v)[G::R], const ThreadCtx<G>& c, float4* lds)
+{
+    constexpr int TO = 1 - FROM;
+    int4* ilds = reinterpret_cast<int4*>(lds);
+    const int ef = c.base_index(FROM);
+    const int et = c.base_index(TO);
+    int lo[G::R];
+    if constexpr (SYNC_BEFORE) __syncthreads();
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const int e = ef | G::reg_index(FROM, jh * 4);
+        ilds[e >> 2] = make_int4(__double2loint(v[jh * 4]), __double2loint(v[jh * 4 + 1]),
+                                 __double2loint(v[jh * 4 + 2]), __double2loint(v[jh * 4 + 3]));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const int4 t = ilds[(et | G::reg_index(TO, jh * 4)) >> 2];
+        lo[jh * 4] = t.x; lo[jh * 4 + 1] = t.y; lo[jh * 4 + 2] = t.z; lo[jh * 4 + 3] = t.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const int e = ef | G::reg_index(FROM, jh * 4);
+        ilds[e >> 2] = make_int4(__double2hiint(v[jh * 4]), __double2hiint(v[jh * 4 + 1]),
+                                 __double2hiint(v[jh * 4 + 2]), __double2hiint(v[jh * 4 + 3]));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const int4 t = ilds[(et | G::reg_index(TO, jh * 4)) >> 2];
+        v[jh * 4] = __hiloint2double(t.x, lo[jh * 4]);
+        v[jh * 4 + 1] = __hiloint2double(t.y, lo[jh * 4 + 1]);
+        v[jh * 4 + 2] = __hiloint2double(t.z, lo[jh * 4 + 2]);
+        v[jh * 4 + 3] = __hiloint2double(t.w, lo[jh * 4 + 3]);
+    }
+}
+
 // ------------------------------------------------------------------ diagonal product
-template <int NT, int C, int LAY>
-__device__ __forceinline__ void diag_multiply(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c,
+template <typename G, int C, int LAY, typename T>
+__device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& c,
                                               const float* dtile, int sl)
 {
-    using G = TileGeom<NT>;
+    constexpr int NT = G::NT;
     const float* base = dtile + tile_offset<NT, C>(c.base_index(LAY), sl);
 #pragma unroll
     for (int jh = 0; jh < G::R / 4; ++jh) {
         const float4 t = *reinterpret_cast<const float4*>(base + tile_offset<NT, C>(G::reg_index(LAY, jh * 4), sl));
-        v[jh * 4] *= t.x; v[jh * 4 + 1] *= t.y; v[jh * 4 + 2] *= t.z; v[jh * 4 + 3] *= t.w;
+        v[jh * 4] *= (T)t.x; v[jh * 4 + 1] *= (T)t.y; v[jh * 4 + 2] *= (T)t.z; v[jh * 4 + 3] *= (T)t.w;
     }
 }
 
-// One (diagonal, transform) step starting in layout LAY; ends in
-// TileGeom::layout_after.  NTRANS counts transposes done so far in the kernel.
-template <int NT, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE>
-__device__ __forceinline__ void spinner_step(float (&v)[TileGeom<NT>::R], const ThreadCtx<NT>& c,
+// One (diagonal, transform) step starting in layout LAY; it ends in the other
+// layout when the tile spans several waves.  Every index bit >= CB is
+// transformed exactly once: register and lane bits of LAY before the transpose,
+// the bits LAY keeps in the wave id after it.
+template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, typename T>
+__device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c,
                                              const float* dtile, int sl, float4* lds)
 {
-    using G = TileGeom<NT>;
-    if constexpr (HAS_DIAG) diag_multiply<NT, C, LAY>(v, c, dtile, sl);
-    local_stages<NT, CB, LAY>(v, c);
+    if constexpr (HAS_DIAG) diag_multiply<G, C, LAY>(v, c, dtile, sl);
+    local_stages<G, CB, LAY>(v, c);
     if constexpr (G::WB > 0) {
-        transpose<NT, LAY, !FIRST_TRANSPOSE>(v, c, lds);
-        wave_owned_stages<NT, CB, 1 - LAY>(v);
+        transpose<G, LAY, !FIRST_TRANSPOSE>(v, c, lds);
+        wave_owned_stages<G, CB, 1 - LAY>(v);
     }
 }
 
-// ------------------------------------------------------------------ accurate sincos for |w| up to a few thousand
-__device__ __forceinline__ void sincos_reduced(float w, float& s, float& c)
+// ------------------------------------------------------------------ cos / sin of w = y * factor
+// fp32 values: plain library sincos of the fp32 product.
+__device__ __forceinline__ void feature_sincos(float y, const TileParams& p, float& s, float& c)
 {
-    sincosf(w, &s, &c);
+    sincosf(y * p.factor, &s, &c);
+}
+// fp64 values: reduce w / (2 pi) to [-1/2, 1/2] revolutions in fp64 (exact
+// subtraction), then evaluate in fp32 on the reduced argument.
+__device__ __forceinline__ void feature_sincos(double y, const TileParams& p, float& s, float& c)
+{
+    const double t = y * p.factor_rev;
+    const double fr = t - __builtin_rint(t);
+    sincospif(2.0f * (float)fr, &s, &c);
 }
 
 // ------------------------------------------------------------------ the tile kernel
+// T       arithmetic type of the butterflies (float, or double for the feature map)
 // NT      log2(tile elements)
 // C       log2(contiguous run) - NT for a contiguous tile, 4 for a column tile
 // NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
-template <int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
-__global__ void __launch_bounds__(TileGeom<NT>::THREADS)
+template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
+__global__ void __launch_bounds__(G::THREADS)
 spinner_tile_kernel(TileParams p)
 {
-    using G = TileGeom<NT>;
+    constexpr int NT = G::NT;
     constexpr int R = G::R;
     constexpr int CB = C >= NT ? 0 : C;          // index bits below CB are not transformed
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    ThreadCtx<NT> c;
+    ThreadCtx<G> c;
     long long tile;
     if constexpr (G::WB > 0) {
         tile = blockIdx.x;
@@ -299,23 +360,23 @@ spinner_tile_kernel(TileParams p)
     __shared__ float4 lds_store[G::WB > 0 ? (1 << NT) / 4 : 1];
     float4* lds = lds_store;
 
-    float v[R];
+    T v[R];
     {
         const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(0), p.sl);
 #pragma unroll
         for (int jh = 0; jh < R / 4; ++jh) {
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
             if (active) t = *reinterpret_cast<const float4*>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
-            v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+            v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
         }
     }
 
     // steps (layout alternates only when a tile spans several waves)
-    spinner_step<NT, C, CB, G::layout_after(0), FIRST_DIAG, true>(v, c, p.d[0] + tile_first, p.sl, lds);
+    spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true>(v, c, p.d[0] + tile_first, p.sl, lds);
     if constexpr (NSTEPS > 1)
-        spinner_step<NT, C, CB, G::layout_after(1), true, false>(v, c, p.d[1] + tile_first, p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(1), true, false>(v, c, p.d[1] + tile_first, p.sl, lds);
     if constexpr (NSTEPS > 2)
-        spinner_step<NT, C, CB, G::layout_after(2), true, false>(v, c, p.d[2] + tile_first, p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(2), true, false>(v, c, p.d[2] + tile_first, p.sl, lds);
 
     constexpr int LAYF = G::layout_after(NSTEPS);
     const int ebase = c.base_index(LAYF);
@@ -326,8 +387,8 @@ spinner_tile_kernel(TileParams p)
 #pragma unroll
         for (int jh = 0; jh < R / 4; ++jh) {
             const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
-            const float a0 = v[jh * 4] * p.factor, a1 = v[jh * 4 + 1] * p.factor;
-            const float a2 = v[jh * 4 + 2] * p.factor, a3 = v[jh * 4 + 3] * p.factor;
+            const float a0 = (float)(v[jh * 4] * (T)p.factor), a1 = (float)(v[jh * 4 + 1] * (T)p.factor);
+            const float a2 = (float)(v[jh * 4 + 2] * (T)p.factor), a3 = (float)(v[jh * 4 + 3] * (T)p.factor);
             if (i + 3 < m && (p.out_stride & 3) == 0) {
                 *reinterpret_cast<float4*>(dst + i) = make_float4(a0, a1, a2, a3);
             } else {
@@ -345,7 +406,7 @@ spinner_tile_kernel(TileParams p)
             float sn[4], cs[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                sincos_reduced(v[jh * 4 + k] * p.factor, sn[k], cs[k]);
+                feature_sincos(v[jh * 4 + k], p, sn[k], cs[k]);
                 sn[k] *= p.inv_sqrt_m;
                 cs[k] *= p.inv_sqrt_m;
             }
@@ -372,17 +433,17 @@ struct HashParams {
     int L;
 };
 
-template <int NT>
-__global__ void __launch_bounds__(TileGeom<NT>::THREADS)
+template <typename G>
+__global__ void __launch_bounds__(G::THREADS)
 spinner_hash_kernel(HashParams p)
 {
-    using G = TileGeom<NT>;
+    constexpr int NT = G::NT;
     constexpr int R = G::R;
     constexpr int n = 1 << NT;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    ThreadCtx<NT> c;
+    ThreadCtx<G> c;
     long long vec;
     if constexpr (G::WB > 0) {
         vec = blockIdx.x;
@@ -420,9 +481,9 @@ spinner_hash_kernel(HashParams p)
         for (int j = 0; j < R; ++j) v[j] = x0[j];
         // a fresh triple starts in layout 0 again, so re-sync before reusing the LDS
         if constexpr (G::WB > 0) __syncthreads();
-        spinner_step<NT, NT, 0, G::layout_after(0), true, true>(v, c, d, 0, lds);
-        spinner_step<NT, NT, 0, G::layout_after(1), true, false>(v, c, d + n, 0, lds);
-        spinner_step<NT, NT, 0, G::layout_after(2), true, false>(v, c, d + 2 * n, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(0), true, true>(v, c, d, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(1), true, false>(v, c, d + n, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(2), true, false>(v, c, d + 2 * n, 0, lds);
 
         constexpr int LAYF = G::layout_after(3);
         const int ebase = c.base_index(LAYF);
