@@ -39,11 +39,11 @@ __device__ __forceinline__ float lane_xor(float v)
     const int s = __builtin_bit_cast(int, v);
     int t;
     if constexpr (MASK == 1)        // quad_perm:[1,0,3,2]
-        t = __builtin_amdgcn_update_dpp(s, s, 0xB1, 0xF, 0xF, false);
+        t = __builtin_amdgcn_update_dpp(0, s, 0xB1, 0xF, 0xF, true);
     else if constexpr (MASK == 2)   // quad_perm:[2,3,0,1]
-        t = __builtin_amdgcn_update_dpp(s, s, 0x4E, 0xF, 0xF, false);
+        t = __builtin_amdgcn_update_dpp(0, s, 0x4E, 0xF, 0xF, true);
     else if constexpr (MASK == 8)   // row_ror:8 (rotation by half a 16-lane row)
-        t = __builtin_amdgcn_update_dpp(s, s, 0x128, 0xF, 0xF, false);
+        t = __builtin_amdgcn_update_dpp(0, s, 0x128, 0xF, 0xF, true);
     else if constexpr (MASK == 4)   // swizzle, bit mode: and=0x1f or=0 xor=4
         t = __builtin_amdgcn_ds_swizzle(s, (4 << 10) | 0x1F);
     else if constexpr (MASK == 16)  // swizzle, bit mode: xor=16
@@ -172,6 +172,8 @@ __device__ __forceinline__ void reg_stage(T (&v)[R])
     }
 }
 
+// Exact lane butterfly: the lane with the mask bit clear gets own + partner,
+// the other one partner - own.
 template <int B, typename T, int R>
 __device__ __forceinline__ void lane_stage(T (&v)[R], float sign_own)
 {
@@ -180,19 +182,87 @@ __device__ __forceinline__ void lane_stage(T (&v)[R], float sign_own)
         v[j] = fused_mul_add(v[j], (T)sign_own, lane_xor<(1 << B)>(v[j]));
 }
 
+// One-instruction lane butterfly for the masks a DPP control can express
+// (xor 1, xor 2 inside a quad, xor 8 inside a row of 16):
+//     own <- own + coef * partner          (v_fmac_f32 with a DPP source)
+// With coef = +1 on the lower lane and -1 on the upper lane this gives a+b on
+// the lower lane and b-a = -(a-b) on the upper one: the upper lane holds the
+// NEGATED difference.  Every later stage is linear, so the kernel keeps a
+// per-lane sign s (true value = s * held value) instead of fixing it at once:
+// in a transform that starts with all s = +1 the coefficients are (+1,-1) and
+// it ends with s = prod over these masks of (-1)^bit; the next transform
+// starts from that state, uses the negated coefficients (-1,+1) and ends with
+// all s = +1 again.  Partners of every other kind of stage (registers, swizzle,
+// bpermute, LDS transpose across waves) share the same s, so those stay exact.
+// An odd number of transforms leaves s to be folded into the output factor.
+// The two wait states a DPP read needs after a VALU write of the same register
+// are supplied by the s_nop at the head of each block.
+#define SPINNER_FMAC_DPP8(CTRL)                                                             \
+    asm volatile("s_nop 1\n\t"                                                              \
+                 "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf"               \
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]) \
+                 : "v"(coef))
+
+template <int MASK>
+__device__ __forceinline__ void fmac_dpp_block8(float* a, float coef)
+{
+    if constexpr (MASK == 1) SPINNER_FMAC_DPP8("quad_perm:[1,0,3,2]");
+    else if constexpr (MASK == 2) SPINNER_FMAC_DPP8("quad_perm:[2,3,0,1]");
+    else { static_assert(MASK == 8, "mask without a DPP control"); SPINNER_FMAC_DPP8("row_ror:8"); }
+}
+
+template <typename T, int R>
+constexpr bool lane_mask_uses_fmac_dpp(int mask)
+{
+    return std::is_same<T, float>::value && R >= 8 && (mask == 1 || mask == 2 || mask == 8);
+}
+
+template <int B, int R>
+__device__ __forceinline__ void lane_stage_fmac_dpp(float (&v)[R], float coef)
+{
+#pragma unroll
+    for (int j = 0; j < R; j += 8) fmac_dpp_block8<(1 << B)>(&v[j], coef);
+}
+
 // All stages of one transform that the current layout can do without moving
 // data between waves: register bits and lane bits at index positions >= CB.
 // SKIP_WAVE_OWNED: skip register bits that the *other* layout's waves hold
 // (those are finished after the transpose instead, so do not do them twice).
-template <typename G, int CB, int LAY, typename T>
+// NEGATE selects the coefficient set of the tracked-sign butterflies (true in
+// every second transform of a kernel, see lane_stage_fmac_dpp).
+template <typename G, int CB, int LAY, bool NEGATE, typename T>
 __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
     static_for<0, G::r>([&](auto q) {
         if constexpr (G::reg_pos(LAY, q.value) >= CB) reg_stage<q.value>(v);
     });
     static_for<0, G::LB>([&](auto b) {
-        if constexpr (G::lane_pos(b.value) >= CB) lane_stage<b.value>(v, c.sg[b.value]);
+        if constexpr (G::lane_pos(b.value) >= CB) {
+            if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value))
+                lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
+            else
+                lane_stage<b.value>(v, c.sg[b.value]);
+        }
     });
+}
+
+// Sign s of the value a lane holds after an odd number of transforms (+1 after
+// an even number): the product of sg over the tracked-sign lane masks.
+template <typename G, int CB, typename T>
+__device__ __forceinline__ float tracked_sign(const ThreadCtx<G>& c)
+{
+    float s = 1.0f;
+    static_for<0, G::LB>([&](auto b) {
+        if constexpr (G::lane_pos(b.value) >= CB && lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) s *= c.sg[b.value];
+    });
+    return s;
 }
 
 // Register stages, in layout LAY, for exactly those index bits that layout
@@ -290,12 +360,12 @@ __device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& 
 // layout when the tile spans several waves.  Every index bit >= CB is
 // transformed exactly once: register and lane bits of LAY before the transpose,
 // the bits LAY keeps in the wave id after it.
-template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, typename T>
+template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, bool NEGATE, typename T>
 __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c,
                                              const float* dtile, int sl, float4* lds)
 {
     if constexpr (HAS_DIAG) diag_multiply<G, C, LAY>(v, c, dtile, sl);
-    local_stages<G, CB, LAY>(v, c);
+    local_stages<G, CB, LAY, NEGATE>(v, c);
     if constexpr (G::WB > 0) {
         transpose<G, LAY, !FIRST_TRANSPOSE>(v, c, lds);
         wave_owned_stages<G, CB, 1 - LAY>(v);
@@ -304,13 +374,13 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 
 // ------------------------------------------------------------------ cos / sin of w = y * factor
 // fp32 values: plain library sincos of the fp32 product.
-__device__ __forceinline__ void feature_sincos(float y, const TileParams& p, float& s, float& c)
+__device__ __forceinline__ void feature_sincos(float y, const TileParams&, float lane_factor, float& s, float& c)
 {
-    sincosf(y * p.factor, &s, &c);
+    sincosf(y * lane_factor, &s, &c);
 }
 // fp64 values: reduce w / (2 pi) to [-1/2, 1/2] revolutions in fp64 (exact
 // subtraction), then evaluate in fp32 on the reduced argument.
-__device__ __forceinline__ void feature_sincos(double y, const TileParams& p, float& s, float& c)
+__device__ __forceinline__ void feature_sincos(double y, const TileParams& p, float, float& s, float& c)
 {
     const double t = y * p.factor_rev;
     const double fr = t - __builtin_rint(t);
@@ -372,45 +442,64 @@ spinner_tile_kernel(TileParams p)
     }
 
     // steps (layout alternates only when a tile spans several waves)
-    spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true>(v, c, p.d[0] + tile_first, p.sl, lds);
+    spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false>(v, c, p.d[0] + tile_first, p.sl, lds);
     if constexpr (NSTEPS > 1)
-        spinner_step<G, C, CB, G::layout_after(1), true, false>(v, c, p.d[1] + tile_first, p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(1), true, false, true>(v, c, p.d[1] + tile_first, p.sl, lds);
     if constexpr (NSTEPS > 2)
-        spinner_step<G, C, CB, G::layout_after(2), true, false>(v, c, p.d[2] + tile_first, p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(2), true, false, false>(v, c, p.d[2] + tile_first, p.sl, lds);
 
     constexpr int LAYF = G::layout_after(NSTEPS);
     const int ebase = c.base_index(LAYF);
     if (!active) return;
     const long long m = p.m;
+    // held values carry the tracked lane sign after an odd number of transforms
+    float lane_factor = p.factor;
+    if constexpr (NSTEPS & 1) lane_factor *= tracked_sign<G, CB, T>(c);
+    // whole tile inside the kept range and rows 16-byte aligned: no per-store checks
+    const bool full = (tile_first + tile_offset<NT, C>((1 << NT) - 1, p.sl) < m) && ((p.out_stride & 3) == 0);
+    float* dst = p.out + vec * p.out_stride;
     if constexpr (EPI == EPI_STORE_NONE) {
-        float* dst = p.out + vec * p.out_stride;
+        if (full) {
+            float* d0 = dst + tile_first + tile_offset<NT, C>(ebase, p.sl);
 #pragma unroll
-        for (int jh = 0; jh < R / 4; ++jh) {
-            const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
-            const float a0 = (float)(v[jh * 4] * (T)p.factor), a1 = (float)(v[jh * 4 + 1] * (T)p.factor);
-            const float a2 = (float)(v[jh * 4 + 2] * (T)p.factor), a3 = (float)(v[jh * 4 + 3] * (T)p.factor);
-            if (i + 3 < m && (p.out_stride & 3) == 0) {
-                *reinterpret_cast<float4*>(dst + i) = make_float4(a0, a1, a2, a3);
-            } else {
-                if (i < m) dst[i] = a0;
-                if (i + 1 < m) dst[i + 1] = a1;
-                if (i + 2 < m) dst[i + 2] = a2;
-                if (i + 3 < m) dst[i + 3] = a3;
+            for (int jh = 0; jh < R / 4; ++jh) {
+                const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
+                const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
+                *reinterpret_cast<float4*>(d0 + tile_offset<NT, C>(G::reg_index(LAYF, jh * 4), p.sl)) =
+                    make_float4(a0, a1, a2, a3);
+            }
+        } else {
+#pragma unroll
+            for (int jh = 0; jh < R / 4; ++jh) {
+                const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
+                const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
+                const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
+                if (i + 3 < m && (p.out_stride & 3) == 0) {
+                    *reinterpret_cast<float4*>(dst + i) = make_float4(a0, a1, a2, a3);
+                } else {
+                    if (i < m) dst[i] = a0;
+                    if (i + 1 < m) dst[i + 1] = a1;
+                    if (i + 2 < m) dst[i + 2] = a2;
+                    if (i + 3 < m) dst[i + 3] = a3;
+                }
             }
         }
     } else {
-        float* dst = p.out + vec * p.out_stride;       // out_stride == 2m
+        // dst row is [cos block of m | sin block of m]
 #pragma unroll
         for (int jh = 0; jh < R / 4; ++jh) {
             const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
             float sn[4], cs[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                feature_sincos(v[jh * 4 + k], p, sn[k], cs[k]);
+                feature_sincos(v[jh * 4 + k], p, lane_factor, sn[k], cs[k]);
                 sn[k] *= p.inv_sqrt_m;
                 cs[k] *= p.inv_sqrt_m;
             }
-            if (i + 3 < m && (m & 3) == 0) {
+            if (full && (m & 3) == 0) {
+                *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+                *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
+            } else if (i + 3 < m && (m & 3) == 0) {
                 *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
                 *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
             } else {
@@ -481,9 +570,9 @@ spinner_hash_kernel(HashParams p)
         for (int j = 0; j < R; ++j) v[j] = x0[j];
         // a fresh triple starts in layout 0 again, so re-sync before reusing the LDS
         if constexpr (G::WB > 0) __syncthreads();
-        spinner_step<G, NT, 0, G::layout_after(0), true, true>(v, c, d, 0, lds);
-        spinner_step<G, NT, 0, G::layout_after(1), true, false>(v, c, d + n, 0, lds);
-        spinner_step<G, NT, 0, G::layout_after(2), true, false>(v, c, d + 2 * n, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(0), true, true, false>(v, c, d, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(1), true, false, true>(v, c, d + n, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(2), true, false, false>(v, c, d + 2 * n, 0, lds);
 
         constexpr int LAYF = G::layout_after(3);
         const int ebase = c.base_index(LAYF);
@@ -496,6 +585,7 @@ spinner_hash_kernel(HashParams p)
             best = take ? v[j] : best;
             best_i = take ? (ebase | G::reg_index(LAYF, j)) : best_i;
         }
+        best *= tracked_sign<G, 0, float>(c);     // three transforms: undo the tracked lane sign
         // across the lanes of the tile
         static_for<0, G::LB>([&](auto b) {
             const float ov = lane_xor<(1 << b.value)>(best);
