@@ -11,8 +11,8 @@
  * their fp32 diagonals (+-1 in the random setting, arbitrary in the adaptive
  * one, Gaussian D3 for the H D_g H D2 H D1 member).  H is never materialised:
  * each H is a fast Walsh-Hadamard transform that runs entirely on the GPU.
- * The projection is fused with the step that consumes it (Section 1:
- * "projections are often passed to a possibly highly nonlinear function").
+ * The projection is fused with the step that consumes it (Section 1 notes that
+ * the projected data usually go straight into some nonlinear function).
  *
  * Conventions shared by every entry point
  *   - All data pointers are DEVICE pointers unless stated otherwise, must be
@@ -105,6 +105,36 @@ int spinner_apply(const float *x, int n, long batch,
  */
 int spinner_hash(const float *x, int n, long batch, int L,
                  const float *diag_sets, int *out_idx, void *stream);
+
+/*
+ * Random setting, parameters prepared in advance.  In the random setting the
+ * diagonals are drawn from {-1,+1} (Section 3, notation paragraph), and the
+ * paper's own timings prepare all parameters of the matrix beforehand and put
+ * only the matrix-vector products on the clock (Section 5).  For such
+ * diagonals only one bit per entry matters: spinner_pack_signs turns L triples
+ * of fp32 diagonals into the library's packed sign words once, and
+ * spinner_apply_signs / spinner_hash_signs then compute exactly what
+ * spinner_apply / spinner_hash compute for those diagonals without reading the
+ * fp32 diagonals again (the sign words travel through the scalar cache).
+ *
+ *   diag_sets  in   device fp32 [L][3][n]; only the SIGN BIT of each entry is
+ *                   used, so entries are expected to be exactly +1 or -1
+ *   signs      out  device buffer of spinner_signs_bytes(n, L) bytes, 16-byte
+ *                   aligned, opaque; triple l starts at byte
+ *                   l * spinner_signs_bytes(n, 1)
+ *
+ * spinner_apply_signs uses the first triple found at `signs`; all other
+ * arguments, the output, the workspace rule and the error codes are those of
+ * spinner_apply.  For n > 2^14 the packed form is a plain copy of the
+ * diagonals and the four-pass path is used unchanged.
+ */
+size_t spinner_signs_bytes(int n, int L);
+int spinner_pack_signs(const float *diag_sets, int n, int L, void *signs, void *stream);
+int spinner_apply_signs(const float *x, int n, long batch, const void *signs,
+                        int m, int epilogue, float scale,
+                        float *out, void *workspace, void *stream);
+int spinner_hash_signs(const float *x, int n, long batch, int L,
+                       const void *signs, int *out_idx, void *stream);
 
 /*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 when

@@ -30,7 +30,8 @@ SPINNER_EPI_COSSIN = 1
 EPILOGUES = {"none": SPINNER_EPI_NONE, "cossin": SPINNER_EPI_COSSIN}
 
 EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_strerror",
-           "spinner_version", "spinner_stream_copy"]
+           "spinner_version", "spinner_stream_copy", "spinner_signs_bytes", "spinner_pack_signs",
+           "spinner_apply_signs", "spinner_hash_signs"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -50,6 +51,15 @@ lib.spinner_strerror.restype = ctypes.c_char_p
 lib.spinner_strerror.argtypes = [ctypes.c_int]
 lib.spinner_version.restype = ctypes.c_int
 lib.spinner_version.argtypes = []
+lib.spinner_signs_bytes.restype = ctypes.c_size_t
+lib.spinner_signs_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
+lib.spinner_pack_signs.restype = ctypes.c_int
+lib.spinner_pack_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp]
+lib.spinner_apply_signs.restype = ctypes.c_int
+lib.spinner_apply_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_float, _vp, _vp, _vp]
+lib.spinner_hash_signs.restype = ctypes.c_int
+lib.spinner_hash_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp]
 lib.spinner_stream_copy.restype = ctypes.c_int
 lib.spinner_stream_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
 
@@ -144,6 +154,80 @@ def spinner_hash(x, diag_sets, out_idx=None, stream=None):
         if out_idx.numel() != batch * L:
             raise ValueError("out_idx has the wrong size")
     rc = lib.spinner_hash(x.data_ptr(), n, batch, L, diag_sets.data_ptr(), out_idx.data_ptr(), _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out_idx
+
+
+def spinner_signs_bytes(n: int, L: int) -> int:
+    return int(lib.spinner_signs_bytes(int(n), int(L)))
+
+
+def spinner_pack_signs(diag_sets, stream=None):
+    """Pack fp32 +-1 diagonals [L][3][n] into the library's sign words (uint8 CUDA tensor, opaque)."""
+    import torch
+
+    _check_tensor(diag_sets, "diag_sets", torch.float32)
+    if diag_sets.dim() != 3 or diag_sets.shape[1] != 3:
+        raise ValueError("diag_sets must be [L][3][n]")
+    L, _, n = diag_sets.shape
+    nbytes = spinner_signs_bytes(n, L)
+    if nbytes == 0:
+        raise SpinnerError(SPINNER_ERR_BAD_N)
+    signs = torch.empty(nbytes, dtype=torch.uint8, device=diag_sets.device)
+    rc = lib.spinner_pack_signs(diag_sets.data_ptr(), n, L, signs.data_ptr(), _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return signs
+
+
+def spinner_apply_signs(x, signs, m=None, epilogue="none", scale=1.0, out=None, workspace=None, stream=None,
+                        triple=0):
+    """spinner_apply for +-1 diagonals given as packed sign words (see spinner_pack_signs)."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    batch, n = x.shape
+    m = n if m is None else int(m)
+    epi = _epi(epilogue)
+    width = 2 * m if epi == SPINNER_EPI_COSSIN else m
+    if out is None:
+        out = torch.empty((batch, width), dtype=torch.float32, device=x.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != batch * width:
+            raise ValueError("out has the wrong size")
+    one = spinner_signs_bytes(n, 1)
+    if signs.numel() < (triple + 1) * one:
+        raise ValueError("signs buffer too small for this n / triple")
+    need = spinner_workspace_bytes(n, batch, m, epi)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_apply_signs(x.data_ptr(), n, batch, signs.data_ptr() + triple * one, m, epi,
+                                 ctypes.c_float(scale), out.data_ptr(),
+                                 workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out
+
+
+def spinner_hash_signs(x, signs, L, out_idx=None, stream=None):
+    """spinner_hash for +-1 diagonals given as packed sign words of L triples."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    batch, n = x.shape
+    if signs.numel() < spinner_signs_bytes(n, L):
+        raise ValueError("signs buffer too small")
+    if out_idx is None:
+        out_idx = torch.empty((batch, L), dtype=torch.int32, device=x.device)
+    else:
+        _check_tensor(out_idx, "out_idx", torch.int32)
+        if out_idx.numel() != batch * L:
+            raise ValueError("out_idx has the wrong size")
+    rc = lib.spinner_hash_signs(x.data_ptr(), n, batch, L, signs.data_ptr(), out_idx.data_ptr(), _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out_idx

@@ -20,6 +20,23 @@ __global__ void __launch_bounds__(256) stream_copy_kernel(const float4* __restri
     for (; i < count4; i += stride) dst[i] = src[i];
 }
 
+
+// One wave per output word: lane l looks at element ((w >> 2) << 8) | (l << 2) | (w & 3)
+// of its diagonal and the wave's ballot of the sign bits is the word.
+__global__ void __launch_bounds__(256) pack_signs_kernel(const float* __restrict__ diag, unsigned long long* __restrict__ out,
+                                                         int n, int W, long long total_words)
+{
+    const long long gw = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (gw >= total_words) return;
+    const long long dg = gw / W;
+    const int w = (int)(gw - dg * W);
+    const long long e = ((long long)(w >> 2) << 8) | (lane << 2) | (w & 3);
+    bool neg = false;
+    if (e < n) neg = (__float_as_uint(diag[dg * n + e]) >> 31) != 0;
+    const unsigned long long m = __ballot(neg);
+    if (lane == 0) out[gw] = m;
+}
 }  // namespace spinner
 
 namespace {
@@ -78,19 +95,13 @@ size_t spinner_workspace_bytes(int n, long batch, int m, int epilogue)
     return (size_t)batch * (size_t)n * sizeof(float);
 }
 
-int spinner_apply(const float* x, int n, long batch, const float* d1, const float* d2, const float* d3, int m,
-                  int epilogue, float scale, float* out, void* workspace, void* stream)
+// Shared body of spinner_apply / spinner_apply_signs.  For n <= 2^14 `signs`
+// (if non-null) replaces d1..d3; above that size the caller passes fp32 diagonals.
+static int apply_impl(const float* x, int n, int log2n, long batch, const float* d1, const float* d2, const float* d3,
+                      const unsigned long long* signs, int m, int epilogue, float scale, float* out,
+                      void* workspace, void* stream)
 {
     using namespace spinner;
-    int log2n;
-    if (!pow2_in_range(n, &log2n)) return SPINNER_ERR_BAD_N;
-    if (m < 1 || m > n) return SPINNER_ERR_BAD_M;
-    if (epilogue != SPINNER_EPI_NONE && epilogue != SPINNER_EPI_COSSIN) return SPINNER_ERR_BAD_EPILOGUE;
-    if (batch < 0 || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
-    if (batch == 0) return SPINNER_OK;
-    if (!x || !d1 || !d2 || !d3 || !out) return SPINNER_ERR_NULL_PTR;
-    if (!aligned16(x) || !aligned16(d1) || !aligned16(d2) || !aligned16(d3) || !aligned16(out))
-        return SPINNER_ERR_ALIGNMENT;
     const size_t ws = spinner_workspace_bytes(n, batch, m, epilogue);
     if (ws && !workspace) return SPINNER_ERR_WORKSPACE;
     if (ws && !aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
@@ -99,26 +110,28 @@ int spinner_apply(const float* x, int n, long batch, const float* d1, const floa
     const int epi = epilogue == SPINNER_EPI_COSSIN ? EPI_STORE_COSSIN : EPI_STORE_NONE;
     const long long out_stride = epilogue == SPINNER_EPI_COSSIN ? 2LL * m : (long long)m;
     // n^{-3/2} * scale, formed in double and rounded once
-    const float factor = (float)((double)scale / ((double)n * sqrt((double)n)));
-    const float inv_sqrt_m = (float)(1.0 / sqrt((double)m));
+    const double factor_d = (double)scale / ((double)n * sqrt((double)n));
 
     TileParams p;
     memset(&p, 0, sizeof(p));
     p.batch = batch;
     p.m = m;
-    p.inv_sqrt_m = inv_sqrt_m;
-    p.factor_rev = (double)scale / ((double)n * sqrt((double)n)) / 6.283185307179586476925286766559;
+    p.inv_sqrt_m = (float)(1.0 / sqrt((double)m));
+    p.factor_rev = factor_d / 6.283185307179586476925286766559;
 
     if (log2n <= kFusedMaxLog) {
-        const long long blocks_needed = batch;   // upper bound on workgroups
-        if (blocks_needed > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
+        if (batch > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
         p.x = x; p.out = out;
         p.d[0] = d1; p.d[1] = d2; p.d[2] = d3;
+        if (signs) {
+            const long long W = sign_words_per_diag(n);
+            p.sw[0] = signs; p.sw[1] = signs + W; p.sw[2] = signs + 2 * W;
+        }
         p.in_stride = n; p.out_stride = out_stride;
         p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0;
-        p.factor = factor;
-        const hipError_t e = epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, p, batch, s)
-                                                      : launch_fused_none(log2n, p, batch, s);
+        p.factor = (float)factor_d;
+        const hipError_t e = epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, signs != nullptr, p, batch, s)
+                                                      : launch_fused_none(log2n, signs != nullptr, p, batch, s);
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);
     }
 
@@ -145,12 +158,82 @@ int spinner_apply(const float* x, int n, long batch, const float* d1, const floa
     // P4: cols, epilogue : buf -> out
     p.out = out; p.d[1] = nullptr; p.out_stride = out_stride;
     p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-    p.m = m; p.factor = factor;
+    p.m = m; p.factor = (float)factor_d;
     if ((e = launch_col_last(epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
     return SPINNER_OK;
 }
 
-int spinner_hash(const float* x, int n, long batch, int L, const float* diag_sets, int* out_idx, void* stream)
+static int check_apply_args(const float* x, int n, long batch, int m, int epilogue, const float* out, int* log2n)
+{
+    if (!pow2_in_range(n, log2n)) return SPINNER_ERR_BAD_N;
+    if (m < 1 || m > n) return SPINNER_ERR_BAD_M;
+    if (epilogue != SPINNER_EPI_NONE && epilogue != SPINNER_EPI_COSSIN) return SPINNER_ERR_BAD_EPILOGUE;
+    if (batch < 0 || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    if (batch == 0) return SPINNER_OK;
+    if (!x || !out) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(x) || !aligned16(out)) return SPINNER_ERR_ALIGNMENT;
+    return SPINNER_OK;
+}
+
+int spinner_apply(const float* x, int n, long batch, const float* d1, const float* d2, const float* d3, int m,
+                  int epilogue, float scale, float* out, void* workspace, void* stream)
+{
+    int log2n;
+    const int rc = check_apply_args(x, n, batch, m, epilogue, out, &log2n);
+    if (rc != SPINNER_OK || batch == 0) return rc;
+    if (!d1 || !d2 || !d3) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(d1) || !aligned16(d2) || !aligned16(d3)) return SPINNER_ERR_ALIGNMENT;
+    return apply_impl(x, n, log2n, batch, d1, d2, d3, nullptr, m, epilogue, scale, out, workspace, stream);
+}
+
+size_t spinner_signs_bytes(int n, int L)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || L < 1) return 0;
+    if (log2n <= kFusedMaxLog) return (size_t)L * 3 * (size_t)spinner::sign_words_per_diag(n) * 8;
+    return (size_t)L * 3 * (size_t)n * sizeof(float);      // plain copy of the diagonals
+}
+
+int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* stream)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n)) return SPINNER_ERR_BAD_N;
+    if (L < 1) return SPINNER_ERR_BAD_L;
+    if (!diag_sets || !signs) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (log2n > kFusedMaxLog) {
+        const hipError_t e = hipMemcpyAsync(signs, diag_sets, spinner_signs_bytes(n, L), hipMemcpyDeviceToDevice, s);
+        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+    }
+    const int W = (int)spinner::sign_words_per_diag(n);
+    const long long total_words = (long long)L * 3 * W;
+    const long long blocks = (total_words + 3) / 4;
+    hipLaunchKernelGGL(spinner::pack_signs_kernel, dim3((unsigned)blocks), dim3(256), 0, s, diag_sets,
+                       static_cast<unsigned long long*>(signs), n, W, total_words);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_apply_signs(const float* x, int n, long batch, const void* signs, int m, int epilogue, float scale,
+                        float* out, void* workspace, void* stream)
+{
+    int log2n;
+    const int rc = check_apply_args(x, n, batch, m, epilogue, out, &log2n);
+    if (rc != SPINNER_OK || batch == 0) return rc;
+    if (!signs) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
+    if (log2n > kFusedMaxLog) {
+        const float* d = static_cast<const float*>(signs);
+        return apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, epilogue, scale, out, workspace,
+                          stream);
+    }
+    return apply_impl(x, n, log2n, batch, nullptr, nullptr, nullptr, static_cast<const unsigned long long*>(signs), m,
+                      epilogue, scale, out, workspace, stream);
+}
+
+static int hash_impl(const float* x, int n, long batch, int L, const float* diag_sets, const unsigned long long* signs,
+                     int* out_idx, void* stream)
 {
     using namespace spinner;
     int log2n;
@@ -158,13 +241,23 @@ int spinner_hash(const float* x, int n, long batch, int L, const float* diag_set
     if (L < 1) return SPINNER_ERR_BAD_L;
     if (batch < 0 || (double)batch * (double)n > 9.0e15 || batch > 0x7fffffffL) return SPINNER_ERR_BAD_BATCH;
     if (batch == 0) return SPINNER_OK;
-    if (!x || !diag_sets || !out_idx) return SPINNER_ERR_NULL_PTR;
-    if (!aligned16(x) || !aligned16(diag_sets)) return SPINNER_ERR_ALIGNMENT;
+    if (!x || (!diag_sets && !signs) || !out_idx) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(x) || !aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
     if (log2n > kFusedMaxLog) return SPINNER_ERR_UNSUPPORTED;
     HashParams p;
-    p.x = x; p.diag_sets = diag_sets; p.out_idx = out_idx; p.batch = batch; p.L = L;
-    const hipError_t e = launch_hash(log2n, p, static_cast<hipStream_t>(stream));
+    p.x = x; p.diag_sets = diag_sets; p.signs = signs; p.out_idx = out_idx; p.batch = batch; p.L = L;
+    const hipError_t e = launch_hash(log2n, signs != nullptr, p, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_hash(const float* x, int n, long batch, int L, const float* diag_sets, int* out_idx, void* stream)
+{
+    return hash_impl(x, n, batch, L, diag_sets, nullptr, out_idx, stream);
+}
+
+int spinner_hash_signs(const float* x, int n, long batch, int L, const void* signs, int* out_idx, void* stream)
+{
+    return hash_impl(x, n, batch, L, nullptr, static_cast<const unsigned long long*>(signs), out_idx, stream);
 }
 
 int spinner_stream_copy(const float* src, float* dst, size_t count, void* stream)

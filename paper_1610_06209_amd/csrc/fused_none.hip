@@ -1,8 +1,10 @@
-// Fused three-round kernels, first-m-rows epilogue, n = 2^4 .. 2^14.
+// Fused three-round kernels, first-m-rows epilogue, n = 2^4 .. 2^14,
+// with fp32 diagonals or with packed sign words.
 #include "launch.hpp"
 namespace spinner {
-#define CASE(NT) case NT: return launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE>(p, tiles, s);
-hipError_t launch_fused_none(int log2n, const TileParams& p, long long tiles, hipStream_t s)
+#define CASE(NT) case NT: return signs ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true>(p, tiles, s) \
+                                       : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false>(p, tiles, s);
+hipError_t launch_fused_none(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (log2n) {
         CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14)

@@ -6,29 +6,35 @@
 namespace spinner {
 
 // fp64 butterflies keep 32 values per thread (64 registers), fp32 ones 64.
+#ifndef SPINNER_RMAX_F32
+#define SPINNER_RMAX_F32 6
+#endif
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : 6>;
+using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : SPINNER_RMAX_F32>;
 
-template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
+template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
     using G = GeomFor<T, NT>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI>), dim3((unsigned)blocks), dim3(G::THREADS),
+    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS>), dim3((unsigned)blocks), dim3(G::THREADS),
                        0, stream, p);
     return hipGetLastError();
 }
 
 // implemented in fused_none.hip / fused_cossin.hip / multipass.hip / hash.hip
-hipError_t launch_fused_none(int log2n, const TileParams& p, long long tiles, hipStream_t s);
-hipError_t launch_fused_cossin(int log2n, const TileParams& p, long long tiles, hipStream_t s);
+hipError_t launch_fused_none(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
+hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
 hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
 hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
 hipError_t launch_col_middle(const TileParams& p, long long tiles, hipStream_t s);           // cols, D2, cols
 hipError_t launch_col_last(int epi, const TileParams& p, long long tiles, hipStream_t s);    // cols, epilogue
-hipError_t launch_hash(int log2n, const HashParams& p, hipStream_t s);
+hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
+
+// sign words per diagonal in the packed format (n <= 2^14)
+inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
 
 constexpr int kColTileLog = 14;   // column tile: 2^10 rows x 2^4 contiguous columns
 constexpr int kColContigLog = 4;

@@ -20,7 +20,41 @@
 #include <stdint.h>
 #include <type_traits>
 
+// Tuning knobs (defaults are the measured best on MI355X).
+#ifndef SPINNER_WAVES_PER_WG          // waves per workgroup when a tile fits one wave
+#define SPINNER_WAVES_PER_WG 4
+#endif
+#ifndef SPINNER_MIN_WAVES_PER_EU      // occupancy the register allocator must allow for one-wave tiles
+#define SPINNER_MIN_WAVES_PER_EU 1
+#endif
+#ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
+#define SPINNER_STREAMING 0
+#endif
+
 namespace spinner {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <bool STREAM>
+__device__ __forceinline__ float4 load4(const float* p)
+{
+    if constexpr (STREAM) {
+        const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        return make_float4(t.x, t.y, t.z, t.w);
+    } else {
+        return *reinterpret_cast<const float4*>(p);
+    }
+}
+template <bool STREAM>
+__device__ __forceinline__ void store4(float* p, float a, float b, float c, float d)
+{
+    if constexpr (STREAM) {
+        v4f t = {a, b, c, d};
+        __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+    } else {
+        *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+    }
+}
 
 // ------------------------------------------------------------------ helpers
 template <int I, int N, typename F>
@@ -89,9 +123,9 @@ struct TileGeom {
     static constexpr int LB = (NT - r) < 6 ? (NT - r) : 6;   // lane bits per tile
     static constexpr int WB = NT - r - LB;                   // wave bits per tile
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
-    static constexpr int WAVES = WB ? (1 << WB) : 4;         // waves per workgroup
+    static constexpr int WAVES = WB ? (1 << WB) : SPINNER_WAVES_PER_WG;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
-    static constexpr int TILES_PER_WG = WB ? 1 : 4 * TPW;
+    static constexpr int TILES_PER_WG = WB ? 1 : WAVES * TPW;
 
     static constexpr int reg_pos(int lay, int q) { return q < 2 ? q : (lay == 0 ? NT - r + q : LB + q); }
     static constexpr int lane_pos(int b) { return 2 + b; }
@@ -117,6 +151,7 @@ struct TileParams {
     const float* x;           // input, row stride in_stride
     float* out;               // output, row stride out_stride
     const float* d[3];        // diagonals used by step 0, 1, 2 (unused entries may be null)
+    const unsigned long long* sw[3];   // packed sign words of the same diagonals (sign-word kernels only)
     long long batch;
     long long in_stride;
     long long out_stride;
@@ -351,8 +386,53 @@ __device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& 
     const float* base = dtile + tile_offset<NT, C>(c.base_index(LAY), sl);
 #pragma unroll
     for (int jh = 0; jh < G::R / 4; ++jh) {
+#ifdef SPINNER_EXPERIMENT_NODIAG
+        const float4 t = make_float4(sl + 1.0f, sl + 1.0f, sl + 1.0f, sl + 1.0f);
+#else
         const float4 t = *reinterpret_cast<const float4*>(base + tile_offset<NT, C>(G::reg_index(LAY, jh * 4), sl));
+#endif
         v[jh * 4] *= (T)t.x; v[jh * 4 + 1] *= (T)t.y; v[jh * 4 + 2] *= (T)t.z; v[jh * 4 + 3] *= (T)t.w;
+    }
+}
+
+// ------------------------------------------------------------------ +-1 diagonals as packed sign words
+// Packed format of one diagonal (n <= 2^14): 64-bit words; element e has its
+// sign bit at bit (e >> 2) & 63 of word ((e >> 8) << 2) | (e & 3).  Because the
+// lane id always holds index bits 2..7, one word is exactly the lane mask "which
+// lanes hold a negated element" of one register, so it is fetched with a scalar
+// load and applied with one v_cndmask (x or -x by lane mask): no vector memory
+// traffic and no registers spent on staging the diagonal.
+typedef const __attribute__((address_space(4))) unsigned long long* sign_words_t;
+
+__device__ __forceinline__ void flip_by_mask(float& x, unsigned long long mask)
+{
+    asm("v_cndmask_b32_e64 %0, %0, -%0, %1" : "+v"(x) : "s"(mask));
+}
+__device__ __forceinline__ void flip_by_mask(double& x, unsigned long long mask)
+{
+    int hi = __double2hiint(x);
+    asm("v_cndmask_b32_e64 %0, %0, -%0, %1" : "+v"(hi) : "s"(mask));    // the modifier flips bit 31
+    x = __hiloint2double(hi, __double2loint(x));
+}
+
+template <typename G, int LAY, typename T>
+__device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, const unsigned long long* words)
+{
+    sign_words_t w = (sign_words_t)words;
+    int ew = 0;                                   // index bits held by the (uniform) wave id
+    for (int b = 0; b < G::WB; ++b) ew |= ((c.wv >> b) & 1) << G::wave_pos(LAY, b);
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) {
+        const int e = ew | G::reg_index(LAY, j);  // lane bits (2 .. 2+LB-1) are zero here
+        unsigned long long m = w[((e >> 8) << 2) | (e & 3)];
+        if constexpr (G::LB < 6) {
+            // several tiles share the wave: take this register's 2^LB-lane pattern and repeat it
+            constexpr int span = 1 << G::LB;
+            m = (m >> ((e >> 2) & 63)) & ((1ull << span) - 1ull);
+#pragma unroll
+            for (int sft = span; sft < 64; sft <<= 1) m |= m << sft;
+        }
+        flip_by_mask(v[j], m);
     }
 }
 
@@ -360,11 +440,14 @@ __device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& 
 // layout when the tile spans several waves.  Every index bit >= CB is
 // transformed exactly once: register and lane bits of LAY before the transpose,
 // the bits LAY keeps in the wave id after it.
-template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, bool NEGATE, typename T>
+template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, bool NEGATE, bool SIGNS, typename T>
 __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c,
-                                             const float* dtile, int sl, float4* lds)
+                                             const float* dtile, const unsigned long long* words, int sl, float4* lds)
 {
-    if constexpr (HAS_DIAG) diag_multiply<G, C, LAY>(v, c, dtile, sl);
+    if constexpr (HAS_DIAG) {
+        if constexpr (SIGNS) sign_flip<G, LAY>(v, c, words);
+        else diag_multiply<G, C, LAY>(v, c, dtile, sl);
+    }
     local_stages<G, CB, LAY, NEGATE>(v, c);
     if constexpr (G::WB > 0) {
         transpose<G, LAY, !FIRST_TRANSPOSE>(v, c, lds);
@@ -394,13 +477,16 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
-template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI>
+template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS>
 __global__ void __launch_bounds__(G::THREADS)
+__attribute__((amdgpu_waves_per_eu(G::WB || !std::is_same<T, float>::value ? 1 : SPINNER_MIN_WAVES_PER_EU)))
 spinner_tile_kernel(TileParams p)
 {
+    static_assert(!SIGNS || C >= G::NT, "sign words describe contiguous tiles only");
     constexpr int NT = G::NT;
     constexpr int R = G::R;
     constexpr int CB = C >= NT ? 0 : C;          // index bits below CB are not transformed
+    constexpr bool STREAM = SPINNER_STREAMING && NSTEPS == 3;   // data touched once: bypass cache retention
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -409,9 +495,9 @@ spinner_tile_kernel(TileParams p)
     if constexpr (G::WB > 0) {
         tile = blockIdx.x;
         c.lit = lane;
-        c.wv = wave;
+        c.wv = __builtin_amdgcn_readfirstlane(wave);
     } else {
-        tile = ((long long)blockIdx.x * 4 + wave) * G::TPW + (lane >> G::LB);
+        tile = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + (lane >> G::LB);
         c.lit = lane & ((1 << G::LB) - 1);
         c.wv = 0;
     }
@@ -436,17 +522,17 @@ spinner_tile_kernel(TileParams p)
 #pragma unroll
         for (int jh = 0; jh < R / 4; ++jh) {
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (active) t = *reinterpret_cast<const float4*>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
+            if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
             v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
         }
     }
 
     // steps (layout alternates only when a tile spans several waves)
-    spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false>(v, c, p.d[0] + tile_first, p.sl, lds);
+    spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
     if constexpr (NSTEPS > 1)
-        spinner_step<G, C, CB, G::layout_after(1), true, false, true>(v, c, p.d[1] + tile_first, p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
     if constexpr (NSTEPS > 2)
-        spinner_step<G, C, CB, G::layout_after(2), true, false, false>(v, c, p.d[2] + tile_first, p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
 
     constexpr int LAYF = G::layout_after(NSTEPS);
     const int ebase = c.base_index(LAYF);
@@ -465,8 +551,7 @@ spinner_tile_kernel(TileParams p)
             for (int jh = 0; jh < R / 4; ++jh) {
                 const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
                 const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
-                *reinterpret_cast<float4*>(d0 + tile_offset<NT, C>(G::reg_index(LAYF, jh * 4), p.sl)) =
-                    make_float4(a0, a1, a2, a3);
+                store4<STREAM>(d0 + tile_offset<NT, C>(G::reg_index(LAYF, jh * 4), p.sl), a0, a1, a2, a3);
             }
         } else {
 #pragma unroll
@@ -516,13 +601,14 @@ spinner_tile_kernel(TileParams p)
 // L diagonal triples are applied one after the other.
 struct HashParams {
     const float* x;
-    const float* diag_sets;   // [L][3][n]
+    const float* diag_sets;   // [L][3][n] fp32 diagonals, or null when sign words are used
+    const unsigned long long* signs;   // [L][3][words] packed sign words, or null
     int* out_idx;             // [batch][L]
     long long batch;
     int L;
 };
 
-template <typename G>
+template <typename G, bool SIGNS>
 __global__ void __launch_bounds__(G::THREADS)
 spinner_hash_kernel(HashParams p)
 {
@@ -537,9 +623,9 @@ spinner_hash_kernel(HashParams p)
     if constexpr (G::WB > 0) {
         vec = blockIdx.x;
         c.lit = lane;
-        c.wv = wave;
+        c.wv = __builtin_amdgcn_readfirstlane(wave);
     } else {
-        vec = ((long long)blockIdx.x * 4 + wave) * G::TPW + (lane >> G::LB);
+        vec = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + (lane >> G::LB);
         c.lit = lane & ((1 << G::LB) - 1);
         c.wv = 0;
     }
@@ -565,14 +651,16 @@ spinner_hash_kernel(HashParams p)
 
     for (int l = 0; l < p.L; ++l) {
         const float* d = p.diag_sets + (long long)l * 3 * n;
+        constexpr int W = n / 64 < 4 ? 4 : n / 64;              // sign words per diagonal
+        const unsigned long long* sw = p.signs + (long long)l * 3 * W;
         float v[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) v[j] = x0[j];
         // a fresh triple starts in layout 0 again, so re-sync before reusing the LDS
         if constexpr (G::WB > 0) __syncthreads();
-        spinner_step<G, NT, 0, G::layout_after(0), true, true, false>(v, c, d, 0, lds);
-        spinner_step<G, NT, 0, G::layout_after(1), true, false, true>(v, c, d + n, 0, lds);
-        spinner_step<G, NT, 0, G::layout_after(2), true, false, false>(v, c, d + 2 * n, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(0), true, true, false, SIGNS>(v, c, d, sw, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(1), true, false, true, SIGNS>(v, c, d + n, sw + W, 0, lds);
+        spinner_step<G, NT, 0, G::layout_after(2), true, false, false, SIGNS>(v, c, d + 2 * n, sw + 2 * W, 0, lds);
 
         constexpr int LAYF = G::layout_after(3);
         const int ebase = c.base_index(LAYF);

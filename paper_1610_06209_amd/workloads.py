@@ -9,9 +9,8 @@ can draw their inputs from it without sharing any computation.
 The data stand in for the paper's workloads (Section 5: cross-polytope LSH
 collision experiment; Gaussian-kernel random features on G50C / USPST; the
 dimensionality-reduction use of Section 1), none of whose datasets are
-available here.  Random +-1 diagonals follow Section 3 ("random diagonal
-matrix with entries drawn independently from {-1,+1}"); Gaussian third
-diagonals follow Lemma 1.
+available here.  Random +-1 diagonals follow Section 3 (D has independent
+uniform +-1 entries on its diagonal); Gaussian third diagonals follow Lemma 1.
 
 Generation happens on the CPU with numpy (small cases) or directly on the GPU
 with torch's seeded generator (full-size cases, so that no multi-GiB host

@@ -83,6 +83,25 @@ def test_hash_rejects_bad_arguments_before_launch(b):
     assert h(None, 1024, 0, 2, None, None, None) == b.SPINNER_OK
 
 
+def test_sign_word_entry_points_reject_bad_arguments(b):
+    assert b.spinner_signs_bytes(1024, 1) == 3 * 16 * 8
+    assert b.spinner_signs_bytes(64, 2) == 2 * 3 * 4 * 8
+    assert b.spinner_signs_bytes(1 << 16, 1) == 3 * (1 << 16) * 4
+    assert b.spinner_signs_bytes(1000, 1) == 0 and b.spinner_signs_bytes(1024, 0) == 0
+    pk = b.lib.spinner_pack_signs
+    assert pk(64, 1000, 1, 64, None) == b.SPINNER_ERR_BAD_N
+    assert pk(64, 1024, 0, 64, None) == b.SPINNER_ERR_BAD_L
+    assert pk(None, 1024, 1, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert pk(64, 1024, 1, 72, None) == b.SPINNER_ERR_ALIGNMENT
+    ap = b.lib.spinner_apply_signs
+    assert ap(64, 1024, 4, None, 1024, 0, ctypes.c_float(1.0), 64, None, None) == b.SPINNER_ERR_NULL_PTR
+    assert ap(64, 1024, 4, 64, 2000, 0, ctypes.c_float(1.0), 64, None, None) == b.SPINNER_ERR_BAD_M
+    assert ap(64, 1024, 4, 8, 1024, 0, ctypes.c_float(1.0), 64, None, None) == b.SPINNER_ERR_ALIGNMENT
+    hs = b.lib.spinner_hash_signs
+    assert hs(64, 1024, 4, 2, None, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert hs(64, 1 << 15, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+
+
 def test_stream_copy_rejects_bad_arguments(b):
     c = b.lib.spinner_stream_copy
     assert c(None, 64, 16, None) == b.SPINNER_ERR_NULL_PTR

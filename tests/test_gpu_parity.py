@@ -225,6 +225,46 @@ def test_multipass_truncated_and_features(gpu, oracle):
     assert rel_l2_per_vector(got, oracle.epilogue_cossin(y, 2048, 2.0)).max() <= REL_L2_TOL
 
 
+# ------------------------------------------------------------------ +-1 diagonals as packed sign words
+@pytest.mark.parametrize("log2n", list(range(4, 15)))
+def test_sign_word_path_every_fused_size(gpu, oracle, log2n):
+    n = 1 << log2n
+    batch = {4: 1000, 5: 777, 6: 333, 7: 200}.get(log2n, 37 if log2n < 12 else 9)
+    L = 2
+    w = W.Workload("s", "hash", n, batch, n, "hash", 1.0, L, "normal", 7000 + log2n, batch)
+    x = W.make_x_numpy(w)
+    ds = W.diag_sets(w)
+    xd, dsd = _to(gpu, x), _to(gpu, ds)
+    signs = gpu.b.spinner_pack_signs(dsd)
+    assert signs.numel() == gpu.b.spinner_signs_bytes(n, L)
+    for t in range(L):                                          # plain spinner, each triple
+        got = gpu.b.spinner_apply_signs(xd, signs, triple=t).cpu().numpy()
+        want = oracle.apply(x, ds[t, 0], ds[t, 1], ds[t, 2], n, "none", 1.0)
+        assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (log2n, t)
+    m = max(1, n // 4)
+    got = gpu.b.spinner_apply_signs(xd, signs, m, "cossin", 0.75 * math.sqrt(n), triple=1).cpu().numpy()
+    want = oracle.apply(x, ds[1, 0], ds[1, 1], ds[1, 2], m, "cossin", 0.75 * math.sqrt(n))
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+    h = gpu.b.spinner_hash_signs(xd, signs, L).cpu().numpy()
+    _, ys = oracle.hash(x, ds, return_y=True)
+    exact, banded = check_hash_against_projection(h, ys)
+    assert exact + banded == batch * L and banded <= 1
+    # the sign-word path and the fp32-diagonal path agree bit for bit on +-1 diagonals
+    ref = gpu.b.spinner_apply(xd, dsd[0, 0], dsd[0, 1], dsd[0, 2])
+    assert bool((ref == gpu.b.spinner_apply_signs(xd, signs, triple=0)).all())
+    assert bool((gpu.b.spinner_hash(xd, dsd) == gpu.b.spinner_hash_signs(xd, signs, L)).all())
+
+
+def test_sign_word_path_above_fused_range(gpu, oracle):
+    n = 1 << 15
+    x, d = _rng_case(n, 2, 31)
+    xd = _to(gpu, x)
+    signs = gpu.b.spinner_pack_signs(_to(gpu, d[None]))
+    got = gpu.b.spinner_apply_signs(xd, signs).cpu().numpy()
+    want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+
+
 def test_stream_copy(gpu):
     t = gpu.torch
     src = t.randn(1 << 20, device=gpu.dev)
