@@ -29,7 +29,10 @@ VALU_PEAK_GOPS = 256 * 64 * 2.4
 # HBM bytes per launch read from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the same counter reads for spinner_stream_copy of known size); see
 # profiles/.  None where no counter run has been made for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/spinner_tile_kernel_n4096_sweep_plain_n2p12.md: (524496.0 KiB x 2.0000) + (1048831.2 KiB x 1.0000)
+    "sweep_plain_n2p12": int((524496.0 * 2.0 + 1048831.2) * 1024),
+}
 
 
 def log(*a):
@@ -53,34 +56,54 @@ def time_calls(torch, fn, steps, warmup):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
-def make_runner(torch, b, W, w, dev):
-    """Allocate inputs/outputs for workload w and return (callable, bytes info)."""
+def make_runner(torch, b, W, w, dev, diagonals):
+    """Allocate inputs/outputs for workload w and return the callable that runs one step.
+
+    diagonals = "signs": the +-1 diagonals are packed once, off the clock, into sign words
+    (spinner_pack_signs) and the step calls spinner_apply_signs / spinner_hash_signs;
+    diagonals = "fp32": the step calls spinner_apply / spinner_hash with the fp32 diagonals."""
     x = W.make_x_torch(w, dev)
     ds = torch.from_numpy(W.diag_sets(w)).to(dev)
+    signs = b.spinner_pack_signs(ds) if diagonals == "signs" else None
     if w.kind == "hash":
         out = torch.empty((w.batch, w.L), dtype=torch.int32, device=dev)
-
-        def fn():
-            b.spinner_hash(x, ds, out_idx=out)
+        if signs is not None:
+            def fn():
+                b.spinner_hash_signs(x, signs, w.L, out_idx=out)
+        else:
+            def fn():
+                b.spinner_hash(x, ds, out_idx=out)
     else:
         width = 2 * w.m if w.epilogue == "cossin" else w.m
         out = torch.empty((w.batch, width), dtype=torch.float32, device=dev)
         need = b.spinner_workspace_bytes(w.n, w.batch, w.m, w.epilogue)
         ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
         d1, d2, d3 = ds[0, 0], ds[0, 1], ds[0, 2]
-
-        def fn():
-            b.spinner_apply(x, d1, d2, d3, w.m, w.epilogue, w.scale, out=out, workspace=ws)
+        if signs is not None:
+            def fn():
+                b.spinner_apply_signs(x, signs, w.m, w.epilogue, w.scale, out=out, workspace=ws)
+        else:
+            def fn():
+                b.spinner_apply(x, d1, d2, d3, w.m, w.epilogue, w.scale, out=out, workspace=ws)
     return fn, x
 
 
-def measure(torch, b, W, w, dev, steps, warmup):
-    fn, x = make_runner(torch, b, W, w, dev)
+def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0):
+    fn, x = make_runner(torch, b, W, w, dev, diagonals)
+    if ramp_ms > 0:
+        # untimed: let the clocks settle under this kernel's own load (the first ~10-20 ms of a
+        # compute-heavy kernel after idle or after a pure copy run measurably slower)
+        t_end = time.perf_counter() + ramp_ms * 1e-3
+        while time.perf_counter() < t_end:
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
     wall_ms, ev_ms = time_calls(torch, fn, steps, warmup)
     alg = W.algorithmic_bytes_per_vector(w) * w.batch
     ops = W.adds_per_vector(w) * w.batch
     res = {
         "workload": w.name, "n": w.n, "batch": w.batch, "m": w.m, "epilogue": w.epilogue, "L": w.L,
+        "diagonals": diagonals,
         "ms_per_step": round(wall_ms, 5), "kernel_ms": round(ev_ms, 5),
         "vectors_per_s": w.batch / (wall_ms * 1e-3),
         "algorithmic_bytes": alg,
@@ -97,6 +120,9 @@ def measure(torch, b, W, w, dev, steps, warmup):
 def copy_ceiling(torch, b, dev, steps, warmup):
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
+    for _ in range(50):                      # bring the GPU out of its idle clocks before anything is timed
+        b.spinner_stream_copy(src, dst)
+    torch.cuda.synchronize()
     _, ev_ms = time_calls(torch, lambda: b.spinner_stream_copy(src, dst), steps, warmup)
     del src, dst
     torch.cuda.empty_cache()
@@ -133,6 +159,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="sweep_plain_n2p12",
                     help="headline workload: sweep_plain_n2pK (K=10..20) or one of the cfg names")
+    ap.add_argument("--diagonals", choices=["signs", "fp32"], default="signs",
+                    help="how the +-1 diagonals reach the kernels: packed sign words prepared in advance "
+                         "(spinner_*_signs) or fp32 arrays (spinner_apply / spinner_hash)")
     ap.add_argument("--quick", action="store_true", help="headline only: no sweep, no configs, no CPU baseline")
     ap.add_argument("--only", action="store_true", help="headline only, and a single JSON line without extras")
     args = ap.parse_args()
@@ -160,29 +189,38 @@ def main():
         raise SystemExit("unknown workload %r" % name)
 
     head = resolve(args.workload)
-    log("[bench] headline %s: n=%d batch=%d" % (head.name, head.n, head.batch))
-    hres = measure(torch, b, W, head, dev, args.steps, args.warmup)
+    copy_gbs = round(copy_ceiling(torch, b, dev, 10, 3), 1)
+    log("[bench] plain copy kernel (1 GiB read + 1 GiB write): %.0f GB/s" % copy_gbs)
+    log("[bench] headline %s: n=%d batch=%d, diagonals as %s" % (head.name, head.n, head.batch, args.diagonals))
+    hres = measure(torch, b, W, head, dev, args.steps, args.warmup, args.diagonals, ramp_ms=200.0)
     log("[bench] %s: %.4f ms/step, %.3e vectors/s, %.0f GB/s (%.1f%% of 8 TB/s)" % (
         head.name, hres["ms_per_step"], hres["vectors_per_s"], hres["achieved_GBs"], 100 * hres["hbm_frac"]))
 
-    extras = {}
+    extras = {"copy_ceiling_GBs": copy_gbs}
     if not (args.quick or args.only):
-        extras["copy_ceiling_GBs"] = round(copy_ceiling(torch, b, dev, 10, 3), 1)
-        log("[bench] plain copy kernel: %.0f GB/s" % extras["copy_ceiling_GBs"])
+        other = "fp32" if args.diagonals == "signs" else "signs"
+        ores = measure(torch, b, W, head, dev, args.steps, args.warmup, other)
+        extras["headline_other_diagonal_form"] = {"diagonals": other, "vectors_per_s": ores["vectors_per_s"],
+                                                  "kernel_ms": ores["kernel_ms"], "GBs": round(ores["achieved_GBs"], 1),
+                                                  "hbm_frac": round(ores["hbm_frac"], 4)}
+        log("[bench] %s with diagonals as %s: %.4f ms, %.0f GB/s (%.1f%%)" % (
+            head.name, other, ores["kernel_ms"], ores["achieved_GBs"], 100 * ores["hbm_frac"]))
         sweep = []
         for k in range(10, 21):
             w = W.sweep_workload(k)
-            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2))
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals)
+            rf = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), "fp32")
             sweep.append({"log2n": k, "batch": w.batch, "ms": round(r["kernel_ms"], 4),
                           "vectors_per_s": round(r["vectors_per_s"], 1), "GBs": round(r["achieved_GBs"], 1),
-                          "hbm_frac": round(r["hbm_frac"], 4)})
-            log("[bench] sweep n=2^%d batch=%d: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)" % (
-                k, w.batch, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"]))
+                          "hbm_frac": round(r["hbm_frac"], 4), "fp32_diag_GBs": round(rf["achieved_GBs"], 1)})
+            log("[bench] sweep n=2^%d batch=%d: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)   [fp32 diagonals: %.0f GB/s]" % (
+                k, w.batch, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
+                rf["achieved_GBs"]))
         extras["sweep"] = sweep
         cfgs = []
         for name in W.CONFIG_ORDER:
             w = W.CONFIGS[name]
-            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2))
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals)
             cfgs.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
                          "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
                          "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
@@ -206,7 +244,9 @@ def main():
         "dtype": "f64" if head.epilogue == "cossin" and head.n <= (1 << 14) else "f32",
         "data": "synthetic",
         "config": {"workload": head.name, "n": head.n, "batch": head.batch, "m": head.m,
-                   "epilogue": head.epilogue, "L": head.L, "diagonals": "rademacher fp32"},
+                   "epilogue": head.epilogue, "L": head.L,
+                   "diagonals": "rademacher, " + ("packed sign words prepared off the clock" if args.diagonals == "signs"
+                                                 else "fp32 arrays")},
         "roofline": {
             "bound": "alu" if head.kind == "hash" else "hbm",
             "achieved": hres["butterfly_adds_Gops"] / 1e3 if head.kind == "hash" else hres["achieved_GBs"],

@@ -5,12 +5,23 @@
 
 namespace spinner {
 
-// fp64 butterflies keep 32 values per thread (64 registers), fp32 ones 64.
+// Registers per thread (2^rmax values) and waves per workgroup for each tile
+// size, from timing sweeps on MI355X: fewer registers per thread buy occupancy
+// (more waves to hide HBM latency) at the price of more lane / LDS stages.
+// fp64 butterflies keep 32 values per thread (64 registers).
+template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? 5 : 6, waves = 4; };
 #ifndef SPINNER_RMAX_F32
-#define SPINNER_RMAX_F32 6
-#endif
+template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4; };
+template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1; };
+template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1; };
+template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4; };
+template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4; };
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : SPINNER_RMAX_F32>;
+using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves>;
+#else   // uniform override used by tuning sweeps
+template <typename T, int NT>
+using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : SPINNER_RMAX_F32, SPINNER_WAVES_PER_WG>;
+#endif
 
 template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)

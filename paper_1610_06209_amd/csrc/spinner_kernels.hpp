@@ -28,7 +28,7 @@
 #define SPINNER_MIN_WAVES_PER_EU 1
 #endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
-#define SPINNER_STREAMING 0
+#define SPINNER_STREAMING 1
 #endif
 
 namespace spinner {
@@ -113,17 +113,20 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //   layout 1 ("mid"): registers hold bits {0,1} and the r-2 bits just above the
 //                     lane bits (only used when a tile spans several waves)
 // Lanes hold bits 2 .. 2+LB-1 in both layouts.
-template <int NT_, int RMAX = 6>
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG>
 struct TileGeom {
     static constexpr int NT = NT_;
+    static_assert(WAVES_1 == 1 || WAVES_1 == 2 || WAVES_1 == 4 || WAVES_1 == 8, "waves per workgroup");
     static_assert(NT >= 4 && NT <= 14, "tile of 2^4 .. 2^14 elements");
     static_assert(RMAX >= 4 && RMAX <= 7, "16 .. 128 elements per thread");
     static constexpr int r = NT >= RMAX + 2 ? RMAX : NT - 2;
     static constexpr int R = 1 << r;
     static constexpr int LB = (NT - r) < 6 ? (NT - r) : 6;   // lane bits per tile
     static constexpr int WB = NT - r - LB;                   // wave bits per tile
+    // one transpose per transform must bring every wave-held bit into a register bit
+    static_assert(WB <= r - 2, "too few registers per thread for this many waves per tile");
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
-    static constexpr int WAVES = WB ? (1 << WB) : SPINNER_WAVES_PER_WG;   // waves per workgroup
+    static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int TILES_PER_WG = WB ? 1 : WAVES * TPW;
 
