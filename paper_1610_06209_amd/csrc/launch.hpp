@@ -19,9 +19,25 @@ template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4;
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves>;
 #else   // uniform override used by tuning sweeps
+constexpr int clamp_rmax(int nt, int want) { return (nt - 3) / 2 > want ? (nt - 3) / 2 : want; }
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : SPINNER_RMAX_F32, SPINNER_WAVES_PER_WG>;
+using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
 #endif
+
+// How many workgroups of a kernel can be resident on the whole device (cached per kernel).
+template <typename K>
+inline long long resident_workgroups(K kernel, int threads)
+{
+    static long long cached = 0;
+    if (cached == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) return 0;
+        cached = (long long)cus * (per_cu > 0 ? per_cu : 1);
+    }
+    return cached;
+}
 
 template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
@@ -30,8 +46,18 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS>), dim3((unsigned)blocks), dim3(G::THREADS),
-                       0, stream, p);
+#if SPINNER_PERSIST
+    {
+        auto kernel = spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, true>;
+        const long long resident = resident_workgroups(kernel, G::THREADS);
+        if (resident > 0 && blocks >= 2 * resident) {      // enough tiles for every workgroup to loop
+            hipLaunchKernelGGL(kernel, dim3((unsigned)resident), dim3(G::THREADS), 0, stream, p);
+            return hipGetLastError();
+        }
+    }
+#endif
+    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, false>), dim3((unsigned)blocks),
+                       dim3(G::THREADS), 0, stream, p);
     return hipGetLastError();
 }
 

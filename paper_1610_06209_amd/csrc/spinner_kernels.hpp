@@ -27,6 +27,18 @@
 #ifndef SPINNER_MIN_WAVES_PER_EU      // occupancy the register allocator must allow for one-wave tiles
 #define SPINNER_MIN_WAVES_PER_EU 1
 #endif
+#ifndef SPINNER_LANE_CHUNK            // registers exchanged per batch in swizzle / bpermute stages (0: all at once)
+#define SPINNER_LANE_CHUNK 32
+#endif
+#ifndef SPINNER_USE_MFMA             // 1: two register bits + lane bits 4,5 go through the fp32 matrix pipe
+#define SPINNER_USE_MFMA 0
+#endif
+#ifndef SPINNER_PERSIST              // 1: persistent workgroups that prefetch their next tile
+#define SPINNER_PERSIST 0
+#endif
+#ifndef SPINNER_LDS_HALVES           // 2: transposes go through an LDS buffer of half a tile, in two trips
+#define SPINNER_LDS_HALVES 1
+#endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -113,7 +125,7 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //   layout 1 ("mid"): registers hold bits {0,1} and the r-2 bits just above the
 //                     lane bits (only used when a tile spans several waves)
 // Lanes hold bits 2 .. 2+LB-1 in both layouts.
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG>
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, bool MFMA_ = (SPINNER_USE_MFMA != 0)>
 struct TileGeom {
     static constexpr int NT = NT_;
     static_assert(WAVES_1 == 1 || WAVES_1 == 2 || WAVES_1 == 4 || WAVES_1 == 8, "waves per workgroup");
@@ -126,6 +138,11 @@ struct TileGeom {
     // one transpose per transform must bring every wave-held bit into a register bit
     static_assert(WB <= r - 2, "too few registers per thread for this many waves per tile");
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
+    // H16 blocks on the matrix pipe need a whole wave per tile and two spare register bits
+    static constexpr bool MFMA = MFMA_ && LB == 6 && r >= 4;
+    // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
+    static constexpr int LDS_HALVES = (SPINNER_LDS_HALVES == 2 && WB >= 1) ? 2 : 1;
+    static constexpr int LDS_FLOAT4 = WB > 0 ? ((1 << NT_) / 4) / LDS_HALVES : 1;
     static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int TILES_PER_WG = WB ? 1 : WAVES * TPW;
@@ -187,6 +204,7 @@ struct ThreadCtx {
     int lit;        // lane within tile
     int wv;         // wave bits of the tile index held by this thread
     float sg[6];    // +1 / -1 by lane bit: sign of the own value in a lane butterfly
+    float ha[4];    // this lane's entries of the (row-permuted) H16 operand, one per k-block
     __device__ __forceinline__ int base_index(int lay) const
     {
         int e = lit << 2;
@@ -195,6 +213,16 @@ struct ThreadCtx {
         return e;
     }
 };
+
+template <typename G>
+__device__ __forceinline__ void init_h16_operand(ThreadCtx<G>& c, int lane)
+{
+    const int i = lane & 15;
+    const int row = ((i & 3) << 2) | (i >> 2);          // permuted row 4a+b -> 4b+a
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+        c.ha[kb] = (__builtin_popcount(row & (4 * kb + (lane >> 4))) & 1) ? -1.0f : 1.0f;
+}
 
 // ------------------------------------------------------------------ butterflies
 template <int Q, typename T, int R>
@@ -215,9 +243,24 @@ __device__ __forceinline__ void reg_stage(T (&v)[R])
 template <int B, typename T, int R>
 __device__ __forceinline__ void lane_stage(T (&v)[R], float sign_own)
 {
+#if SPINNER_LANE_CHUNK > 0
+    // exchange and combine a few registers at a time so that the exchanged copies of
+    // only one chunk are alive at once (register pressure decides occupancy here)
+    constexpr int CH = SPINNER_LANE_CHUNK < R ? SPINNER_LANE_CHUNK : R;
+#pragma unroll
+    for (int j0 = 0; j0 < R; j0 += CH) {
+        T t[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) t[j] = lane_xor<(1 << B)>(v[j0 + j]);
+#pragma unroll
+        for (int j = 0; j < CH; ++j) v[j0 + j] = fused_mul_add(v[j0 + j], (T)sign_own, t[j]);
+        if (CH < R) __builtin_amdgcn_sched_barrier(0);
+    }
+#else
 #pragma unroll
     for (int j = 0; j < R; ++j)
         v[j] = fused_mul_add(v[j], (T)sign_own, lane_xor<(1 << B)>(v[j]));
+#endif
 }
 
 // One-instruction lane butterfly for the masks a DPP control can express
@@ -273,16 +316,42 @@ __device__ __forceinline__ void lane_stage_fmac_dpp(float (&v)[R], float coef)
 // data between waves: register bits and lane bits at index positions >= CB.
 // SKIP_WAVE_OWNED: skip register bits that the *other* layout's waves hold
 // (those are finished after the transpose instead, so do not do them twice).
+// Four butterfly stages at once on the fp32 matrix pipe: the 16-point transform over
+// the two highest register bits (k-block kb) and lane bits 4,5, for each of the 16
+// columns lane%16, as D = A_0 X_0 + .. + A_3 X_3 with v_mfma_f32_16x16x4_f32.  The B
+// operand of k-block kb is register kb as it stands (lane l holds row 4 kb + l/16,
+// column l%16).  The instruction returns row 4 (l/16) + v in result register v; with
+// the rows of H16 permuted by 4a+b -> 4b+a in the A operand, result register v of
+// lane-group l/16 is transform coefficient 4 v + l/16, i.e. it lands exactly where
+// the butterfly network would have left it.  The matrix pipe runs beside the vector
+// ALU, which is the unit this kernel saturates.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename G>
+__device__ __forceinline__ void mfma_stage(float (&v)[G::R], const ThreadCtx<G>& c)
+{
+    constexpr int Q = G::R / 4;
+#pragma unroll
+    for (int jl = 0; jl < Q; ++jl) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(c.ha[kb], v[jl + kb * Q], acc, 0, 0, 0);
+        v[jl] = acc[0]; v[jl + Q] = acc[1]; v[jl + 2 * Q] = acc[2]; v[jl + 3 * Q] = acc[3];
+    }
+}
+
 // NEGATE selects the coefficient set of the tracked-sign butterflies (true in
 // every second transform of a kernel, see lane_stage_fmac_dpp).
 template <typename G, int CB, int LAY, bool NEGATE, typename T>
 __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
+    constexpr bool MF = G::MFMA && std::is_same<T, float>::value;
     static_for<0, G::r>([&](auto q) {
-        if constexpr (G::reg_pos(LAY, q.value) >= CB) reg_stage<q.value>(v);
+        if constexpr (G::reg_pos(LAY, q.value) >= CB && !(MF && q.value >= G::r - 2)) reg_stage<q.value>(v);
     });
+    if constexpr (MF) mfma_stage<G>(v, c);
     static_for<0, G::LB>([&](auto b) {
-        if constexpr (G::lane_pos(b.value) >= CB) {
+        if constexpr (G::lane_pos(b.value) >= CB && !(MF && b.value >= 4)) {
             if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value))
                 lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
             else
@@ -322,20 +391,47 @@ template <typename G, int FROM, bool SYNC_BEFORE>
 __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& c, float4* lds)
 {
     constexpr int TO = 1 - FROM;
-    if constexpr (SYNC_BEFORE) __syncthreads();     // earlier readers of lds are done
-    const int ef = c.base_index(FROM);
+    if constexpr (G::LDS_HALVES == 1) {
+        if constexpr (SYNC_BEFORE) __syncthreads();     // earlier readers of lds are done
+        const int ef = c.base_index(FROM);
 #pragma unroll
-    for (int jh = 0; jh < G::R / 4; ++jh) {
-        const int e = ef | G::reg_index(FROM, jh * 4);
-        lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
-    }
-    __syncthreads();
-    const int et = c.base_index(TO);
+        for (int jh = 0; jh < G::R / 4; ++jh) {
+            const int e = ef | G::reg_index(FROM, jh * 4);
+            lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
+        }
+        __syncthreads();
+        const int et = c.base_index(TO);
 #pragma unroll
-    for (int jh = 0; jh < G::R / 4; ++jh) {
-        const int e = et | G::reg_index(TO, jh * 4);
-        const float4 t = lds[e >> 2];
-        v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+        for (int jh = 0; jh < G::R / 4; ++jh) {
+            const int e = et | G::reg_index(TO, jh * 4);
+            const float4 t = lds[e >> 2];
+            v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+        }
+    } else {
+        // Two trips through an LDS buffer of half the tile: trip h moves the elements whose
+        // index bit 1 is h, i.e. registers 4k+2h and 4k+2h+1 of every thread (8 bytes per
+        // lane, consecutive lanes on consecutive addresses).  Each thread receives exactly
+        // the register slots it has just sent, so nothing is overwritten before it is sent.
+        // Halving the footprint doubles the workgroups a CU can hold.
+        float2* lds2 = reinterpret_cast<float2*>(lds);
+        const int ef = c.base_index(FROM);
+        const int et = c.base_index(TO);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h == 1 || SYNC_BEFORE) __syncthreads();
+#pragma unroll
+            for (int jh = 0; jh < G::R / 4; ++jh) {
+                const int e = ef | G::reg_index(FROM, jh * 4);
+                lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int jh = 0; jh < G::R / 4; ++jh) {
+                const int e = et | G::reg_index(TO, jh * 4);
+                const float2 t = lds2[e >> 2];
+                v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
+            }
+        }
     }
 }
 
@@ -480,7 +576,7 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
-template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS>
+template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, bool PERSIST>
 __global__ void __launch_bounds__(G::THREADS)
 __attribute__((amdgpu_waves_per_eu(G::WB || !std::is_same<T, float>::value ? 1 : SPINNER_MIN_WAVES_PER_EU)))
 spinner_tile_kernel(TileParams p)
@@ -506,96 +602,126 @@ spinner_tile_kernel(TileParams p)
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
+    init_h16_operand(c, lane);
 
     const long long total = p.batch << p.tiles_per_vec_log;
-    const bool active = tile < total;
-    long long vec = 0, q = 0;
-    if (active) {
-        if (p.tiles_per_vec_log == 0) { vec = tile; }
-        else { q = tile / p.batch; vec = tile - q * p.batch; }   // neighbours share the diagonal block
-    }
-    const long long tile_first = q << p.tb;      // first element of the tile inside its vector
+    // A persistent workgroup walks over tiles tile, tile + stride, ... and issues the loads
+    // of its next tile before it starts computing the current one, so HBM latency is paid
+    // while the vector ALU is busy rather than by occupancy alone.
+    const long long stride = PERSIST ? (long long)gridDim.x * G::TILES_PER_WG : 0;
+    long long wg_first = (long long)blockIdx.x * G::TILES_PER_WG;      // lowest tile of this workgroup
 
-    __shared__ float4 lds_store[G::WB > 0 ? (1 << NT) / 4 : 1];
+    __shared__ float4 lds_store[(std::is_same<T, float>::value || G::WB == 0) ? G::LDS_FLOAT4 : (1 << NT) / 4];
     float4* lds = lds_store;
 
-    T v[R];
-    {
-        const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(0), p.sl);
+    auto locate = [&](long long t, long long& vec, long long& q) {
+        vec = 0; q = 0;
+        if (t < total) {
+            if (p.tiles_per_vec_log == 0) { vec = t; }
+            else { q = t / p.batch; vec = t - q * p.batch; }   // neighbours share the diagonal block
+        }
+    };
+    float4 nx[R / 4];
+    auto issue_loads = [&](long long t) {
+        long long vec, q;
+        locate(t, vec, q);
+        const float* src = p.x + vec * p.in_stride + (q << p.tb) + tile_offset<NT, C>(c.base_index(0), p.sl);
 #pragma unroll
         for (int jh = 0; jh < R / 4; ++jh) {
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
-            v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
+            nx[jh] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < total) nx[jh] = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
         }
-    }
+    };
+    issue_loads(tile);
 
-    // steps (layout alternates only when a tile spans several waves)
-    spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
-    if constexpr (NSTEPS > 1)
-        spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
-    if constexpr (NSTEPS > 2)
-        spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
+    for (;;) {
+        const bool active = tile < total;
+        long long vec, q;
+        locate(tile, vec, q);
+        const long long tile_first = q << p.tb;      // first element of the tile inside its vector
 
-    constexpr int LAYF = G::layout_after(NSTEPS);
-    const int ebase = c.base_index(LAYF);
-    if (!active) return;
-    const long long m = p.m;
-    // held values carry the tracked lane sign after an odd number of transforms
-    float lane_factor = p.factor;
-    if constexpr (NSTEPS & 1) lane_factor *= tracked_sign<G, CB, T>(c);
-    // whole tile inside the kept range and rows 16-byte aligned: no per-store checks
-    const bool full = (tile_first + tile_offset<NT, C>((1 << NT) - 1, p.sl) < m) && ((p.out_stride & 3) == 0);
-    float* dst = p.out + vec * p.out_stride;
-    if constexpr (EPI == EPI_STORE_NONE) {
-        if (full) {
-            float* d0 = dst + tile_first + tile_offset<NT, C>(ebase, p.sl);
+        T v[R];
 #pragma unroll
-            for (int jh = 0; jh < R / 4; ++jh) {
-                const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
-                const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
-                store4<STREAM>(d0 + tile_offset<NT, C>(G::reg_index(LAYF, jh * 4), p.sl), a0, a1, a2, a3);
-            }
-        } else {
-#pragma unroll
-            for (int jh = 0; jh < R / 4; ++jh) {
-                const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
-                const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
-                const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
-                if (i + 3 < m && (p.out_stride & 3) == 0) {
-                    *reinterpret_cast<float4*>(dst + i) = make_float4(a0, a1, a2, a3);
+        for (int jh = 0; jh < R / 4; ++jh) {
+            v[jh * 4] = (T)nx[jh].x; v[jh * 4 + 1] = (T)nx[jh].y; v[jh * 4 + 2] = (T)nx[jh].z; v[jh * 4 + 3] = (T)nx[jh].w;
+        }
+        if constexpr (PERSIST) {
+            if (wg_first + stride < total) issue_loads(tile + stride);
+        }
+
+        // steps (layout alternates only when a tile spans several waves)
+        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, !PERSIST, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
+        if constexpr (NSTEPS > 1)
+            spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
+        if constexpr (NSTEPS > 2)
+            spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
+
+        constexpr int LAYF = G::layout_after(NSTEPS);
+        const int ebase = c.base_index(LAYF);
+        if (active) {
+            const long long m = p.m;
+            // held values carry the tracked lane sign after an odd number of transforms
+            float lane_factor = p.factor;
+            if constexpr (NSTEPS & 1) lane_factor *= tracked_sign<G, CB, T>(c);
+            // whole tile inside the kept range and rows 16-byte aligned: no per-store checks
+            const bool full = (tile_first + tile_offset<NT, C>((1 << NT) - 1, p.sl) < m) && ((p.out_stride & 3) == 0);
+            float* dst = p.out + vec * p.out_stride;
+            if constexpr (EPI == EPI_STORE_NONE) {
+                if (full) {
+                    float* d0 = dst + tile_first + tile_offset<NT, C>(ebase, p.sl);
+        #pragma unroll
+                    for (int jh = 0; jh < R / 4; ++jh) {
+                        const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
+                        const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
+                        store4<STREAM>(d0 + tile_offset<NT, C>(G::reg_index(LAYF, jh * 4), p.sl), a0, a1, a2, a3);
+                    }
                 } else {
-                    if (i < m) dst[i] = a0;
-                    if (i + 1 < m) dst[i + 1] = a1;
-                    if (i + 2 < m) dst[i + 2] = a2;
-                    if (i + 3 < m) dst[i + 3] = a3;
+        #pragma unroll
+                    for (int jh = 0; jh < R / 4; ++jh) {
+                        const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
+                        const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
+                        const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
+                        if (i + 3 < m && (p.out_stride & 3) == 0) {
+                            *reinterpret_cast<float4*>(dst + i) = make_float4(a0, a1, a2, a3);
+                        } else {
+                            if (i < m) dst[i] = a0;
+                            if (i + 1 < m) dst[i + 1] = a1;
+                            if (i + 2 < m) dst[i + 2] = a2;
+                            if (i + 3 < m) dst[i + 3] = a3;
+                        }
+                    }
+                }
+            } else {
+                // dst row is [cos block of m | sin block of m]
+        #pragma unroll
+                for (int jh = 0; jh < R / 4; ++jh) {
+                    const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
+                    float sn[4], cs[4];
+        #pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        feature_sincos(v[jh * 4 + k], p, lane_factor, sn[k], cs[k]);
+                        sn[k] *= p.inv_sqrt_m;
+                        cs[k] *= p.inv_sqrt_m;
+                    }
+                    if (full && (m & 3) == 0) {
+                        *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+                        *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
+                    } else if (i + 3 < m && (m & 3) == 0) {
+                        *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+                        *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
+                    } else {
+        #pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            if (i + k < m) { dst[i + k] = cs[k]; dst[m + i + k] = sn[k]; }
+                    }
                 }
             }
-        }
-    } else {
-        // dst row is [cos block of m | sin block of m]
-#pragma unroll
-        for (int jh = 0; jh < R / 4; ++jh) {
-            const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
-            float sn[4], cs[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                feature_sincos(v[jh * 4 + k], p, lane_factor, sn[k], cs[k]);
-                sn[k] *= p.inv_sqrt_m;
-                cs[k] *= p.inv_sqrt_m;
-            }
-            if (full && (m & 3) == 0) {
-                *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
-                *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
-            } else if (i + 3 < m && (m & 3) == 0) {
-                *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
-                *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (i + k < m) { dst[i + k] = cs[k]; dst[m + i + k] = sn[k]; }
-            }
-        }
+        }   // active
+
+        if constexpr (!PERSIST) break;
+        wg_first += stride;
+        tile += stride;
+        if (wg_first >= total) break;
     }
 }
 
@@ -634,9 +760,10 @@ spinner_hash_kernel(HashParams p)
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
+    init_h16_operand(c, lane);
     const bool active = vec < p.batch;
 
-    __shared__ float4 lds_store[G::WB > 0 ? (1 << NT) / 4 : 1];
+    __shared__ float4 lds_store[G::LDS_FLOAT4];
     __shared__ float red_val[G::WB > 0 ? G::WAVES : 1];
     __shared__ int red_idx[G::WB > 0 ? G::WAVES : 1];
     float4* lds = lds_store;
