@@ -136,6 +136,8 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     }
 
     // four passes; rows are contiguous runs of 2^nr elements, there are 2^kColRowsLog of them
+    const ColShape cs = col_shape_for(log2n);
+    const int kColRowsLog = cs.rows_log, kColContigLog = cs.contig_log;
     const int nr = log2n - kColRowsLog;
     float* buf = ws ? static_cast<float*>(workspace) : out;
     const long long row_tiles = (long long)batch << kColRowsLog;
@@ -151,7 +153,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     // P2: cols, D2, cols : buf -> buf
     p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
     p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-    if ((e = launch_col_middle(p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+    if ((e = launch_col_middle(kColRowsLog, kColContigLog, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
     // P3: rows, D3, rows : buf -> buf
     p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
     if ((e = launch_row_middle(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
@@ -159,7 +161,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     p.out = out; p.d[1] = nullptr; p.out_stride = out_stride;
     p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
     p.m = m; p.factor = (float)factor_d;
-    if ((e = launch_col_last(epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+    if ((e = launch_col_last(kColRowsLog, kColContigLog, epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
     return SPINNER_OK;
 }
 

@@ -1,16 +1,24 @@
 // Host-side launch helpers shared by the translation units that instantiate
 // the kernels (split only to compile them in parallel).
 #pragma once
+#include <stdlib.h>
+
 #include "spinner_kernels.hpp"
 
 namespace spinner {
+
+constexpr int clamp_rmax(int nt, int want) { return (nt - 3) / 2 > want ? (nt - 3) / 2 : want; }
 
 // Registers per thread (2^rmax values) and waves per workgroup for each tile
 // size, from timing sweeps on MI355X: fewer registers per thread buy occupancy
 // (more waves to hide HBM latency) at the price of more lane / LDS stages.
 // fp64 butterflies keep 32 values per thread (64 registers).
-template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? 5 : 6, waves = 4; };
+#ifndef SPINNER_RMAX_F64
+#define SPINNER_RMAX_F64 5
+#endif
+template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4; };
 #ifndef SPINNER_RMAX_F32
+template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64 < 5 ? SPINNER_RMAX_F64 : 4, waves = 4; };
 template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4; };
 template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1; };
 template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1; };
@@ -19,9 +27,8 @@ template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4;
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves>;
 #else   // uniform override used by tuning sweeps
-constexpr int clamp_rmax(int nt, int want) { return (nt - 3) / 2 > want ? (nt - 3) / 2 : want; }
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? 5 : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
+using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
 #endif
 
 // How many workgroups of a kernel can be resident on the whole device (cached per kernel).
@@ -66,15 +73,28 @@ hipError_t launch_fused_none(int log2n, bool signs, const TileParams& p, long lo
 hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
 hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
 hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
-hipError_t launch_col_middle(const TileParams& p, long long tiles, hipStream_t s);           // cols, D2, cols
-hipError_t launch_col_last(int epi, const TileParams& p, long long tiles, hipStream_t s);    // cols, epilogue
+hipError_t launch_col_middle(int rows_log, int contig_log, const TileParams& p, long long tiles, hipStream_t s);          // cols, D2, cols
+hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
 
 // sign words per diagonal in the packed format (n <= 2^14)
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
 
-constexpr int kColTileLog = 14;   // column tile: 2^10 rows x 2^4 contiguous columns
-constexpr int kColContigLog = 4;
-constexpr int kColRowsLog = kColTileLog - kColContigLog;
+// Shape of the column tiles of the four-pass schedule: 2^rows_log rows (all rows of the
+// matrix view) by 2^contig_log contiguous columns.  Up to n = 2^21 the matrix view has
+// 2^7 rows and a column tile is 128 rows x 32 columns (128-byte segments, 2^12 elements:
+// one wave, no LDS, no barriers); larger n take more rows so that a row (a contiguous
+// tile of n / rows elements) still fits on chip.  128-byte segments measured 25-30 %
+// faster than 64-byte ones.
+struct ColShape { int rows_log, contig_log; };
+inline ColShape col_shape_for(int log2n)
+{
+    // rows_log grows only as far as needed to keep a row (n / rows elements) within 2^14
+    ColShape cs = log2n <= 21 ? ColShape{7, 5} : (log2n == 22 ? ColShape{8, 5} : (log2n == 23 ? ColShape{9, 5} : ColShape{10, 4}));
+#ifdef SPINNER_TUNING_HOOKS
+    if (const char* e = getenv("SPINNER_COL_SHAPE")) { cs.rows_log = e[0] - '0'; if (e[1] >= '0' && e[1] <= '9') { cs.rows_log = cs.rows_log * 10 + (e[1] - '0'); e++; } cs.contig_log = e[2] - '0'; }
+#endif
+    return cs;
+}
 
 }  // namespace spinner

@@ -1,7 +1,7 @@
 // Passes of the four-pass schedule for n > 2^14.  The vector is viewed as a
-// 2^10 x 2^(N-10) row-major matrix; H_n = H_rows (x) H_cols acts as a transform
-// along rows (contiguous tiles) and along columns (tiles of 2^10 rows x 16
-// columns).  Row and column transforms commute and a diagonal is elementwise, so
+// 2^R x 2^(N-R) row-major matrix (R = 8 up to n = 2^20, else 10); H_n = H_rows (x)
+// H_cols acts as a transform along rows (contiguous tiles) and along columns
+// (tiles of all 2^R rows x 16 contiguous columns).  Row and column transforms commute and a diagonal is elementwise, so
 //   P1: D1, rows   P2: cols, D2, cols   P3: rows, D3, rows   P4: cols, epilogue
 // equals H D3 H D2 H D1 with four trips through HBM instead of six.
 #include "launch.hpp"
@@ -24,13 +24,35 @@ hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipSt
     }
 }
 #undef ROWCASE
-hipError_t launch_col_middle(const TileParams& p, long long tiles, hipStream_t s)
+#define COLCASE(NT, C, STEPS, EPI) if (rows_log + contig_log == NT && contig_log == C) return launch_tile<float, NT, C, STEPS, false, EPI>(p, tiles, s);
+hipError_t launch_col_middle(int rows_log, int contig_log, const TileParams& p, long long tiles, hipStream_t s)
 {
-    return launch_tile<float, kColTileLog, kColContigLog, 2, false, EPI_STORE_NONE>(p, tiles, s);
+    COLCASE(12, 5, 2, EPI_STORE_NONE)
+    COLCASE(13, 5, 2, EPI_STORE_NONE)
+    COLCASE(14, 5, 2, EPI_STORE_NONE)
+    COLCASE(14, 4, 2, EPI_STORE_NONE)
+#ifdef SPINNER_TUNING_HOOKS
+    COLCASE(12, 4, 2, EPI_STORE_NONE) COLCASE(12, 6, 2, EPI_STORE_NONE) COLCASE(13, 6, 2, EPI_STORE_NONE)
+#endif
+    return hipErrorInvalidValue;
 }
-hipError_t launch_col_last(int epi, const TileParams& p, long long tiles, hipStream_t s)
+hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s)
 {
-    if (epi == EPI_STORE_COSSIN) return launch_tile<float, kColTileLog, kColContigLog, 1, false, EPI_STORE_COSSIN>(p, tiles, s);
-    return launch_tile<float, kColTileLog, kColContigLog, 1, false, EPI_STORE_NONE>(p, tiles, s);
+    if (epi == EPI_STORE_COSSIN) {
+        COLCASE(12, 5, 1, EPI_STORE_COSSIN)
+        COLCASE(13, 5, 1, EPI_STORE_COSSIN)
+    COLCASE(14, 5, 1, EPI_STORE_COSSIN)
+        COLCASE(14, 4, 1, EPI_STORE_COSSIN)
+        return hipErrorInvalidValue;
+    }
+    COLCASE(12, 5, 1, EPI_STORE_NONE)
+    COLCASE(13, 5, 1, EPI_STORE_NONE)
+    COLCASE(14, 5, 1, EPI_STORE_NONE)
+    COLCASE(14, 4, 1, EPI_STORE_NONE)
+#ifdef SPINNER_TUNING_HOOKS
+    COLCASE(12, 4, 1, EPI_STORE_NONE) COLCASE(12, 6, 1, EPI_STORE_NONE) COLCASE(13, 6, 1, EPI_STORE_NONE)
+#endif
+    return hipErrorInvalidValue;
 }
+#undef COLCASE
 }  // namespace spinner

@@ -204,13 +204,49 @@ def test_hash_antipodal_symmetry_full_gpu(gpu):
 
 
 # ------------------------------------------------------------------ n above the fused range (four passes)
-@pytest.mark.parametrize("log2n,batch", [(15, 3), (16, 2), (18, 2), (20, 2)])
+@pytest.mark.parametrize("log2n,batch", [(15, 3), (16, 2), (18, 2), (20, 2), (21, 1)])
 def test_multipass_plain(gpu, oracle, log2n, batch):
     n = 1 << log2n
     x, d = _rng_case(n, batch, 900 + log2n, gaussian_d3=(log2n == 16))
     got = _run_apply(gpu, x, d, n, "none", 1.0)
     want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
     assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("log2n", [19, 22, 23, 24])
+def test_multipass_largest_sizes_by_properties(gpu, log2n):
+    # The O(n^2)-per-factor oracle takes minutes per vector here, so these sizes are checked by
+    # what holds at any size: (a) D = I maps e_j to column j of H, entry (-1)^popcount(i&j)/sqrt(n);
+    # (b) for +-1 diagonals the product is orthogonal and H D2 H D3 H (H D3 H D2 H D1 x) = D1 x,
+    # so a second call with diagonals (1, d3, d2) must return D1 x; (c) the norm is preserved.
+    # n = 2^19 is also covered by the oracle-backed sizes around it and ties the two kinds of check.
+    t = gpu.torch
+    n = 1 << log2n
+    one = t.ones(n, dtype=t.float32, device=gpu.dev)
+    js = [0, 1, 12345 % n, n // 2 + 77, n - 1]
+    x = t.zeros((len(js), n), dtype=t.float32, device=gpu.dev)
+    for k, j in enumerate(js):
+        x[k, j] = 1.0
+    y = gpu.b.spinner_apply(x, one, one, one)
+    idx = t.arange(n, device=gpu.dev, dtype=t.int64)
+    for k, j in enumerate(js):
+        v = idx & j
+        par = t.zeros_like(v)
+        for sft in range(log2n):
+            par ^= (v >> sft) & 1
+        want = (1.0 - 2.0 * par.double()) / math.sqrt(n)
+        assert float((y[k].double() - want).abs().max()) <= 1e-6 / math.sqrt(n) * 4 + 1e-12, (log2n, j)
+    del x, y
+    g = t.Generator(device=gpu.dev)
+    g.manual_seed(99 + log2n)
+    xr = t.randn((2, n), generator=g, device=gpu.dev, dtype=t.float32)
+    d = (1.0 - 2.0 * t.randint(0, 2, (3, n), generator=g, device=gpu.dev)).float()
+    yr = gpu.b.spinner_apply(xr, d[0], d[1], d[2])
+    nx, ny = xr.double().norm(dim=1), yr.double().norm(dim=1)
+    assert float(((ny / nx) - 1).abs().max()) < 1e-5
+    z = gpu.b.spinner_apply(yr, one, d[2], d[1])
+    err = ((z * d[0]).double() - xr.double()).norm(dim=1) / nx
+    assert float(err.max()) < 1e-5, float(err.max())
 
 
 def test_multipass_truncated_and_features(gpu, oracle):
