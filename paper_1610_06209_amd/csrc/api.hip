@@ -130,8 +130,11 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         p.in_stride = n; p.out_stride = out_stride;
         p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0;
         p.factor = (float)factor_d;
+        // how many of the highest index bits lie entirely above the kept rows
+        int prune = 0;
+        while (prune < log2n && (long long)m <= ((long long)n >> (prune + 1))) ++prune;
         const hipError_t e = epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, signs != nullptr, p, batch, s)
-                                                      : launch_fused_none(log2n, signs != nullptr, p, batch, s);
+                                                      : launch_fused_none(log2n, signs != nullptr, prune, p, batch, s);
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);
     }
 

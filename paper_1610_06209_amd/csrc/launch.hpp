@@ -46,7 +46,7 @@ inline long long resident_workgroups(K kernel, int threads)
     return cached;
 }
 
-template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false>
+template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
     using G = GeomFor<T, NT>;
@@ -54,8 +54,8 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
 #if SPINNER_PERSIST
-    {
-        auto kernel = spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, true>;
+    if (PRUNE == 0) {
+        auto kernel = spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, true, 0>;
         const long long resident = resident_workgroups(kernel, G::THREADS);
         if (resident > 0 && blocks >= 2 * resident) {      // enough tiles for every workgroup to loop
             hipLaunchKernelGGL(kernel, dim3((unsigned)resident), dim3(G::THREADS), 0, stream, p);
@@ -63,13 +63,14 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
         }
     }
 #endif
-    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, false>), dim3((unsigned)blocks),
+    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, false, PRUNE>), dim3((unsigned)blocks),
                        dim3(G::THREADS), 0, stream, p);
     return hipGetLastError();
 }
 
 // implemented in fused_none.hip / fused_cossin.hip / multipass.hip / hash.hip
-hipError_t launch_fused_none(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
+hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s);
+constexpr int kPruneBits = 4;   // the pruned variant drops the 4 highest index bits in the last round (m <= n/16)
 hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
 hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
 hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows

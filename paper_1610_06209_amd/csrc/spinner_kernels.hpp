@@ -225,11 +225,12 @@ __device__ __forceinline__ void init_h16_operand(ThreadCtx<G>& c, int lane)
 }
 
 // ------------------------------------------------------------------ butterflies
-template <int Q, typename T, int R>
+// RL: number of leading registers that are still needed (all R unless the last round is pruned)
+template <int Q, int RL = 0, typename T, int R>
 __device__ __forceinline__ void reg_stage(T (&v)[R])
 {
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
+    for (int j = 0; j < (RL ? RL : R); ++j) {
         if (!(j & (1 << Q))) {
             const T a = v[j], b = v[j | (1 << Q)];
             v[j] = a + b;
@@ -240,9 +241,10 @@ __device__ __forceinline__ void reg_stage(T (&v)[R])
 
 // Exact lane butterfly: the lane with the mask bit clear gets own + partner,
 // the other one partner - own.
-template <int B, typename T, int R>
-__device__ __forceinline__ void lane_stage(T (&v)[R], float sign_own)
+template <int B, int RL = 0, typename T, int RR>
+__device__ __forceinline__ void lane_stage(T (&v)[RR], float sign_own)
 {
+    constexpr int R = RL ? RL : RR;
 #if SPINNER_LANE_CHUNK > 0
     // exchange and combine a few registers at a time so that the exchanged copies of
     // only one chunk are alive at once (register pressure decides occupancy here)
@@ -291,6 +293,23 @@ __device__ __forceinline__ void lane_stage(T (&v)[R], float sign_own)
                  : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]) \
                  : "v"(coef))
 
+#define SPINNER_FMAC_DPP4(CTRL)                                                             \
+    asm volatile("s_nop 1\n\t"                                                              \
+                 "v_fmac_f32_dpp %0, %0, %4 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %1, %1, %4 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %2, %2, %4 " CTRL " row_mask:0xf bank_mask:0xf\n\t"          \
+                 "v_fmac_f32_dpp %3, %3, %4 " CTRL " row_mask:0xf bank_mask:0xf"               \
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])                             \
+                 : "v"(coef))
+
+template <int MASK>
+__device__ __forceinline__ void fmac_dpp_block4(float* a, float coef)
+{
+    if constexpr (MASK == 1) SPINNER_FMAC_DPP4("quad_perm:[1,0,3,2]");
+    else if constexpr (MASK == 2) SPINNER_FMAC_DPP4("quad_perm:[2,3,0,1]");
+    else { static_assert(MASK == 8, "mask without a DPP control"); SPINNER_FMAC_DPP4("row_ror:8"); }
+}
+
 template <int MASK>
 __device__ __forceinline__ void fmac_dpp_block8(float* a, float coef)
 {
@@ -305,11 +324,17 @@ constexpr bool lane_mask_uses_fmac_dpp(int mask)
     return std::is_same<T, float>::value && R >= 8 && (mask == 1 || mask == 2 || mask == 8);
 }
 
-template <int B, int R>
+template <int B, int RL = 0, int R>
 __device__ __forceinline__ void lane_stage_fmac_dpp(float (&v)[R], float coef)
 {
+    constexpr int N = RL ? RL : R;
+    if constexpr (N >= 8) {
 #pragma unroll
-    for (int j = 0; j < R; j += 8) fmac_dpp_block8<(1 << B)>(&v[j], coef);
+        for (int j = 0; j < N; j += 8) fmac_dpp_block8<(1 << B)>(&v[j], coef);
+    } else {
+        static_assert(N == 4, "register groups come in fours");
+        fmac_dpp_block4<(1 << B)>(&v[0], coef);
+    }
 }
 
 // All stages of one transform that the current layout can do without moving
@@ -387,27 +412,33 @@ __device__ __forceinline__ void wave_owned_stages(T (&v)[G::R])
 // Moves every element from its (wave, lane, register) place in layout FROM to
 // its place in the other layout.  Both sides access the LDS as 16 bytes per
 // lane with consecutive lanes on consecutive addresses (no bank conflicts).
-template <typename G, int FROM, bool SYNC_BEFORE>
-__device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& c, float4* lds)
+// RW / RR: how many leading registers are written / read (all of them unless the last
+// round is pruned); `reads` is false for a wave that needs nothing from this exchange.
+template <typename G, int FROM, bool SYNC_BEFORE, int RW = 0, int RR = 0>
+__device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& c, float4* lds, bool reads = true)
 {
     constexpr int TO = 1 - FROM;
+    constexpr int NW = RW ? RW : G::R, NR = RR ? RR : G::R;
     if constexpr (G::LDS_HALVES == 1) {
         if constexpr (SYNC_BEFORE) __syncthreads();     // earlier readers of lds are done
         const int ef = c.base_index(FROM);
 #pragma unroll
-        for (int jh = 0; jh < G::R / 4; ++jh) {
+        for (int jh = 0; jh < NW / 4; ++jh) {
             const int e = ef | G::reg_index(FROM, jh * 4);
             lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
         }
         __syncthreads();
         const int et = c.base_index(TO);
+        if (reads) {
 #pragma unroll
-        for (int jh = 0; jh < G::R / 4; ++jh) {
-            const int e = et | G::reg_index(TO, jh * 4);
-            const float4 t = lds[e >> 2];
-            v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+            for (int jh = 0; jh < NR / 4; ++jh) {
+                const int e = et | G::reg_index(TO, jh * 4);
+                const float4 t = lds[e >> 2];
+                v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+            }
         }
     } else {
+        static_assert(G::LDS_HALVES == 1 || (RW == 0 && RR == 0), "pruned rounds use the whole-tile exchange");
         // Two trips through an LDS buffer of half the tile: trip h moves the elements whose
         // index bit 1 is h, i.e. registers 4k+2h and 4k+2h+1 of every thread (8 bytes per
         // lane, consecutive lanes on consecutive addresses).  Each thread receives exactly
@@ -554,6 +585,110 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
     }
 }
 
+// ------------------------------------------------------------------ last round when only m <= n / 2^P outputs are kept
+// Rows 0 .. n/2^P - 1 of H_n are (1^T (x) H_{n/2^P}) / sqrt(n): on the P highest index
+// bits the last transform only needs the "sum" output of each butterfly.  Where such a
+// bit is held by the register index, the stage is a plain add that halves the set of
+// live registers (always a leading block, because pruned bits are the highest register
+// bits of either layout); where it is held by the wave id, the waves whose bit is 1 have
+// nothing left to do after the transpose; where it is held by the lane id nothing is
+// saved.  All later stages, the exchange and the store touch live registers only.
+template <typename G>
+constexpr unsigned prune_positions(int P) { return P > 0 ? (((1u << P) - 1u) << (G::NT - P)) : 0u; }
+
+// live registers in layout lay once the pruned positions in `done` have been reduced
+template <typename G>
+constexpr int live_regs(int lay, unsigned done)
+{
+    int rl = G::R;
+    for (int q = 0; q < G::r; ++q)
+        if ((done >> G::reg_pos(lay, q)) & 1u) rl >>= 1;
+    return rl;
+}
+template <typename G>
+constexpr unsigned reg_positions(int lay)
+{
+    unsigned m = 0;
+    for (int q = 0; q < G::r; ++q) m |= 1u << G::reg_pos(lay, q);
+    return m;
+}
+template <typename G>
+constexpr unsigned wave_positions(int lay)
+{
+    unsigned m = 0;
+    for (int b = 0; b < G::WB; ++b) m |= 1u << G::wave_pos(lay, b);
+    return m;
+}
+// registers live at the end of a pruned last step that started in layout LAY
+template <typename G>
+constexpr int pruned_final_regs(int lay, int P)
+{
+    const unsigned pm = prune_positions<G>(P);
+    if (G::WB == 0) return live_regs<G>(lay, pm & reg_positions<G>(lay));
+    return live_regs<G>(1 - lay, pm & (reg_positions<G>(lay) | wave_positions<G>(lay)));
+}
+
+template <int HALF, typename T, int R>
+__device__ __forceinline__ void sum_stage(T (&v)[R])
+{
+#pragma unroll
+    for (int j = 0; j < HALF; ++j) v[j] = v[j] + v[j + HALF];
+}
+
+// register stages of layout LAY over positions in `want`: pruned ones (sum only) first,
+// from the highest register bit down, then the ordinary ones on what is still live
+template <typename G, int LAY, unsigned WANT, unsigned PM, unsigned DONE0, typename T>
+__device__ __forceinline__ void pruned_reg_stages(T (&v)[G::R])
+{
+    static_for<0, G::r>([&](auto qq) {
+        constexpr int q = G::r - 1 - qq.value;
+        constexpr unsigned bit = 1u << G::reg_pos(LAY, q);
+        if constexpr ((WANT & bit) && (PM & bit)) {
+            static_assert(live_regs<G>(LAY, DONE0 | (PM & WANT & ~(bit | (bit - 1u)))) == (2 << q), "pruned bits must top the live block");
+            sum_stage<(1 << q)>(v);
+        }
+    });
+    constexpr int RL = live_regs<G>(LAY, DONE0 | (PM & WANT));
+    static_for<0, G::r>([&](auto q) {
+        constexpr unsigned bit = 1u << G::reg_pos(LAY, q.value);
+        if constexpr ((WANT & bit) && !(PM & bit) && (1 << q.value) < RL) reg_stage<q.value, RL>(v);
+    });
+}
+
+// The last (diagonal, transform) step with the P highest index bits pruned.  Returns,
+// through wave_live, whether this wave still holds outputs; pruned_final_regs() tells
+// how many leading registers do.
+template <typename G, int C, int CB, int LAY, bool NEGATE, bool SIGNS, int P>
+__device__ __forceinline__ void spinner_step_pruned(float (&v)[G::R], const ThreadCtx<G>& c, const float* dtile,
+                                                    const unsigned long long* words, int sl, float4* lds,
+                                                    bool& wave_live)
+{
+    static_assert(C >= G::NT && CB == 0, "pruning is for whole-vector tiles");
+    constexpr unsigned PM = prune_positions<G>(P);
+    constexpr unsigned REGS = reg_positions<G>(LAY);
+    if constexpr (SIGNS) sign_flip<G, LAY>(v, c, words);
+    else diag_multiply<G, C, LAY>(v, c, dtile, sl);
+    pruned_reg_stages<G, LAY, REGS, PM, 0u>(v);
+    constexpr unsigned DONE1 = PM & REGS;
+    constexpr int RL1 = live_regs<G>(LAY, DONE1);
+    static_for<0, G::LB>([&](auto b) {
+        if constexpr (lane_mask_uses_fmac_dpp<float, G::R>(1 << b.value))
+            lane_stage_fmac_dpp<b.value, RL1>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
+        else
+            lane_stage<b.value, RL1>(v, c.sg[b.value]);
+    });
+    wave_live = true;
+    if constexpr (G::WB > 0) {
+        constexpr int TO = 1 - LAY;
+        constexpr unsigned WAVES_FROM = wave_positions<G>(LAY);
+        constexpr int RL2 = live_regs<G>(TO, DONE1);
+        // a wave of the new layout is live iff its wave-held bits avoid the reduced positions
+        wave_live = (c.base_index(TO) & (int)DONE1) == 0;
+        transpose<G, LAY, true, RL1, RL2>(v, c, lds, wave_live);
+        if (wave_live) pruned_reg_stages<G, TO, WAVES_FROM, PM, DONE1>(v);
+    }
+}
+
 // ------------------------------------------------------------------ cos / sin of w = y * factor
 // fp32 values: plain library sincos of the fp32 product.
 __device__ __forceinline__ void feature_sincos(float y, const TileParams&, float lane_factor, float& s, float& c)
@@ -579,7 +714,7 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
-template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, bool PERSIST>
+template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, bool PERSIST, int PRUNE = 0>
 __global__ void __launch_bounds__(G::THREADS)
 __attribute__((amdgpu_waves_per_eu(G::WB || !std::is_same<T, float>::value ? 1 : SPINNER_MIN_WAVES_PER_EU)))
 spinner_tile_kernel(TileParams p)
@@ -656,31 +791,41 @@ spinner_tile_kernel(TileParams p)
         spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, !PERSIST, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
         if constexpr (NSTEPS > 1)
             spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
-        if constexpr (NSTEPS > 2)
-            spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
+        bool wave_live = true;
+        if constexpr (NSTEPS > 2) {
+            if constexpr (PRUNE > 0)
+                spinner_step_pruned<G, C, CB, G::layout_after(2), false, SIGNS, PRUNE>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds, wave_live);
+            else
+                spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
+        }
+        static_assert(PRUNE == 0 || (NSTEPS == 3 && std::is_same<T, float>::value && !PERSIST), "pruning: fused fp32 kernels only");
+        constexpr int RF = PRUNE > 0 ? pruned_final_regs<G>(G::layout_after(2), PRUNE) : R;   // registers that hold outputs
 
         constexpr int LAYF = G::layout_after(NSTEPS);
         const int ebase = c.base_index(LAYF);
-        if (active) {
+        if (active && wave_live) {
             const long long m = p.m;
             // held values carry the tracked lane sign after an odd number of transforms
             float lane_factor = p.factor;
             if constexpr (NSTEPS & 1) lane_factor *= tracked_sign<G, CB, T>(c);
             // whole tile inside the kept range and rows 16-byte aligned: no per-store checks
-            const bool full = (tile_first + tile_offset<NT, C>((1 << NT) - 1, p.sl) < m) && ((p.out_stride & 3) == 0);
+            // (with a pruned last round, lanes whose pruned bits are set hold nothing to store)
+            constexpr bool LANES_PRUNED = PRUNE > 0 && ((prune_positions<G>(PRUNE) >> 2) & ((1u << G::LB) - 1u)) != 0;
+            const bool full = !LANES_PRUNED && (tile_first + tile_offset<NT, C>((1 << (NT - PRUNE)) - 1, p.sl) < m) &&
+                              ((p.out_stride & 3) == 0);
             float* dst = p.out + vec * p.out_stride;
             if constexpr (EPI == EPI_STORE_NONE) {
                 if (full) {
                     float* d0 = dst + tile_first + tile_offset<NT, C>(ebase, p.sl);
         #pragma unroll
-                    for (int jh = 0; jh < R / 4; ++jh) {
+                    for (int jh = 0; jh < RF / 4; ++jh) {
                         const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
                         const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
                         store4<STREAM>(d0 + tile_offset<NT, C>(G::reg_index(LAYF, jh * 4), p.sl), a0, a1, a2, a3);
                     }
                 } else {
         #pragma unroll
-                    for (int jh = 0; jh < R / 4; ++jh) {
+                    for (int jh = 0; jh < RF / 4; ++jh) {
                         const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
                         const float a0 = (float)(v[jh * 4] * (T)lane_factor), a1 = (float)(v[jh * 4 + 1] * (T)lane_factor);
                         const float a2 = (float)(v[jh * 4 + 2] * (T)lane_factor), a3 = (float)(v[jh * 4 + 3] * (T)lane_factor);
@@ -697,7 +842,7 @@ spinner_tile_kernel(TileParams p)
             } else {
                 // dst row is [cos block of m | sin block of m]
         #pragma unroll
-                for (int jh = 0; jh < R / 4; ++jh) {
+                for (int jh = 0; jh < RF / 4; ++jh) {
                     const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
                     float sn[4], cs[4];
         #pragma unroll

@@ -138,6 +138,36 @@ def test_first_m_rows(gpu, oracle, n, m, scale):
     assert rel_l2_per_vector(got, want).max() <= (REL_L2_TOL if m > 8 else 2e-5)
 
 
+@pytest.mark.parametrize("log2n", list(range(8, 15)))
+def test_first_m_rows_with_pruned_last_round(gpu, oracle, log2n):
+    # m <= n/16 takes the kernels whose last round only forms the sums it needs on the four
+    # highest index bits; both diagonal forms, exact and ragged m.
+    n = 1 << log2n
+    batch = 21 if log2n < 12 else 5
+    w = W.Workload("p", "apply", n, batch, n, "none", 1.0, 1, "normal_heavy", 8800 + log2n, batch)
+    x = W.make_x_numpy(w)
+    ds = W.diag_sets(w)
+    xd, dsd = _to(gpu, x), _to(gpu, ds)
+    signs = gpu.b.spinner_pack_signs(dsd)
+    y = oracle.spinner(x, ds[0, 0], ds[0, 1], ds[0, 2])
+    typical = np.linalg.norm(y, axis=1) / math.sqrt(n)          # size of one coordinate of y
+
+    def check(got, want, m, scale, what):
+        assert got.shape == (batch, m)
+        if m > 8:
+            assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (log2n, m, what)
+        else:   # a handful of numbers can cancel to almost nothing: bound the error by a typical coordinate
+            err = np.linalg.norm(got.astype(np.float64) - want, axis=1) / (scale * typical * math.sqrt(m))
+            assert err.max() <= REL_L2_TOL, (log2n, m, what, err.max())
+
+    for m in (n // 16, n // 16 - 3, n // 64, 1, n // 16 + 1):
+        scale = math.sqrt(n / m)
+        want = oracle.epilogue_none(y, m, scale)
+        check(gpu.b.spinner_apply(xd, dsd[0, 0], dsd[0, 1], dsd[0, 2], m, "none", scale).cpu().numpy(), want, m, scale,
+              "fp32 diagonals")
+        check(gpu.b.spinner_apply_signs(xd, signs, m, "none", scale).cpu().numpy(), want, m, scale, "sign words")
+
+
 # ------------------------------------------------------------------ random features
 @pytest.mark.parametrize("n,m,scale", [(64, 64, 8.0), (1024, 1024, 32.0), (1024, 100, 3.0), (4096, 4096, 64.0),
                                        (16384, 16384, 1.0)])
