@@ -199,7 +199,7 @@ def main():
     extras = {"copy_ceiling_GBs": copy_gbs}
     if not (args.quick or args.only):
         other = "fp32" if args.diagonals == "signs" else "signs"
-        ores = measure(torch, b, W, head, dev, args.steps, args.warmup, other)
+        ores = measure(torch, b, W, head, dev, args.steps, args.warmup, other, ramp_ms=100.0)
         extras["headline_other_diagonal_form"] = {"diagonals": other, "vectors_per_s": ores["vectors_per_s"],
                                                   "kernel_ms": ores["kernel_ms"], "GBs": round(ores["achieved_GBs"], 1),
                                                   "hbm_frac": round(ores["hbm_frac"], 4)}
@@ -208,8 +208,8 @@ def main():
         sweep = []
         for k in range(10, 21):
             w = W.sweep_workload(k)
-            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals)
-            rf = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), "fp32")
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
+            rf = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), "fp32", ramp_ms=60.0)
             sweep.append({"log2n": k, "batch": w.batch, "ms": round(r["kernel_ms"], 4),
                           "vectors_per_s": round(r["vectors_per_s"], 1), "GBs": round(r["achieved_GBs"], 1),
                           "hbm_frac": round(r["hbm_frac"], 4), "fp32_diag_GBs": round(rf["achieved_GBs"], 1)})
@@ -220,7 +220,7 @@ def main():
         cfgs = []
         for name in W.CONFIG_ORDER:
             w = W.CONFIGS[name]
-            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals)
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
             cfgs.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
                          "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
                          "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})

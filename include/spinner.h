@@ -74,15 +74,16 @@ typedef enum {
  *                  (1 for the plain spinner, sqrt(n/m) for a norm-preserving
  *                  reduction, sqrt(n)/sigma for Gaussian-kernel features)
  *   out       out  device fp32 [batch][m] (NONE) or [batch][2m] (COSSIN).
- *                  May alias x only when n <= 2^14, m == n and epilogue is NONE.
+ *                  May alias x only when n <= 2^16, m == n and epilogue is NONE.
  *   workspace      device scratch of spinner_workspace_bytes(...) bytes, or
  *                  NULL when that is 0
  *   stream         hipStream_t
  *
- * n <= 2^14: one fused kernel (all three sign-flip + transform rounds on chip).
- * n  > 2^14: four passes over HBM using the Kronecker structure
- *            H_{ab} = H_a (x) H_b of the Sylvester matrix; intermediate passes
- *            run in place in `out` when m == n, else in `workspace`.
+ * Up to the fused limit (n <= 2^16 for SPINNER_EPI_NONE, n <= 2^14 for
+ * SPINNER_EPI_COSSIN) one kernel keeps the vector on chip for all three sign-flip +
+ * transform rounds.  Above it the call makes four passes over HBM using the
+ * Kronecker structure H_{ab} = H_a (x) H_b of the Sylvester matrix; intermediate
+ * passes run in place in `out` when m == n, else in `workspace`.
  */
 int spinner_apply(const float *x, int n, long batch,
                   const float *d1, const float *d2, const float *d3,
@@ -137,8 +138,8 @@ int spinner_hash_signs(const float *x, int n, long batch, int L,
                        const void *signs, int *out_idx, void *stream);
 
 /*
- * Bytes of device scratch spinner_apply needs for these arguments: 0 when
- * n <= 2^14 or when m == n with epilogue NONE; otherwise batch * n * 4.
+ * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the
+ * fused limit, and above it when m == n with epilogue NONE; otherwise batch * n * 4.
  * Returns 0 for invalid arguments (spinner_apply reports those).
  */
 size_t spinner_workspace_bytes(int n, long batch, int m, int epilogue);

@@ -60,7 +60,11 @@ bool pow2_in_range(int n, int* log2n)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-constexpr int kFusedMaxLog = 14;
+int fused_max_log(int epilogue)
+{
+    return epilogue == SPINNER_EPI_NONE ? spinner::kFusedMaxLogPlain : spinner::kFusedMaxLogOther;
+}
+
 
 }  // namespace
 
@@ -90,7 +94,7 @@ size_t spinner_workspace_bytes(int n, long batch, int m, int epilogue)
 {
     int log2n;
     if (!pow2_in_range(n, &log2n) || batch <= 0 || m < 1 || m > n) return 0;
-    if (log2n <= kFusedMaxLog) return 0;
+    if (log2n <= fused_max_log(epilogue)) return 0;
     if (m == n && epilogue == SPINNER_EPI_NONE) return 0;
     return (size_t)batch * (size_t)n * sizeof(float);
 }
@@ -119,7 +123,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     p.inv_sqrt_m = (float)(1.0 / sqrt((double)m));
     p.factor_rev = factor_d / 6.283185307179586476925286766559;
 
-    if (log2n <= kFusedMaxLog) {
+    if (log2n <= fused_max_log(epilogue)) {
         if (batch > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
         p.x = x; p.out = out;
         p.d[0] = d1; p.d[1] = d2; p.d[2] = d3;
@@ -195,7 +199,7 @@ size_t spinner_signs_bytes(int n, int L)
 {
     int log2n;
     if (!pow2_in_range(n, &log2n) || L < 1) return 0;
-    if (log2n <= kFusedMaxLog) return (size_t)L * 3 * (size_t)spinner::sign_words_per_diag(n) * 8;
+    if (log2n <= spinner::kFusedMaxLogOther) return (size_t)L * 3 * (size_t)spinner::sign_words_per_diag(n) * 8;
     return (size_t)L * 3 * (size_t)n * sizeof(float);      // plain copy of the diagonals
 }
 
@@ -207,7 +211,7 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     if (!diag_sets || !signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (log2n > kFusedMaxLog) {
+    if (log2n > spinner::kFusedMaxLogOther) {
         const hipError_t e = hipMemcpyAsync(signs, diag_sets, spinner_signs_bytes(n, L), hipMemcpyDeviceToDevice, s);
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);
     }
@@ -228,7 +232,7 @@ int spinner_apply_signs(const float* x, int n, long batch, const void* signs, in
     if (rc != SPINNER_OK || batch == 0) return rc;
     if (!signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > kFusedMaxLog) {
+    if (log2n > spinner::kFusedMaxLogOther) {
         const float* d = static_cast<const float*>(signs);
         return apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, epilogue, scale, out, workspace,
                           stream);
@@ -248,7 +252,7 @@ static int hash_impl(const float* x, int n, long batch, int L, const float* diag
     if (batch == 0) return SPINNER_OK;
     if (!x || (!diag_sets && !signs) || !out_idx) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(x) || !aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > kFusedMaxLog) return SPINNER_ERR_UNSUPPORTED;
+    if (log2n > kFusedMaxLogOther) return SPINNER_ERR_UNSUPPORTED;
     HashParams p;
     p.x = x; p.diag_sets = diag_sets; p.signs = signs; p.out_idx = out_idx; p.batch = batch; p.L = L;
     const hipError_t e = launch_hash(log2n, signs != nullptr, p, static_cast<hipStream_t>(stream));

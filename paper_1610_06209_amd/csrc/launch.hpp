@@ -9,6 +9,10 @@ namespace spinner {
 
 constexpr int clamp_rmax(int nt, int want) { return (nt - 3) / 2 > want ? (nt - 3) / 2 : want; }
 
+// largest n (log2) that a single fused kernel handles, per epilogue / entry point
+constexpr int kFusedMaxLogPlain = 16;     // fp32 butterflies, first-m-rows epilogue
+constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
+
 // Registers per thread (2^rmax values) and waves per workgroup for each tile
 // size, from timing sweeps on MI355X: fewer registers per thread buy occupancy
 // (more waves to hide HBM latency) at the price of more lane / LDS stages.
@@ -24,6 +28,8 @@ template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1;
 template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1; };
 template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4; };
 template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4; };
+template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4; };   // 8 waves per tile
+template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4; };   // 16 waves per tile
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves>;
 #else   // uniform override used by tuning sweeps

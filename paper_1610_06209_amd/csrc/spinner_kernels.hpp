@@ -39,6 +39,9 @@
 #ifndef SPINNER_LDS_HALVES           // 2: transposes go through an LDS buffer of half a tile, in two trips
 #define SPINNER_LDS_HALVES 1
 #endif
+#ifndef SPINNER_SYNC_AFTER_READ      // 1: the barrier that protects the LDS buffer from the next writers sits right
+#define SPINNER_SYNC_AFTER_READ 1    //    after the reads (waves are still in step there) instead of before the next writes
+#endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -129,7 +132,7 @@ template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, bool MFMA_ 
 struct TileGeom {
     static constexpr int NT = NT_;
     static_assert(WAVES_1 == 1 || WAVES_1 == 2 || WAVES_1 == 4 || WAVES_1 == 8, "waves per workgroup");
-    static_assert(NT >= 4 && NT <= 14, "tile of 2^4 .. 2^14 elements");
+    static_assert(NT >= 4 && NT <= 16, "tile of 2^4 .. 2^16 elements");
     static_assert(RMAX >= 4 && RMAX <= 7, "16 .. 128 elements per thread");
     static constexpr int r = NT >= RMAX + 2 ? RMAX : NT - 2;
     static constexpr int R = 1 << r;
@@ -141,7 +144,8 @@ struct TileGeom {
     // H16 blocks on the matrix pipe need a whole wave per tile and two spare register bits
     static constexpr bool MFMA = MFMA_ && LB == 6 && r >= 4;
     // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
-    static constexpr int LDS_HALVES = (SPINNER_LDS_HALVES == 2 && WB >= 1) ? 2 : 1;
+    // (tiles above 2^14 elements always take as many trips as keep the buffer at 64 KiB)
+    static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : ((SPINNER_LDS_HALVES == 2 && WB >= 1) ? 2 : 1);
     static constexpr int LDS_FLOAT4 = WB > 0 ? ((1 << NT_) / 4) / LDS_HALVES : 1;
     static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
@@ -420,7 +424,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
     constexpr int TO = 1 - FROM;
     constexpr int NW = RW ? RW : G::R, NR = RR ? RR : G::R;
     if constexpr (G::LDS_HALVES == 1) {
-        if constexpr (SYNC_BEFORE) __syncthreads();     // earlier readers of lds are done
+        if constexpr (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ) __syncthreads();     // earlier readers of lds are done
         const int ef = c.base_index(FROM);
 #pragma unroll
         for (int jh = 0; jh < NW / 4; ++jh) {
@@ -437,32 +441,49 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
                 v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
             }
         }
+        if constexpr (SPINNER_SYNC_AFTER_READ != 0) __syncthreads();   // buffer free for the next exchange
     } else {
         static_assert(G::LDS_HALVES == 1 || (RW == 0 && RR == 0), "pruned rounds use the whole-tile exchange");
-        // Two trips through an LDS buffer of half the tile: trip h moves the elements whose
-        // index bit 1 is h, i.e. registers 4k+2h and 4k+2h+1 of every thread (8 bytes per
-        // lane, consecutive lanes on consecutive addresses).  Each thread receives exactly
-        // the register slots it has just sent, so nothing is overwritten before it is sent.
-        // Halving the footprint doubles the workgroups a CU can hold.
-        float2* lds2 = reinterpret_cast<float2*>(lds);
+        // Several trips through an LDS buffer of a half (quarter) of the tile: trip h moves
+        // registers 4k+2h, 4k+2h+1 (register 4k+h) of every thread, i.e. the elements with a
+        // given value of index bit 1 (bits 1..0): 8 (4) bytes per lane, consecutive lanes on
+        // consecutive addresses.  Each thread receives exactly the register slots it has just
+        // sent, so nothing is overwritten before it is sent.  A smaller footprint lets a CU
+        // hold more workgroups, and lets tiles of 2^15 and 2^16 elements fit at all.
         const int ef = c.base_index(FROM);
         const int et = c.base_index(TO);
+        if constexpr (G::LDS_HALVES == 2) {
+            float2* lds2 = reinterpret_cast<float2*>(lds);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            if (h == 1 || SYNC_BEFORE) __syncthreads();
+            for (int h = 0; h < 2; ++h) {
+                if (h == 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
 #pragma unroll
-            for (int jh = 0; jh < G::R / 4; ++jh) {
-                const int e = ef | G::reg_index(FROM, jh * 4);
-                lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
+                for (int jh = 0; jh < G::R / 4; ++jh) {
+                    const int e = ef | G::reg_index(FROM, jh * 4);
+                    lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int jh = 0; jh < G::R / 4; ++jh) {
+                    const int e = et | G::reg_index(TO, jh * 4);
+                    const float2 t = lds2[e >> 2];
+                    v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
+                }
             }
-            __syncthreads();
+        } else {
+            static_assert(G::LDS_HALVES == 4, "one, two or four trips");
+            float* lds1 = reinterpret_cast<float*>(lds);
 #pragma unroll
-            for (int jh = 0; jh < G::R / 4; ++jh) {
-                const int e = et | G::reg_index(TO, jh * 4);
-                const float2 t = lds2[e >> 2];
-                v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
+            for (int h = 0; h < 4; ++h) {
+                if (h >= 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
+#pragma unroll
+                for (int jh = 0; jh < G::R / 4; ++jh) lds1[(ef | G::reg_index(FROM, jh * 4)) >> 2] = v[jh * 4 + h];
+                __syncthreads();
+#pragma unroll
+                for (int jh = 0; jh < G::R / 4; ++jh) v[jh * 4 + h] = lds1[(et | G::reg_index(TO, jh * 4)) >> 2];
             }
         }
+        if constexpr (SPINNER_SYNC_AFTER_READ != 0) __syncthreads();
     }
 }
 
@@ -788,10 +809,19 @@ spinner_tile_kernel(TileParams p)
         }
 
         // steps (layout alternates only when a tile spans several waves)
+#ifdef SPINNER_EXPERIMENT_NOCOMPUTE
+        if (p.m < 0)      // never true: keeps the code but skips it (memory-shape experiment)
+#endif
         spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, !PERSIST, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
+#ifdef SPINNER_EXPERIMENT_NOCOMPUTE
+        if (p.m < 0)
+#endif
         if constexpr (NSTEPS > 1)
             spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
         bool wave_live = true;
+#ifdef SPINNER_EXPERIMENT_NOCOMPUTE
+        if (p.m < 0)
+#endif
         if constexpr (NSTEPS > 2) {
             if constexpr (PRUNE > 0)
                 spinner_step_pruned<G, C, CB, G::layout_after(2), false, SIGNS, PRUNE>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds, wave_live);

@@ -161,6 +161,12 @@ def sample_rows(batch: int, count: int, seed: int) -> np.ndarray:
     return np.sort(np.concatenate([[0, batch - 1], mid])).astype(np.int64)
 
 
+def fused_max_n(epilogue: str) -> int:
+    """Largest n one fused kernel handles: 2^16 for the plain / first-m-rows epilogue (fp32
+    butterflies), 2^14 for the fp64 feature map and for hashing."""
+    return (1 << 16) if epilogue == "none" else (1 << 14)
+
+
 def algorithmic_bytes_per_vector(w: Workload) -> int:
     """Bytes the method must move per vector: x once, the epilogue's output once
     (diagonals are shared by the batch and amortise to zero).  For n above the
@@ -169,7 +175,7 @@ def algorithmic_bytes_per_vector(w: Workload) -> int:
     if w.kind == "hash":
         return 4 * n + 4 * w.L
     out = 8 * w.m if w.epilogue == "cossin" else 4 * w.m
-    if n > (1 << 14):
+    if n > fused_max_n(w.epilogue):
         return 4 * 8 * n if w.m == n else 3 * 8 * n + 4 * n + out
     return 4 * n + out
 

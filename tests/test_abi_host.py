@@ -42,6 +42,8 @@ def test_version_and_messages(b):
 
 def test_workspace_bytes(b):
     assert b.spinner_workspace_bytes(1 << 14, 32768, 1024, "none") == 0
+    assert b.spinner_workspace_bytes(1 << 16, 64, 1024, "none") == 0            # still one fused kernel
+    assert b.spinner_workspace_bytes(1 << 15, 64, 1024, "cossin") == 64 * (1 << 15) * 4
     assert b.spinner_workspace_bytes(1 << 20, 256, 1 << 20, "none") == 0          # in place in out
     assert b.spinner_workspace_bytes(1 << 20, 256, 1024, "none") == 256 * (1 << 20) * 4
     assert b.spinner_workspace_bytes(1 << 20, 256, 1 << 20, "cossin") == 256 * (1 << 20) * 4

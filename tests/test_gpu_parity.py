@@ -60,11 +60,11 @@ def _run_apply(g, x, d, m, epilogue, scale, **kw):
 
 
 # ------------------------------------------------------------------ fused sizes, plain spinner
-@pytest.mark.parametrize("log2n", list(range(4, 15)))
+@pytest.mark.parametrize("log2n", list(range(4, 17)))
 def test_plain_spinner_every_fused_size(gpu, oracle, log2n):
     n = 1 << log2n
     # ragged batch: not a multiple of the vectors a workgroup handles, several workgroups
-    batch = {4: 1000, 5: 777, 6: 333, 7: 200}.get(log2n, 37 if log2n < 12 else 9)
+    batch = {4: 1000, 5: 777, 6: 333, 7: 200, 15: 5, 16: 3}.get(log2n, 37 if log2n < 12 else 9)
     x, d = _rng_case(n, batch, 1000 + log2n, gaussian_d3=(log2n % 2 == 0))
     got = _run_apply(gpu, x, d, n, "none", 1.0)
     want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
