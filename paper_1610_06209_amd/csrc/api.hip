@@ -146,29 +146,42 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     const ColShape cs = col_shape_for(log2n);
     const int kColRowsLog = cs.rows_log, kColContigLog = cs.contig_log;
     const int nr = log2n - kColRowsLog;
-    float* buf = ws ? static_cast<float*>(workspace) : out;
-    const long long row_tiles = (long long)batch << kColRowsLog;
-    const long long col_tiles = (long long)batch << (nr - kColContigLog);
-    if (row_tiles > 0x7fffffffLL * 4 || col_tiles > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
+    float* buf_all = ws ? static_cast<float*>(workspace) : out;
+    // The batch is walked in slices of about 192 MiB, all four passes per slice, so that the
+    // three intermediate trips of a slice find most of it in the 256 MB memory-side cache
+    // (measured 10-15 % faster than pass-by-pass over the whole batch; smaller slices leave
+    // too few tiles per launch).
+    const long long slice_bytes = 192LL << 20;
+    long long slice = slice_bytes / (4LL * n);
+    if (slice < 8) slice = 8;          // very long vectors: keep enough tiles per launch to fill the chip
+    if (slice > batch) slice = batch;
+    if ((slice << kColRowsLog) > 0x7fffffffLL * 4 || (slice << (nr - kColContigLog)) > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
 
-    hipError_t e;
-    // P1: D1, rows : x -> buf
-    p.x = x; p.out = buf; p.d[0] = d1; p.d[1] = nullptr; p.d[2] = nullptr;
-    p.in_stride = n; p.out_stride = n; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
-    p.m = n; p.factor = 1.0f;
-    if ((e = launch_row_first(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
-    // P2: cols, D2, cols : buf -> buf
-    p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
-    p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-    if ((e = launch_col_middle(kColRowsLog, kColContigLog, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
-    // P3: rows, D3, rows : buf -> buf
-    p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
-    if ((e = launch_row_middle(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
-    // P4: cols, epilogue : buf -> out
-    p.out = out; p.d[1] = nullptr; p.out_stride = out_stride;
-    p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-    p.m = m; p.factor = (float)factor_d;
-    if ((e = launch_col_last(kColRowsLog, kColContigLog, epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+    for (long long b0 = 0; b0 < batch; b0 += slice) {
+        const long long nb = batch - b0 < slice ? batch - b0 : slice;
+        const long long row_tiles = nb << kColRowsLog;
+        const long long col_tiles = nb << (nr - kColContigLog);
+        float* buf = buf_all + b0 * (long long)n;
+        hipError_t e;
+        p.batch = nb;
+        // P1: D1, rows : x -> buf
+        p.x = x + b0 * (long long)n; p.out = buf; p.d[0] = d1; p.d[1] = nullptr; p.d[2] = nullptr;
+        p.in_stride = n; p.out_stride = n; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
+        p.m = n; p.factor = 1.0f;
+        if ((e = launch_row_first(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
+        // P2: cols, D2, cols : buf -> buf
+        p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
+        p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
+        if ((e = launch_col_middle(kColRowsLog, kColContigLog, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+        // P3: rows, D3, rows : buf -> buf
+        p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
+        if ((e = launch_row_middle(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
+        // P4: cols, epilogue : buf -> out
+        p.out = out + b0 * out_stride; p.d[1] = nullptr; p.out_stride = out_stride;
+        p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
+        p.m = m; p.factor = (float)factor_d;
+        if ((e = launch_col_last(kColRowsLog, kColContigLog, epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+    }
     return SPINNER_OK;
 }
 
