@@ -23,6 +23,12 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4; };
 #ifndef SPINNER_RMAX_F32
 template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64 < 5 ? SPINNER_RMAX_F64 : 4, waves = 4; };
+template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4; };
+template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4; };
+template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4; };
+template <> struct Tuning<float, 7> { static constexpr int rmax = 3, waves = 4; };
+template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4; };
+template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4; };
 template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4; };
 template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1; };
 template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1; };

@@ -133,7 +133,7 @@ struct TileGeom {
     static constexpr int NT = NT_;
     static_assert(WAVES_1 == 1 || WAVES_1 == 2 || WAVES_1 == 4 || WAVES_1 == 8, "waves per workgroup");
     static_assert(NT >= 4 && NT <= 16, "tile of 2^4 .. 2^16 elements");
-    static_assert(RMAX >= 4 && RMAX <= 7, "16 .. 128 elements per thread");
+    static_assert(RMAX >= 2 && RMAX <= 7, "4 .. 128 elements per thread");
     static constexpr int r = NT >= RMAX + 2 ? RMAX : NT - 2;
     static constexpr int R = 1 << r;
     static constexpr int LB = (NT - r) < 6 ? (NT - r) : 6;   // lane bits per tile
