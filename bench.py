@@ -30,8 +30,9 @@ VALU_PEAK_GOPS = 256 * 64 * 2.4
 # each scaled by what the same counter reads for spinner_stream_copy of known size); see
 # profiles/.  None where no counter run has been made for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/spinner_tile_kernel_n4096_sweep_plain_n2p12.md: (524496.0 KiB x 2.0000) + (1048831.2 KiB x 1.0000)
-    "sweep_plain_n2p12": int((524496.0 * 2.0 + 1048831.2) * 1024),
+    # profiles/spinner_tile_kernel_f32_n4096_sweep_plain_n2p12.md:
+    # (FETCH_SIZE 524490.0 KiB x 2.0000) + (WRITE_SIZE 1048859.8 KiB x 1.0000), scale factors from the copy kernel
+    "sweep_plain_n2p12": int((524490.0 * (1048576.0 / 524297.5) + 1048859.75) * 1024),
 }
 
 
