@@ -20,11 +20,14 @@ What each function follows:
 * ``epilogue_hash``      - Section 4, Theorem 4 and its proof: the hash of a
   vector is the signed canonical direction closest to its projection, i.e.
   ``argmax_i |y_i|`` together with the sign of that coordinate.
+* ``epilogue_signbits`` / ``angular_estimate`` - Section 5 (angular kernel):
+  the pointwise sign of the projection, and the kernel estimate
+  ``1 - d_H / d'`` from the Hamming distance of two such sign vectors.
 
 Readings where the paper is silent: Sylvester row order; bucket ``i`` for
 ``+e_i`` and ``i + n`` for ``-e_i``; lowest index wins exact ties; a zero
-coordinate counts as positive; features are concatenated (cos block, then sin
-block), not interleaved.
+coordinate counts as positive (hash and sign bits alike); features are
+concatenated (cos block, then sin block), not interleaved.
 
 Parity status: every function here is pinned by the CPU tests (``tests/
 test_oracle_*.py``) against closed forms, library constructions of the Hadamard
@@ -162,6 +165,22 @@ def epilogue_hash(y: np.ndarray) -> np.ndarray:
     return (istar + n * (ystar < 0)).astype(np.int32)
 
 
+def epilogue_signbits(y: np.ndarray, m: int) -> np.ndarray:
+    """uint8 [..., m]: 1 where the coordinate is negative, 0 otherwise (zero counts as
+    positive): s = sign applied pointwise to the first m coordinates (Section 5)."""
+    return (y[..., :m] < 0).astype(np.uint8)
+
+
+def angular_estimate(bits_a: np.ndarray, bits_b: np.ndarray) -> np.ndarray:
+    """[Ba][Bb] estimates 1 - d_H(s(Ax_i), s(Ax_j)) / d' of the angular kernel from two
+    sets of sign vectors (Section 5)."""
+    bits_a = np.asarray(bits_a, dtype=np.uint8)
+    bits_b = np.asarray(bits_b, dtype=np.uint8)
+    m = bits_a.shape[-1]
+    dh = (bits_a[:, None, :] != bits_b[None, :, :]).sum(axis=-1)
+    return 1.0 - dh.astype(np.float64) / float(m)
+
+
 def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,
           kron_a: int | None = None, nthreads: int = 0) -> np.ndarray:
     """Whole path for one diagonal triple: spinner then the named epilogue, fp64."""
@@ -170,6 +189,8 @@ def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,
         return epilogue_none(y, m, scale)
     if epilogue == "cossin":
         return epilogue_cossin(y, m, scale)
+    if epilogue == "signbits":
+        return epilogue_signbits(y, m)
     raise ValueError("unknown epilogue %r" % (epilogue,))
 
 

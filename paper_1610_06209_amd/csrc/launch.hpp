@@ -20,24 +20,24 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 #ifndef SPINNER_RMAX_F64
 #define SPINNER_RMAX_F64 5
 #endif
-template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4; };
+template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0; };
 #ifndef SPINNER_RMAX_F32
-template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64 < 5 ? SPINNER_RMAX_F64 : 4, waves = 4; };
-template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4; };
-template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4; };
-template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4; };
-template <> struct Tuning<float, 7> { static constexpr int rmax = 3, waves = 4; };
-template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4; };
-template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4; };
-template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4; };
-template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1; };
-template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1; };
-template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4; };
-template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4; };
-template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4; };   // 8 waves per tile
-template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4; };   // 16 waves per tile
+template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64 < 5 ? SPINNER_RMAX_F64 : 4, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 7> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1, min_waves = 0; };
+template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1, min_waves = 0; };
+template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4, min_waves = 0; };
+template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4, min_waves = 4; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
+template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4, min_waves = 0; };   // 16 waves per tile
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves>;
+using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, (SPINNER_USE_MFMA != 0), Tuning<T, NT>::min_waves>;
 #else   // uniform override used by tuning sweeps
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;

@@ -27,6 +27,9 @@
 #ifndef SPINNER_MIN_WAVES_PER_EU      // occupancy the register allocator must allow for one-wave tiles
 #define SPINNER_MIN_WAVES_PER_EU 1
 #endif
+#ifndef SPINNER_MIN_WAVES_MULTI       // the same for fp32 tiles that span several waves
+#define SPINNER_MIN_WAVES_MULTI 1
+#endif
 #ifndef SPINNER_LANE_CHUNK            // registers exchanged per batch in swizzle / bpermute stages (0: all at once)
 #define SPINNER_LANE_CHUNK 32
 #endif
@@ -128,8 +131,10 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //   layout 1 ("mid"): registers hold bits {0,1} and the r-2 bits just above the
 //                     lane bits (only used when a tile spans several waves)
 // Lanes hold bits 2 .. 2+LB-1 in both layouts.
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, bool MFMA_ = (SPINNER_USE_MFMA != 0)>
+// MINW_: occupancy (waves per SIMD) the register allocator must allow; 0 leaves it to the knobs above
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, bool MFMA_ = (SPINNER_USE_MFMA != 0), int MINW_ = 0>
 struct TileGeom {
+    static constexpr int MIN_WAVES = MINW_;
     static constexpr int NT = NT_;
     static_assert(WAVES_1 == 1 || WAVES_1 == 2 || WAVES_1 == 4 || WAVES_1 == 8, "waves per workgroup");
     static_assert(NT >= 4 && NT <= 16, "tile of 2^4 .. 2^16 elements");
@@ -737,7 +742,7 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
 template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, bool PERSIST, int PRUNE = 0>
 __global__ void __launch_bounds__(G::THREADS)
-__attribute__((amdgpu_waves_per_eu(G::WB || !std::is_same<T, float>::value ? 1 : SPINNER_MIN_WAVES_PER_EU)))
+__attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_WAVES ? G::MIN_WAVES : (G::WB ? SPINNER_MIN_WAVES_MULTI : SPINNER_MIN_WAVES_PER_EU))))
 spinner_tile_kernel(TileParams p)
 {
     static_assert(!SIGNS || C >= G::NT, "sign words describe contiguous tiles only");

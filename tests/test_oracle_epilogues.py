@@ -194,3 +194,75 @@ def test_close_points_collide_more_often_than_far_points(oracle):
     p_near = np.mean(oracle.hash(near, ds) == hx)
     p_far = np.mean(oracle.hash(far, ds) == hx)
     assert p_near > 0.5 and p_far < 0.1
+
+
+# ------------------------------------------------------------------ sign bits / angular kernel (Section 5)
+def test_signbits_rules_on_literal_values(oracle):
+    y = np.array([[0.0, -0.0, 1.5, -1.5, 1e-300, -1e-300, -2.0, 3.0]])
+    assert oracle.epilogue_signbits(y, 8).tolist() == [[0, 0, 0, 1, 0, 1, 1, 0]]     # zero of either sign counts as positive
+    assert oracle.epilogue_signbits(y, 4).tolist() == [[0, 0, 0, 1]]                  # first m coordinates
+    assert oracle.epilogue_signbits(y, 8).dtype == np.uint8
+
+
+def test_signbits_recover_a_planted_sign_pattern(oracle):
+    # D = I  =>  y = H^3 x = H x;  x = H c with c in {-1,+1}^n  =>  y = c exactly (n = 64: 1/sqrt(n) = 1/8 is exact)
+    n = 64
+    rng = np.random.Generator(np.random.PCG64(5))
+    c = _rademacher(rng, (5, n)).astype(np.float64)
+    Hn = scipy.linalg.hadamard(n).astype(np.float64) / 8.0
+    x = (c @ Hn).astype(np.float32)                       # multiples of 1/8, exact in fp32
+    ones = np.ones(n, dtype=np.float32)
+    bits = oracle.apply(x, ones, ones, ones, n, "signbits", 1.0)
+    assert np.array_equal(bits, (c < 0).astype(np.uint8))
+    # a single canonical direction: y = -e_j has exactly one negative coordinate, y = +e_j none
+    for j in (0, 5, n - 1):
+        e = Hn[:, j].astype(np.float32)[None, :]
+        assert oracle.apply(e, ones, ones, ones, n, "signbits", 1.0).sum() == 0
+        b = oracle.apply(-e, ones, ones, ones, n, "signbits", 1.0)[0]
+        assert b.sum() == 1 and b[j] == 1
+
+
+def test_signbits_antipodal_scale_and_truncation(oracle):
+    w = W.Workload("ang_small", "apply", 256, 50, 256, "none", 1.0, 1, "normal", 91, 50)
+    x = W.make_x_numpy(w)
+    d = W.diag_sets(w)[0]
+    y = oracle.spinner(x, d[0], d[1], d[2])
+    b = oracle.epilogue_signbits(y, 256)
+    assert np.array_equal(b, (np.sign(y) == -1).astype(np.uint8))
+    assert np.array_equal(oracle.apply(-x, d[0], d[1], d[2], 256, "signbits", 1.0), 1 - b)      # no exact zeros for this draw
+    assert np.array_equal(oracle.apply(np.float32(4.0) * x, d[0], d[1], d[2], 256, "signbits", 1.0), b)
+    assert np.array_equal(oracle.apply(x, d[0], d[1], d[2], 64, "signbits", 1.0), b[:, :64])
+    # about half the coordinates are negative, independently of the input (Remark 1: balanced rows)
+    assert abs(b.mean() - 0.5) < 0.02
+
+
+def test_angular_estimate_on_literal_bits(oracle):
+    a = np.array([[0, 1, 1, 0]], dtype=np.uint8)
+    b = np.array([[0, 1, 0, 1], [0, 1, 1, 0], [1, 0, 0, 1]], dtype=np.uint8)
+    assert oracle.angular_estimate(a, b).tolist() == [[0.5, 1.0, 0.0]]
+    g = oracle.angular_estimate(b, b)
+    assert np.array_equal(g, g.T) and np.array_equal(np.diag(g), np.ones(3))
+
+
+def test_angular_estimate_approaches_the_angular_kernel(oracle):
+    # K(x_i, x_j) = 1 - theta / pi (Section 5); pairs built with a known angle, averaged over independent triples
+    n, triples = 1024, 16
+    rng = np.random.Generator(np.random.PCG64(2024))
+    u = rng.standard_normal(n)
+    u /= np.linalg.norm(u)
+    v = rng.standard_normal(n)
+    v -= (v @ u) * u
+    v /= np.linalg.norm(v)
+    thetas = np.array([math.pi / 6, math.pi / 3, math.pi / 2, 2 * math.pi / 3, 0.9 * math.pi])
+    xa = (3.0 * u)[None, :].astype(np.float32)                                           # lengths do not matter
+    xb = np.stack([0.7 * (math.cos(t) * u + math.sin(t) * v) for t in thetas]).astype(np.float32)
+    est = np.zeros(len(thetas))
+    for k in range(triples):
+        d = W.rademacher_diagonals(n, 3, 1000 + k)
+        ba = oracle.apply(xa, d[0], d[1], d[2], n, "signbits", 1.0)
+        bb = oracle.apply(xb, d[0], d[1], d[2], n, "signbits", 1.0)
+        est += oracle.angular_estimate(ba, bb)[0]
+    est /= triples
+    exact = 1.0 - thetas / math.pi
+    # binomial standard deviation of the estimate: sqrt(p (1 - p) / (n * triples)) <= 0.004
+    assert np.max(np.abs(est - exact)) < 0.02, (est, exact)
