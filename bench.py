@@ -74,6 +74,17 @@ def make_runner(torch, b, W, w, dev, diagonals):
         else:
             def fn():
                 b.spinner_hash(x, ds, out_idx=out)
+    elif w.kind == "codes":
+        out = torch.empty((w.batch, w.m // 64), dtype=torch.int64, device=dev)
+        need = b.spinner_codes_workspace_bytes(w.n, w.batch)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
+        d1, d2, d3 = ds[0, 0], ds[0, 1], ds[0, 2]
+        if signs is not None:
+            def fn():
+                b.spinner_sign_codes_signs(x, signs, w.m, codes=out, workspace=ws)
+        else:
+            def fn():
+                b.spinner_sign_codes(x, d1, d2, d3, w.m, codes=out, workspace=ws)
     else:
         width = 2 * w.m if w.epilogue == "cossin" else w.m
         out = torch.empty((w.batch, width), dtype=torch.float32, device=dev)
@@ -114,6 +125,25 @@ def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0):
         "valu_frac_adds_only": ops / (ev_ms * 1e-3) / 1e9 / VALU_PEAK_GOPS,
     }
     del fn, x
+    torch.cuda.empty_cache()
+    return res
+
+
+def measure_gram(torch, b, dev, rows, m, steps, warmup):
+    """Hamming Gram matrix of `rows` x `rows` random codes of m bits: pairs/s and the share of the plain
+    vector-ALU instruction rate that its xor + popcount floor (4 instructions per 64 bits and pair) reaches."""
+    codes = torch.randint(-2**62, 2**62, (rows, m // 64), dtype=torch.int64, device=dev)
+    out = torch.empty((rows, rows), dtype=torch.float32, device=dev)
+    fn = lambda: b.spinner_angular_gram(codes, codes, m, out=out)
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    _, ev_ms = time_calls(torch, fn, steps, warmup)
+    pairs = rows * rows
+    res = {"workload": "angular_gram_%dx%d_m%d" % (rows, rows, m), "ms": round(ev_ms, 4),
+           "pairs_per_s": pairs / (ev_ms * 1e-3),
+           "valu_frac_xor_popcount_floor": pairs * (m / 16.0) / (ev_ms * 1e-3) / 1e9 / VALU_PEAK_GOPS}
+    del codes, out
     torch.cuda.empty_cache()
     return res
 
@@ -185,6 +215,8 @@ def main():
     def resolve(name):
         if name in W.CONFIGS:
             return W.CONFIGS[name]
+        if name in W.NEXT:
+            return W.NEXT[name]
         if name.startswith("sweep_plain_n2p"):
             return W.sweep_workload(int(name[len("sweep_plain_n2p"):]))
         raise SystemExit("unknown workload %r" % name)
@@ -229,8 +261,23 @@ def main():
                 name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
                 100 * r["valu_frac_adds_only"]))
         extras["configs"] = cfgs
+        nxt = []
+        for name, w in W.NEXT.items():
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
+            nxt.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
+                        "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
+                        "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
+            log("[bench] %s: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)  butterfly adds at %.1f%% of VALU peak" % (
+                name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
+                100 * r["valu_frac_adds_only"]))
+        g = measure_gram(torch, b, dev, 16384, 4096, max(3, args.steps // 2), max(2, args.warmup // 2))
+        log("[bench] %s: %.4f ms  %.3e pairs/s  xor+popcount floor at %.1f%% of VALU peak" % (
+            g["workload"], g["ms"], g["pairs_per_s"], 100 * g["valu_frac_xor_popcount_floor"]))
+        nxt.append(g)
+        extras["next_rows"] = nxt
 
     traffic = MEASURED_TRAFFIC_BYTES.get(head.name)
+    alu_bound = head.kind in ("hash", "codes")
     line = {
         "metric": "HD3HD2HD1 vectors/s + achieved HBM GB/s vs peak, fp32, n=2^10..2^20",
         "value": hres["vectors_per_s"],
@@ -249,11 +296,12 @@ def main():
                    "diagonals": "rademacher, " + ("packed sign words prepared off the clock" if args.diagonals == "signs"
                                                  else "fp32 arrays")},
         "roofline": {
-            "bound": "alu" if head.kind == "hash" else "hbm",
-            "achieved": hres["butterfly_adds_Gops"] / 1e3 if head.kind == "hash" else hres["achieved_GBs"],
-            "peak": VALU_PEAK_GOPS / 1e3 if head.kind == "hash" else HBM_PEAK_GBS,
-            "unit": "TFLOP/s" if head.kind == "hash" else "GB/s",
-            "frac": hres["valu_frac_adds_only"] if head.kind == "hash" else hres["hbm_frac"],
+            # hashing and sign codes write next to nothing and are bound by the plain fp32 vector ALU
+            "bound": "alu" if alu_bound else "hbm",
+            "achieved": hres["butterfly_adds_Gops"] / 1e3 if alu_bound else hres["achieved_GBs"],
+            "peak": VALU_PEAK_GOPS / 1e3 if alu_bound else HBM_PEAK_GBS,
+            "unit": "TFLOP/s" if alu_bound else "GB/s",
+            "frac": hres["valu_frac_adds_only"] if alu_bound else hres["hbm_frac"],
             "traffic": traffic,
             "kernel_ms": hres["kernel_ms"],
             "algorithmic_bytes": hres["algorithmic_bytes"],

@@ -138,6 +138,48 @@ int spinner_hash_signs(const float *x, int n, long batch, int L,
                        const void *signs, int *out_idx, void *stream);
 
 /*
+ * Angular-kernel features (Section 5, kernel approximation): the non-linear
+ * map applied pointwise to the projection is the sign function, and the
+ * kernel 1 - theta/pi between two inputs is estimated by 1 - d_H / d' from
+ * the Hamming distance d_H of their d' = m sign bits.
+ *
+ * spinner_sign_codes computes, for each row of x, the signs of the first m
+ * coordinates of y = H D3 H D2 H D1 x, packed one bit per coordinate:
+ * bit = 1 where y_i < 0, 0 otherwise (a zero of either sign counts as
+ * positive, as in spinner_hash).  The bits are stored in 64-bit words in the
+ * order in which the hardware produces them (the comparison mask of one
+ * register over one wave): coordinate e lives in bit (e >> 2) & 63 of word
+ * ((e >> 8) << 2) | (e & 3) of its row; spinner_code_position returns this
+ * pair on the host.  Any fixed order gives the same Hamming distances.
+ *
+ *   x, d1..d3  in   as for spinner_apply
+ *   m          in   coordinates kept: a multiple of 256, 256 <= m <= n
+ *   codes      out  device, spinner_code_bytes(m) = m / 8 bytes per row,
+ *                   rows contiguous, 16-byte aligned
+ *   workspace  in   device scratch of spinner_codes_workspace_bytes(n, batch)
+ *                   bytes (0 for n <= 2^16: one fused pass; above that the
+ *                   projection is formed in the workspace by the four-pass
+ *                   path and its signs are packed by a second kernel)
+ *
+ * spinner_sign_codes_signs is the same for diagonals packed by
+ * spinner_pack_signs.  n must be at least 256 (SPINNER_ERR_UNSUPPORTED below).
+ *
+ * spinner_angular_gram computes out[i][j] = 1 - d_H(a_i, b_j) / m (fp32,
+ * row-major [na][nb]) for two sets of codes of the same m; the Hamming
+ * distances are exact integers.  na is limited to 64 * 65535 rows per call.
+ */
+size_t spinner_code_bytes(int m);
+size_t spinner_codes_workspace_bytes(int n, long batch);
+int spinner_code_position(int coordinate, int *word, int *bit);
+int spinner_sign_codes(const float *x, int n, long batch,
+                       const float *d1, const float *d2, const float *d3,
+                       int m, void *codes, void *workspace, void *stream);
+int spinner_sign_codes_signs(const float *x, int n, long batch, const void *signs,
+                             int m, void *codes, void *workspace, void *stream);
+int spinner_angular_gram(const void *codes_a, long na, const void *codes_b, long nb,
+                         int m, float *out, void *stream);
+
+/*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the
  * fused limit, and above it when m == n with epilogue NONE; otherwise batch * n * 4.
  * Returns 0 for invalid arguments (spinner_apply reports those).

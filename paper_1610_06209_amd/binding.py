@@ -32,12 +32,18 @@ EPILOGUES = {"none": SPINNER_EPI_NONE, "cossin": SPINNER_EPI_COSSIN}
 
 EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_strerror",
            "spinner_version", "spinner_stream_copy", "spinner_signs_bytes", "spinner_pack_signs",
-           "spinner_apply_signs", "spinner_hash_signs"]
+           "spinner_apply_signs", "spinner_hash_signs", "spinner_code_bytes", "spinner_codes_workspace_bytes",
+           "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         "libspinner.so is not built: run `python -m paper_1610_06209_amd.build` "
         "(or __graft_entry__.build()); there is no fallback path")
+
+# PyTorch ships its own HIP runtime and loads it by path; the library must bind to that same copy (it owns
+# the device memory and the streams handed in here), so torch is loaded first and the library's
+# dependency on libamdhip64 then resolves to the runtime already in the process.
+import torch  # noqa: E402,F401
 
 lib = ctypes.CDLL(LIB_PATH)
 _vp = ctypes.c_void_p
@@ -63,6 +69,18 @@ lib.spinner_hash_signs.restype = ctypes.c_int
 lib.spinner_hash_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp]
 lib.spinner_stream_copy.restype = ctypes.c_int
 lib.spinner_stream_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
+lib.spinner_code_bytes.restype = ctypes.c_size_t
+lib.spinner_code_bytes.argtypes = [ctypes.c_int]
+lib.spinner_codes_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_codes_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_long]
+lib.spinner_code_position.restype = ctypes.c_int
+lib.spinner_code_position.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+lib.spinner_sign_codes.restype = ctypes.c_int
+lib.spinner_sign_codes.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
+lib.spinner_sign_codes_signs.restype = ctypes.c_int
+lib.spinner_sign_codes_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, ctypes.c_int, _vp, _vp, _vp]
+lib.spinner_angular_gram.restype = ctypes.c_int
+lib.spinner_angular_gram.argtypes = [_vp, ctypes.c_long, _vp, ctypes.c_long, ctypes.c_int, _vp, _vp]
 
 
 class SpinnerError(RuntimeError):
@@ -246,3 +264,110 @@ def spinner_stream_copy(src, dst, stream=None):
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return dst
+
+
+def spinner_code_bytes(m: int) -> int:
+    return int(lib.spinner_code_bytes(int(m)))
+
+
+def spinner_codes_workspace_bytes(n: int, batch: int) -> int:
+    return int(lib.spinner_codes_workspace_bytes(int(n), int(batch)))
+
+
+def spinner_code_position(coordinate: int):
+    """(word, bit) of a coordinate inside a row of sign codes."""
+    w, b = ctypes.c_int(), ctypes.c_int()
+    rc = lib.spinner_code_position(int(coordinate), ctypes.byref(w), ctypes.byref(b))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return w.value, b.value
+
+
+def _codes_out(x, m, codes):
+    import torch
+
+    batch = x.shape[0]
+    nbytes = spinner_code_bytes(m)
+    if nbytes == 0:
+        raise SpinnerError(SPINNER_ERR_BAD_M)
+    if codes is None:
+        codes = torch.empty((batch, nbytes // 8), dtype=torch.int64, device=x.device)
+    else:
+        _check_tensor(codes, "codes", torch.int64)
+        if codes.numel() != batch * (nbytes // 8):
+            raise ValueError("codes has the wrong size")
+    return codes
+
+
+def _codes_workspace(x, workspace):
+    import torch
+
+    batch, n = x.shape
+    need = spinner_codes_workspace_bytes(n, batch)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    return workspace
+
+
+def spinner_sign_codes(x, d1, d2, d3, m=None, codes=None, workspace=None, stream=None):
+    """Sign bits of the first m coordinates of H D3 H D2 H D1 x, int64 CUDA tensor [batch][m/64]."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    for name, d in (("d1", d1), ("d2", d2), ("d3", d3)):
+        _check_tensor(d, name, torch.float32)
+    batch, n = x.shape
+    m = n if m is None else int(m)
+    codes = _codes_out(x, m, codes)
+    workspace = _codes_workspace(x, workspace)
+    rc = lib.spinner_sign_codes(x.data_ptr(), n, batch, d1.data_ptr(), d2.data_ptr(), d3.data_ptr(), m, codes.data_ptr(),
+                                workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return codes
+
+
+def spinner_sign_codes_signs(x, signs, m=None, codes=None, workspace=None, stream=None, triple=0):
+    """spinner_sign_codes for +-1 diagonals given as packed sign words (see spinner_pack_signs)."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    batch, n = x.shape
+    m = n if m is None else int(m)
+    codes = _codes_out(x, m, codes)
+    workspace = _codes_workspace(x, workspace)
+    one = spinner_signs_bytes(n, 1)
+    if signs.numel() < (triple + 1) * one:
+        raise ValueError("signs buffer too small for this n / triple")
+    rc = lib.spinner_sign_codes_signs(x.data_ptr(), n, batch, signs.data_ptr() + triple * one, m, codes.data_ptr(),
+                                      workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return codes
+
+
+def spinner_angular_gram(codes_a, codes_b, m, out=None, stream=None):
+    """out[i][j] = 1 - Hamming(codes_a[i], codes_b[j]) / m, fp32 CUDA tensor [na][nb]."""
+    import torch
+
+    _check_tensor(codes_a, "codes_a", torch.int64)
+    _check_tensor(codes_b, "codes_b", torch.int64)
+    words = spinner_code_bytes(m) // 8
+    if words == 0:
+        raise SpinnerError(SPINNER_ERR_BAD_M)
+    if codes_a.shape[-1] != words or codes_b.shape[-1] != words:
+        raise ValueError("codes do not have m / 64 words per row")
+    na, nb = codes_a.shape[0], codes_b.shape[0]
+    if out is None:
+        out = torch.empty((na, nb), dtype=torch.float32, device=codes_a.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != na * nb:
+            raise ValueError("out has the wrong size")
+    rc = lib.spinner_angular_gram(codes_a.data_ptr(), na, codes_b.data_ptr(), nb, int(m), out.data_ptr(),
+                                  _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out

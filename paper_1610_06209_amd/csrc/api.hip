@@ -60,9 +60,12 @@ bool pow2_in_range(int n, int* log2n)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// internal epilogue id of the sign-code entry points (not part of spinner_epilogue_t)
+constexpr int kEpiSignBits = 2;
+
 int fused_max_log(int epilogue)
 {
-    return epilogue == SPINNER_EPI_NONE ? spinner::kFusedMaxLogPlain : spinner::kFusedMaxLogOther;
+    return epilogue == SPINNER_EPI_COSSIN ? spinner::kFusedMaxLogOther : spinner::kFusedMaxLogPlain;
 }
 
 
@@ -70,7 +73,7 @@ int fused_max_log(int epilogue)
 
 extern "C" {
 
-int spinner_version(void) { return 100; }
+int spinner_version(void) { return 110; }
 
 const char* spinner_strerror(int status)
 {
@@ -112,7 +115,8 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int epi = epilogue == SPINNER_EPI_COSSIN ? EPI_STORE_COSSIN : EPI_STORE_NONE;
-    const long long out_stride = epilogue == SPINNER_EPI_COSSIN ? 2LL * m : (long long)m;
+    // row stride of the output: floats, or 64-bit words for sign codes
+    const long long out_stride = epilogue == SPINNER_EPI_COSSIN ? 2LL * m : (epilogue == kEpiSignBits ? m / 64 : (long long)m);
     // n^{-3/2} * scale, formed in double and rounded once
     const double factor_d = (double)scale / ((double)n * sqrt((double)n));
 
@@ -137,8 +141,9 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         // how many of the highest index bits lie entirely above the kept rows
         int prune = 0;
         while (prune < log2n && (long long)m <= ((long long)n >> (prune + 1))) ++prune;
-        const hipError_t e = epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, signs != nullptr, p, batch, s)
-                                                      : launch_fused_none(log2n, signs != nullptr, prune, p, batch, s);
+        const hipError_t e = epilogue == kEpiSignBits ? launch_fused_signbits(log2n, signs != nullptr, prune, p, batch, s)
+                             : epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, signs != nullptr, p, batch, s)
+                                                       : launch_fused_none(log2n, signs != nullptr, prune, p, batch, s);
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);
     }
 
@@ -280,6 +285,84 @@ int spinner_hash(const float* x, int n, long batch, int L, const float* diag_set
 int spinner_hash_signs(const float* x, int n, long batch, int L, const void* signs, int* out_idx, void* stream)
 {
     return hash_impl(x, n, batch, L, nullptr, static_cast<const unsigned long long*>(signs), out_idx, stream);
+}
+
+// ------------------------------------------------------------------ sign codes (angular kernel)
+size_t spinner_code_bytes(int m) { return (m >= 256 && m % 256 == 0) ? (size_t)m / 8 : 0; }
+
+size_t spinner_codes_workspace_bytes(int n, long batch)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || batch <= 0) return 0;
+    return log2n <= spinner::kFusedMaxLogPlain ? 0 : (size_t)batch * (size_t)n * sizeof(float);
+}
+
+int spinner_code_position(int coordinate, int* word, int* bit)
+{
+    if (coordinate < 0 || !word || !bit) return SPINNER_ERR_NULL_PTR;
+    *word = ((coordinate >> 8) << 2) | (coordinate & 3);
+    *bit = (coordinate >> 2) & 63;
+    return SPINNER_OK;
+}
+
+static int codes_impl(const float* x, int n, long batch, const float* d1, const float* d2, const float* d3,
+                      const unsigned long long* signs, int m, void* codes, void* workspace, void* stream)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n)) return SPINNER_ERR_BAD_N;
+    if (log2n < spinner::kCodeMinLog) return SPINNER_ERR_UNSUPPORTED;
+    if (m < 256 || m > n || m % 256) return SPINNER_ERR_BAD_M;
+    if (batch < 0 || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    if (batch == 0) return SPINNER_OK;
+    if (!x || !codes) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(x) || !aligned16(codes)) return SPINNER_ERR_ALIGNMENT;
+    if (log2n <= spinner::kFusedMaxLogPlain)
+        return apply_impl(x, n, log2n, batch, d1, d2, d3, signs, m, kEpiSignBits, 1.0f, static_cast<float*>(codes), nullptr,
+                          stream);
+    // above the fused range: the whole projection goes to the workspace (four passes), then its signs are packed
+    if (!workspace) return SPINNER_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
+    float* y = static_cast<float*>(workspace);
+    const int rc = apply_impl(x, n, log2n, batch, d1, d2, d3, nullptr, n, SPINNER_EPI_NONE, 1.0f, y, nullptr, stream);
+    if (rc != SPINNER_OK) return rc;
+    const hipError_t e = spinner::launch_pack_codes(y, n, static_cast<unsigned long long*>(codes), m, batch,
+                                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_sign_codes(const float* x, int n, long batch, const float* d1, const float* d2, const float* d3, int m,
+                       void* codes, void* workspace, void* stream)
+{
+    if (batch > 0 && (!d1 || !d2 || !d3)) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(d1) || !aligned16(d2) || !aligned16(d3)) return SPINNER_ERR_ALIGNMENT;
+    return codes_impl(x, n, batch, d1, d2, d3, nullptr, m, codes, workspace, stream);
+}
+
+int spinner_sign_codes_signs(const float* x, int n, long batch, const void* signs, int m, void* codes, void* workspace,
+                             void* stream)
+{
+    if (batch > 0 && !signs) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
+    if (n > (1 << spinner::kFusedMaxLogOther)) {     // the packed form is a plain copy of the diagonals at these sizes
+        const float* d = static_cast<const float*>(signs);
+        return codes_impl(x, n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, codes, workspace, stream);
+    }
+    return codes_impl(x, n, batch, nullptr, nullptr, nullptr, static_cast<const unsigned long long*>(signs), m, codes,
+                      workspace, stream);
+}
+
+int spinner_angular_gram(const void* codes_a, long na, const void* codes_b, long nb, int m, float* out, void* stream)
+{
+    if (m < 256 || m % 256) return SPINNER_ERR_BAD_M;
+    if (na < 0 || nb < 0 || (double)na * (double)nb > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    if (na == 0 || nb == 0) return SPINNER_OK;
+    if (!codes_a || !codes_b || !out) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(codes_a) || !aligned16(codes_b) || !aligned16(out)) return SPINNER_ERR_ALIGNMENT;
+    if ((na + 63) / 64 > 65535) return SPINNER_ERR_BAD_BATCH;
+    const hipError_t e = spinner::launch_hamming_gram(static_cast<const unsigned long long*>(codes_a), na,
+                                                      static_cast<const unsigned long long*>(codes_b), nb, m, out,
+                                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 
 int spinner_stream_copy(const float* src, float* dst, size_t count, void* stream)

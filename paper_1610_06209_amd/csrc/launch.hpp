@@ -89,6 +89,12 @@ hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipSt
 hipError_t launch_col_middle(int rows_log, int contig_log, const TileParams& p, long long tiles, hipStream_t s);          // cols, D2, cols
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
+// sign codes (angular-kernel features): fused kernels for n = 2^8 .. 2^16, packing of an fp32 projection, Gram matrix
+constexpr int kCodeMinLog = 8;
+hipError_t launch_fused_signbits(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s);
+hipError_t launch_pack_codes(const float* y, long long y_stride, unsigned long long* codes, int m, long long batch, hipStream_t s);
+hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const unsigned long long* b, long long nb, int m,
+                               float* out, hipStream_t s);
 
 // sign words per diagonal in the packed format (n <= 2^14)
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }

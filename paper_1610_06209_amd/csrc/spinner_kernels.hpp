@@ -193,7 +193,7 @@ struct TileParams {
     float inv_sqrt_m;         // COSSIN only
 };
 
-enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1 };
+enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1, EPI_STORE_SIGNBITS = 2 };
 
 // Position of tile element e inside its vector, relative to the tile's base:
 // the low C bits are contiguous, the rest walks rows of 2^sl elements.
@@ -739,7 +739,8 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // C       log2(contiguous run) - NT for a contiguous tile, 4 for a column tile
 // NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
-// EPI     EPI_STORE_NONE or EPI_STORE_COSSIN (applied with p.factor, limit p.m)
+// EPI     EPI_STORE_NONE, EPI_STORE_COSSIN (applied with p.factor, limit p.m) or EPI_STORE_SIGNBITS
+//         (p.out holds 64-bit code words, p.out_stride counts words, p.m is a multiple of 256)
 template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, bool PERSIST, int PRUNE = 0>
 __global__ void __launch_bounds__(G::THREADS)
 __attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_WAVES ? G::MIN_WAVES : (G::WB ? SPINNER_MIN_WAVES_MULTI : SPINNER_MIN_WAVES_PER_EU))))
@@ -872,6 +873,43 @@ spinner_tile_kernel(TileParams p)
                             if (i + 2 < m) dst[i + 2] = a2;
                             if (i + 3 < m) dst[i + 3] = a3;
                         }
+                    }
+                }
+            } else if constexpr (EPI == EPI_STORE_SIGNBITS) {
+                // Code word ((e >> 8) << 2) | (e & 3) holds, in bit (e >> 2) & 63, whether coordinate e
+                // is negative.  Lanes hold index bits 2..7, so the wave-wide comparison mask of one
+                // register is one whole word; lane j then stores the word of register j.
+                static_assert(G::LB == 6 && C >= NT && std::is_same<T, float>::value && RF <= 64,
+                              "sign codes: fp32 contiguous tiles with a whole wave per 256 coordinates");
+                // The compare is written out with an explicit scalar destination: through the VCC alias
+                // (what the compiler would pick) a lane write right behind it reads a stale mask, and
+                // inline asm is invisible to the compiler's hazard pass.  Four compares are issued before
+                // their lane writes, and the lane writes feed four independent accumulators so that they
+                // do not form one long dependent chain.
+                static_assert(RF % 4 == 0, "registers come in groups of four");
+                int lo4[4] = {0, 0, 0, 0}, hi4[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int j0 = 0; j0 < RF; j0 += 4) {
+                    unsigned long long mk[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float yk = (float)v[j0 + k] * lane_factor;
+                        asm volatile("v_cmp_gt_f32_e64 %0, 0, %1" : "=s"(mk[k]) : "v"(yk));
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(lo4[k]) : "s"((int)(unsigned)mk[k]), "n"(j0 + k));
+                        asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(hi4[k]) : "s"((int)(unsigned)(mk[k] >> 32)), "n"(j0 + k));
+                    }
+                }
+                const int lo = lo4[0] | lo4[1] | lo4[2] | lo4[3], hi = hi4[0] | hi4[1] | hi4[2] | hi4[3];
+                if (lane < RF) {
+                    const int wavebits = ebase & ~(63 << 2);
+                    const int e = wavebits | (lane & 3) | ((lane >> 2) << G::reg_pos(LAYF, 2));
+                    if (tile_first + e < m) {
+                        unsigned long long* codes = reinterpret_cast<unsigned long long*>(p.out) + vec * p.out_stride;
+                        const long long i = tile_first + e;
+                        codes[((i >> 8) << 2) | (i & 3)] = ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
                     }
                 }
             } else {

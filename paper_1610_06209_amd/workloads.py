@@ -61,6 +61,13 @@ CONFIGS = {
 }
 CONFIG_ORDER = list(CONFIGS)
 
+# Rows beyond the five benchmark configurations (measured beside them, same recipe style).
+NEXT = {
+    # Angular-kernel sign codes (Section 5) on the shape of the random-feature configuration.
+    "next_angular_n4096": Workload("next_angular_n4096", "codes", 4096, 131072, 4096, "signbits", 1.0, 1,
+                                   "mixture64", BASE_SEED + 6, 128),
+}
+
 
 def sweep_workload(log2n: int, total_elems_log2: int = 28) -> Workload:
     """Plain spinner, full output, batch = 2^total / n (the size sweep of the metric)."""
@@ -174,6 +181,8 @@ def algorithmic_bytes_per_vector(w: Workload) -> int:
     n = w.n
     if w.kind == "hash":
         return 4 * n + 4 * w.L
+    if w.kind == "codes":                       # one bit per kept coordinate leaves the chip
+        return 4 * n + w.m // 8 if n <= fused_max_n("none") else 4 * 8 * n + 4 * w.m + w.m // 8
     out = 8 * w.m if w.epilogue == "cossin" else 4 * w.m
     if n > fused_max_n(w.epilogue):
         return 4 * 8 * n if w.m == n else 3 * 8 * n + 4 * n + out

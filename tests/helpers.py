@@ -38,3 +38,27 @@ def check_hash_against_projection(idx_gpu: np.ndarray, y: np.ndarray, band: floa
             assert (g >= n) == (y[l][v, i] < 0), (v, l, g)
             banded += 1
     return exact, banded
+
+
+SIGN_BAND = 1e-5           # coordinates with |y_i| <= SIGN_BAND * max|y| may take either sign bit
+
+
+def unpack_sign_codes(codes: np.ndarray, m: int) -> np.ndarray:
+    """codes: integer array [batch][m/64] of 64-bit words -> uint8 [batch][m], bit of coordinate e taken from
+    bit (e >> 2) & 63 of word ((e >> 8) << 2) | (e & 3) (the layout documented in include/spinner.h)."""
+    words = codes.view(np.uint64)
+    e = np.arange(m)
+    w = ((e >> 8) << 2) | (e & 3)
+    b = ((e >> 2) & 63).astype(np.uint64)
+    return ((words[:, w] >> b) & np.uint64(1)).astype(np.uint8)
+
+
+def check_sign_bits(bits_gpu: np.ndarray, y: np.ndarray, m: int, band: float = SIGN_BAND) -> int:
+    """bits_gpu uint8 [batch][m] against the oracle's fp64 projection y [batch][n]: exact wherever |y_i| exceeds
+    band * max|y| of its vector (an fp32 path cannot resolve the sign of a coordinate that is zero to rounding).
+    Returns the number of coordinates that fell inside the band."""
+    want = (y[:, :m] < 0).astype(np.uint8)
+    clear = np.abs(y[:, :m]) > band * np.abs(y).max(axis=1, keepdims=True)
+    bad = (bits_gpu != want) & clear
+    assert not bad.any(), np.argwhere(bad)[:5]
+    return int((~clear).sum())

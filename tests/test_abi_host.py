@@ -104,6 +104,38 @@ def test_sign_word_entry_points_reject_bad_arguments(b):
     assert hs(64, 1 << 15, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
 
 
+def test_sign_code_entry_points_host_side(b):
+    assert b.spinner_code_bytes(256) == 32 and b.spinner_code_bytes(4096) == 512
+    assert b.spinner_code_bytes(0) == 0 and b.spinner_code_bytes(320) == 0 and b.spinner_code_bytes(128) == 0
+    assert b.spinner_codes_workspace_bytes(1 << 16, 100) == 0
+    assert b.spinner_codes_workspace_bytes(1 << 17, 100) == 100 * (1 << 17) * 4
+    # the documented layout: 64 consecutive multiples-of-four offsets share a word; every (word, bit) is hit once
+    assert b.spinner_code_position(0) == (0, 0) and b.spinner_code_position(1) == (1, 0)
+    assert b.spinner_code_position(4) == (0, 1) and b.spinner_code_position(255) == (3, 63)
+    assert b.spinner_code_position(256) == (4, 0) and b.spinner_code_position(1023) == (15, 63)
+    seen = {b.spinner_code_position(e) for e in range(2048)}
+    assert len(seen) == 2048 and max(w for w, _ in seen) == 2048 // 64 - 1
+    sc = b.lib.spinner_sign_codes
+    assert sc(64, 1000, 4, 64, 64, 64, 256, 64, None, None) == b.SPINNER_ERR_BAD_N
+    assert sc(64, 128, 4, 64, 64, 64, 128, 64, None, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert sc(64, 1024, 4, 64, 64, 64, 300, 64, None, None) == b.SPINNER_ERR_BAD_M
+    assert sc(64, 1024, 4, 64, 64, 64, 2048, 64, None, None) == b.SPINNER_ERR_BAD_M
+    assert sc(64, 1024, 4, None, 64, 64, 1024, 64, None, None) == b.SPINNER_ERR_NULL_PTR
+    assert sc(64, 1024, 4, 64, 64, 64, 1024, None, None, None) == b.SPINNER_ERR_NULL_PTR
+    assert sc(64, 1024, 4, 64, 64, 64, 1024, 72, None, None) == b.SPINNER_ERR_ALIGNMENT
+    assert sc(64, 1 << 17, 4, 64, 64, 64, 1024, 64, None, None) == b.SPINNER_ERR_WORKSPACE
+    assert sc(64, 1024, 0, None, None, None, 1024, None, None, None) == b.SPINNER_OK       # empty batch: nothing to do
+    ss = b.lib.spinner_sign_codes_signs
+    assert ss(64, 1024, 4, None, 1024, 64, None, None) == b.SPINNER_ERR_NULL_PTR
+    assert ss(64, 1024, 4, 64, 100, 64, None, None) == b.SPINNER_ERR_BAD_M
+    ag = b.lib.spinner_angular_gram
+    assert ag(64, 4, 64, 4, 100, 64, None) == b.SPINNER_ERR_BAD_M
+    assert ag(None, 4, 64, 4, 256, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert ag(64, 4, 64, 4, 256, 68, None) == b.SPINNER_ERR_ALIGNMENT
+    assert ag(64, -1, 64, 4, 256, 64, None) == b.SPINNER_ERR_BAD_BATCH
+    assert ag(None, 0, None, 4, 256, None, None) == b.SPINNER_OK
+
+
 def test_stream_copy_rejects_bad_arguments(b):
     c = b.lib.spinner_stream_copy
     assert c(None, 64, 16, None) == b.SPINNER_ERR_NULL_PTR

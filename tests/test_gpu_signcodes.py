@@ -1,0 +1,186 @@
+"""GPU parity of the angular-kernel step (Section 5): sign codes of the projection and the Hamming estimate
+of the kernel, called through the C ABI, against the fp64 oracle.
+
+Sign bits must agree exactly wherever the oracle's coordinate is not zero to rounding (tests/helpers.py);
+Hamming distances are integers and must agree exactly with those of the bits the GPU itself produced.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import scipy.linalg
+
+from helpers import check_sign_bits, unpack_sign_codes
+from paper_1610_06209_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1610_06209_amd import binding
+
+    class G:
+        pass
+
+    g = G()
+    g.torch = torch
+    g.b = binding
+    g.dev = torch.device("cuda:0")
+    return g
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print("\n[gpu-case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+
+
+def _to(g, a):
+    return g.torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
+
+
+def _case(n, batch, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((batch, n)).astype(np.float32)
+    d = (1.0 - 2.0 * rng.integers(0, 2, (3, n))).astype(np.float32)
+    return x, d
+
+
+def _codes(g, x, d, m, signs=False):
+    xt = _to(g, x)
+    if signs:
+        sw = g.b.spinner_pack_signs(_to(g, d[None]))
+        c = g.b.spinner_sign_codes_signs(xt, sw, m)
+    else:
+        c = g.b.spinner_sign_codes(xt, _to(g, d[0]), _to(g, d[1]), _to(g, d[2]), m)
+    g.torch.cuda.synchronize()
+    return c
+
+
+@pytest.mark.parametrize("log2n", list(range(8, 17)))
+def test_sign_codes_every_fused_size(gpu, oracle, log2n):
+    n = 1 << log2n
+    batch = {15: 5, 16: 3}.get(log2n, 37 if log2n < 12 else 9)        # ragged: several workgroups and a tail
+    x, d = _case(n, batch, 4000 + log2n)
+    y = oracle.spinner(x, d[0], d[1], d[2])
+    for signs in (False, True):
+        c = _codes(gpu, x, d, n, signs=signs)
+        assert tuple(c.shape) == (batch, n // 64)
+        bits = unpack_sign_codes(c.cpu().numpy(), n)
+        in_band = check_sign_bits(bits, y, n)
+        assert in_band <= batch * n * 1e-4                             # the band is not what makes the test pass
+
+
+@pytest.mark.parametrize("n,m", [(512, 256), (4096, 1024), (4096, 256), (8192, 512), (16384, 1024), (16384, 256),
+                                 (16384, 2048), (65536, 4096), (32768, 256)])
+def test_sign_codes_first_m_coordinates(gpu, oracle, n, m):
+    # m <= n / 16 takes the kernels whose last round is pruned (n = 2^12 .. 2^14)
+    batch = 6 if n >= 32768 else 21
+    x, d = _case(n, batch, 4100 + n // 256 + m)
+    y = oracle.spinner(x, d[0], d[1], d[2])
+    for signs in (False, True):
+        c = _codes(gpu, x, d, m, signs=signs)
+        assert tuple(c.shape) == (batch, m // 64)
+        check_sign_bits(unpack_sign_codes(c.cpu().numpy(), m), y, m)
+
+
+def test_sign_codes_zero_rule_and_planted_pattern(gpu):
+    # D = I: y = H x.  x = H c (c in {-1,+1}^n, n = 1024 so 1/sqrt(n) = 1/32 is exact) gives y = c with every
+    # intermediate value exact in fp32; x = +-H e_j gives y = +-e_j with n - 1 exact zeros, of either sign bit.
+    n = 1024
+    rng = np.random.default_rng(77)
+    c = (1.0 - 2.0 * rng.integers(0, 2, (4, n))).astype(np.float64)
+    Hn = scipy.linalg.hadamard(n).astype(np.float64) / 32.0
+    ones = np.ones((3, n), dtype=np.float32)
+    bits = unpack_sign_codes(_codes(gpu, (c @ Hn).astype(np.float32), ones, n).cpu().numpy(), n)
+    assert np.array_equal(bits, (c < 0).astype(np.uint8))
+    js = [0, 3, 517, n - 1]
+    e = np.stack([Hn[:, j] for j in js]).astype(np.float32)
+    for signs in (False, True):
+        assert unpack_sign_codes(_codes(gpu, e, ones, n, signs=signs).cpu().numpy(), n).sum() == 0
+        neg = unpack_sign_codes(_codes(gpu, -e, ones, n, signs=signs).cpu().numpy(), n)
+        assert neg.sum() == len(js) and all(neg[k, j] == 1 for k, j in enumerate(js))
+    zero = unpack_sign_codes(_codes(gpu, np.zeros((3, n), np.float32), ones, n).cpu().numpy(), n)
+    assert zero.sum() == 0
+    # antipodal inputs give complementary codes where no coordinate is zero
+    x, d = _case(n, 11, 78)
+    a = unpack_sign_codes(_codes(gpu, x, d, n).cpu().numpy(), n)
+    b = unpack_sign_codes(_codes(gpu, -x, d, n).cpu().numpy(), n)
+    assert np.array_equal(a, 1 - b)
+
+
+def test_sign_codes_above_fused_range(gpu, oracle):
+    n, m, batch = 1 << 17, 1 << 12, 3
+    x, d = _case(n, batch, 4200)
+    y = oracle.spinner(x, d[0], d[1], d[2])
+    assert gpu.b.spinner_codes_workspace_bytes(n, batch) == batch * n * 4
+    for signs in (False, True):
+        c = _codes(gpu, x, d, m, signs=signs)
+        check_sign_bits(unpack_sign_codes(c.cpu().numpy(), m), y, m)
+    full = _codes(gpu, x, d, n)
+    check_sign_bits(unpack_sign_codes(full.cpu().numpy(), n), y, n)
+
+
+def test_sign_codes_argument_errors(gpu):
+    b, t = gpu.b, gpu.torch
+    x = t.zeros((2, 512), dtype=t.float32, device=gpu.dev)
+    d = t.ones(512, dtype=t.float32, device=gpu.dev)
+    with pytest.raises(b.SpinnerError) as e:
+        b.spinner_sign_codes(x, d, d, d, 320)                          # not a multiple of 256
+    assert e.value.status == b.SPINNER_ERR_BAD_M
+    x64 = t.zeros((2, 64), dtype=t.float32, device=gpu.dev)
+    d64 = t.ones(64, dtype=t.float32, device=gpu.dev)
+    codes = t.zeros((2, 4), dtype=t.int64, device=gpu.dev)
+    rc = b.lib.spinner_sign_codes(x64.data_ptr(), 64, 2, d64.data_ptr(), d64.data_ptr(), d64.data_ptr(), 256,
+                                  codes.data_ptr(), None, None)
+    assert rc == b.SPINNER_ERR_UNSUPPORTED
+    empty = b.spinner_sign_codes(x[:0], d, d, d, 512)
+    assert tuple(empty.shape) == (0, 8)
+
+
+@pytest.mark.parametrize("na,nb,m", [(5, 7, 256), (70, 130, 1024), (64, 64, 4096), (129, 1, 2304), (200, 333, 16384)])
+def test_angular_gram_is_exact_on_its_codes(gpu, oracle, na, nb, m):
+    rng = np.random.default_rng(na * 1000 + nb)
+    ca = rng.integers(-2**63, 2**63 - 1, (na, m // 64), dtype=np.int64)
+    cb = rng.integers(-2**63, 2**63 - 1, (nb, m // 64), dtype=np.int64)
+    cb[: min(na, nb)] = ca[: min(na, nb)]                              # some identical rows: estimate exactly 1
+    got = gpu.b.spinner_angular_gram(_to(gpu, ca), _to(gpu, cb), m)
+    gpu.torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    want = oracle.angular_estimate(unpack_sign_codes(ca, m), unpack_sign_codes(cb, m))
+    assert got.shape == (na, nb)
+    # Hamming distances are integers: recover them and compare exactly
+    assert np.array_equal(np.rint((1.0 - got.astype(np.float64)) * m), np.rint((1.0 - want) * m))
+    assert np.abs(got - want).max() <= 2e-7
+    assert np.all(np.diag(got[: min(na, nb), : min(na, nb)]) == 1.0)
+
+
+def test_angular_kernel_end_to_end(gpu, oracle):
+    # pairs of known angle: codes on the GPU, Gram on the GPU, against 1 - theta / pi (Section 5) and against
+    # the oracle's estimate from its own sign bits
+    n, triples = 4096, 8
+    rng = np.random.default_rng(99)
+    u = rng.standard_normal(n); u /= np.linalg.norm(u)
+    v = rng.standard_normal(n); v -= (v @ u) * u; v /= np.linalg.norm(v)
+    thetas = np.array([math.pi / 8, math.pi / 4, math.pi / 2, 0.75 * math.pi])
+    xa = (2.0 * u)[None, :].astype(np.float32)
+    xb = np.stack([0.5 * (math.cos(t) * u + math.sin(t) * v) for t in thetas]).astype(np.float32)
+    est = np.zeros(len(thetas))
+    for k in range(triples):
+        d = W.rademacher_diagonals(n, 3, 7000 + k)
+        ca, cb = _codes(gpu, xa, d, n), _codes(gpu, xb, d, n)
+        g = gpu.b.spinner_angular_gram(ca, cb, n)
+        gpu.torch.cuda.synchronize()
+        g = g.cpu().numpy()[0]
+        want = oracle.angular_estimate(oracle.apply(xa, d[0], d[1], d[2], n, "signbits", 1.0),
+                                       oracle.apply(xb, d[0], d[1], d[2], n, "signbits", 1.0))[0]
+        assert np.abs(g - want).max() <= 4.0 / n            # at most a few coordinates that are zero to rounding
+        est += g
+    est /= triples
+    assert np.abs(est - (1.0 - thetas / math.pi)).max() < 0.015
