@@ -23,8 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# fp32 VALU peak without packed math: 256 CUs x 64 lanes x 2.4 GHz operations per second
-VALU_PEAK_GOPS = 256 * 64 * 2.4
+# plain fp32 vector-ALU peak: 256 CUs x 4 SIMDs x 32 lanes per cycle x 2.4 GHz operations per second (one wave64
+# instruction per two cycles and SIMD: the published 157.3 TFLOP/s counted as one operation per lane instead
+# of the two of a fused multiply-add); packed fp32 forms are not used
+VALU_PEAK_GOPS = 256 * 4 * 32 * 2.4
 
 # HBM bytes per launch read from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the same counter reads for spinner_stream_copy of known size); see

@@ -45,6 +45,12 @@
 #ifndef SPINNER_SYNC_AFTER_READ      // 1: the barrier that protects the LDS buffer from the next writers sits right
 #define SPINNER_SYNC_AFTER_READ 1    //    after the reads (waves are still in step there) instead of before the next writes
 #endif
+#ifndef SPINNER_EXPERIMENT_KNOCKOUT   // timing experiments only (results are wrong): bit 0 drops the lane stages that
+#define SPINNER_EXPERIMENT_KNOCKOUT 0 // cross the LDS crossbar, 1 the DPP lane stages, 2 the register stages, 3 the LDS
+#endif                                // traffic of the transposes (barriers stay), 4 the diagonals
+#ifndef SPINNER_LANE_SWAPS           // 1: in tiles that span several waves, lane bits 4 and 5 are transformed by swapping
+#define SPINNER_LANE_SWAPS 1         //    lane halves with register pairs (vector ALU) instead of LDS-crossbar exchanges
+#endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -166,6 +172,16 @@ struct TileGeom {
             if ((j >> q) & 1) e |= 1 << reg_pos(lay, q);
         return e;
     }
+    // "Swapped" state of a tile (see lane_swap_stages): physical register bits 2, 3 hold the index
+    // bits of lane bits 4, 5 (positions 6, 7) and the lanes hold the index bits of register bits 2, 3.
+    static constexpr bool LANE_SWAPS = SPINNER_LANE_SWAPS != 0 && WB > 0 && LB == 6 && r >= 4;
+    static constexpr int reg_index_sw(int lay, int j)
+    {
+        int e = 0;
+        for (int q = 0; q < r; ++q)
+            if ((j >> q) & 1) e |= 1 << (q == 2 ? 6 : (q == 3 ? 7 : reg_pos(lay, q)));
+        return e;
+    }
     static constexpr bool is_wave_pos(int lay, int pos)
     {
         for (int b = 0; b < WB; ++b)
@@ -217,6 +233,14 @@ struct ThreadCtx {
     __device__ __forceinline__ int base_index(int lay) const
     {
         int e = lit << 2;
+        for (int b = 0; b < G::WB; ++b)
+            e |= ((wv >> b) & 1) << G::wave_pos(lay, b);
+        return e;
+    }
+    // the same in the swapped state: lane bits 4, 5 carry the index bits of register bits 2, 3
+    __device__ __forceinline__ int base_index_sw(int lay) const
+    {
+        int e = ((lit & 15) << 2) | (((lit >> 4) & 1) << G::reg_pos(lay, 2)) | (((lit >> 5) & 1) << G::reg_pos(lay, 3));
         for (int b = 0; b < G::WB; ++b)
             e |= ((wv >> b) & 1) << G::wave_pos(lay, b);
         return e;
@@ -346,6 +370,41 @@ __device__ __forceinline__ void lane_stage_fmac_dpp(float (&v)[R], float coef)
     }
 }
 
+// Lane bits 4 and 5 without the LDS crossbar.  v_permlane16_swap exchanges the odd 16-lane rows
+// of its first register with the even rows of its second, v_permlane32_swap the upper half of the
+// first with the lower half of the second.  Applied to a register pair (a, b) that differs in one
+// register bit, either leaves in a and b the two inputs of every butterfly across that lane bit,
+// so a plain register stage finishes it.  Afterwards the register bit holds what the lane bit
+// held and vice versa ("swapped" state); the next LDS transpose reads the data from there.
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+template <int LANE_BIT>
+__device__ __forceinline__ void lane_swap(float& a, float& b)
+{
+    uint2v t;
+    if constexpr (LANE_BIT == 4) t = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    else t = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(t.x);
+    b = __uint_as_float(t.y);
+}
+template <int LANE_BIT>
+__device__ __forceinline__ void lane_swap(double& a, double& b)
+{
+    float alo = __int_as_float(__double2loint(a)), ahi = __int_as_float(__double2hiint(a));
+    float blo = __int_as_float(__double2loint(b)), bhi = __int_as_float(__double2hiint(b));
+    lane_swap<LANE_BIT>(alo, blo);
+    lane_swap<LANE_BIT>(ahi, bhi);
+    a = __hiloint2double(__float_as_int(ahi), __float_as_int(alo));
+    b = __hiloint2double(__float_as_int(bhi), __float_as_int(blo));
+}
+template <int LANE_BIT, int Q, typename T, int R>
+__device__ __forceinline__ void lane_swap_stage(T (&v)[R])
+{
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+        if (!(j & (1 << Q))) lane_swap<LANE_BIT>(v[j], v[j | (1 << Q)]);
+    reg_stage<Q>(v);
+}
+
 // All stages of one transform that the current layout can do without moving
 // data between waves: register bits and lane bits at index positions >= CB.
 // SKIP_WAVE_OWNED: skip register bits that the *other* layout's waves hold
@@ -376,22 +435,30 @@ __device__ __forceinline__ void mfma_stage(float (&v)[G::R], const ThreadCtx<G>&
 
 // NEGATE selects the coefficient set of the tracked-sign butterflies (true in
 // every second transform of a kernel, see lane_stage_fmac_dpp).
-template <typename G, int CB, int LAY, bool NEGATE, typename T>
+template <typename G, int CB, int LAY, bool NEGATE, bool SWAP = false, typename T>
 __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
     constexpr bool MF = G::MFMA && std::is_same<T, float>::value;
+    static_assert(!SWAP || (!MF && CB == 0), "lane swaps: whole-vector tiles without the matrix pipe");
     static_for<0, G::r>([&](auto q) {
-        if constexpr (G::reg_pos(LAY, q.value) >= CB && !(MF && q.value >= G::r - 2)) reg_stage<q.value>(v);
+        if constexpr (G::reg_pos(LAY, q.value) >= CB && !(MF && q.value >= G::r - 2) && !(SPINNER_EXPERIMENT_KNOCKOUT & 4))
+            reg_stage<q.value>(v);
     });
     if constexpr (MF) mfma_stage<G>(v, c);
     static_for<0, G::LB>([&](auto b) {
-        if constexpr (G::lane_pos(b.value) >= CB && !(MF && b.value >= 4)) {
-            if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value))
-                lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
-            else
+        if constexpr (G::lane_pos(b.value) >= CB && !(MF && b.value >= 4) && !(SWAP && b.value >= 4)) {
+            if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) {
+                if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 2))
+                    lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
+            } else if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 1)) {
                 lane_stage<b.value>(v, c.sg[b.value]);
+            }
         }
     });
+    if constexpr (SWAP) {
+        lane_swap_stage<4, 2>(v);
+        lane_swap_stage<5, 3>(v);
+    }
 }
 
 // Sign s of the value a lane holds after an odd number of transforms (+1 after
@@ -423,22 +490,25 @@ __device__ __forceinline__ void wave_owned_stages(T (&v)[G::R])
 // lane with consecutive lanes on consecutive addresses (no bank conflicts).
 // RW / RR: how many leading registers are written / read (all of them unless the last
 // round is pruned); `reads` is false for a wave that needs nothing from this exchange.
-template <typename G, int FROM, bool SYNC_BEFORE, int RW = 0, int RR = 0>
+// SW: the data start in the swapped state (lane_swap_stages); they always arrive in the normal one.
+template <typename G, int FROM, bool SYNC_BEFORE, int RW = 0, int RR = 0, bool SW = false>
 __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& c, float4* lds, bool reads = true)
 {
     constexpr int TO = 1 - FROM;
+    static_assert(!SW || (RW == 0 && RR == 0), "pruned rounds do not use lane swaps");
     constexpr int NW = RW ? RW : G::R, NR = RR ? RR : G::R;
     if constexpr (G::LDS_HALVES == 1) {
         if constexpr (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ) __syncthreads();     // earlier readers of lds are done
-        const int ef = c.base_index(FROM);
+        const int ef = SW ? c.base_index_sw(FROM) : c.base_index(FROM);
 #pragma unroll
         for (int jh = 0; jh < NW / 4; ++jh) {
-            const int e = ef | G::reg_index(FROM, jh * 4);
-            lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
+            const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
+            if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 8))
+                lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
         }
         __syncthreads();
         const int et = c.base_index(TO);
-        if (reads) {
+        if (reads && !(SPINNER_EXPERIMENT_KNOCKOUT & 8)) {
 #pragma unroll
             for (int jh = 0; jh < NR / 4; ++jh) {
                 const int e = et | G::reg_index(TO, jh * 4);
@@ -455,7 +525,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
         // consecutive addresses.  Each thread receives exactly the register slots it has just
         // sent, so nothing is overwritten before it is sent.  A smaller footprint lets a CU
         // hold more workgroups, and lets tiles of 2^15 and 2^16 elements fit at all.
-        const int ef = c.base_index(FROM);
+        const int ef = SW ? c.base_index_sw(FROM) : c.base_index(FROM);
         const int et = c.base_index(TO);
         if constexpr (G::LDS_HALVES == 2) {
             float2* lds2 = reinterpret_cast<float2*>(lds);
@@ -464,7 +534,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
                 if (h == 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
 #pragma unroll
                 for (int jh = 0; jh < G::R / 4; ++jh) {
-                    const int e = ef | G::reg_index(FROM, jh * 4);
+                    const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
                     lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
                 }
                 __syncthreads();
@@ -482,7 +552,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
             for (int h = 0; h < 4; ++h) {
                 if (h >= 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
 #pragma unroll
-                for (int jh = 0; jh < G::R / 4; ++jh) lds1[(ef | G::reg_index(FROM, jh * 4)) >> 2] = v[jh * 4 + h];
+                for (int jh = 0; jh < G::R / 4; ++jh) lds1[(ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4))) >> 2] = v[jh * 4 + h];
                 __syncthreads();
 #pragma unroll
                 for (int jh = 0; jh < G::R / 4; ++jh) v[jh * 4 + h] = lds1[(et | G::reg_index(TO, jh * 4)) >> 2];
@@ -494,18 +564,18 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
 
 // fp64 values cross in two trips (low words, then high words) so that the LDS
 // footprint stays 4 bytes per element.
-template <typename G, int FROM, bool SYNC_BEFORE>
+template <typename G, int FROM, bool SYNC_BEFORE, bool SW = false>
 __device__ __forceinline__ void transpose(double (&v)[G::R], const ThreadCtx<G>& c, float4* lds)
 {
     constexpr int TO = 1 - FROM;
     int4* ilds = reinterpret_cast<int4*>(lds);
-    const int ef = c.base_index(FROM);
+    const int ef = SW ? c.base_index_sw(FROM) : c.base_index(FROM);
     const int et = c.base_index(TO);
     int lo[G::R];
     if constexpr (SYNC_BEFORE) __syncthreads();
 #pragma unroll
     for (int jh = 0; jh < G::R / 4; ++jh) {
-        const int e = ef | G::reg_index(FROM, jh * 4);
+        const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
         ilds[e >> 2] = make_int4(__double2loint(v[jh * 4]), __double2loint(v[jh * 4 + 1]),
                                  __double2loint(v[jh * 4 + 2]), __double2loint(v[jh * 4 + 3]));
     }
@@ -518,7 +588,7 @@ __device__ __forceinline__ void transpose(double (&v)[G::R], const ThreadCtx<G>&
     __syncthreads();
 #pragma unroll
     for (int jh = 0; jh < G::R / 4; ++jh) {
-        const int e = ef | G::reg_index(FROM, jh * 4);
+        const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
         ilds[e >> 2] = make_int4(__double2hiint(v[jh * 4]), __double2hiint(v[jh * 4 + 1]),
                                  __double2hiint(v[jh * 4 + 2]), __double2hiint(v[jh * 4 + 3]));
     }
@@ -600,13 +670,18 @@ template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOS
 __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c,
                                              const float* dtile, const unsigned long long* words, int sl, float4* lds)
 {
-    if constexpr (HAS_DIAG) {
+    if constexpr (HAS_DIAG && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) {
         if constexpr (SIGNS) sign_flip<G, LAY>(v, c, words);
         else diag_multiply<G, C, LAY>(v, c, dtile, sl);
     }
-    local_stages<G, CB, LAY, NEGATE>(v, c);
+#ifndef SPINNER_LANE_SWAPS_F64
+#define SPINNER_LANE_SWAPS_F64 1
+#endif
+    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB == 0 && !G::MFMA;
+    local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
     if constexpr (G::WB > 0) {
-        transpose<G, LAY, !FIRST_TRANSPOSE>(v, c, lds);
+        if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
+        else transpose<G, LAY, !FIRST_TRANSPOSE, SWAP>(v, c, lds);
         wave_owned_stages<G, CB, 1 - LAY>(v);
     }
 }
