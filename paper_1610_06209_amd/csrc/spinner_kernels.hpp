@@ -51,6 +51,12 @@
 #ifndef SPINNER_LANE_SWAPS           // 1: in tiles that span several waves, lane bits 4 and 5 are transformed by swapping
 #define SPINNER_LANE_SWAPS 1         //    lane halves with register pairs (vector ALU) instead of LDS-crossbar exchanges
 #endif
+#ifndef SPINNER_MASK4_DPP            // 1: the lane exchange across lane bit 2 uses two bank-masked DPP row shifts instead of ds_swizzle
+#define SPINNER_MASK4_DPP 0
+#endif
+#ifndef SPINNER_DPP_MASKS            // lane masks (of 1, 2, 8) whose butterflies use the one-instruction DPP form; the
+#define SPINNER_DPP_MASKS 0xB        // others go through the LDS crossbar (tuning experiments)
+#endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -102,8 +108,15 @@ __device__ __forceinline__ float lane_xor(float v)
         t = __builtin_amdgcn_update_dpp(0, s, 0x4E, 0xF, 0xF, true);
     else if constexpr (MASK == 8)   // row_ror:8 (rotation by half a 16-lane row)
         t = __builtin_amdgcn_update_dpp(0, s, 0x128, 0xF, 0xF, true);
-    else if constexpr (MASK == 4)   // swizzle, bit mode: and=0x1f or=0 xor=4
+    else if constexpr (MASK == 4) { // swizzle, bit mode: and=0x1f or=0 xor=4
+#if SPINNER_MASK4_DPP
+        // two bank-masked row shifts: banks 1, 3 take the lane four below, banks 0, 2 the lane four above
+        t = __builtin_amdgcn_update_dpp(0, s, 0x114, 0xF, 0xA, false);
+        t = __builtin_amdgcn_update_dpp(t, s, 0x104, 0xF, 0x5, false);
+#else
         t = __builtin_amdgcn_ds_swizzle(s, (4 << 10) | 0x1F);
+#endif
+    }
     else if constexpr (MASK == 16)  // swizzle, bit mode: xor=16
         t = __builtin_amdgcn_ds_swizzle(s, (16 << 10) | 0x1F);
     else {                          // MASK == 32: crosses the 32-lane halves
@@ -354,7 +367,7 @@ __device__ __forceinline__ void fmac_dpp_block8(float* a, float coef)
 template <typename T, int R>
 constexpr bool lane_mask_uses_fmac_dpp(int mask)
 {
-    return std::is_same<T, float>::value && R >= 8 && (mask == 1 || mask == 2 || mask == 8);
+    return std::is_same<T, float>::value && R >= 8 && (mask == 1 || mask == 2 || mask == 8) && (SPINNER_DPP_MASKS & mask);
 }
 
 template <int B, int RL = 0, int R>
