@@ -6,9 +6,12 @@
 namespace spinner {
 // The epilogue needs a whole wave per 256 coordinates (six lane bits per tile), so the
 // values per thread are capped at n / 64.
+#ifndef SPINNER_CODE_RMAX       // tuning experiments: cap on the values per thread (log2) of the sign-code kernels
+#define SPINNER_CODE_RMAX 6
+#endif
 template <int NT>
-using GeomCode = TileGeom<NT, (Tuning<float, NT>::rmax < NT - 6 ? Tuning<float, NT>::rmax : NT - 6), Tuning<float, NT>::waves,
-                          false, Tuning<float, NT>::min_waves>;
+using GeomCode = TileGeom<NT, clamp_rmax(NT, (Tuning<float, NT>::rmax < NT - 6 ? (Tuning<float, NT>::rmax < SPINNER_CODE_RMAX ? Tuning<float, NT>::rmax : SPINNER_CODE_RMAX) : NT - 6)),
+                          Tuning<float, NT>::waves, false, Tuning<float, NT>::min_waves>;
 
 template <int NT, bool SIGNS, int PRUNE>
 static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStream_t stream)

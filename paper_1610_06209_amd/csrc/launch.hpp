@@ -22,7 +22,10 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 #endif
 template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0; };
 #ifndef SPINNER_RMAX_F32
-template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64 < 5 ? SPINNER_RMAX_F64 : 4, waves = 4, min_waves = 0; };
+#ifndef SPINNER_RMAX_F64_N12
+#define SPINNER_RMAX_F64_N12 4
+#endif
+template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64_N12, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
