@@ -34,7 +34,7 @@ template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4, 
 template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1, min_waves = 0; };
-template <> struct Tuning<float, 12> { static constexpr int rmax = 6, waves = 1, min_waves = 0; };
+template <> struct Tuning<float, 12> { static constexpr int rmax = 4, waves = 4, min_waves = 0; };   // 4 waves per tile, 16 KiB LDS
 template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4, min_waves = 0; };
 template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4, min_waves = 4; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
