@@ -20,6 +20,11 @@ What each function follows:
 * ``epilogue_hash``      - Section 4, Theorem 4 and its proof: the hash of a
   vector is the signed canonical direction closest to its projection, i.e.
   ``argmax_i |y_i|`` together with the sign of that coordinate.
+* ``layer_forward`` / ``layer_backward`` - the adaptive setting (Section 1, Section 3.2 "adaptive"
+  diagonals, Section 5 neural networks): the HD3HD2HD1 block as a layer with learned diagonals.
+  The backward pass is the transpose of the layer's Jacobian written out with dense matrices:
+  ``dx = scale * D1 H D2 H D3 H dy`` (H is symmetric) and, for each diagonal, the sum over the batch of
+  (signal arriving at the diagonal from the output side) times (activation entering it from the input side).
 * ``epilogue_signbits`` / ``angular_estimate`` - Section 5 (angular kernel):
   the pointwise sign of the projection, and the kernel estimate
   ``1 - d_H / d'`` from the Hamming distance of two such sign vectors.
@@ -179,6 +184,34 @@ def angular_estimate(bits_a: np.ndarray, bits_b: np.ndarray) -> np.ndarray:
     m = bits_a.shape[-1]
     dh = (bits_a[:, None, :] != bits_b[None, :, :]).sum(axis=-1)
     return 1.0 - dh.astype(np.float64) / float(m)
+
+
+def layer_forward(x, d1, d2, d3, scale: float = 1.0, nthreads: int = 0):
+    """y = scale * H D3 H D2 H D1 x together with the activations that enter D2 and D3:
+    b1 = H D1 x and b2 = H D2 b1 (all fp64, [batch][n])."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    d1, d2, d3 = (np.asarray(d, dtype=np.float64) for d in (d1, d2, d3))
+    b1 = hadamard_apply(x * d1)
+    b2 = hadamard_apply(b1 * d2)
+    y = float(scale) * hadamard_apply(b2 * d3)
+    return y, b1, b2
+
+
+def layer_backward(x, d1, d2, d3, dy, scale: float = 1.0):
+    """Gradients of L with respect to x and to the three diagonals, given dy = dL/dy for
+    y = scale * H D3 H D2 H D1 x.  Returns (dx [batch][n], dd [3][n]); dd sums over the batch."""
+    d1, d2, d3 = (np.asarray(d, dtype=np.float64) for d in (d1, d2, d3))
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    dy = np.ascontiguousarray(dy, dtype=np.float64)
+    _, b1, b2 = layer_forward(x, d1, d2, d3, scale)
+    g3 = float(scale) * hadamard_apply(dy)        # dL/d(D3 b2): H^T = H
+    dd3 = (g3 * b2).sum(axis=0)
+    g2 = hadamard_apply(g3 * d3)                  # dL/d(D2 b1)
+    dd2 = (g2 * b1).sum(axis=0)
+    g1 = hadamard_apply(g2 * d2)                  # dL/d(D1 x)
+    dd1 = (g1 * x).sum(axis=0)
+    dx = g1 * d1
+    return dx, np.stack([dd1, dd2, dd3])
 
 
 def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,

@@ -452,7 +452,7 @@ template <typename G, int CB, int LAY, bool NEGATE, bool SWAP = false, typename 
 __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
     constexpr bool MF = G::MFMA && std::is_same<T, float>::value;
-    static_assert(!SWAP || (!MF && CB == 0), "lane swaps: whole-vector tiles without the matrix pipe");
+    static_assert(!SWAP || (!MF && CB <= G::lane_pos(4)), "lane swaps: lane bits 4 and 5 must be transformed, without the matrix pipe");
     static_for<0, G::r>([&](auto q) {
         if constexpr (G::reg_pos(LAY, q.value) >= CB && !(MF && q.value >= G::r - 2) && !(SPINNER_EXPERIMENT_KNOCKOUT & 4))
             reg_stage<q.value>(v);
@@ -690,7 +690,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 #ifndef SPINNER_LANE_SWAPS_F64
 #define SPINNER_LANE_SWAPS_F64 1
 #endif
-    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB == 0 && !G::MFMA;
+    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(4) && !G::MFMA;
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
     if constexpr (G::WB > 0) {
         if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
