@@ -150,6 +150,36 @@ def measure_gram(torch, b, dev, rows, m, steps, warmup):
     return res
 
 
+def measure_layer(torch, b, dev, n, batch, steps, warmup):
+    """Adaptive layer: forward (keeps two activations) + backward (dx and the three diagonal gradients).
+    Algorithmic bytes per element: forward 4 read + 12 written, backward 16 read + 4 written."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(1610 + n)
+    x = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
+    dy = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
+    d = 1.0 + 0.5 * torch.randn((3, n), generator=g, device=dev, dtype=torch.float32)
+    y = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    saved = torch.empty((2, batch, n), dtype=torch.float32, device=dev)
+    dd = torch.empty((3, n), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(16, b.spinner_layer_workspace_bytes(n, batch)), dtype=torch.uint8, device=dev)
+    fwd = lambda: b.spinner_layer_forward(x, d[0], d[1], d[2], 1.0, y=y, saved=saved)
+    bwd = lambda: b.spinner_layer_backward(dy, x, saved, d[0], d[1], d[2], 1.0, dx=dx, dd=dd, workspace=ws)
+    for _ in range(10):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    _, f_ms = time_calls(torch, fwd, steps, warmup)
+    _, b_ms = time_calls(torch, bwd, steps, warmup)
+    wall_ms, _ = time_calls(torch, lambda: (fwd(), bwd()), steps, warmup)
+    el = batch * n
+    res = {"workload": "adaptive_layer_n%d_b%d" % (n, batch), "forward_ms": round(f_ms, 4), "backward_ms": round(b_ms, 4),
+           "step_us_wall": round(wall_ms * 1e3, 2),
+           "forward_GBs": round(16.0 * el / (f_ms * 1e-3) / 1e9, 1), "backward_GBs": round(20.0 * el / (b_ms * 1e-3) / 1e9, 1)}
+    del x, dy, d, y, dx, saved, dd, ws
+    torch.cuda.empty_cache()
+    return res
+
+
 def copy_ceiling(torch, b, dev, steps, warmup):
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
@@ -276,6 +306,19 @@ def main():
         log("[bench] %s: %.4f ms  %.3e pairs/s  xor+popcount floor at %.1f%% of VALU peak" % (
             g["workload"], g["ms"], g["pairs_per_s"], 100 * g["valu_frac_xor_popcount_floor"]))
         nxt.append(g)
+        lay = measure_layer(torch, b, dev, 4096, 65536, max(3, args.steps // 2), max(2, args.warmup // 2))
+        log("[bench] %s: forward %.4f ms (%.0f GB/s), backward %.4f ms (%.0f GB/s)" % (
+            lay["workload"], lay["forward_ms"], lay["forward_GBs"], lay["backward_ms"], lay["backward_GBs"]))
+        nxt.append(lay)
+        # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
+        tbl = []
+        for k in range(4, 13):
+            r = measure_layer(torch, b, dev, 1 << k, 1024, 20, 5)
+            tbl.append({"h": 1 << k, "step_us_wall": r["step_us_wall"],
+                        "kernels_us": round((r["forward_ms"] + r["backward_ms"]) * 1e3, 2)})
+        log("[bench] adaptive layer, batch 1024, h=2^4..2^12, forward+backward us per step, wall (kernels): " +
+            " ".join("%.1f (%.1f)" % (t["step_us_wall"], t["kernels_us"]) for t in tbl))
+        nxt.append({"workload": "adaptive_layer_table2_sizes_b1024", "rows": tbl})
         extras["next_rows"] = nxt
 
     traffic = MEASURED_TRAFFIC_BYTES.get(head.name)

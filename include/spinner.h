@@ -180,6 +180,41 @@ int spinner_angular_gram(const void *codes_a, long na, const void *codes_b, long
                          int m, float *out, void *stream);
 
 /*
+ * Adaptive setting (Section 1; Section 3.2: the diagonals may be learned; Section 5,
+ * neural networks: a fully connected layer re-parametrised as H D3 H D2 H D1 with
+ * learned diagonals).  spinner_layer_forward computes y = scale * H D3 H D2 H D1 x
+ * like spinner_apply (m = n, epilogue NONE) and keeps the two activations the backward
+ * pass needs (those entering D2 and D3) in `saved`; spinner_layer_backward computes,
+ * from dy = dL/dy,
+ *     dx  = scale * D1 H D2 H D3 H dy                       (H is symmetric)
+ *     dd  = [dL/dd1, dL/dd2, dL/dd3], each summed over the batch:
+ *           dL/ddk[i] = sum_b (signal arriving at Dk from the output side)[b][i]
+ *                             * (activation entering Dk)[b][i].
+ *
+ *   x, dy      in   device fp32 [batch][n]
+ *   d1..d3     in   device fp32 [n], arbitrary values
+ *   y, dx      out  device fp32 [batch][n]; dx may alias dy
+ *   saved      out/in  device, spinner_layer_saved_bytes(n, batch) = 2 * batch * n * 4
+ *                   bytes, opaque (unnormalised activations); written by the forward
+ *                   call, passed unchanged to the backward call of the same x, d1..d3
+ *   dd         out  device fp32 [3][n], overwritten
+ *   workspace  in   device scratch of spinner_layer_workspace_bytes(n, batch) bytes
+ *                   (per-workgroup partial sums; they are added up in fp64)
+ *
+ * n = 2^4 .. 2^14 (SPINNER_ERR_UNSUPPORTED above), batch < 2^31.  Same ownership,
+ * alignment and error rules as spinner_apply.
+ */
+size_t spinner_layer_saved_bytes(int n, long batch);
+size_t spinner_layer_workspace_bytes(int n, long batch);
+int spinner_layer_forward(const float *x, int n, long batch,
+                          const float *d1, const float *d2, const float *d3,
+                          float scale, float *y, void *saved, void *stream);
+int spinner_layer_backward(const float *dy, const float *x, const void *saved,
+                           int n, long batch,
+                           const float *d1, const float *d2, const float *d3,
+                           float scale, float *dx, float *dd, void *workspace, void *stream);
+
+/*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the
  * fused limit, and above it when m == n with epilogue NONE; otherwise batch * n * 4.
  * Returns 0 for invalid arguments (spinner_apply reports those).

@@ -33,7 +33,9 @@ EPILOGUES = {"none": SPINNER_EPI_NONE, "cossin": SPINNER_EPI_COSSIN}
 EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_strerror",
            "spinner_version", "spinner_stream_copy", "spinner_signs_bytes", "spinner_pack_signs",
            "spinner_apply_signs", "spinner_hash_signs", "spinner_code_bytes", "spinner_codes_workspace_bytes",
-           "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram"]
+           "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram",
+           "spinner_layer_saved_bytes", "spinner_layer_workspace_bytes", "spinner_layer_forward",
+           "spinner_layer_backward"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -81,6 +83,15 @@ lib.spinner_sign_codes_signs.restype = ctypes.c_int
 lib.spinner_sign_codes_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, ctypes.c_int, _vp, _vp, _vp]
 lib.spinner_angular_gram.restype = ctypes.c_int
 lib.spinner_angular_gram.argtypes = [_vp, ctypes.c_long, _vp, ctypes.c_long, ctypes.c_int, _vp, _vp]
+lib.spinner_layer_saved_bytes.restype = ctypes.c_size_t
+lib.spinner_layer_saved_bytes.argtypes = [ctypes.c_int, ctypes.c_long]
+lib.spinner_layer_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_layer_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_long]
+lib.spinner_layer_forward.restype = ctypes.c_int
+lib.spinner_layer_forward.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp]
+lib.spinner_layer_backward.restype = ctypes.c_int
+lib.spinner_layer_backward.argtypes = [_vp, _vp, _vp, ctypes.c_int, ctypes.c_long, _vp, _vp, _vp, ctypes.c_float, _vp, _vp,
+                                       _vp, _vp]
 
 
 class SpinnerError(RuntimeError):
@@ -371,3 +382,62 @@ def spinner_angular_gram(codes_a, codes_b, m, out=None, stream=None):
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out
+
+
+def spinner_layer_saved_bytes(n: int, batch: int) -> int:
+    return int(lib.spinner_layer_saved_bytes(int(n), int(batch)))
+
+
+def spinner_layer_workspace_bytes(n: int, batch: int) -> int:
+    return int(lib.spinner_layer_workspace_bytes(int(n), int(batch)))
+
+
+def spinner_layer_forward(x, d1, d2, d3, scale=1.0, y=None, saved=None, stream=None):
+    """y = scale * H D3 H D2 H D1 x and the opaque activations the backward pass needs: returns (y, saved)."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    for name, d in (("d1", d1), ("d2", d2), ("d3", d3)):
+        _check_tensor(d, name, torch.float32)
+    batch, n = x.shape
+    if y is None:
+        y = torch.empty_like(x)
+    else:
+        _check_tensor(y, "y", torch.float32)
+    if saved is None:
+        saved = torch.empty((2, batch, n), dtype=torch.float32, device=x.device)
+    else:
+        _check_tensor(saved, "saved", torch.float32)
+        if saved.numel() != 2 * batch * n:
+            raise ValueError("saved has the wrong size")
+    rc = lib.spinner_layer_forward(x.data_ptr(), n, batch, d1.data_ptr(), d2.data_ptr(), d3.data_ptr(),
+                                   ctypes.c_float(scale), y.data_ptr(), saved.data_ptr(), _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return y, saved
+
+
+def spinner_layer_backward(dy, x, saved, d1, d2, d3, scale=1.0, dx=None, dd=None, workspace=None, stream=None):
+    """Gradients for x ([batch][n]) and for the three diagonals ([3][n], summed over the batch): returns (dx, dd)."""
+    import torch
+
+    for name, t in (("dy", dy), ("x", x), ("saved", saved), ("d1", d1), ("d2", d2), ("d3", d3)):
+        _check_tensor(t, name, torch.float32)
+    batch, n = x.shape
+    if dy.shape != x.shape or saved.numel() != 2 * batch * n:
+        raise ValueError("dy / saved do not match x")
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dd is None:
+        dd = torch.empty((3, n), dtype=torch.float32, device=x.device)
+    need = spinner_layer_workspace_bytes(n, batch)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    if workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_layer_backward(dy.data_ptr(), x.data_ptr(), saved.data_ptr(), n, batch, d1.data_ptr(), d2.data_ptr(),
+                                    d3.data_ptr(), ctypes.c_float(scale), dx.data_ptr(), dd.data_ptr(), workspace.data_ptr(),
+                                    _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return dx, dd

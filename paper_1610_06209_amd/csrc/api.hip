@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include "launch.hpp"
+#include "layer_params.hpp"
 
 namespace spinner {
 // ------------------------------------------------------------------ plain copy (measurement aid)
@@ -73,7 +74,7 @@ int fused_max_log(int epilogue)
 
 extern "C" {
 
-int spinner_version(void) { return 110; }
+int spinner_version(void) { return 120; }
 
 const char* spinner_strerror(int status)
 {
@@ -362,6 +363,79 @@ int spinner_angular_gram(const void* codes_a, long na, const void* codes_b, long
     const hipError_t e = spinner::launch_hamming_gram(static_cast<const unsigned long long*>(codes_a), na,
                                                       static_cast<const unsigned long long*>(codes_b), nb, m, out,
                                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+// ------------------------------------------------------------------ adaptive layer
+size_t spinner_layer_saved_bytes(int n, long batch)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || log2n > spinner::kLayerMaxLog || batch <= 0) return 0;
+    return 2 * (size_t)batch * (size_t)n * sizeof(float);
+}
+
+size_t spinner_layer_workspace_bytes(int n, long batch)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || log2n > spinner::kLayerMaxLog || batch <= 0) return 0;
+    return (size_t)spinner::layer_backward_slots(log2n, batch) * 3 * (size_t)n * sizeof(float);
+}
+
+static int check_layer_args(int n, long batch, int* log2n)
+{
+    if (!pow2_in_range(n, log2n)) return SPINNER_ERR_BAD_N;
+    if (*log2n > spinner::kLayerMaxLog) return SPINNER_ERR_UNSUPPORTED;
+    if (batch < 0 || batch > 0x7fffffffL || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    return SPINNER_OK;
+}
+
+int spinner_layer_forward(const float* x, int n, long batch, const float* d1, const float* d2, const float* d3,
+                          float scale, float* y, void* saved, void* stream)
+{
+    int log2n;
+    const int rc = check_layer_args(n, batch, &log2n);
+    if (rc != SPINNER_OK || batch == 0) return rc;
+    if (!x || !d1 || !d2 || !d3 || !y || !saved) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(x) || !aligned16(d1) || !aligned16(d2) || !aligned16(d3) || !aligned16(y) || !aligned16(saved))
+        return SPINNER_ERR_ALIGNMENT;
+    spinner::LayerForwardParams p;
+    p.x = x; p.d[0] = d1; p.d[1] = d2; p.d[2] = d3; p.y = y;
+    p.saved1 = static_cast<float*>(saved);
+    p.saved2 = p.saved1 + (size_t)batch * n;
+    p.batch = batch;
+    p.factor = (float)((double)scale / ((double)n * sqrt((double)n)));
+    const hipError_t e = spinner::launch_layer_forward(log2n, p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_layer_backward(const float* dy, const float* x, const void* saved, int n, long batch, const float* d1,
+                           const float* d2, const float* d3, float scale, float* dx, float* dd, void* workspace,
+                           void* stream)
+{
+    int log2n;
+    const int rc = check_layer_args(n, batch, &log2n);
+    if (rc != SPINNER_OK) return rc;
+    if (batch == 0) return SPINNER_OK;
+    if (!dy || !x || !saved || !d1 || !d2 || !d3 || !dx || !dd) return SPINNER_ERR_NULL_PTR;
+    if (!workspace) return SPINNER_ERR_WORKSPACE;
+    if (!aligned16(dy) || !aligned16(x) || !aligned16(saved) || !aligned16(d1) || !aligned16(d2) || !aligned16(d3) ||
+        !aligned16(dx) || !aligned16(dd) || !aligned16(workspace))
+        return SPINNER_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const double factor = (double)scale / ((double)n * sqrt((double)n));
+    spinner::LayerBackwardParams p;
+    p.dy = dy; p.x = x;
+    p.saved1 = static_cast<const float*>(saved);
+    p.saved2 = p.saved1 + (size_t)batch * n;
+    p.d[0] = d1; p.d[1] = d2; p.d[2] = d3;
+    p.dx = dx;
+    p.partial = static_cast<float*>(workspace);
+    p.batch = batch;
+    p.slots = spinner::layer_backward_slots(log2n, batch);
+    p.factor = (float)factor;
+    hipError_t e = spinner::launch_layer_backward(log2n, p, s);
+    if (e != hipSuccess) return hip_fail(e);
+    e = spinner::launch_layer_reduce(p.partial, p.slots, 3LL * n, factor, dd, s);
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 

@@ -102,6 +102,15 @@ hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const 
 // sign words per diagonal in the packed format (n <= 2^14)
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
 
+// adaptive layer (forward with saved activations, backward); the parameter structs are in layer_kernels.hpp
+struct LayerForwardParams;
+struct LayerBackwardParams;
+constexpr int kLayerMaxLog = 14;
+hipError_t launch_layer_forward(int log2n, const LayerForwardParams& p, hipStream_t s);
+long long layer_backward_slots(int log2n, long long batch);      // partial-sum rows the backward kernel writes
+hipError_t launch_layer_backward(int log2n, const LayerBackwardParams& p, hipStream_t s);
+hipError_t launch_layer_reduce(const float* partial, long long slots, long long len, double factor, float* dd, hipStream_t s);
+
 // Shape of the column tiles of the four-pass schedule: 2^rows_log rows (all rows of the
 // matrix view) by 2^contig_log contiguous columns.  Up to n = 2^21 the matrix view has
 // 2^7 rows and a column tile is 128 rows x 32 columns (128-byte segments, 2^12 elements:

@@ -1,0 +1,154 @@
+// Adaptive setting: the HD3HD2HD1 block as a layer with learned diagonals (forward pass that keeps
+// the activations entering D2 and D3, and the backward pass).  Built from the same tile geometry,
+// butterfly stages and LDS transposes as the projection kernels in spinner_kernels.hpp.
+//
+// Nothing is normalised on the way: with H_u the +-1 Hadamard matrix,
+//   saved1 = H_u D1 x            (= sqrt(n) * b1),
+//   saved2 = H_u D2 saved1       (= n * b2),
+//   y      = scale n^{-3/2} H_u D3 saved2.
+// Backward, with t1 = H_u dy, t2 = H_u D3 t1, t3 = H_u D2 t2 and c = scale n^{-3/2}:
+//   dD3 = c sum_b t1 * saved2,  dD2 = c sum_b t2 * saved1,  dD1 = c sum_b t3 * x,  dx = c D1 t3.
+#pragma once
+#include "layer_params.hpp"
+#include "spinner_kernels.hpp"
+
+namespace spinner {
+
+template <typename G, int LAY>
+__device__ __forceinline__ void tile_load(float (&v)[G::R], const ThreadCtx<G>& c, const float* base, bool active)
+{
+    const float* src = base + c.base_index(LAY);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (active) t = *reinterpret_cast<const float4*>(src + G::reg_index(LAY, jh * 4));
+        v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
+    }
+}
+
+template <typename G, int LAY>
+__device__ __forceinline__ void tile_store(const float (&v)[G::R], const ThreadCtx<G>& c, float* base, float f)
+{
+    float* dst = base + c.base_index(LAY);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh)
+        *reinterpret_cast<float4*>(dst + G::reg_index(LAY, jh * 4)) =
+            make_float4(v[jh * 4] * f, v[jh * 4 + 1] * f, v[jh * 4 + 2] * f, v[jh * 4 + 3] * f);
+}
+
+// acc += g * (tile of `base` in layout LAY)
+template <typename G, int LAY>
+__device__ __forceinline__ void tile_mac(float (&acc)[G::R], const float (&g)[G::R], const ThreadCtx<G>& c, const float* base)
+{
+    const float* src = base + c.base_index(LAY);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        const float4 t = *reinterpret_cast<const float4*>(src + G::reg_index(LAY, jh * 4));
+        acc[jh * 4] = __builtin_fmaf(g[jh * 4], t.x, acc[jh * 4]);
+        acc[jh * 4 + 1] = __builtin_fmaf(g[jh * 4 + 1], t.y, acc[jh * 4 + 1]);
+        acc[jh * 4 + 2] = __builtin_fmaf(g[jh * 4 + 2], t.z, acc[jh * 4 + 2]);
+        acc[jh * 4 + 3] = __builtin_fmaf(g[jh * 4 + 3], t.w, acc[jh * 4 + 3]);
+    }
+}
+
+template <typename G>
+__device__ __forceinline__ void layer_ctx(ThreadCtx<G>& c, long long& slot)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    if constexpr (G::WB > 0) {
+        slot = blockIdx.x;
+        c.lit = lane;
+        c.wv = __builtin_amdgcn_readfirstlane(wave);
+    } else {
+        slot = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + (lane >> G::LB);
+        c.lit = lane & ((1 << G::LB) - 1);
+        c.wv = 0;
+    }
+#pragma unroll
+    for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
+    init_h16_operand(c, lane);
+}
+
+// One vector per tile.  The held values carry the tracked lane sign after an odd number of
+// transforms (see lane_stage_fmac_dpp); it is folded into the factors of what is stored.
+template <typename G>
+__global__ void __launch_bounds__(G::THREADS) layer_forward_kernel(LayerForwardParams p)
+{
+    constexpr int NT = G::NT;
+    constexpr int n = 1 << NT;
+    ThreadCtx<G> c;
+    long long vec;
+    layer_ctx(c, vec);
+    const bool active = vec < p.batch;
+    const long long off = (active ? vec : 0) * (long long)n;
+    __shared__ float4 lds_store[G::LDS_FLOAT4];
+    float4* lds = lds_store;
+    const float sgn = tracked_sign<G, 0, float>(c);
+
+    float v[G::R];
+    tile_load<G, G::layout_after(0)>(v, c, p.x + off, active);
+    spinner_step<G, NT, 0, G::layout_after(0), true, true, false, false>(v, c, p.d[0], nullptr, 0, lds);
+    if (active) tile_store<G, G::layout_after(1)>(v, c, p.saved1 + off, sgn);
+    spinner_step<G, NT, 0, G::layout_after(1), true, false, true, false>(v, c, p.d[1], nullptr, 0, lds);
+    if (active) tile_store<G, G::layout_after(2)>(v, c, p.saved2 + off, 1.0f);
+    spinner_step<G, NT, 0, G::layout_after(2), true, false, false, false>(v, c, p.d[2], nullptr, 0, lds);
+    if (active) tile_store<G, G::layout_after(3)>(v, c, p.y + off, p.factor * sgn);
+}
+
+// Slot s (one tile position of one workgroup) handles vectors s, s + slots, s + 2 slots, ... and
+// keeps its three per-coordinate sums in registers; they are written once at the end.
+template <typename G>
+__global__ void __launch_bounds__(G::THREADS) layer_backward_kernel(LayerBackwardParams p)
+{
+    constexpr int NT = G::NT;
+    constexpr int n = 1 << NT;
+    constexpr int R = G::R;
+    constexpr int L1 = G::layout_after(1), L2 = G::layout_after(2), L3 = G::layout_after(3);
+    ThreadCtx<G> c;
+    long long slot;
+    layer_ctx(c, slot);
+    __shared__ float4 lds_store[G::LDS_FLOAT4];
+    float4* lds = lds_store;
+    const float sgn = tracked_sign<G, 0, float>(c);
+
+    float acc1[R], acc2[R], acc3[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) { acc1[j] = 0.f; acc2[j] = 0.f; acc3[j] = 0.f; }
+
+    // every wave of a workgroup runs the same number of rounds (the barriers inside the steps need that)
+    const long long first = G::WB > 0 ? (long long)blockIdx.x : (long long)blockIdx.x * G::TILES_PER_WG;
+    for (long long base = first; base < p.batch; base += p.slots) {
+        const long long vec = base + (slot - first);
+        const bool active = vec < p.batch;
+        const long long off = (active ? vec : 0) * (long long)n;
+        float g[R];
+        tile_load<G, G::layout_after(0)>(g, c, p.dy + off, active);
+        spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
+        if (active) tile_mac<G, L1>(acc3, g, c, p.saved2 + off);
+        spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
+        if (active) tile_mac<G, L2>(acc2, g, c, p.saved1 + off);
+        spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
+        if (active) {
+            tile_mac<G, L3>(acc1, g, c, p.x + off);
+            // dx = factor * D1 t3
+            const float* d1 = p.d[0] + c.base_index(L3);
+            float* dst = p.dx + off + c.base_index(L3);
+            const float f = p.factor * sgn;
+#pragma unroll
+            for (int jh = 0; jh < R / 4; ++jh) {
+                const float4 t = *reinterpret_cast<const float4*>(d1 + G::reg_index(L3, jh * 4));
+                *reinterpret_cast<float4*>(dst + G::reg_index(L3, jh * 4)) =
+                    make_float4(g[jh * 4] * f * t.x, g[jh * 4 + 1] * f * t.y, g[jh * 4 + 2] * f * t.z, g[jh * 4 + 3] * f * t.w);
+            }
+        }
+    }
+    if (slot < p.slots) {
+        float* part = p.partial + slot * 3LL * n;
+        tile_store<G, L3>(acc1, c, part, sgn);            // t3 carries the tracked sign (three transforms)
+        tile_store<G, L2>(acc2, c, part + n, 1.0f);       // t2: two transforms
+        tile_store<G, L1>(acc3, c, part + 2 * n, sgn);    // t1: one transform
+    }
+}
+
+}  // namespace spinner

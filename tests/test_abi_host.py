@@ -136,6 +136,31 @@ def test_sign_code_entry_points_host_side(b):
     assert ag(None, 0, None, 4, 256, None, None) == b.SPINNER_OK
 
 
+def test_layer_entry_points_host_side(b):
+    assert b.spinner_layer_saved_bytes(1024, 10) == 2 * 10 * 1024 * 4
+    assert b.spinner_layer_saved_bytes(1 << 15, 10) == 0 and b.spinner_layer_saved_bytes(1000, 10) == 0
+    # one partial row of 3 n floats per tile slot: small batches take one slot per vector (rounded up to whole workgroups)
+    assert b.spinner_layer_workspace_bytes(4096, 8) == 8 * 3 * 4096 * 4
+    assert b.spinner_layer_workspace_bytes(4096, 1 << 20) == 1024 * 3 * 4096 * 4
+    assert b.spinner_layer_workspace_bytes(16, 1 << 20) == 8192 * 3 * 16 * 4          # bounded number of partial rows
+    assert b.spinner_layer_workspace_bytes(1 << 15, 8) == 0
+    f = b.lib.spinner_layer_forward
+    one = ctypes.c_float(1.0)
+    assert f(64, 1000, 4, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_BAD_N
+    assert f(64, 1 << 15, 4, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert f(64, 1024, -1, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_BAD_BATCH
+    assert f(64, 1024, 4, 64, None, 64, one, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert f(64, 1024, 4, 64, 64, 64, one, 64, None, None) == b.SPINNER_ERR_NULL_PTR
+    assert f(64, 1024, 4, 64, 64, 64, one, 72, 64, None) == b.SPINNER_ERR_ALIGNMENT
+    assert f(None, 1024, 0, None, None, None, one, None, None, None) == b.SPINNER_OK
+    g = b.lib.spinner_layer_backward
+    assert g(64, 64, 64, 1000, 4, 64, 64, 64, one, 64, 64, 64, None) == b.SPINNER_ERR_BAD_N
+    assert g(64, 64, 64, 1024, 4, 64, 64, 64, one, 64, 64, None, None) == b.SPINNER_ERR_WORKSPACE
+    assert g(64, None, 64, 1024, 4, 64, 64, 64, one, 64, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert g(64, 64, 64, 1024, 4, 64, 64, 64, one, 64, 68, 64, None) == b.SPINNER_ERR_ALIGNMENT
+    assert g(None, None, None, 1024, 0, None, None, None, one, None, None, None, None) == b.SPINNER_OK
+
+
 def test_stream_copy_rejects_bad_arguments(b):
     c = b.lib.spinner_stream_copy
     assert c(None, 64, 16, None) == b.SPINNER_ERR_NULL_PTR

@@ -1,0 +1,125 @@
+"""GPU parity of the adaptive layer (learned diagonals): forward with saved activations and backward pass,
+called through the C ABI, against the fp64 oracle on the same fp32 inputs.
+
+Tolerance: relative L2 error <= 1e-5 per vector for y and dx, and per diagonal for the three parameter
+gradients (which sum over the batch)."""
+import sys
+
+import numpy as np
+import pytest
+
+from helpers import REL_L2_TOL, rel_l2_per_vector
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1610_06209_amd import binding
+
+    class G:
+        pass
+
+    g = G()
+    g.torch = torch
+    g.b = binding
+    g.dev = torch.device("cuda:0")
+    return g
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print("\n[gpu-case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+
+
+def _to(g, a):
+    return g.torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
+
+
+def _case(n, batch, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((batch, n)).astype(np.float32)
+    d = (rng.standard_normal((3, n)) * 0.5 + 1.0).astype(np.float32)       # learned diagonals: arbitrary reals
+    dy = rng.standard_normal((batch, n)).astype(np.float32)
+    return x, d, dy
+
+
+def _run(g, x, d, dy, scale):
+    xt, dt, dyt = _to(g, x), _to(g, d), _to(g, dy)
+    y, saved = g.b.spinner_layer_forward(xt, dt[0], dt[1], dt[2], scale)
+    dx, dd = g.b.spinner_layer_backward(dyt, xt, saved, dt[0], dt[1], dt[2], scale)
+    g.torch.cuda.synchronize()
+    return y.cpu().numpy(), dx.cpu().numpy(), dd.cpu().numpy()
+
+
+def _check(oracle, x, d, dy, scale, y, dx, dd):
+    wy, _, _ = oracle.layer_forward(x, d[0], d[1], d[2], scale)
+    wdx, wdd = oracle.layer_backward(x, d[0], d[1], d[2], dy, scale)
+    assert rel_l2_per_vector(y, wy).max() <= REL_L2_TOL
+    assert rel_l2_per_vector(dx, wdx).max() <= REL_L2_TOL
+    err = rel_l2_per_vector(dd, wdd)
+    assert err.max() <= REL_L2_TOL, err
+
+
+@pytest.mark.parametrize("log2n", list(range(4, 15)))
+def test_layer_forward_backward_every_size(gpu, oracle, log2n):
+    n = 1 << log2n
+    batch = {4: 1000, 5: 777, 6: 333, 7: 200, 13: 7, 14: 5}.get(log2n, 37 if log2n < 12 else 9)
+    x, d, dy = _case(n, batch, 6000 + log2n)
+    scale = 1.0 if log2n % 2 else 0.37
+    y, dx, dd = _run(gpu, x, d, dy, scale)
+    _check(oracle, x, d, dy, scale, y, dx, dd)
+
+
+@pytest.mark.parametrize("n,batch", [(64, 70000), (256, 20000), (2048, 2300), (4096, 1100)])
+def test_layer_backward_many_vectors_per_slot(gpu, oracle, n, batch):
+    # more vectors than resident tile slots: every slot accumulates several vectors, the last round is ragged
+    x, d, dy = _case(n, batch, 6100 + n)
+    assert gpu.b.spinner_layer_workspace_bytes(n, batch) < batch * 3 * n * 4
+    y, dx, dd = _run(gpu, x, d, dy, 1.0)
+    _check(oracle, x, d, dy, 1.0, y, dx, dd)
+
+
+def test_layer_special_cases(gpu, oracle):
+    n, batch = 1024, 19
+    x, d, dy = _case(n, batch, 6200)
+    ones = np.ones((3, n), dtype=np.float32)
+    # identity diagonals: y = H x, dx = H dy, and all three parameter gradients equal sum_b (H dy) * (H^k x) terms
+    y, dx, dd = _run(gpu, x, ones, dy, 1.0)
+    _check(oracle, x, ones, dy, 1.0, y, dx, dd)
+    # forward agrees with the projection entry point on the same inputs
+    xt, dt = _to(gpu, x), _to(gpu, d)
+    y2, _ = gpu.b.spinner_layer_forward(xt, dt[0], dt[1], dt[2], 2.0)
+    y3 = gpu.b.spinner_apply(xt, dt[0], dt[1], dt[2], n, "none", 2.0)
+    gpu.torch.cuda.synchronize()
+    assert rel_l2_per_vector(y2.cpu().numpy(), y3.cpu().numpy().astype(np.float64)).max() <= 1e-6
+    # dx written over dy; two runs give identical bits (no atomics anywhere)
+    dyt = _to(gpu, dy)
+    _, saved = gpu.b.spinner_layer_forward(xt, dt[0], dt[1], dt[2], 1.0)
+    dx1, dd1 = gpu.b.spinner_layer_backward(dyt, xt, saved, dt[0], dt[1], dt[2], 1.0)
+    dx2, dd2 = gpu.b.spinner_layer_backward(dyt, xt, saved, dt[0], dt[1], dt[2], 1.0, dx=dyt)
+    gpu.torch.cuda.synchronize()
+    assert gpu.torch.equal(dx1, dx2) and gpu.torch.equal(dd1, dd2) and dx2.data_ptr() == dyt.data_ptr()
+    # the layer is linear in each diagonal: sum_i d_k[i] dd_k[i] = <dy, y>
+    y1, _, dd3 = _run(gpu, x, d, dy, 1.0)
+    inner = float((dy.astype(np.float64) * y1).sum())
+    for k in range(3):
+        assert abs(float((d[k].astype(np.float64) * dd3[k]).sum()) - inner) <= 1e-4 * abs(inner) + 1e-3
+
+
+def test_layer_empty_batch_and_errors(gpu):
+    b, t = gpu.b, gpu.torch
+    d = t.ones(256, dtype=t.float32, device=gpu.dev)
+    x = t.zeros((0, 256), dtype=t.float32, device=gpu.dev)
+    y, saved = b.spinner_layer_forward(x, d, d, d)
+    assert tuple(y.shape) == (0, 256)
+    big = t.zeros((2, 1 << 15), dtype=t.float32, device=gpu.dev)
+    dbig = t.ones(1 << 15, dtype=t.float32, device=gpu.dev)
+    with pytest.raises(b.SpinnerError) as e:
+        b.spinner_layer_forward(big, dbig, dbig, dbig)
+    assert e.value.status == b.SPINNER_ERR_UNSUPPORTED
