@@ -25,6 +25,9 @@ What each function follows:
   The backward pass is the transpose of the layer's Jacobian written out with dense matrices:
   ``dx = scale * D1 H D2 H D3 H dy`` (H is symmetric) and, for each diagonal, the sum over the batch of
   (signal arriving at the diagonal from the output side) times (activation entering it from the input side).
+* ``sketch`` / ``sketched_gram`` - the Newton-sketch use of the Supplement ("Additional experiments"):
+  an m x n sketching matrix S (the first m rows of a spinner, scaled) applied to the columns of a
+  weighted data matrix diag(w) A, and the d x d matrix (S diag(w) A)^T (S diag(w) A) that replaces the Hessian.
 * ``epilogue_signbits`` / ``angular_estimate`` - Section 5 (angular kernel):
   the pointwise sign of the projection, and the kernel estimate
   ``1 - d_H / d'`` from the Hamming distance of two such sign vectors.
@@ -212,6 +215,23 @@ def layer_backward(x, d1, d2, d3, dy, scale: float = 1.0):
     dd1 = (g1 * x).sum(axis=0)
     dx = g1 * d1
     return dx, np.stack([dd1, dd2, dd3])
+
+
+def sketch(A, w, d1, d2, d3, m: int, scale: float, nthreads: int = 0) -> np.ndarray:
+    """B = S diag(w) A, fp64 [m][d], for A fp32 [n][d], row weights w fp32 [n] (None: all ones) and
+    S = scale * (first m rows of H D3 H D2 H D1).  The spinner acts on each column of diag(w) A."""
+    A = np.asarray(A, dtype=np.float32)
+    if w is not None:
+        A = (A * np.asarray(w, dtype=np.float32)[:, None]).astype(np.float32)     # the product the fp32 path forms
+    cols = np.ascontiguousarray(A.T)                                               # [d][n]: one vector per column
+    y = spinner(cols, d1, d2, d3, nthreads=nthreads)
+    return float(scale) * np.ascontiguousarray(y[:, :m].T)
+
+
+def sketched_gram(B) -> np.ndarray:
+    """(S diag(w) A)^T (S diag(w) A), fp64 [d][d]."""
+    B = np.asarray(B, dtype=np.float64)
+    return B.T @ B
 
 
 def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,

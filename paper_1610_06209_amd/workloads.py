@@ -158,6 +158,24 @@ def make_x_torch(w: Workload, device, batch: int | None = None):
     return x.contiguous()
 
 
+def newton_sketch_problem(n: int, d: int, seed: int):
+    """Data of the Supplement's logistic-regression experiment: rows a_i ~ N(0, Sigma) with
+    Sigma_jk = 0.99^|j-k| (generated as a stationary AR(1) sequence along each row), and the row weights
+    w_i = sqrt(p_i (1 - p_i)), p_i = 1 / (1 + exp(-a_i^T x)), at a seeded iterate x.  Returns (A fp32 [n][d], w fp32 [n])."""
+    rng = np.random.Generator(np.random.PCG64(seed ^ 0x4E5754))
+    rho = 0.99
+    eps = rng.standard_normal((n, d), dtype=np.float32)
+    A = np.empty((n, d), dtype=np.float32)
+    A[:, 0] = eps[:, 0]
+    c = np.float32(math.sqrt(1.0 - rho * rho))
+    for j in range(1, d):
+        A[:, j] = np.float32(rho) * A[:, j - 1] + c * eps[:, j]
+    x = (rng.standard_normal(d) / math.sqrt(d)).astype(np.float32)
+    p = 1.0 / (1.0 + np.exp(-(A.astype(np.float64) @ x.astype(np.float64))))
+    w = np.sqrt(p * (1.0 - p)).astype(np.float32)
+    return A, w
+
+
 def sample_rows(batch: int, count: int, seed: int) -> np.ndarray:
     """Row indices a full-size parity check looks at: first, last and a seeded draw."""
     count = min(count, batch)
