@@ -180,6 +180,35 @@ def measure_layer(torch, b, dev, n, batch, steps, warmup):
     return res
 
 
+def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup):
+    """Newton sketch: B = S diag(w) A (transposes + projection) and the d x d Gram matrix on the matrix pipe."""
+    import math as _m
+
+    g = torch.Generator(device=dev)
+    g.manual_seed(1610 + d)
+    A = torch.randn((n, d), generator=g, device=dev, dtype=torch.float32)
+    w = torch.rand(n, generator=g, device=dev, dtype=torch.float32) * 0.5
+    ds = torch.from_numpy(W.rademacher_diagonals(n, 3, 77)).to(dev)
+    Bm = torch.empty((m, d), dtype=torch.float32, device=dev)
+    G = torch.empty((d, d), dtype=torch.float32, device=dev)
+    ws = torch.empty(b.spinner_sketch_workspace_bytes(n, d, m), dtype=torch.uint8, device=dev)
+    sk = lambda: b.spinner_sketch(A, w, ds[0], ds[1], ds[2], m, _m.sqrt(n / m), out=Bm, workspace=ws)
+    gws = torch.empty(max(16, b.spinner_sketch_gram_workspace_bytes(m, d)), dtype=torch.uint8, device=dev)
+    gr = lambda: b.spinner_sketch_gram(Bm, out=G, workspace=gws)
+    for _ in range(10):
+        sk(); gr()
+    torch.cuda.synchronize()
+    _, s_ms = time_calls(torch, sk, steps, warmup)
+    _, g_ms = time_calls(torch, gr, steps, warmup)
+    res = {"workload": "newton_sketch_n%d_d%d_m%d" % (n, d, m), "sketch_ms": round(s_ms, 4), "gram_ms": round(g_ms, 4),
+           # the method's own bytes: A read once, B written once
+           "sketch_GBs": round((4.0 * n * d + 4.0 * m * d) / (s_ms * 1e-3) / 1e9, 1),
+           "gram_TFLOPs": round(2.0 * m * d * d / (g_ms * 1e-3) / 1e12, 2), "gram_mfma_frac": round(2.0 * m * d * d / (g_ms * 1e-3) / 157.3e12, 4)}
+    del A, w, ds, Bm, G, ws, gws
+    torch.cuda.empty_cache()
+    return res
+
+
 def copy_ceiling(torch, b, dev, steps, warmup):
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
@@ -310,6 +339,10 @@ def main():
         log("[bench] %s: forward %.4f ms (%.0f GB/s), backward %.4f ms (%.0f GB/s)" % (
             lay["workload"], lay["forward_ms"], lay["forward_GBs"], lay["backward_ms"], lay["backward_GBs"]))
         nxt.append(lay)
+        skt = measure_sketch(torch, b, W, dev, 1 << 16, 512, 2048, 10, 3)
+        log("[bench] %s: sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
+            skt["workload"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
+        nxt.append(skt)
         # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
         tbl = []
         for k in range(4, 13):

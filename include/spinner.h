@@ -215,6 +215,36 @@ int spinner_layer_backward(const float *dy, const float *x, const void *saved,
                            float scale, float *dx, float *dd, void *workspace, void *stream);
 
 /*
+ * Newton sketch (Supplement, "Additional experiments"): the Hessian A^T W A of a
+ * generalised linear model is replaced by (S W^{1/2} A)^T (S W^{1/2} A), with S an
+ * m x n sketching matrix - here scale * (first m rows of H D3 H D2 H D1), which acts
+ * on the COLUMNS of the row-major data matrix.
+ *
+ * spinner_sketch computes B = S diag(w) A.
+ *   A          in   device fp32 [n][d] row-major (n observations of dimension d)
+ *   w          in   device fp32 [n] row weights (e.g. the square roots of the Hessian
+ *                   weights), or NULL for none
+ *   d1..d3     in   device fp32 [n]
+ *   m, scale   in   rows of the sketch, extra factor (sqrt(n/m) makes E[S^T S] = I)
+ *   B          out  device fp32 [m][d] row-major
+ *   workspace  in   device scratch of spinner_sketch_workspace_bytes(n, d, m) bytes:
+ *                   the matrix is transposed (weights applied on the way) so that each
+ *                   column becomes one contiguous vector, projected with the same
+ *                   kernels as spinner_apply, and the result transposed back
+ * spinner_sketch_gram computes G = B^T B (device fp32 [d][d], all of it, symmetric)
+ * on the fp32 matrix pipe; the sum over the m rows is split into slabs that are added
+ * up in a fixed order, for which it needs spinner_sketch_gram_workspace_bytes(m, d)
+ * bytes of device scratch (0 for small m).
+ * n a power of two in [2^4, 2^24]; d and m arbitrary (1 <= m <= n).
+ */
+size_t spinner_sketch_workspace_bytes(int n, int d, int m);
+int spinner_sketch(const float *A, int n, int d, const float *w,
+                   const float *d1, const float *d2, const float *d3,
+                   int m, float scale, float *B, void *workspace, void *stream);
+size_t spinner_sketch_gram_workspace_bytes(int m, int d);
+int spinner_sketch_gram(const float *B, int m, int d, float *G, void *workspace, void *stream);
+
+/*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the
  * fused limit, and above it when m == n with epilogue NONE; otherwise batch * n * 4.
  * Returns 0 for invalid arguments (spinner_apply reports those).

@@ -35,7 +35,8 @@ EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_
            "spinner_apply_signs", "spinner_hash_signs", "spinner_code_bytes", "spinner_codes_workspace_bytes",
            "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram",
            "spinner_layer_saved_bytes", "spinner_layer_workspace_bytes", "spinner_layer_forward",
-           "spinner_layer_backward"]
+           "spinner_layer_backward", "spinner_sketch_workspace_bytes", "spinner_sketch", "spinner_sketch_gram",
+           "spinner_sketch_gram_workspace_bytes"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -92,6 +93,14 @@ lib.spinner_layer_forward.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, _vp
 lib.spinner_layer_backward.restype = ctypes.c_int
 lib.spinner_layer_backward.argtypes = [_vp, _vp, _vp, ctypes.c_int, ctypes.c_long, _vp, _vp, _vp, ctypes.c_float, _vp, _vp,
                                        _vp, _vp]
+lib.spinner_sketch_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_sketch_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+lib.spinner_sketch.restype = ctypes.c_int
+lib.spinner_sketch.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp, _vp, ctypes.c_int, ctypes.c_float, _vp, _vp, _vp]
+lib.spinner_sketch_gram.restype = ctypes.c_int
+lib.spinner_sketch_gram.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp]
+lib.spinner_sketch_gram_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_sketch_gram_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
 
 
 class SpinnerError(RuntimeError):
@@ -441,3 +450,64 @@ def spinner_layer_backward(dy, x, saved, d1, d2, d3, scale=1.0, dx=None, dd=None
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return dx, dd
+
+
+def spinner_sketch_workspace_bytes(n: int, d: int, m: int) -> int:
+    return int(lib.spinner_sketch_workspace_bytes(int(n), int(d), int(m)))
+
+
+def spinner_sketch(A, w, d1, d2, d3, m, scale=1.0, out=None, workspace=None, stream=None):
+    """B = scale * (first m rows of H D3 H D2 H D1) diag(w) A for A fp32 [n][d]; w may be None.  Returns B [m][d]."""
+    import torch
+
+    _check_tensor(A, "A", torch.float32)
+    for name, t in (("d1", d1), ("d2", d2), ("d3", d3)):
+        _check_tensor(t, name, torch.float32)
+    if w is not None:
+        _check_tensor(w, "w", torch.float32)
+    n, d = A.shape
+    if out is None:
+        out = torch.empty((int(m), d), dtype=torch.float32, device=A.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != int(m) * d:
+            raise ValueError("out has the wrong size")
+    need = spinner_sketch_workspace_bytes(n, d, m)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=A.device)
+    if workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_sketch(A.data_ptr(), n, d, w.data_ptr() if w is not None else None, d1.data_ptr(), d2.data_ptr(),
+                            d3.data_ptr(), int(m), ctypes.c_float(scale), out.data_ptr(), workspace.data_ptr(),
+                            _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out
+
+
+def spinner_sketch_gram_workspace_bytes(m: int, d: int) -> int:
+    return int(lib.spinner_sketch_gram_workspace_bytes(int(m), int(d)))
+
+
+def spinner_sketch_gram(B, out=None, workspace=None, stream=None):
+    """G = B^T B, fp32 CUDA tensor [d][d]."""
+    import torch
+
+    _check_tensor(B, "B", torch.float32)
+    m, d = B.shape
+    if out is None:
+        out = torch.empty((d, d), dtype=torch.float32, device=B.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != d * d:
+            raise ValueError("out has the wrong size")
+    need = spinner_sketch_gram_workspace_bytes(m, d)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=B.device)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_sketch_gram(B.data_ptr(), m, d, out.data_ptr(), workspace.data_ptr() if workspace is not None else None,
+                                 _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out

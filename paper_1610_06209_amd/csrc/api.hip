@@ -74,7 +74,7 @@ int fused_max_log(int epilogue)
 
 extern "C" {
 
-int spinner_version(void) { return 120; }
+int spinner_version(void) { return 130; }
 
 const char* spinner_strerror(int status)
 {
@@ -436,6 +436,63 @@ int spinner_layer_backward(const float* dy, const float* x, const void* saved, i
     hipError_t e = spinner::launch_layer_backward(log2n, p, s);
     if (e != hipSuccess) return hip_fail(e);
     e = spinner::launch_layer_reduce(p.partial, p.slots, 3LL * n, factor, dd, s);
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+// ------------------------------------------------------------------ Newton sketch
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t spinner_sketch_workspace_bytes(int n, int d, int m)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || d < 1 || m < 1 || m > n) return 0;
+    return align256((size_t)d * n * sizeof(float)) + align256((size_t)d * m * sizeof(float)) +
+           spinner_workspace_bytes(n, d, m, SPINNER_EPI_NONE);
+}
+
+int spinner_sketch(const float* A, int n, int d, const float* w, const float* d1, const float* d2, const float* d3, int m,
+                   float scale, float* B, void* workspace, void* stream)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n)) return SPINNER_ERR_BAD_N;
+    if (m < 1 || m > n) return SPINNER_ERR_BAD_M;
+    if (d < 0 || (double)d * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    if (d == 0) return SPINNER_OK;
+    if (!A || !d1 || !d2 || !d3 || !B) return SPINNER_ERR_NULL_PTR;
+    if (!workspace) return SPINNER_ERR_WORKSPACE;
+    if (!aligned16(A) || !aligned16(w) || !aligned16(d1) || !aligned16(d2) || !aligned16(d3) || !aligned16(B) ||
+        !aligned16(workspace))
+        return SPINNER_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    float* At = reinterpret_cast<float*>(base);                                             // [d][n]
+    float* Ut = reinterpret_cast<float*>(base + align256((size_t)d * n * sizeof(float)));   // [d][m]
+    void* ws2 = base + align256((size_t)d * n * sizeof(float)) + align256((size_t)d * m * sizeof(float));
+    hipError_t e = spinner::launch_transpose_scale(A, n, d, w, At, s);
+    if (e != hipSuccess) return hip_fail(e);
+    const int rc = apply_impl(At, n, log2n, d, d1, d2, d3, nullptr, m, SPINNER_EPI_NONE, scale, Ut,
+                              spinner_workspace_bytes(n, d, m, SPINNER_EPI_NONE) ? ws2 : nullptr, stream);
+    if (rc != SPINNER_OK) return rc;
+    e = spinner::launch_transpose_scale(Ut, d, m, nullptr, B, s);
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+size_t spinner_sketch_gram_workspace_bytes(int m, int d)
+{
+    if (m < 1 || d < 1) return 0;
+    const int ks = spinner::sketch_gram_slabs(m, d);
+    return ks > 1 ? (size_t)ks * d * d * sizeof(float) : 0;
+}
+
+int spinner_sketch_gram(const float* B, int m, int d, float* G, void* workspace, void* stream)
+{
+    if (m < 0 || d < 0) return SPINNER_ERR_BAD_BATCH;
+    if (m == 0 || d == 0) return SPINNER_OK;
+    if (!B || !G) return SPINNER_ERR_NULL_PTR;
+    if (spinner_sketch_gram_workspace_bytes(m, d) && !workspace) return SPINNER_ERR_WORKSPACE;
+    if (!aligned16(B) || !aligned16(G) || !aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
+    const hipError_t e = spinner::launch_sketch_gram(B, m, d, G, static_cast<float*>(workspace),
+                                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 

@@ -111,6 +111,12 @@ long long layer_backward_slots(int log2n, long long batch);      // partial-sum 
 hipError_t launch_layer_backward(int log2n, const LayerBackwardParams& p, hipStream_t s);
 hipError_t launch_layer_reduce(const float* partial, long long slots, long long len, double factor, float* dd, hipStream_t s);
 
+// Newton sketch: transposition with optional row weights, Gram matrix on the matrix pipe
+hipError_t launch_transpose_scale(const float* src, long long rows, long long cols, const float* row_scale, float* dst,
+                                  hipStream_t s);
+int sketch_gram_slabs(int m, int d);      // d x d slabs of scratch the Gram kernel needs (1: none)
+hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* slabs, hipStream_t s);
+
 // Shape of the column tiles of the four-pass schedule: 2^rows_log rows (all rows of the
 // matrix view) by 2^contig_log contiguous columns.  Up to n = 2^21 the matrix view has
 // 2^7 rows and a column tile is 128 rows x 32 columns (128-byte segments, 2^12 elements:

@@ -1,0 +1,140 @@
+// Newton-sketch helpers: transposition with optional row weights (the sketch acts on the columns
+// of a row-major data matrix) and the Gram matrix B^T B on the fp32 matrix pipe.
+#include "launch.hpp"
+namespace spinner {
+
+// dst[c][r] = src[r][c] * (row_scale ? row_scale[r] : 1), src is [rows][cols] row-major.
+// 64 x 64 tiles through LDS (row padded by one word), both sides coalesced.
+__global__ void __launch_bounds__(256) transpose_scale_kernel(const float* __restrict__ src, long long rows, long long cols,
+                                                              const float* __restrict__ row_scale, float* __restrict__ dst)
+{
+    __shared__ float tile[64][65];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const long long r0 = (long long)blockIdx.y * 64, c0 = (long long)blockIdx.x * 64;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const long long r = r0 + ty + 4 * k, c = c0 + tx;
+        float v = 0.f;
+        if (r < rows && c < cols) v = src[r * cols + c] * (row_scale ? row_scale[r] : 1.0f);
+        tile[ty + 4 * k][tx] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const long long c = c0 + ty + 4 * k, r = r0 + tx;
+        if (r < rows && c < cols) dst[c * rows + r] = tile[tx][ty + 4 * k];
+    }
+}
+
+hipError_t launch_transpose_scale(const float* src, long long rows, long long cols, const float* row_scale, float* dst,
+                                  hipStream_t s)
+{
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const long long gx = (cols + 63) / 64, gy = (rows + 63) / 64;
+    if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(transpose_scale_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, src, rows, cols, row_scale, dst);
+    return hipGetLastError();
+}
+
+// G = B^T B for B [m][d] row-major: G[a][b] = sum_k B[k][a] B[k][b].  A workgroup of four waves owns a
+// 128 x 128 block of G (each wave 64 x 64 = 2 x 2 tiles of v_mfma_f32_32x32x2_f32) and walks k in chunks
+// of 16 rows of B staged in LDS.  Both MFMA operands are rows of B: lane l supplies B[k + l / 32][. + l % 32].
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr int kGramBlock = 128, kGramK = 16;
+// Split over k: block z handles rows [z * kchunk, (z + 1) * kchunk) of B and writes its own d x d slab of `out`
+// (G itself when there is a single slab); the slabs are added up afterwards in a fixed order.
+__global__ void __launch_bounds__(256) sketch_gram_kernel(const float* __restrict__ B, int m_total, int d, int kchunk,
+                                                          float* __restrict__ out)
+{
+    const int k_begin = blockIdx.z * kchunk;
+    const int m = k_begin + kchunk < m_total ? k_begin + kchunk : m_total;
+    float* G = out + (long long)blockIdx.z * d * d;
+    __shared__ float sa[kGramK][kGramBlock];
+    __shared__ float sb[kGramK][kGramBlock];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wa = wave >> 1, wb = wave & 1;
+    const int a0 = blockIdx.y * kGramBlock, b0 = blockIdx.x * kGramBlock;
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
+
+    for (int k0 = k_begin; k0 < m; k0 += kGramK) {
+        // 16 rows x 128 columns per operand, 256 threads: 8 values per thread and operand
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int idx = q * 256 + threadIdx.x;
+            const int kk = idx >> 7, col = idx & 127;
+            const bool row_ok = k0 + kk < m;
+            sa[kk][col] = (row_ok && a0 + col < d) ? B[(long long)(k0 + kk) * d + a0 + col] : 0.f;
+            sb[kk][col] = (row_ok && b0 + col < d) ? B[(long long)(k0 + kk) * d + b0 + col] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < kGramK; kk += 2) {
+            float fa[2], fb[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                fa[t] = sa[kk + (lane >> 5)][wa * 64 + t * 32 + (lane & 31)];
+                fb[t] = sb[kk + (lane >> 5)][wb * 64 + t * 32 + (lane & 31)];
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[u], acc[t][u], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // result register v of lane l holds row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = a0 + wa * 64 + t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int col = b0 + wb * 64 + u * 32 + (lane & 31);
+                if (row < d && col < d) G[(long long)row * d + col] = acc[t][u][v];
+            }
+}
+
+__global__ void __launch_bounds__(256) gram_reduce_kernel(const float* __restrict__ slabs, int count, long long len,
+                                                          float* __restrict__ G)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= len) return;
+    float s = 0.f;
+    for (int k = 0; k < count; ++k) s += slabs[k * len + i];
+    G[i] = s;
+}
+
+// number of k-slabs: enough blocks to fill the chip, at least 64 rows of B per slab, at most 64 slabs
+int sketch_gram_slabs(int m, int d)
+{
+    const long long tiles = (long long)((d + kGramBlock - 1) / kGramBlock) * ((d + kGramBlock - 1) / kGramBlock);
+    long long ks = (512 + tiles - 1) / tiles;
+    if (ks > (m + 63) / 64) ks = (m + 63) / 64;
+    if (ks > 64) ks = 64;
+    return ks < 1 ? 1 : (int)ks;
+}
+
+hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* slabs, hipStream_t s)
+{
+    if (m <= 0 || d <= 0) return hipSuccess;
+    const int g = (d + kGramBlock - 1) / kGramBlock;
+    if (g > 65535) return hipErrorInvalidConfiguration;
+    const int ks = sketch_gram_slabs(m, d);
+    int kchunk = (m + ks - 1) / ks;
+    kchunk = (kchunk + kGramK - 1) / kGramK * kGramK;
+    hipLaunchKernelGGL(sketch_gram_kernel, dim3((unsigned)g, (unsigned)g, (unsigned)ks), dim3(256), 0, s, B, m, d, kchunk,
+                       ks > 1 ? slabs : G);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || ks == 1) return e;
+    const long long len = (long long)d * d;
+    hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)((len + 255) / 256)), dim3(256), 0, s, slabs, ks, len, G);
+    return hipGetLastError();
+}
+}  // namespace spinner
