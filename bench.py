@@ -59,6 +59,34 @@ def time_calls(torch, fn, steps, warmup):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
+def time_graph(torch, fn, calls_per_graph, replays):
+    """ms per call when `calls_per_graph` calls of fn are captured once into a HIP graph and replayed: what a
+    launch-bound loop costs without the per-call host work.  The replayed result is what eager calls produce
+    (fn writes the same outputs either way)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(calls_per_graph):
+            fn()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * calls_per_graph)
+
+
 def make_runner(torch, b, W, w, dev, diagonals):
     """Allocate inputs/outputs for workload w and return the callable that runs one step.
 
@@ -102,7 +130,7 @@ def make_runner(torch, b, W, w, dev, diagonals):
     return fn, x
 
 
-def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0):
+def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0, graph=False):
     fn, x = make_runner(torch, b, W, w, dev, diagonals)
     if ramp_ms > 0:
         # untimed: let the clocks settle under this kernel's own load (the first ~10-20 ms of a
@@ -113,6 +141,7 @@ def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0):
                 fn()
             torch.cuda.synchronize()
     wall_ms, ev_ms = time_calls(torch, fn, steps, warmup)
+    graph_ms = time_graph(torch, fn, 20, 10) if graph else None
     alg = W.algorithmic_bytes_per_vector(w) * w.batch
     ops = W.adds_per_vector(w) * w.batch
     res = {
@@ -125,6 +154,7 @@ def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0):
         "hbm_frac": alg / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "butterfly_adds_Gops": ops / (ev_ms * 1e-3) / 1e9,
         "valu_frac_adds_only": ops / (ev_ms * 1e-3) / 1e9 / VALU_PEAK_GOPS,
+        "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
     }
     del fn, x
     torch.cuda.empty_cache()
@@ -314,10 +344,15 @@ def main():
         cfgs = []
         for name in W.CONFIG_ORDER:
             w = W.CONFIGS[name]
-            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
+            # the smallest configuration is launch-bound: also time it as a captured HIP graph of 20 steps
+            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0,
+                        graph=(w.batch * w.n <= (1 << 20)))
             cfgs.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
                          "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
                          "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
+            if r["graph_ms_per_step"] is not None:
+                cfgs[-1]["graph_ms_per_step"] = r["graph_ms_per_step"]
+                log("[bench] %s as a HIP graph of 20 steps: %.5f ms per step" % (name, r["graph_ms_per_step"]))
             log("[bench] %s: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)  butterfly adds at %.1f%% of VALU peak" % (
                 name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
                 100 * r["valu_frac_adds_only"]))

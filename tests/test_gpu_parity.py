@@ -338,3 +338,36 @@ def test_stream_copy(gpu):
     gpu.b.spinner_stream_copy(src, dst)
     t.cuda.synchronize()
     assert bool((src == dst).all())
+
+
+def test_captured_graph_replays_match_eager(gpu, oracle):
+    # the launch-bound small configuration is meant to be captured into a HIP graph: every replay, with eager
+    # work and synchronisations in between, must give the bits of the eager call
+    t, b = gpu.torch, gpu.b
+    n, batch = 256, 1024
+    x, d = _rng_case(n, batch, 4242)
+    xt = _to(gpu, x)
+    signs = b.spinner_pack_signs(_to(gpu, d[None]))
+    eager = b.spinner_apply_signs(xt, signs, n, "none", 1.0)
+    t.cuda.synchronize()
+    want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+    assert rel_l2_per_vector(eager.cpu().numpy(), want).max() <= REL_L2_TOL
+    out = t.zeros_like(eager)
+    side = t.cuda.Stream()
+    side.wait_stream(t.cuda.current_stream())
+    with t.cuda.stream(side):
+        b.spinner_apply_signs(xt, signs, n, "none", 1.0, out=out)
+    t.cuda.current_stream().wait_stream(side)
+    t.cuda.synchronize()
+    graph = t.cuda.CUDAGraph()
+    with t.cuda.graph(graph):
+        for _ in range(4):
+            b.spinner_apply_signs(xt, signs, n, "none", 1.0, out=out)
+    for rep in range(3):
+        out.fill_(float(rep))                      # eager work between replays
+        other = b.spinner_apply_signs(xt * 2.0, signs, n, "none", 1.0)
+        t.cuda.synchronize()
+        graph.replay()
+        t.cuda.synchronize()
+        assert t.equal(out, eager), rep
+        assert t.equal(other, eager * 2.0)         # exact: a power-of-two factor commutes with every rounding
