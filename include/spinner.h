@@ -138,6 +138,26 @@ int spinner_hash_signs(const float *x, int n, long batch, int L,
                        const void *signs, int *out_idx, void *stream);
 
 /*
+ * Stacked blocks (Section 3.2: independently constructed m x n spinners stacked
+ * vertically give a k x n matrix, k = L m, for k <= n and k > n alike; Section 5
+ * uses this when more random features than input dimensions are wanted).
+ * spinner_apply_blocks applies L independent triples to the same x and writes the
+ * L blocks side by side:
+ *   NONE    out[batch][L m]:   columns [l m, (l+1) m) hold scale * (first m rows of
+ *                              H D3 H D2 H D1 x) for triple l
+ *   COSSIN  out[batch][2 L m]: (1/sqrt(L m)) [cos block of L m | sin block of L m],
+ *                              triple l in columns [l m, (l+1) m) of either block
+ *   diag_sets  in   device fp32 [L][3][n], order d1, d2, d3 within a triple
+ *   workspace  in   spinner_blocks_workspace_bytes(n, batch, m, epilogue) bytes
+ * For L > 1, m must be a multiple of 4.  x is read once per block.  Otherwise as
+ * spinner_apply (which is the case L = 1).
+ */
+size_t spinner_blocks_workspace_bytes(int n, long batch, int m, int epilogue);
+int spinner_apply_blocks(const float *x, int n, long batch, int L,
+                         const float *diag_sets, int m, int epilogue, float scale,
+                         float *out, void *workspace, void *stream);
+
+/*
  * Angular-kernel features (Section 5, kernel approximation): the non-linear
  * map applied pointwise to the projection is the sign function, and the
  * kernel 1 - theta/pi between two inputs is estimated by 1 - d_H / d' from

@@ -25,6 +25,7 @@ What each function follows:
   The backward pass is the transpose of the layer's Jacobian written out with dense matrices:
   ``dx = scale * D1 H D2 H D3 H dy`` (H is symmetric) and, for each diagonal, the sum over the batch of
   (signal arriving at the diagonal from the output side) times (activation entering it from the input side).
+* ``apply_blocks``       - Section 3.2: independently constructed m x n blocks stacked vertically.
 * ``sketch`` / ``sketched_gram`` - the Newton-sketch use of the Supplement ("Additional experiments"):
   an m x n sketching matrix S (the first m rows of a spinner, scaled) applied to the columns of a
   weighted data matrix diag(w) A, and the d x d matrix (S diag(w) A)^T (S diag(w) A) that replaces the Hessian.
@@ -244,6 +245,19 @@ def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,
         return epilogue_cossin(y, m, scale)
     if epilogue == "signbits":
         return epilogue_signbits(y, m)
+    raise ValueError("unknown epilogue %r" % (epilogue,))
+
+
+def apply_blocks(x, diag_sets: np.ndarray, m: int, epilogue: str, scale: float, nthreads: int = 0) -> np.ndarray:
+    """Section 3.2: L independently constructed m x n blocks stacked vertically (k = L m rows).  Returns the
+    k coordinates, block after block ("none"), or (1/sqrt(k)) [cos of all k ; sin of all k] ("cossin")."""
+    diag_sets = np.ascontiguousarray(diag_sets, dtype=np.float32)
+    ys = [spinner(x, t[0], t[1], t[2], nthreads=nthreads)[:, :m] for t in diag_sets]
+    w = float(scale) * np.concatenate(ys, axis=-1)
+    if epilogue == "none":
+        return w
+    if epilogue == "cossin":
+        return np.concatenate([np.cos(w), np.sin(w)], axis=-1) / np.sqrt(float(w.shape[-1]))
     raise ValueError("unknown epilogue %r" % (epilogue,))
 
 

@@ -36,7 +36,7 @@ EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_
            "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram",
            "spinner_layer_saved_bytes", "spinner_layer_workspace_bytes", "spinner_layer_forward",
            "spinner_layer_backward", "spinner_sketch_workspace_bytes", "spinner_sketch", "spinner_sketch_gram",
-           "spinner_sketch_gram_workspace_bytes"]
+           "spinner_sketch_gram_workspace_bytes", "spinner_blocks_workspace_bytes", "spinner_apply_blocks"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -101,6 +101,11 @@ lib.spinner_sketch_gram.restype = ctypes.c_int
 lib.spinner_sketch_gram.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp]
 lib.spinner_sketch_gram_workspace_bytes.restype = ctypes.c_size_t
 lib.spinner_sketch_gram_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
+lib.spinner_blocks_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_blocks_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_long, ctypes.c_int, ctypes.c_int]
+lib.spinner_apply_blocks.restype = ctypes.c_int
+lib.spinner_apply_blocks.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_float, _vp, _vp, _vp]
 
 
 class SpinnerError(RuntimeError):
@@ -508,6 +513,39 @@ def spinner_sketch_gram(B, out=None, workspace=None, stream=None):
         raise ValueError("workspace too small")
     rc = lib.spinner_sketch_gram(B.data_ptr(), m, d, out.data_ptr(), workspace.data_ptr() if workspace is not None else None,
                                  _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out
+
+
+def spinner_apply_blocks(x, diag_sets, m=None, epilogue="none", scale=1.0, out=None, workspace=None, stream=None):
+    """L independent triples (diag_sets fp32 [L][3][n]) applied to the same x, their m-row blocks side by side:
+    out [batch][L m] (epilogue none) or [batch][2 L m] (cos block | sin block)."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    _check_tensor(diag_sets, "diag_sets", torch.float32)
+    batch, n = x.shape
+    if diag_sets.dim() != 3 or diag_sets.shape[1] != 3 or diag_sets.shape[2] != n:
+        raise ValueError("diag_sets must be [L][3][n]")
+    L = diag_sets.shape[0]
+    m = n if m is None else int(m)
+    epi = _epi(epilogue)
+    width = (2 * m if epi == SPINNER_EPI_COSSIN else m) * L
+    if out is None:
+        out = torch.empty((batch, width), dtype=torch.float32, device=x.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != batch * width:
+            raise ValueError("out has the wrong size")
+    need = int(lib.spinner_blocks_workspace_bytes(n, batch, m, epi))
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_apply_blocks(x.data_ptr(), n, batch, L, diag_sets.data_ptr(), m, epi, ctypes.c_float(scale),
+                                  out.data_ptr(), workspace.data_ptr() if workspace is not None else None,
+                                  _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out

@@ -105,19 +105,23 @@ size_t spinner_workspace_bytes(int n, long batch, int m, int epilogue)
 
 // Shared body of spinner_apply / spinner_apply_signs.  For n <= 2^14 `signs`
 // (if non-null) replaces d1..d3; above that size the caller passes fp32 diagonals.
+// blocks > 1: this call writes block `block` of a row that stacks `blocks` independent m-row blocks
+// (out already points at the block's first column; see spinner_apply_blocks).
 static int apply_impl(const float* x, int n, int log2n, long batch, const float* d1, const float* d2, const float* d3,
                       const unsigned long long* signs, int m, int epilogue, float scale, float* out,
-                      void* workspace, void* stream)
+                      void* workspace, void* stream, int blocks = 1)
 {
     using namespace spinner;
-    const size_t ws = spinner_workspace_bytes(n, batch, m, epilogue);
+    // a block of a stacked row never runs its passes in place: its output rows are wider than n
+    const size_t ws = (blocks > 1 && log2n > fused_max_log(epilogue)) ? (size_t)batch * (size_t)n * sizeof(float)
+                                                                      : spinner_workspace_bytes(n, batch, m, epilogue);
     if (ws && !workspace) return SPINNER_ERR_WORKSPACE;
     if (ws && !aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int epi = epilogue == SPINNER_EPI_COSSIN ? EPI_STORE_COSSIN : EPI_STORE_NONE;
     // row stride of the output: floats, or 64-bit words for sign codes
-    const long long out_stride = epilogue == SPINNER_EPI_COSSIN ? 2LL * m : (epilogue == kEpiSignBits ? m / 64 : (long long)m);
+    const long long out_stride = (epilogue == SPINNER_EPI_COSSIN ? 2LL * m : (epilogue == kEpiSignBits ? m / 64 : (long long)m)) * blocks;
     // n^{-3/2} * scale, formed in double and rounded once
     const double factor_d = (double)scale / ((double)n * sqrt((double)n));
 
@@ -125,7 +129,8 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     memset(&p, 0, sizeof(p));
     p.batch = batch;
     p.m = m;
-    p.inv_sqrt_m = (float)(1.0 / sqrt((double)m));
+    p.inv_sqrt_m = (float)(1.0 / sqrt((double)m * blocks));
+    p.sin_off = (long long)m * blocks;
     p.factor_rev = factor_d / 6.283185307179586476925286766559;
 
     if (log2n <= fused_max_log(epilogue)) {
@@ -494,6 +499,37 @@ int spinner_sketch_gram(const float* B, int m, int d, float* G, void* workspace,
     const hipError_t e = spinner::launch_sketch_gram(B, m, d, G, static_cast<float*>(workspace),
                                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+// ------------------------------------------------------------------ stacked independent blocks
+size_t spinner_blocks_workspace_bytes(int n, long batch, int m, int epilogue)
+{
+    // above the fused range every block runs its passes in the workspace (its output is a slice of wider rows)
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || batch <= 0 || m < 1 || m > n) return 0;
+    return log2n <= fused_max_log(epilogue) ? 0 : (size_t)batch * (size_t)n * sizeof(float);
+}
+
+int spinner_apply_blocks(const float* x, int n, long batch, int L, const float* diag_sets, int m, int epilogue, float scale,
+                         float* out, void* workspace, void* stream)
+{
+    int log2n;
+    const int rc = check_apply_args(x, n, batch, m, epilogue, out, &log2n);
+    if (rc != SPINNER_OK) return rc;
+    if (L < 1) return SPINNER_ERR_BAD_L;
+    if (L > 1 && (m & 3)) return SPINNER_ERR_BAD_M;
+    if (batch == 0) return SPINNER_OK;
+    if (!diag_sets) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(diag_sets)) return SPINNER_ERR_ALIGNMENT;
+    if (spinner_blocks_workspace_bytes(n, batch, m, epilogue) && !workspace) return SPINNER_ERR_WORKSPACE;
+    for (int l = 0; l < L; ++l) {
+        const float* d = diag_sets + (size_t)l * 3 * n;
+        // block l owns columns [l m, (l + 1) m) of the cos part (and of the sin part, L m further on)
+        const int r = apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, epilogue, scale,
+                                 out + (size_t)l * m, workspace, stream, L);
+        if (r != SPINNER_OK) return r;
+    }
+    return SPINNER_OK;
 }
 
 int spinner_stream_copy(const float* src, float* dst, size_t count, void* stream)

@@ -219,7 +219,8 @@ struct TileParams {
     int m;                    // coordinates kept by the epilogue
     float factor;             // n^{-3/2} * scale (or 1 for an intermediate pass)
     double factor_rev;        // factor / (2 pi), fp64: w in revolutions for the fp64 feature path
-    float inv_sqrt_m;         // COSSIN only
+    float inv_sqrt_m;         // COSSIN only: 1 / sqrt(number of features of the whole row)
+    long long sin_off;        // COSSIN only: distance from a cos entry to its sin entry (m for a single block)
 };
 
 enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1, EPI_STORE_SIGNBITS = 2 };
@@ -1001,7 +1002,8 @@ spinner_tile_kernel(TileParams p)
                     }
                 }
             } else {
-                // dst row is [cos block of m | sin block of m]
+                // dst row is [cos block | sin block]; the sin entry of coordinate i sits sin_off floats after its cos entry
+                const long long so = p.sin_off;
         #pragma unroll
                 for (int jh = 0; jh < RF / 4; ++jh) {
                     const long long i = tile_first + tile_offset<NT, C>(ebase | G::reg_index(LAYF, jh * 4), p.sl);
@@ -1012,16 +1014,16 @@ spinner_tile_kernel(TileParams p)
                         sn[k] *= p.inv_sqrt_m;
                         cs[k] *= p.inv_sqrt_m;
                     }
-                    if (full && (m & 3) == 0) {
+                    if (full && ((m | so) & 3) == 0) {
                         *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
-                        *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
-                    } else if (i + 3 < m && (m & 3) == 0) {
+                        *reinterpret_cast<float4*>(dst + so + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
+                    } else if (i + 3 < m && ((m | so | p.out_stride) & 3) == 0) {
                         *reinterpret_cast<float4*>(dst + i) = make_float4(cs[0], cs[1], cs[2], cs[3]);
-                        *reinterpret_cast<float4*>(dst + m + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
+                        *reinterpret_cast<float4*>(dst + so + i) = make_float4(sn[0], sn[1], sn[2], sn[3]);
                     } else {
         #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            if (i + k < m) { dst[i + k] = cs[k]; dst[m + i + k] = sn[k]; }
+                            if (i + k < m) { dst[i + k] = cs[k]; dst[so + i + k] = sn[k]; }
                     }
                 }
             }

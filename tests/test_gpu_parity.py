@@ -371,3 +371,40 @@ def test_captured_graph_replays_match_eager(gpu, oracle):
         t.cuda.synchronize()
         assert t.equal(out, eager), rep
         assert t.equal(other, eager * 2.0)         # exact: a power-of-two factor commutes with every rounding
+
+
+@pytest.mark.parametrize("n,m,L,epilogue,scale,batch", [(1024, 1024, 3, "none", 1.0, 21), (1024, 256, 4, "cossin", 32.0, 21),
+                                                        (4096, 4096, 2, "cossin", 64.0, 9), (4096, 1000, 3, "none", 2.0, 9),
+                                                        (1 << 15, 512, 2, "cossin", 8.0, 3), (1 << 17, 1 << 17, 2, "none", 1.0, 2),
+                                                        (1 << 17, 1024, 3, "none", 4.0, 2)])
+def test_stacked_blocks(gpu, oracle, n, m, L, epilogue, scale, batch):
+    # Section 3.2: L independently drawn m-row blocks side by side (k = L m may exceed n)
+    rng = np.random.default_rng(n + m + L)
+    x = rng.standard_normal((batch, n)).astype(np.float32)
+    if epilogue == "cossin":
+        x *= np.float32(4.0 / math.sqrt(n))            # keeps w = scale * y at a few radians
+    ds = W.rademacher_diagonals(n, 3 * L, 9000 + L + m).reshape(L, 3, n)
+    got = gpu.b.spinner_apply_blocks(_to(gpu, x), _to(gpu, ds), m, epilogue, scale)
+    gpu.torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    want = oracle.apply_blocks(x, ds, m, epilogue, scale)
+    assert got.shape == want.shape
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+    if L > 1 and n <= 4096:
+        # block l of the stacked call is what the single-triple call gives for triple l (up to the 1/sqrt(L) of the features)
+        one = _run_apply(gpu, x, ds[1], m, epilogue, scale)
+        if epilogue == "none":
+            assert np.array_equal(got[:, m:2 * m], one)
+        else:
+            assert np.allclose(got[:, m:2 * m] * math.sqrt(L), one[:, :m], rtol=1e-6, atol=1e-7)
+
+
+def test_stacked_blocks_errors(gpu):
+    b, t = gpu.b, gpu.torch
+    x = t.zeros((2, 256), dtype=t.float32, device=gpu.dev)
+    ds = t.ones((2, 3, 256), dtype=t.float32, device=gpu.dev)
+    with pytest.raises(b.SpinnerError) as e:
+        b.spinner_apply_blocks(x, ds, 30, "none", 1.0)          # L > 1 needs m % 4 == 0
+    assert e.value.status == b.SPINNER_ERR_BAD_M
+    assert tuple(b.spinner_apply_blocks(x, ds[:1], 30, "none", 1.0).shape) == (2, 30)
+    assert tuple(b.spinner_apply_blocks(x[:0], ds, 32, "cossin", 1.0).shape) == (0, 128)

@@ -266,3 +266,38 @@ def test_angular_estimate_approaches_the_angular_kernel(oracle):
     exact = 1.0 - thetas / math.pi
     # binomial standard deviation of the estimate: sqrt(p (1 - p) / (n * triples)) <= 0.004
     assert np.max(np.abs(est - exact)) < 0.02, (est, exact)
+
+
+# ------------------------------------------------------------------ stacked blocks (Section 3.2)
+def test_stacked_blocks_are_the_stacked_dense_matrix(oracle):
+    n, m, L = 64, 16, 3
+    rng = np.random.Generator(np.random.PCG64(31))
+    x = rng.standard_normal((7, n)).astype(np.float32)
+    ds = _rademacher(rng, (L, 3, n))
+    H = scipy.linalg.hadamard(n) / 8.0
+    stacked = np.concatenate([(H @ np.diag(t[2]) @ H @ np.diag(t[1]) @ H @ np.diag(t[0]))[:m] for t in ds])   # [L m][n]
+    got = oracle.apply_blocks(x, ds, m, "none", 2.0)
+    assert got.shape == (7, L * m)
+    assert np.allclose(got, 2.0 * x.astype(np.float64) @ stacked.T, atol=1e-12)
+    # one block is the plain call
+    assert np.array_equal(oracle.apply_blocks(x, ds[:1], m, "none", 2.0), oracle.apply(x, ds[0, 0], ds[0, 1], ds[0, 2], m, "none", 2.0))
+    f = oracle.apply_blocks(x, ds, m, "cossin", 3.0)
+    assert f.shape == (7, 2 * L * m)
+    assert np.allclose(np.linalg.norm(f, axis=1), 1.0, atol=1e-12)
+    w = 3.0 * x.astype(np.float64) @ stacked.T
+    assert np.allclose(f[:, : L * m], np.cos(w) / math.sqrt(L * m), atol=1e-12)
+    assert np.allclose(f[:, L * m:], np.sin(w) / math.sqrt(L * m), atol=1e-12)
+
+
+def test_more_features_than_dimensions_sharpen_the_kernel_estimate(oracle):
+    # Section 5: k > n random features through stacked blocks; the Gaussian-kernel estimate error falls like 1/sqrt(k)
+    n, sigma = 64, 1.0
+    rng = np.random.Generator(np.random.PCG64(32))
+    x = rng.standard_normal((40, n)).astype(np.float32) * 0.15
+    exact = np.exp(-((x[:, None, :].astype(np.float64) - x[None, :, :]) ** 2).sum(-1) / (2 * sigma ** 2))
+    errs = []
+    for L in (1, 16):
+        ds = W.rademacher_diagonals(n, 3 * L, 500 + L).reshape(L, 3, n)
+        f = oracle.apply_blocks(x, ds, n, "cossin", math.sqrt(n) / sigma)
+        errs.append(np.linalg.norm(f @ f.T - exact) / np.linalg.norm(exact))
+    assert errs[1] < 0.5 * errs[0], errs
