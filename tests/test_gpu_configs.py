@@ -128,3 +128,86 @@ def test_cfg5_large_n2p20(gpu, oracle):
     # stays below log(n)/sqrt(n); the full spinner output is balanced as well
     ymax = (y.abs().max(dim=1).values.double() / _norms(x)).max()
     assert float(ymax) <= math.log(w.n) / math.sqrt(w.n)
+
+
+# ------------------------------------------------------------------ the rows beyond the five configurations, at the sizes bench.py times
+def test_next_angular_n4096_full_size(gpu, oracle):
+    from helpers import check_sign_bits, unpack_sign_codes
+
+    w = W.NEXT["next_angular_n4096"]
+    x = W.make_x_torch(w, gpu.dev)
+    ds = W.diag_sets(w)
+    signs = gpu.b.spinner_pack_signs(gpu.torch.from_numpy(ds).to(gpu.dev))
+    codes = gpu.b.spinner_sign_codes_signs(x, signs, w.m)
+    gpu.torch.cuda.synchronize()
+    assert tuple(codes.shape) == (w.batch, w.m // 64)
+    rows = W.sample_rows(w.batch, w.oracle_rows, w.seed)
+    idx = gpu.torch.from_numpy(rows).to(gpu.dev)
+    xs = x[idx].cpu().numpy()
+    y = oracle.spinner(xs, ds[0, 0], ds[0, 1], ds[0, 2])
+    check_sign_bits(unpack_sign_codes(codes[idx].cpu().numpy(), w.m), y, w.m)
+    # size-independent property on the whole output: about half the bits are set in every code (balanced rows)
+    v = codes.view(gpu.torch.int32)
+    v = v - ((v >> 1) & 0x55555555)
+    v = (v & 0x33333333) + ((v >> 2) & 0x33333333)
+    v = (v + (v >> 4)) & 0x0F0F0F0F
+    ones = ((v * 0x01010101) >> 24) & 0xFF            # popcount of every 32-bit half word
+    frac = ones.sum(dim=1).double() / w.m
+    assert float((frac - 0.5).abs().max()) < 0.06       # binomial: 4 sigma = 4 * 0.5 / sqrt(4096) = 0.031
+
+
+def test_adaptive_layer_full_size(gpu, oracle):
+    # the shape bench.py times: n = 4096, batch 65536; sampled rows for y and dx, all of dd through linearity
+    t, b = gpu.torch, gpu.b
+    n, batch = 4096, 65536
+    g = t.Generator(device=gpu.dev)
+    g.manual_seed(20260)
+    x = t.randn((batch, n), generator=g, device=gpu.dev, dtype=t.float32)
+    dy = t.randn((batch, n), generator=g, device=gpu.dev, dtype=t.float32)
+    d = 1.0 + 0.5 * t.randn((3, n), generator=g, device=gpu.dev, dtype=t.float32)
+    y, saved = b.spinner_layer_forward(x, d[0], d[1], d[2], 1.0)
+    dx, dd = b.spinner_layer_backward(dy, x, saved, d[0], d[1], d[2], 1.0)
+    t.cuda.synchronize()
+    rows = W.sample_rows(batch, 16, 99)
+    idx = t.from_numpy(rows).to(gpu.dev)
+    dn = d.cpu().numpy()
+    xs, dys = x[idx].cpu().numpy(), dy[idx].cpu().numpy()
+    wy, _, _ = oracle.layer_forward(xs, dn[0], dn[1], dn[2], 1.0)
+    wdx, _ = oracle.layer_backward(xs, dn[0], dn[1], dn[2], dys, 1.0)
+    assert rel_l2_per_vector(y[idx].cpu().numpy(), wy).max() <= REL_L2_TOL
+    assert rel_l2_per_vector(dx[idx].cpu().numpy(), wdx).max() <= REL_L2_TOL
+    # the layer is linear in each diagonal, so sum_i d_k[i] dd_k[i] = <dy, y> over the whole batch, for every k
+    inner = float((dy.double() * y.double()).sum())
+    for k in range(3):
+        got = float((d[k].double() * dd[k].double()).sum())
+        assert abs(got - inner) <= 1e-5 * abs(inner) + 1e-2 * math.sqrt(batch * n), (k, got, inner)
+    # and the batch sum is additive: the gradient of the whole batch is the sum of the gradients of its two halves
+    h = batch // 2
+    _, dd_a = b.spinner_layer_backward(dy[:h], x[:h], saved.view(2, batch, n)[:, :h].contiguous(), d[0], d[1], d[2], 1.0)
+    _, dd_b = b.spinner_layer_backward(dy[h:], x[h:], saved.view(2, batch, n)[:, h:].contiguous(), d[0], d[1], d[2], 1.0)
+    t.cuda.synchronize()
+    num = (dd_a.double() + dd_b.double() - dd.double()).norm(dim=1)
+    assert float((num / dd.double().norm(dim=1)).max()) <= REL_L2_TOL
+
+
+def test_newton_sketch_bench_size(gpu, oracle):
+    # n = 2^16, d = 512, m = 2048 as in bench.py; the O(n^2) oracle checks a few columns, the Gram matrix all of B
+    n, d, m = 1 << 16, 512, 2048
+    A, wts = W.newton_sketch_problem(n, d, 31337)
+    dg = W.rademacher_diagonals(n, 3, 31338)
+    scale = math.sqrt(n / m)
+    At = gpu.torch.from_numpy(A).to(gpu.dev)
+    B = gpu.b.spinner_sketch(At, gpu.torch.from_numpy(wts).to(gpu.dev), *[gpu.torch.from_numpy(dg[k]).to(gpu.dev) for k in range(3)],
+                             m, scale)
+    G = gpu.b.spinner_sketch_gram(B)
+    gpu.torch.cuda.synchronize()
+    cols = np.array([0, 1, 255, 300, 511])
+    want = oracle.sketch(A[:, cols], wts, dg[0], dg[1], dg[2], m, scale)
+    Bn = B.cpu().numpy()
+    assert rel_l2_per_vector(Bn[:, cols].T, want.T).max() <= REL_L2_TOL
+    Gw = oracle.sketched_gram(Bn)
+    assert np.linalg.norm(G.cpu().numpy() - Gw) <= 1e-5 * np.linalg.norm(Gw)
+    # the sketched Hessian approximates A^T W A: relative error of order sqrt(d / m) (loose bound)
+    WA = (A * wts[:, None]).astype(np.float64)
+    exact = WA.T @ WA
+    assert np.linalg.norm(Gw - exact) / np.linalg.norm(exact) < 0.5
