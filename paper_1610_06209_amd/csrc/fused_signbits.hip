@@ -11,7 +11,7 @@ namespace spinner {
 #endif
 template <int NT>
 using GeomCode = TileGeom<NT, clamp_rmax(NT, (Tuning<float, NT>::rmax < NT - 6 ? (Tuning<float, NT>::rmax < SPINNER_CODE_RMAX ? Tuning<float, NT>::rmax : SPINNER_CODE_RMAX) : NT - 6)),
-                          Tuning<float, NT>::waves, false, Tuning<float, NT>::min_waves>;
+                          Tuning<float, NT>::waves, Tuning<float, NT>::min_waves>;
 
 template <int NT, bool SIGNS, int PRUNE>
 static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStream_t stream)
@@ -21,7 +21,7 @@ static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStre
     const long long blocks = (tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((spinner_tile_kernel<float, G, NT, 3, true, EPI_STORE_SIGNBITS, SIGNS, false, PRUNE>),
+    hipLaunchKernelGGL((spinner_tile_kernel<float, G, NT, 3, true, EPI_STORE_SIGNBITS, SIGNS, PRUNE>),
                        dim3((unsigned)blocks), dim3(G::THREADS), 0, stream, p);
     return hipGetLastError();
 }

@@ -40,26 +40,11 @@ template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4,
 template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4, min_waves = 4; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
 template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4, min_waves = 0; };   // 16 waves per tile
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, (SPINNER_USE_MFMA != 0), Tuning<T, NT>::min_waves>;
+using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, Tuning<T, NT>::min_waves>;
 #else   // uniform override used by tuning sweeps
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
 #endif
-
-// How many workgroups of a kernel can be resident on the whole device (cached per kernel).
-template <typename K>
-inline long long resident_workgroups(K kernel, int threads)
-{
-    static long long cached = 0;
-    if (cached == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) return 0;
-        cached = (long long)cus * (per_cu > 0 ? per_cu : 1);
-    }
-    return cached;
-}
 
 template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
@@ -68,17 +53,7 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-#if SPINNER_PERSIST
-    if (PRUNE == 0) {
-        auto kernel = spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, true, 0>;
-        const long long resident = resident_workgroups(kernel, G::THREADS);
-        if (resident > 0 && blocks >= 2 * resident) {      // enough tiles for every workgroup to loop
-            hipLaunchKernelGGL(kernel, dim3((unsigned)resident), dim3(G::THREADS), 0, stream, p);
-            return hipGetLastError();
-        }
-    }
-#endif
-    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, false, PRUNE>), dim3((unsigned)blocks),
+    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, PRUNE>), dim3((unsigned)blocks),
                        dim3(G::THREADS), 0, stream, p);
     return hipGetLastError();
 }

@@ -6,7 +6,7 @@ namespace spinner {
 // value in registers beside the signal itself
 constexpr int layer_rmax(int nt) { return nt <= 5 ? 2 : (nt <= 9 ? 3 : (nt <= 12 ? 4 : 5)); }
 template <int NT>
-using LayerGeom = TileGeom<NT, layer_rmax(NT), 4, false, 0>;
+using LayerGeom = TileGeom<NT, layer_rmax(NT), 4>;
 
 // dd[i] = factor * sum over slots of partial[slot][i], summed in fp64 in a fixed order.  A block owns 16
 // columns; its 16 slot lanes walk the slots with stride 16 and are then added up through LDS.

@@ -67,7 +67,6 @@ __device__ __forceinline__ void layer_ctx(ThreadCtx<G>& c, long long& slot)
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
-    init_h16_operand(c, lane);
 }
 
 // One vector per tile.  The held values carry the tracked lane sign after an odd number of

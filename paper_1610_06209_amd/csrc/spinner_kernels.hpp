@@ -33,12 +33,6 @@
 #ifndef SPINNER_LANE_CHUNK            // registers exchanged per batch in swizzle / bpermute stages (0: all at once)
 #define SPINNER_LANE_CHUNK 32
 #endif
-#ifndef SPINNER_USE_MFMA             // 1: two register bits + lane bits 4,5 go through the fp32 matrix pipe
-#define SPINNER_USE_MFMA 0
-#endif
-#ifndef SPINNER_PERSIST              // 1: persistent workgroups that prefetch their next tile
-#define SPINNER_PERSIST 0
-#endif
 #ifndef SPINNER_LDS_HALVES           // 2: transposes go through an LDS buffer of half a tile, in two trips
 #define SPINNER_LDS_HALVES 1
 #endif
@@ -151,7 +145,7 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //                     lane bits (only used when a tile spans several waves)
 // Lanes hold bits 2 .. 2+LB-1 in both layouts.
 // MINW_: occupancy (waves per SIMD) the register allocator must allow; 0 leaves it to the knobs above
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, bool MFMA_ = (SPINNER_USE_MFMA != 0), int MINW_ = 0>
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0>
 struct TileGeom {
     static constexpr int MIN_WAVES = MINW_;
     static constexpr int NT = NT_;
@@ -165,8 +159,6 @@ struct TileGeom {
     // one transpose per transform must bring every wave-held bit into a register bit
     static_assert(WB <= r - 2, "too few registers per thread for this many waves per tile");
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
-    // H16 blocks on the matrix pipe need a whole wave per tile and two spare register bits
-    static constexpr bool MFMA = MFMA_ && LB == 6 && r >= 4;
     // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
     // (tiles above 2^14 elements always take as many trips as keep the buffer at 64 KiB)
     static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : ((SPINNER_LDS_HALVES == 2 && WB >= 1) ? 2 : 1);
@@ -243,7 +235,6 @@ struct ThreadCtx {
     int lit;        // lane within tile
     int wv;         // wave bits of the tile index held by this thread
     float sg[6];    // +1 / -1 by lane bit: sign of the own value in a lane butterfly
-    float ha[4];    // this lane's entries of the (row-permuted) H16 operand, one per k-block
     __device__ __forceinline__ int base_index(int lay) const
     {
         int e = lit << 2;
@@ -260,16 +251,6 @@ struct ThreadCtx {
         return e;
     }
 };
-
-template <typename G>
-__device__ __forceinline__ void init_h16_operand(ThreadCtx<G>& c, int lane)
-{
-    const int i = lane & 15;
-    const int row = ((i & 3) << 2) | (i >> 2);          // permuted row 4a+b -> 4b+a
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-        c.ha[kb] = (__builtin_popcount(row & (4 * kb + (lane >> 4))) & 1) ? -1.0f : 1.0f;
-}
 
 // ------------------------------------------------------------------ butterflies
 // RL: number of leading registers that are still needed (all R unless the last round is pruned)
@@ -423,44 +404,18 @@ __device__ __forceinline__ void lane_swap_stage(T (&v)[R])
 // data between waves: register bits and lane bits at index positions >= CB.
 // SKIP_WAVE_OWNED: skip register bits that the *other* layout's waves hold
 // (those are finished after the transpose instead, so do not do them twice).
-// Four butterfly stages at once on the fp32 matrix pipe: the 16-point transform over
-// the two highest register bits (k-block kb) and lane bits 4,5, for each of the 16
-// columns lane%16, as D = A_0 X_0 + .. + A_3 X_3 with v_mfma_f32_16x16x4_f32.  The B
-// operand of k-block kb is register kb as it stands (lane l holds row 4 kb + l/16,
-// column l%16).  The instruction returns row 4 (l/16) + v in result register v; with
-// the rows of H16 permuted by 4a+b -> 4b+a in the A operand, result register v of
-// lane-group l/16 is transform coefficient 4 v + l/16, i.e. it lands exactly where
-// the butterfly network would have left it.  The matrix pipe runs beside the vector
-// ALU, which is the unit this kernel saturates.
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-template <typename G>
-__device__ __forceinline__ void mfma_stage(float (&v)[G::R], const ThreadCtx<G>& c)
-{
-    constexpr int Q = G::R / 4;
-#pragma unroll
-    for (int jl = 0; jl < Q; ++jl) {
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(c.ha[kb], v[jl + kb * Q], acc, 0, 0, 0);
-        v[jl] = acc[0]; v[jl + Q] = acc[1]; v[jl + 2 * Q] = acc[2]; v[jl + 3 * Q] = acc[3];
-    }
-}
-
 // NEGATE selects the coefficient set of the tracked-sign butterflies (true in
 // every second transform of a kernel, see lane_stage_fmac_dpp).
 template <typename G, int CB, int LAY, bool NEGATE, bool SWAP = false, typename T>
 __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
-    constexpr bool MF = G::MFMA && std::is_same<T, float>::value;
-    static_assert(!SWAP || (!MF && CB <= G::lane_pos(4)), "lane swaps: lane bits 4 and 5 must be transformed, without the matrix pipe");
+    static_assert(!SWAP || CB <= G::lane_pos(4), "lane swaps: lane bits 4 and 5 must be among the transformed ones");
     static_for<0, G::r>([&](auto q) {
-        if constexpr (G::reg_pos(LAY, q.value) >= CB && !(MF && q.value >= G::r - 2) && !(SPINNER_EXPERIMENT_KNOCKOUT & 4))
+        if constexpr (G::reg_pos(LAY, q.value) >= CB && !(SPINNER_EXPERIMENT_KNOCKOUT & 4))
             reg_stage<q.value>(v);
     });
-    if constexpr (MF) mfma_stage<G>(v, c);
     static_for<0, G::LB>([&](auto b) {
-        if constexpr (G::lane_pos(b.value) >= CB && !(MF && b.value >= 4) && !(SWAP && b.value >= 4)) {
+        if constexpr (G::lane_pos(b.value) >= CB && !(SWAP && b.value >= 4)) {
             if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) {
                 if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 2))
                     lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
@@ -691,7 +646,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 #ifndef SPINNER_LANE_SWAPS_F64
 #define SPINNER_LANE_SWAPS_F64 1
 #endif
-    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(4) && !G::MFMA;
+    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(4);
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
     if constexpr (G::WB > 0) {
         if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
@@ -830,7 +785,7 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE, EPI_STORE_COSSIN (applied with p.factor, limit p.m) or EPI_STORE_SIGNBITS
 //         (p.out holds 64-bit code words, p.out_stride counts words, p.m is a multiple of 256)
-template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, bool PERSIST, int PRUNE = 0>
+template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, int PRUNE = 0>
 __global__ void __launch_bounds__(G::THREADS)
 __attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_WAVES ? G::MIN_WAVES : (G::WB ? SPINNER_MIN_WAVES_MULTI : SPINNER_MIN_WAVES_PER_EU))))
 spinner_tile_kernel(TileParams p)
@@ -856,58 +811,37 @@ spinner_tile_kernel(TileParams p)
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
-    init_h16_operand(c, lane);
 
     const long long total = p.batch << p.tiles_per_vec_log;
-    // A persistent workgroup walks over tiles tile, tile + stride, ... and issues the loads
-    // of its next tile before it starts computing the current one, so HBM latency is paid
-    // while the vector ALU is busy rather than by occupancy alone.
-    const long long stride = PERSIST ? (long long)gridDim.x * G::TILES_PER_WG : 0;
-    long long wg_first = (long long)blockIdx.x * G::TILES_PER_WG;      // lowest tile of this workgroup
 
     __shared__ float4 lds_store[(std::is_same<T, float>::value || G::WB == 0) ? G::LDS_FLOAT4 : (1 << NT) / 4];
     float4* lds = lds_store;
 
-    auto locate = [&](long long t, long long& vec, long long& q) {
-        vec = 0; q = 0;
-        if (t < total) {
-            if (p.tiles_per_vec_log == 0) { vec = t; }
-            else { q = t / p.batch; vec = t - q * p.batch; }   // neighbours share the diagonal block
-        }
-    };
-    float4 nx[R / 4];
-    auto issue_loads = [&](long long t) {
-        long long vec, q;
-        locate(t, vec, q);
-        const float* src = p.x + vec * p.in_stride + (q << p.tb) + tile_offset<NT, C>(c.base_index(0), p.sl);
-#pragma unroll
-        for (int jh = 0; jh < R / 4; ++jh) {
-            nx[jh] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t < total) nx[jh] = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
-        }
-    };
-    issue_loads(tile);
-
-    for (;;) {
+    {
         const bool active = tile < total;
-        long long vec, q;
-        locate(tile, vec, q);
+        long long vec = 0, q = 0;
+        if (active) {
+            if (p.tiles_per_vec_log == 0) { vec = tile; }
+            else { q = tile / p.batch; vec = tile - q * p.batch; }   // neighbours share the diagonal block
+        }
         const long long tile_first = q << p.tb;      // first element of the tile inside its vector
 
         T v[R];
+        {
+            const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(0), p.sl);
 #pragma unroll
-        for (int jh = 0; jh < R / 4; ++jh) {
-            v[jh * 4] = (T)nx[jh].x; v[jh * 4 + 1] = (T)nx[jh].y; v[jh * 4 + 2] = (T)nx[jh].z; v[jh * 4 + 3] = (T)nx[jh].w;
-        }
-        if constexpr (PERSIST) {
-            if (wg_first + stride < total) issue_loads(tile + stride);
+            for (int jh = 0; jh < R / 4; ++jh) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
+                v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
+            }
         }
 
         // steps (layout alternates only when a tile spans several waves)
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
         if (p.m < 0)      // never true: keeps the code but skips it (memory-shape experiment)
 #endif
-        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, !PERSIST, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
         if (p.m < 0)
 #endif
@@ -923,7 +857,7 @@ spinner_tile_kernel(TileParams p)
             else
                 spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
         }
-        static_assert(PRUNE == 0 || (NSTEPS == 3 && std::is_same<T, float>::value && !PERSIST), "pruning: fused fp32 kernels only");
+        static_assert(PRUNE == 0 || (NSTEPS == 3 && std::is_same<T, float>::value), "pruning: fused fp32 kernels only");
         constexpr int RF = PRUNE > 0 ? pruned_final_regs<G>(G::layout_after(2), PRUNE) : R;   // registers that hold outputs
 
         constexpr int LAYF = G::layout_after(NSTEPS);
@@ -1028,11 +962,6 @@ spinner_tile_kernel(TileParams p)
                 }
             }
         }   // active
-
-        if constexpr (!PERSIST) break;
-        wg_first += stride;
-        tile += stride;
-        if (wg_first >= total) break;
     }
 }
 
@@ -1071,7 +1000,6 @@ spinner_hash_kernel(HashParams p)
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
-    init_h16_operand(c, lane);
     const bool active = vec < p.batch;
 
     __shared__ float4 lds_store[G::LDS_FLOAT4];
