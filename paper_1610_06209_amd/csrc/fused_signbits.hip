@@ -9,14 +9,16 @@ namespace spinner {
 #ifndef SPINNER_CODE_RMAX       // tuning experiments: cap on the values per thread (log2) of the sign-code kernels
 #define SPINNER_CODE_RMAX 6
 #endif
-template <int NT>
-using GeomCode = TileGeom<NT, clamp_rmax(NT, (Tuning<float, NT>::rmax < NT - 6 ? (Tuning<float, NT>::rmax < SPINNER_CODE_RMAX ? Tuning<float, NT>::rmax : SPINNER_CODE_RMAX) : NT - 6)),
-                          Tuning<float, NT>::waves, Tuning<float, NT>::min_waves>;
+template <typename TU, int NT>
+using GeomCodeFrom = TileGeom<NT, clamp_rmax(NT, (TU::rmax < NT - 6 ? (TU::rmax < SPINNER_CODE_RMAX ? TU::rmax : SPINNER_CODE_RMAX) : NT - 6)),
+                              TU::waves, TU::min_waves, TU::trips>;
+template <int NT, bool PRUNED>
+using GeomCode = std::conditional_t<PRUNED, GeomCodeFrom<PrunedTuning<float, NT>, NT>, GeomCodeFrom<Tuning<float, NT>, NT>>;
 
 template <int NT, bool SIGNS, int PRUNE>
 static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStream_t stream)
 {
-    using G = GeomCode<NT>;
+    using G = GeomCode<NT, (PRUNE > 0)>;
     static_assert(G::TILES_PER_WG >= 1 && G::LB == 6, "one tile per wave or several waves per tile");
     const long long blocks = (tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;

@@ -20,28 +20,39 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 #ifndef SPINNER_RMAX_F64
 #define SPINNER_RMAX_F64 5
 #endif
-template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0; };
+template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0, trips = 0; };
 #ifndef SPINNER_RMAX_F32
 #ifndef SPINNER_RMAX_F64_N12
 #define SPINNER_RMAX_F64_N12 4
 #endif
-template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64_N12, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 7> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1, min_waves = 0; };
-template <> struct Tuning<float, 12> { static constexpr int rmax = 4, waves = 4, min_waves = 0; };   // 4 waves per tile, 16 KiB LDS
-template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 14> { static constexpr int rmax = 5, waves = 4, min_waves = 0; };
-template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4, min_waves = 4; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
-template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4, min_waves = 0; };   // 16 waves per tile
+template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64_N12, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 7> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 12> { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };   // 4 waves per tile, 16 KiB LDS
+template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
+// n = 2^14: four waves of 64 values per tile, held to 128 registers, exchanging through half-size LDS buffers:
+// four tiles share a compute unit (two with 32 values on eight waves and a whole-tile buffer); measured +5 %
+template <> struct Tuning<float, 14> { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 2; };
+template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 0; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
+template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4, min_waves = 0, trips = 0; };   // 16 waves per tile
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, Tuning<T, NT>::min_waves>;
+using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, Tuning<T, NT>::min_waves, Tuning<T, NT>::trips>;
+// the pruned last round exchanges whole tiles: its kernels keep a whole-tile buffer
+template <typename T, int NT> struct PrunedTuning : Tuning<T, NT> {};
+template <> struct PrunedTuning<float, 14> { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
+template <typename T, int NT>
+using PrunedGeomFor = TileGeom<NT, PrunedTuning<T, NT>::rmax, PrunedTuning<T, NT>::waves, PrunedTuning<T, NT>::min_waves, PrunedTuning<T, NT>::trips>;
 #else   // uniform override used by tuning sweeps
+template <typename T, int NT> struct PrunedTuning { static constexpr int rmax = clamp_rmax(NT, SPINNER_RMAX_F32), waves = SPINNER_WAVES_PER_WG, min_waves = 0, trips = 0; };
+template <typename T, int NT> struct Tuning : PrunedTuning<T, NT> {};
+template <typename T, int NT>
+using PrunedGeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
 #endif
@@ -49,7 +60,7 @@ using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPI
 template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
-    using G = GeomFor<T, NT>;
+    using G = std::conditional_t<(PRUNE > 0), PrunedGeomFor<T, NT>, GeomFor<T, NT>>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;

@@ -145,7 +145,8 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //                     lane bits (only used when a tile spans several waves)
 // Lanes hold bits 2 .. 2+LB-1 in both layouts.
 // MINW_: occupancy (waves per SIMD) the register allocator must allow; 0 leaves it to the knobs above
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0>
+// TRIPS_: 2 sends the exchanges of a tile of up to 2^14 elements through an LDS buffer of half the tile, in two trips
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0, int TRIPS_ = 0>
 struct TileGeom {
     static constexpr int MIN_WAVES = MINW_;
     static constexpr int NT = NT_;
@@ -161,7 +162,7 @@ struct TileGeom {
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
     // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
     // (tiles above 2^14 elements always take as many trips as keep the buffer at 64 KiB)
-    static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : ((SPINNER_LDS_HALVES == 2 && WB >= 1) ? 2 : 1);
+    static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : (((SPINNER_LDS_HALVES == 2 || TRIPS_ == 2) && WB >= 1) ? 2 : 1);
     static constexpr int LDS_FLOAT4 = WB > 0 ? ((1 << NT_) / 4) / LDS_HALVES : 1;
     static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
