@@ -9,14 +9,12 @@ namespace spinner {
                                         : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false, kPruneBits>(p, tiles, s);
 hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s)
 {
-#if SPINNER_LDS_HALVES != 2      // the pruned round uses the whole-tile exchange
     if (prune >= kPruneBits) {
         switch (log2n) {
             PCASE(8) PCASE(9) PCASE(10) PCASE(11) PCASE(12) PCASE(13) PCASE(14)
         default: break;
         }
     }
-#endif
     switch (log2n) {
         CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14)
         CASE(15) CASE(16)

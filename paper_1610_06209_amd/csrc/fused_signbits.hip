@@ -33,14 +33,12 @@ static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStre
                                         : launch_code_tile<NT, false, kPruneBits>(p, tiles, s);
 hipError_t launch_fused_signbits(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s)
 {
-#if SPINNER_LDS_HALVES != 2      // the pruned round uses the whole-tile exchange
     if (prune >= kPruneBits) {
         switch (log2n) {
             PCASE(12) PCASE(13) PCASE(14)
         default: break;
         }
     }
-#endif
     switch (log2n) {
         CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
     default: return hipErrorInvalidValue;

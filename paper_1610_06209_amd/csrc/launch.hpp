@@ -43,9 +43,8 @@ template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4,
 template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4, min_waves = 0, trips = 0; };   // 16 waves per tile
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, Tuning<T, NT>::min_waves, Tuning<T, NT>::trips>;
-// the pruned last round exchanges whole tiles: its kernels keep a whole-tile buffer
+// geometry of the kernels whose last round is pruned (a separate table so that it can be tuned apart)
 template <typename T, int NT> struct PrunedTuning : Tuning<T, NT> {};
-template <> struct PrunedTuning<float, 14> { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
 template <typename T, int NT>
 using PrunedGeomFor = TileGeom<NT, PrunedTuning<T, NT>::rmax, PrunedTuning<T, NT>::waves, PrunedTuning<T, NT>::min_waves, PrunedTuning<T, NT>::trips>;
 #else   // uniform override used by tuning sweeps

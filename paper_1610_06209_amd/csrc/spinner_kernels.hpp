@@ -488,7 +488,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
         }
         if constexpr (SPINNER_SYNC_AFTER_READ != 0) __syncthreads();   // buffer free for the next exchange
     } else {
-        static_assert(G::LDS_HALVES == 1 || (RW == 0 && RR == 0), "pruned rounds use the whole-tile exchange");
+        static_assert(G::LDS_HALVES <= 2 || (RW == 0 && RR == 0), "pruned rounds exchange in one or two trips");
         // Several trips through an LDS buffer of a half (quarter) of the tile: trip h moves
         // registers 4k+2h, 4k+2h+1 (register 4k+h) of every thread, i.e. the elements with a
         // given value of index bit 1 (bits 1..0): 8 (4) bytes per lane, consecutive lanes on
@@ -503,16 +503,18 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
             for (int h = 0; h < 2; ++h) {
                 if (h == 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
 #pragma unroll
-                for (int jh = 0; jh < G::R / 4; ++jh) {
+                for (int jh = 0; jh < NW / 4; ++jh) {
                     const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
                     lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
                 }
                 __syncthreads();
+                if (reads) {
 #pragma unroll
-                for (int jh = 0; jh < G::R / 4; ++jh) {
-                    const int e = et | G::reg_index(TO, jh * 4);
-                    const float2 t = lds2[e >> 2];
-                    v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
+                    for (int jh = 0; jh < NR / 4; ++jh) {
+                        const int e = et | G::reg_index(TO, jh * 4);
+                        const float2 t = lds2[e >> 2];
+                        v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
+                    }
                 }
             }
         } else {
