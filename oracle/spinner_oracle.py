@@ -25,6 +25,9 @@ What each function follows:
   The backward pass is the transpose of the layer's Jacobian written out with dense matrices:
   ``dx = scale * D1 H D2 H D3 H dy`` (H is symmetric) and, for each diagonal, the sum over the batch of
   (signal arriving at the diagonal from the output side) times (activation entering it from the input side).
+* ``struct_matrix`` / ``struct_apply`` - the members G_struct D2 H D1 of the family (Lemma 1 and the remark after
+  it; Theorem 3; Section 5 experiments): G_struct a Gaussian circulant, skew-circulant, Toeplitz or Hankel matrix,
+  written out densely from its generating vector.
 * ``apply_blocks``       - Section 3.2: independently constructed m x n blocks stacked vertically.
 * ``sketch`` / ``sketched_gram`` - the Newton-sketch use of the Supplement ("Additional experiments"):
   an m x n sketching matrix S (the first m rows of a spinner, scaled) applied to the columns of a
@@ -246,6 +249,43 @@ def apply(x, d1, d2, d3, m: int, epilogue: str, scale: float,
     if epilogue == "signbits":
         return epilogue_signbits(y, m)
     raise ValueError("unknown epilogue %r" % (epilogue,))
+
+
+STRUCT_KINDS = ("circulant", "skew_circulant", "toeplitz", "hankel")
+
+
+def struct_matrix(kind: str, params, n: int) -> np.ndarray:
+    """Dense n x n structured matrix from its generating vector (fp64).
+
+    circulant       params g[n]:     row 0 is g, each next row is the previous one shifted right cyclically
+                                     (Section 3, notation): G[i][j] = g[(j - i) mod n]
+    skew_circulant  params g[n]:     the same, but an entry that wraps around changes sign
+    toeplitz        params t[2n-1]:  constant along diagonals, G[i][j] = t[j - i + n - 1]
+    hankel          params h[2n-1]:  constant along anti-diagonals, G[i][j] = h[i + j]"""
+    p = np.asarray(params, dtype=np.float64)
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    if kind == "circulant":
+        assert p.shape == (n,)
+        return p[(j - i) % n]
+    if kind == "skew_circulant":
+        assert p.shape == (n,)
+        return np.where(j >= i, 1.0, -1.0) * p[(j - i) % n]
+    if kind == "toeplitz":
+        assert p.shape == (2 * n - 1,)
+        return p[j - i + n - 1]
+    if kind == "hankel":
+        assert p.shape == (2 * n - 1,)
+        return p[i + j]
+    raise ValueError("unknown structured matrix %r" % (kind,))
+
+
+def struct_apply(x, kind: str, params, d1, d2, m: int, scale: float) -> np.ndarray:
+    """scale * (first m rows of G_struct D2 H D1 x), fp64 [batch][m]."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    n = x.shape[-1]
+    t = hadamard_apply(x * np.asarray(d1, dtype=np.float64)) * np.asarray(d2, dtype=np.float64)
+    G = struct_matrix(kind, params, n)
+    return float(scale) * (t @ G[:m].T)
 
 
 def apply_blocks(x, diag_sets: np.ndarray, m: int, epilogue: str, scale: float, nthreads: int = 0) -> np.ndarray:
