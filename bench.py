@@ -239,6 +239,28 @@ def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup):
     return res
 
 
+def measure_struct(torch, b, dev, kind, n, batch, steps, warmup):
+    """G_struct D2 H D1 member: one tile-kernel pass (H D1 x) plus the LDS-resident FFT convolution."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(1610 + n)
+    x = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
+    d = (1.0 - 2.0 * torch.randint(0, 2, (2, n), generator=g, device=dev)).to(torch.float32)
+    params = torch.randn(int(b.lib.spinner_struct_params(b.STRUCT_KINDS[kind], n)), generator=g, device=dev, dtype=torch.float32)
+    spec = b.spinner_struct_prepare(kind, params, n)
+    out = torch.empty((batch, n), dtype=torch.float32, device=dev)
+    ws = torch.empty(batch * n * 4, dtype=torch.uint8, device=dev)
+    fn = lambda: b.spinner_struct_apply(x, kind, spec, d[0], d[1], n, 1.0, out=out, workspace=ws)
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    _, ms = time_calls(torch, fn, steps, warmup)
+    res = {"workload": "struct_%s_n%d_b%d" % (kind, n, batch), "ms": round(ms, 4), "vectors_per_s": batch / (ms * 1e-3),
+           "GBs_of_8B_per_element": round(8.0 * batch * n / (ms * 1e-3) / 1e9, 1)}
+    del x, d, params, spec, out, ws
+    torch.cuda.empty_cache()
+    return res
+
+
 def copy_ceiling(torch, b, dev, steps, warmup):
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
@@ -405,6 +427,11 @@ def main():
         log("[bench] %s: sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
             skt["workload"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
         nxt.append(skt)
+        for kind in ("circulant", "toeplitz"):
+            st = measure_struct(torch, b, dev, kind, 4096, 16384, 5, 2)
+            log("[bench] %s: %.4f ms  %.3e vec/s  (%.0f GB/s counting 8 B per element)" % (
+                st["workload"], st["ms"], st["vectors_per_s"], st["GBs_of_8B_per_element"]))
+            nxt.append(st)
         # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
         tbl = []
         for k in range(4, 13):

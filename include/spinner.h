@@ -265,6 +265,33 @@ size_t spinner_sketch_gram_workspace_bytes(int m, int d);
 int spinner_sketch_gram(const float *B, int m, int d, float *G, void *workspace, void *stream);
 
 /*
+ * The G_struct D2 H D1 members of the family (Lemma 1 and the remark after it; Theorem 3;
+ * used beside H D3 H D2 H D1 in the experiments of Section 5): the third block is a
+ * structured matrix given by a generating vector, Gaussian in the random setting.
+ *   SPINNER_STRUCT_CIRCULANT       g[n]:    row 0 is g, every next row is the previous
+ *                                           one shifted right cyclically: G[i][j] = g[(j - i) mod n]
+ *   SPINNER_STRUCT_SKEW_CIRCULANT  g[n]:    the same, an entry that wraps around changes sign
+ *   SPINNER_STRUCT_TOEPLITZ        t[2n-1]: G[i][j] = t[j - i + n - 1]
+ *   SPINNER_STRUCT_HANKEL          h[2n-1]: G[i][j] = h[i + j]
+ * spinner_struct_prepare turns the generating vector (device fp32,
+ * spinner_struct_params(kind, n) entries) into the opaque `spectrum` (device,
+ * spinner_struct_spectrum_bytes(kind, n) bytes) once, off the clock, as the paper
+ * prepares all parameters in advance.  spinner_struct_apply computes
+ *     out[batch][m] = scale * (first m rows of G_struct D2 H D1 x)
+ * with H the normalised Hadamard matrix; workspace: batch * n * 4 bytes of device
+ * scratch (H D1 x).  The product with G_struct is an O(n log n) FFT convolution.
+ * n = 2^5 .. 2^14 for the circulant, .. 2^13 for the others (SPINNER_ERR_UNSUPPORTED
+ * outside); an unknown kind gives SPINNER_ERR_BAD_EPILOGUE.
+ */
+enum { SPINNER_STRUCT_CIRCULANT = 0, SPINNER_STRUCT_SKEW_CIRCULANT = 1, SPINNER_STRUCT_TOEPLITZ = 2, SPINNER_STRUCT_HANKEL = 3 };
+size_t spinner_struct_params(int kind, int n);
+size_t spinner_struct_spectrum_bytes(int kind, int n);
+int spinner_struct_prepare(int kind, const float *params, int n, void *spectrum, void *stream);
+int spinner_struct_apply(const float *x, int n, long batch, int kind, const void *spectrum,
+                         const float *d1, const float *d2, int m, float scale,
+                         float *out, void *workspace, void *stream);
+
+/*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the
  * fused limit, and above it when m == n with epilogue NONE; otherwise batch * n * 4.
  * Returns 0 for invalid arguments (spinner_apply reports those).

@@ -36,7 +36,8 @@ EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_
            "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram",
            "spinner_layer_saved_bytes", "spinner_layer_workspace_bytes", "spinner_layer_forward",
            "spinner_layer_backward", "spinner_sketch_workspace_bytes", "spinner_sketch", "spinner_sketch_gram",
-           "spinner_sketch_gram_workspace_bytes", "spinner_blocks_workspace_bytes", "spinner_apply_blocks"]
+           "spinner_sketch_gram_workspace_bytes", "spinner_blocks_workspace_bytes", "spinner_apply_blocks",
+           "spinner_struct_params", "spinner_struct_spectrum_bytes", "spinner_struct_prepare", "spinner_struct_apply"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -106,6 +107,16 @@ lib.spinner_blocks_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_long, ctyp
 lib.spinner_apply_blocks.restype = ctypes.c_int
 lib.spinner_apply_blocks.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_float, _vp, _vp, _vp]
+lib.spinner_struct_params.restype = ctypes.c_size_t
+lib.spinner_struct_params.argtypes = [ctypes.c_int, ctypes.c_int]
+lib.spinner_struct_spectrum_bytes.restype = ctypes.c_size_t
+lib.spinner_struct_spectrum_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
+lib.spinner_struct_prepare.restype = ctypes.c_int
+lib.spinner_struct_prepare.argtypes = [ctypes.c_int, _vp, ctypes.c_int, _vp, _vp]
+lib.spinner_struct_apply.restype = ctypes.c_int
+lib.spinner_struct_apply.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp, ctypes.c_int, ctypes.c_float,
+                                     _vp, _vp, _vp]
+STRUCT_KINDS = {"circulant": 0, "skew_circulant": 1, "toeplitz": 2, "hankel": 3}
 
 
 class SpinnerError(RuntimeError):
@@ -546,6 +557,50 @@ def spinner_apply_blocks(x, diag_sets, m=None, epilogue="none", scale=1.0, out=N
     rc = lib.spinner_apply_blocks(x.data_ptr(), n, batch, L, diag_sets.data_ptr(), m, epi, ctypes.c_float(scale),
                                   out.data_ptr(), workspace.data_ptr() if workspace is not None else None,
                                   _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out
+
+
+def spinner_struct_prepare(kind, params, n, stream=None):
+    """Opaque spectrum (uint8 CUDA tensor) of a structured third block from its generating vector (fp32 CUDA tensor)."""
+    import torch
+
+    k = STRUCT_KINDS[kind] if isinstance(kind, str) else int(kind)
+    _check_tensor(params, "params", torch.float32)
+    nbytes = int(lib.spinner_struct_spectrum_bytes(k, int(n)))
+    if nbytes == 0:
+        raise SpinnerError(SPINNER_ERR_UNSUPPORTED)
+    if params.numel() != int(lib.spinner_struct_params(k, int(n))):
+        raise ValueError("generating vector has the wrong length")
+    spec = torch.empty(nbytes, dtype=torch.uint8, device=params.device)
+    rc = lib.spinner_struct_prepare(k, params.data_ptr(), int(n), spec.data_ptr(), _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return spec
+
+
+def spinner_struct_apply(x, kind, spectrum, d1, d2, m=None, scale=1.0, out=None, workspace=None, stream=None):
+    """out [batch][m] = scale * (first m rows of G_struct D2 H D1 x)."""
+    import torch
+
+    k = STRUCT_KINDS[kind] if isinstance(kind, str) else int(kind)
+    for name, t in (("x", x), ("d1", d1), ("d2", d2)):
+        _check_tensor(t, name, torch.float32)
+    batch, n = x.shape
+    m = n if m is None else int(m)
+    if out is None:
+        out = torch.empty((batch, m), dtype=torch.float32, device=x.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != batch * m:
+            raise ValueError("out has the wrong size")
+    if workspace is None:
+        workspace = torch.empty(max(16, batch * n * 4), dtype=torch.uint8, device=x.device)
+    if workspace.numel() * workspace.element_size() < batch * n * 4:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_struct_apply(x.data_ptr(), n, batch, k, spectrum.data_ptr(), d1.data_ptr(), d2.data_ptr(), m,
+                                  ctypes.c_float(scale), out.data_ptr(), workspace.data_ptr(), _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out

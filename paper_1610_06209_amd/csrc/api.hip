@@ -74,7 +74,7 @@ int fused_max_log(int epilogue)
 
 extern "C" {
 
-int spinner_version(void) { return 130; }
+int spinner_version(void) { return 140; }
 
 const char* spinner_strerror(int status)
 {
@@ -530,6 +530,79 @@ int spinner_apply_blocks(const float* x, int n, long batch, int L, const float* 
         if (r != SPINNER_OK) return r;
     }
     return SPINNER_OK;
+}
+
+// ------------------------------------------------------------------ G_struct D2 H D1 members
+static int struct_log2p(int kind, int log2n) { return kind == SPINNER_STRUCT_CIRCULANT ? log2n : log2n + 1; }
+
+static int check_struct(int kind, int n, int* log2n)
+{
+    if (kind < SPINNER_STRUCT_CIRCULANT || kind > SPINNER_STRUCT_HANKEL) return SPINNER_ERR_BAD_EPILOGUE;
+    if (!pow2_in_range(n, log2n)) return SPINNER_ERR_BAD_N;
+    // H D1 x comes from the one-step tile kernels (n >= 32); the transform of length P must fit the LDS (P <= 2^14)
+    if (*log2n < 5 || struct_log2p(kind, *log2n) > 14) return SPINNER_ERR_UNSUPPORTED;
+    return SPINNER_OK;
+}
+
+size_t spinner_struct_params(int kind, int n)
+{
+    int log2n;
+    if (check_struct(kind, n, &log2n) != SPINNER_OK) return 0;
+    return (kind == SPINNER_STRUCT_CIRCULANT || kind == SPINNER_STRUCT_SKEW_CIRCULANT) ? (size_t)n : 2 * (size_t)n - 1;
+}
+
+size_t spinner_struct_spectrum_bytes(int kind, int n)
+{
+    int log2n;
+    if (check_struct(kind, n, &log2n) != SPINNER_OK) return 0;
+    const size_t P = (size_t)1 << struct_log2p(kind, log2n);
+    return P * 8 + (P / 2) * 8;                       // spectrum, then the twiddle table
+}
+
+int spinner_struct_prepare(int kind, const float* params, int n, void* spectrum, void* stream)
+{
+    int log2n;
+    const int rc = check_struct(kind, n, &log2n);
+    if (rc != SPINNER_OK) return rc;
+    if (!params || !spectrum) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(params) || !aligned16(spectrum)) return SPINNER_ERR_ALIGNMENT;
+    const int lp = struct_log2p(kind, log2n);
+    float2* spec = static_cast<float2*>(spectrum);
+    const hipError_t e = spinner::launch_struct_prepare(params, kind, n, lp, spec, spec + ((size_t)1 << lp),
+                                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_struct_apply(const float* x, int n, long batch, int kind, const void* spectrum, const float* d1, const float* d2,
+                         int m, float scale, float* out, void* workspace, void* stream)
+{
+    int log2n;
+    const int rc = check_struct(kind, n, &log2n);
+    if (rc != SPINNER_OK) return rc;
+    if (m < 1 || m > n) return SPINNER_ERR_BAD_M;
+    if (batch < 0 || batch > 0x7fffffffL || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    if (batch == 0) return SPINNER_OK;
+    if (!x || !spectrum || !d1 || !d2 || !out) return SPINNER_ERR_NULL_PTR;
+    if (!workspace) return SPINNER_ERR_WORKSPACE;
+    if (!aligned16(x) || !aligned16(spectrum) || !aligned16(d1) || !aligned16(d2) || !aligned16(out) || !aligned16(workspace))
+        return SPINNER_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // t = H D1 x (one diagonal, one normalised transform) into the workspace
+    spinner::TileParams p;
+    memset(&p, 0, sizeof(p));
+    float* t = static_cast<float*>(workspace);
+    p.x = x; p.out = t; p.d[0] = d1;
+    p.batch = batch; p.in_stride = n; p.out_stride = n;
+    p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0; p.m = n;
+    p.factor = (float)(1.0 / sqrt((double)n));
+    hipError_t e = spinner::launch_row_first(log2n, p, batch, s);
+    if (e != hipSuccess) return hip_fail(e);
+    const int lp = struct_log2p(kind, log2n);
+    const float2* spec = static_cast<const float2*>(spectrum);
+    e = spinner::launch_struct_conv(t, d2, spec, spec + ((size_t)1 << lp), out, batch, n, lp, m,
+                                    kind == SPINNER_STRUCT_HANKEL ? 1 : 0,
+                                    (float)((double)scale / (double)((size_t)1 << lp)), s);
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 
 int spinner_stream_copy(const float* src, float* dst, size_t count, void* stream)

@@ -102,6 +102,11 @@ hipError_t launch_transpose_scale(const float* src, long long rows, long long co
 int sketch_gram_slabs(int m, int d);      // d x d slabs of scratch the Gram kernel needs (1: none)
 hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* slabs, hipStream_t s);
 
+// G_struct D2 H D1 members: spectrum of the structured block, FFT convolution (structured.hip)
+hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, hipStream_t s);
+hipError_t launch_struct_conv(const float* t, const float* d2, const float2* spec, const float2* tw, float* out, long long batch,
+                              int n, int log2p, int m, int reverse, float factor, hipStream_t s);
+
 // Shape of the column tiles of the four-pass schedule: 2^rows_log rows (all rows of the
 // matrix view) by 2^contig_log contiguous columns.  Up to n = 2^21 the matrix view has
 // 2^7 rows and a column tile is 128 rows x 32 columns (128-byte segments, 2^12 elements:
