@@ -211,3 +211,35 @@ def test_newton_sketch_bench_size(gpu, oracle):
     WA = (A * wts[:, None]).astype(np.float64)
     exact = WA.T @ WA
     assert np.linalg.norm(Gw - exact) / np.linalg.norm(exact) < 0.5
+
+
+def test_more_than_2_to_32_elements(gpu, oracle):
+    # 64-bit indexing: 5 * 2^20 vectors of 1024 floats are 5.4e9 elements (20 GiB in, 20 GiB out); sampled rows
+    # against the oracle, among them the last rows, whose element offsets do not fit 32 bits
+    t, b = gpu.torch, gpu.b
+    n, batch = 1024, 5 << 20
+    g = t.Generator(device=gpu.dev)
+    g.manual_seed(77)
+    x = t.empty((batch, n), dtype=t.float32, device=gpu.dev)
+    step = 1 << 20
+    for s in range(0, batch, step):
+        x[s:s + step] = t.randn((step, n), generator=g, device=gpu.dev, dtype=t.float32)
+    ds = W.rademacher_diagonals(n, 3, 78)
+    dsd = t.from_numpy(ds).to(gpu.dev)
+    signs = b.spinner_pack_signs(dsd[None].contiguous())
+    out = b.spinner_apply_signs(x, signs, n, "none", 1.0)
+    t.cuda.synchronize()
+    rows = np.array([0, 1, (1 << 21) - 1, 1 << 21, (1 << 22) + 5, batch - 2, batch - 1])
+    idx = t.from_numpy(rows).to(gpu.dev)
+    want = oracle.apply(x[idx].cpu().numpy(), ds[0], ds[1], ds[2], n, "none", 1.0)
+    assert rel_l2_per_vector(out[idx].cpu().numpy(), want).max() <= REL_L2_TOL
+    # isometry on the whole output, in chunks
+    for s in range(0, batch, step):
+        a, c = _norms(out[s:s + step]), _norms(x[s:s + step])
+        assert float(((a - c).abs() / c).max()) < 1e-5
+    del out
+    t.cuda.empty_cache()
+    idx_out = b.spinner_hash_signs(x, signs, 1)
+    t.cuda.synchronize()
+    hw = oracle.hash(x[idx].cpu().numpy(), ds[None])
+    assert np.array_equal(idx_out[idx].cpu().numpy(), hw)
