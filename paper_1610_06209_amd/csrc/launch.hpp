@@ -20,46 +20,69 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 #ifndef SPINNER_RMAX_F64
 #define SPINNER_RMAX_F64 5
 #endif
-template <typename T, int NT> struct Tuning { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0, trips = 0; };
+struct NotWide { static constexpr int wide = 0, start = 0; };
+template <typename T, int NT> struct Tuning : NotWide { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0, trips = 0; };
 #ifndef SPINNER_RMAX_F32
 #ifndef SPINNER_RMAX_F64_N12
 #define SPINNER_RMAX_F64_N12 4
 #endif
-template <> struct Tuning<double, 12> { static constexpr int rmax = SPINNER_RMAX_F64_N12, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 4> { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 5> { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 6> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 7> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 8> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 9> { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 10> { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 11> { static constexpr int rmax = 6, waves = 1, min_waves = 0, trips = 0; };
-template <> struct Tuning<float, 12> { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };   // 4 waves per tile, 16 KiB LDS
-template <> struct Tuning<float, 13> { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<double, 12> : NotWide { static constexpr int rmax = SPINNER_RMAX_F64_N12, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 4> : NotWide { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 5> : NotWide { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 6> : NotWide { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 7> : NotWide { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 8> : NotWide { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 9> : NotWide { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 10> : NotWide { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 11> : NotWide { static constexpr int rmax = 6, waves = 1, min_waves = 0, trips = 0; };
+template <> struct Tuning<float, 12> : NotWide { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };   // 4 waves per tile, 16 KiB LDS
+template <> struct Tuning<float, 13> : NotWide { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
 // n = 2^14: four waves of 64 values per tile, held to 128 registers, exchanging through half-size LDS buffers:
 // four tiles share a compute unit (two with 32 values on eight waves and a whole-tile buffer); measured +5 %
-template <> struct Tuning<float, 14> { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 2; };
-template <> struct Tuning<float, 15> { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 0; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
-template <> struct Tuning<float, 16> { static constexpr int rmax = 6, waves = 4, min_waves = 0, trips = 0; };   // 16 waves per tile
+template <> struct Tuning<float, 14> : NotWide { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 2; };
+template <> struct Tuning<float, 15> : NotWide { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 0; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
+template <> struct Tuning<float, 16> : NotWide { static constexpr int rmax = 6, waves = 4, min_waves = 0, trips = 0; };   // 16 waves per tile
+template <typename TU, int NT>
+using GeomFrom = TileGeom<NT, TU::rmax, TU::waves, TU::min_waves, TU::trips, TU::wide, TU::start>;   // wide, start: see WideF32 below
 template <typename T, int NT>
-using GeomFor = TileGeom<NT, Tuning<T, NT>::rmax, Tuning<T, NT>::waves, Tuning<T, NT>::min_waves, Tuning<T, NT>::trips>;
+using GeomFor = GeomFrom<Tuning<T, NT>, NT>;
+// Fused fp32 kernels with packed sign words for vectors of 2^12 .. 2^14 elements use exchanges that also
+// trade lane bits 4, 5 for register bits (TileGeom's WIDE_; column tiles never do), through half-size LDS buffers:
+// 32 values per thread on two waves at 2^12, 64 values held to 128 registers on two / four waves at 2^13 / 2^14.
+// Measured against the tables above: 2^12 0.374 -> 0.345 ms (the copy kernel's time), 2^13 -8 %, 2^14 -2 to -4 %;
+// no gain for fp64 butterflies or for the pruned last round, which keep the narrow exchanges.
+#ifndef SPINNER_WIDE_F32         // bit N set: fp32 contiguous tiles of 2^N elements use wide exchanges (tuning experiments)
+#define SPINNER_WIDE_F32 0x7000
+#endif
+#ifndef SPINNER_WIDE_START       // layout in which the wide kernels load their tile
+#define SPINNER_WIDE_START 0
+#endif
+template <int NT> struct WideF32 { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = SPINNER_WIDE_START; };
+template <typename T, int NT>
+using ContigTuning = std::conditional_t<std::is_same<T, float>::value && ((SPINNER_WIDE_F32 >> NT) & 1) != 0, WideF32<NT>, Tuning<T, NT>>;
+template <typename T, int NT>
+using ContigGeomFor = GeomFrom<ContigTuning<T, NT>, NT>;
 // geometry of the kernels whose last round is pruned (a separate table so that it can be tuned apart)
 template <typename T, int NT> struct PrunedTuning : Tuning<T, NT> {};
 template <typename T, int NT>
-using PrunedGeomFor = TileGeom<NT, PrunedTuning<T, NT>::rmax, PrunedTuning<T, NT>::waves, PrunedTuning<T, NT>::min_waves, PrunedTuning<T, NT>::trips>;
+using PrunedGeomFor = GeomFrom<PrunedTuning<T, NT>, NT>;
 #else   // uniform override used by tuning sweeps
-template <typename T, int NT> struct PrunedTuning { static constexpr int rmax = clamp_rmax(NT, SPINNER_RMAX_F32), waves = SPINNER_WAVES_PER_WG, min_waves = 0, trips = 0; };
+template <typename T, int NT> struct PrunedTuning { static constexpr int rmax = clamp_rmax(NT, SPINNER_RMAX_F32), waves = SPINNER_WAVES_PER_WG, min_waves = 0, trips = 0, wide = 0, start = 0; };
 template <typename T, int NT> struct Tuning : PrunedTuning<T, NT> {};
 template <typename T, int NT>
 using PrunedGeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
 template <typename T, int NT>
 using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
+template <typename T, int NT> using ContigGeomFor = GeomFor<T, NT>;
 #endif
 
 template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
-    using G = std::conditional_t<(PRUNE > 0), PrunedGeomFor<T, NT>, GeomFor<T, NT>>;
+    // wide exchanges pay with packed sign words only: fp32 diagonals read in layout 1 come in 256-byte runs,
+    // which measured 2-5 % slower than the narrow exchange (also for the row passes above 2^16)
+    using G = std::conditional_t<(PRUNE > 0), PrunedGeomFor<T, NT>,
+                                 std::conditional_t<(C >= NT && SIGNS && NSTEPS == 3), ContigGeomFor<T, NT>, GeomFor<T, NT>>>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;

@@ -143,10 +143,17 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //   layout 0 ("top"): registers hold bits {0,1} and the top r-2 bits
 //   layout 1 ("mid"): registers hold bits {0,1} and the r-2 bits just above the
 //                     lane bits (only used when a tile spans several waves)
-// Lanes hold bits 2 .. 2+LB-1 in both layouts.
+// Lanes hold bits 2 .. 2+LB-1 in both layouts, except with WIDE_ (below).
 // MINW_: occupancy (waves per SIMD) the register allocator must allow; 0 leaves it to the knobs above
 // TRIPS_: 2 sends the exchanges of a tile of up to 2^14 elements through an LDS buffer of half the tile, in two trips
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0, int TRIPS_ = 0>
+// WIDE_: the exchange between the layouts also trades lane bits 4, 5 for register bits.  Layout 1 then keeps
+//        bits {0,1}, 6, 7 and layout 0's wave bits in registers, layout 0's register bits 2, 3 in lane bits
+//        4, 5 and layout 0's next register bits in the wave id (what is left stays where it was).  A transform
+//        is then register stages, four lane stages (bits 2..5), the exchange, and register stages again:
+//        lane bits 4, 5 never need a cross-lane butterfly.  Accesses stay 16 bytes per lane in runs of 16 lanes.
+// START_: layout in which a kernel loads its tile (1: a three-round kernel ends in layout 0, where the lanes
+//        hold index bits 2..7 again, which the sign-code epilogue needs)
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0, int TRIPS_ = 0, int WIDE_ = 0, int START_ = 0>
 struct TileGeom {
     static constexpr int MIN_WAVES = MINW_;
     static constexpr int NT = NT_;
@@ -168,9 +175,17 @@ struct TileGeom {
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int TILES_PER_WG = WB ? 1 : WAVES * TPW;
 
-    static constexpr int reg_pos(int lay, int q) { return q < 2 ? q : (lay == 0 ? NT - r + q : LB + q); }
-    static constexpr int lane_pos(int b) { return 2 + b; }
-    static constexpr int wave_pos(int lay, int b) { return lay == 0 ? 2 + LB + b : LB + r + b; }
+    static constexpr bool WIDE = WIDE_ != 0 && LB == 6 && WB >= 1 && (r - 2) >= 2 + WB;
+    static constexpr int LANE_STAGES = WIDE ? 4 : LB;        // lane bits that are transformed by lane exchanges
+    static constexpr int reg_pos(int lay, int q)
+    {
+        if (q < 2) return q;
+        if (lay == 0) return NT - r + q;
+        if (!WIDE) return LB + q;
+        return q < 4 + WB ? 4 + q : NT - r + q;
+    }
+    static constexpr int lane_pos(int lay, int b) { return (WIDE && lay == 1 && b >= 4) ? NT - r + 2 + (b - 4) : 2 + b; }
+    static constexpr int wave_pos(int lay, int b) { return lay == 0 ? 2 + LB + b : (WIDE ? NT - r + 4 + b : LB + r + b); }
     static constexpr int reg_index(int lay, int j)
     {
         int e = 0;
@@ -180,7 +195,7 @@ struct TileGeom {
     }
     // "Swapped" state of a tile (see lane_swap_stages): physical register bits 2, 3 hold the index
     // bits of lane bits 4, 5 (positions 6, 7) and the lanes hold the index bits of register bits 2, 3.
-    static constexpr bool LANE_SWAPS = SPINNER_LANE_SWAPS != 0 && WB > 0 && LB == 6 && r >= 4;
+    static constexpr bool LANE_SWAPS = SPINNER_LANE_SWAPS != 0 && WB > 0 && LB == 6 && r >= 4 && !WIDE;
     static constexpr int reg_index_sw(int lay, int j)
     {
         int e = 0;
@@ -188,14 +203,14 @@ struct TileGeom {
             if ((j >> q) & 1) e |= 1 << (q == 2 ? 6 : (q == 3 ? 7 : reg_pos(lay, q)));
         return e;
     }
-    static constexpr bool is_wave_pos(int lay, int pos)
+    static constexpr bool is_reg_pos(int lay, int pos)
     {
-        for (int b = 0; b < WB; ++b)
-            if (wave_pos(lay, b) == pos) return true;
+        for (int q = 0; q < r; ++q)
+            if (reg_pos(lay, q) == pos) return true;
         return false;
     }
     // layout in force after `steps` complete (diag, transform) steps
-    static constexpr int layout_after(int steps) { return WB ? (steps & 1) : 0; }
+    static constexpr int layout_after(int steps) { return WB ? ((steps + START_) & 1) : 0; }
 };
 
 struct TileParams {
@@ -239,6 +254,8 @@ struct ThreadCtx {
     __device__ __forceinline__ int base_index(int lay) const
     {
         int e = lit << 2;
+        if constexpr (G::WIDE)
+            if (lay == 1) e = ((lit & 15) << 2) | (((lit >> 4) & 1) << G::lane_pos(1, 4)) | (((lit >> 5) & 1) << G::lane_pos(1, 5));
         for (int b = 0; b < G::WB; ++b)
             e |= ((wv >> b) & 1) << G::wave_pos(lay, b);
         return e;
@@ -410,13 +427,14 @@ __device__ __forceinline__ void lane_swap_stage(T (&v)[R])
 template <typename G, int CB, int LAY, bool NEGATE, bool SWAP = false, typename T>
 __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c)
 {
-    static_assert(!SWAP || CB <= G::lane_pos(4), "lane swaps: lane bits 4 and 5 must be among the transformed ones");
+    static_assert(!G::WIDE || CB == 0, "wide exchanges are for contiguous tiles");
+    static_assert(!SWAP || CB <= G::lane_pos(LAY, 4), "lane swaps: lane bits 4 and 5 must be among the transformed ones");
     static_for<0, G::r>([&](auto q) {
         if constexpr (G::reg_pos(LAY, q.value) >= CB && !(SPINNER_EXPERIMENT_KNOCKOUT & 4))
             reg_stage<q.value>(v);
     });
-    static_for<0, G::LB>([&](auto b) {
-        if constexpr (G::lane_pos(b.value) >= CB && !(SWAP && b.value >= 4)) {
+    static_for<0, G::LANE_STAGES>([&](auto b) {
+        if constexpr (G::lane_pos(LAY, b.value) >= CB && !(SWAP && b.value >= 4)) {
             if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) {
                 if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 2))
                     lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
@@ -438,20 +456,39 @@ __device__ __forceinline__ float tracked_sign(const ThreadCtx<G>& c)
 {
     float s = 1.0f;
     static_for<0, G::LB>([&](auto b) {
-        if constexpr (G::lane_pos(b.value) >= CB && lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) s *= c.sg[b.value];
+        if constexpr (G::lane_pos(0, b.value) >= CB && lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) s *= c.sg[b.value];
     });
     return s;
 }
 
 // Register stages, in layout LAY, for exactly those index bits that layout
-// 1-LAY keeps in the wave id (the part of a transform left after a transpose).
+// 1-LAY does not keep in registers (the part of a transform left after a transpose).
 template <typename G, int CB, int LAY, typename T>
 __device__ __forceinline__ void wave_owned_stages(T (&v)[G::R])
 {
     static_for<0, G::r>([&](auto q) {
         constexpr int pos = G::reg_pos(LAY, q.value);
-        if constexpr (pos >= CB && G::is_wave_pos(1 - LAY, pos)) reg_stage<q.value>(v);
+        if constexpr (pos >= CB && !G::is_reg_pos(1 - LAY, pos)) reg_stage<q.value>(v);
     });
+}
+
+// Slots of the two-trip exchange of a WIDE geometry: element e goes to slot
+//     (e >> 2) ^ (bit P4 of e) << 4 ^ (bit P5 of e) << 5,      P4, P5 = index bits of lane bits 4, 5 in layout 1.
+// In layout 0 those two bits are register bits (the xor is known per register: four bases), in layout 1 they
+// are lane bits and slot bits 4, 5 are register bits (again four bases, one per value of those register bits).
+template <typename G>
+constexpr int wide_slot_k(int lay, int rj)
+{
+    return lay == 0 ? (((rj >> G::lane_pos(1, 4)) & 1) | (((rj >> G::lane_pos(1, 5)) & 1) << 1)) : ((rj >> 6) & 3);
+}
+template <typename G>
+constexpr int wide_slot_off(int lay, int rj) { return lay == 0 ? (rj >> 2) : ((rj >> 2) & ~48); }
+template <typename G, int LAY>
+__device__ __forceinline__ void wide_slot_bases(const ThreadCtx<G>& c, int ebase, int (&b)[4])
+{
+    const int x = (c.lit >> 4) & 3;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) b[k] = LAY == 0 ? ((ebase >> 2) ^ (k << 4)) : ((ebase >> 2) | ((k ^ x) << 4));
 }
 
 // ------------------------------------------------------------------ LDS transpose between layouts
@@ -497,7 +534,33 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
         // hold more workgroups, and lets tiles of 2^15 and 2^16 elements fit at all.
         const int ef = SW ? c.base_index_sw(FROM) : c.base_index(FROM);
         const int et = c.base_index(TO);
-        if constexpr (G::LDS_HALVES == 2) {
+        if constexpr (G::LDS_HALVES == 2 && G::WIDE) {
+            // 8 bytes per lane: in layout 1 lane bits 4, 5 hold high index bits, so the four runs of 16 lanes would
+            // fall on the same banks.  Slot bits 4, 5 (index bits 6, 7) are therefore xored with those two high
+            // bits: every access of a wave then covers 64 different 8-byte slots of a 512-byte window.
+            float2* lds2 = reinterpret_cast<float2*>(lds);
+            int bw[4], br[4];
+            wide_slot_bases<G, FROM>(c, ef, bw);
+            wide_slot_bases<G, TO>(c, et, br);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (h == 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
+#pragma unroll
+                for (int jh = 0; jh < NW / 4; ++jh) {
+                    const int rj = G::reg_index(FROM, jh * 4);
+                    lds2[bw[wide_slot_k<G>(FROM, rj)] + wide_slot_off<G>(FROM, rj)] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
+                }
+                __syncthreads();
+                if (reads) {
+#pragma unroll
+                    for (int jh = 0; jh < NR / 4; ++jh) {
+                        const int rj = G::reg_index(TO, jh * 4);
+                        const float2 t = lds2[br[wide_slot_k<G>(TO, rj)] + wide_slot_off<G>(TO, rj)];
+                        v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
+                    }
+                }
+            }
+        } else if constexpr (G::LDS_HALVES == 2) {
             float2* lds2 = reinterpret_cast<float2*>(lds);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -619,6 +682,23 @@ __device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, c
     sign_words_t w = (sign_words_t)words;
     int ew = 0;                                   // index bits held by the (uniform) wave id
     for (int b = 0; b < G::WB; ++b) ew |= ((c.wv >> b) & 1) << G::wave_pos(LAY, b);
+    if constexpr (G::WIDE && LAY == 1) {
+        // lanes hold index bits 2..5 and two high bits: the lane mask of a register is put together from
+        // the 16-bit fields (bits 2..5; bits 6, 7 are register bits here) of four words of the packed format
+#pragma unroll
+        for (int j = 0; j < G::R; ++j) {
+            const int e = ew | G::reg_index(1, j);
+            unsigned long long m = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ek = e | ((k & 1) << G::lane_pos(1, 4)) | ((k >> 1) << G::lane_pos(1, 5));
+                const unsigned long long wk = w[((ek >> 8) << 2) | (ek & 3)];
+                m |= ((wk >> (((ek >> 6) & 3) << 4)) & 0xFFFFull) << (16 * k);
+            }
+            flip_by_mask(v[j], m);
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < G::R; ++j) {
         const int e = ew | G::reg_index(LAY, j);  // lane bits (2 .. 2+LB-1) are zero here
@@ -649,7 +729,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 #ifndef SPINNER_LANE_SWAPS_F64
 #define SPINNER_LANE_SWAPS_F64 1
 #endif
-    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(4);
+    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(LAY, 4);
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
     if constexpr (G::WB > 0) {
         if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
@@ -686,10 +766,10 @@ constexpr unsigned reg_positions(int lay)
     return m;
 }
 template <typename G>
-constexpr unsigned wave_positions(int lay)
+constexpr unsigned lane_positions(int lay)
 {
     unsigned m = 0;
-    for (int b = 0; b < G::WB; ++b) m |= 1u << G::wave_pos(lay, b);
+    for (int b = 0; b < G::LB; ++b) m |= 1u << G::lane_pos(lay, b);
     return m;
 }
 // registers live at the end of a pruned last step that started in layout LAY
@@ -698,7 +778,7 @@ constexpr int pruned_final_regs(int lay, int P)
 {
     const unsigned pm = prune_positions<G>(P);
     if (G::WB == 0) return live_regs<G>(lay, pm & reg_positions<G>(lay));
-    return live_regs<G>(1 - lay, pm & (reg_positions<G>(lay) | wave_positions<G>(lay)));
+    return live_regs<G>(1 - lay, pm & (reg_positions<G>(lay) | reg_positions<G>(1 - lay)));
 }
 
 template <int HALF, typename T, int R>
@@ -744,7 +824,7 @@ __device__ __forceinline__ void spinner_step_pruned(float (&v)[G::R], const Thre
     pruned_reg_stages<G, LAY, REGS, PM, 0u>(v);
     constexpr unsigned DONE1 = PM & REGS;
     constexpr int RL1 = live_regs<G>(LAY, DONE1);
-    static_for<0, G::LB>([&](auto b) {
+    static_for<0, G::LANE_STAGES>([&](auto b) {
         if constexpr (lane_mask_uses_fmac_dpp<float, G::R>(1 << b.value))
             lane_stage_fmac_dpp<b.value, RL1>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
         else
@@ -753,12 +833,12 @@ __device__ __forceinline__ void spinner_step_pruned(float (&v)[G::R], const Thre
     wave_live = true;
     if constexpr (G::WB > 0) {
         constexpr int TO = 1 - LAY;
-        constexpr unsigned WAVES_FROM = wave_positions<G>(LAY);
+        constexpr unsigned POST = reg_positions<G>(TO) & ~REGS;     // bits that become register bits only now
         constexpr int RL2 = live_regs<G>(TO, DONE1);
-        // a wave of the new layout is live iff its wave-held bits avoid the reduced positions
+        // a thread of the new layout is live iff its wave- and lane-held bits avoid the reduced positions
         wave_live = (c.base_index(TO) & (int)DONE1) == 0;
         transpose<G, LAY, true, RL1, RL2>(v, c, lds, wave_live);
-        if (wave_live) pruned_reg_stages<G, TO, WAVES_FROM, PM, DONE1>(v);
+        if (wave_live) pruned_reg_stages<G, TO, POST, PM, DONE1>(v);
     }
 }
 
@@ -831,11 +911,11 @@ spinner_tile_kernel(TileParams p)
 
         T v[R];
         {
-            const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(0), p.sl);
+            const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(G::layout_after(0)), p.sl);
 #pragma unroll
             for (int jh = 0; jh < R / 4; ++jh) {
                 float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(0, jh * 4), p.sl));
+                if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
                 v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
             }
         }
@@ -872,7 +952,7 @@ spinner_tile_kernel(TileParams p)
             if constexpr (NSTEPS & 1) lane_factor *= tracked_sign<G, CB, T>(c);
             // whole tile inside the kept range and rows 16-byte aligned: no per-store checks
             // (with a pruned last round, lanes whose pruned bits are set hold nothing to store)
-            constexpr bool LANES_PRUNED = PRUNE > 0 && ((prune_positions<G>(PRUNE) >> 2) & ((1u << G::LB) - 1u)) != 0;
+            constexpr bool LANES_PRUNED = PRUNE > 0 && (prune_positions<G>(PRUNE) & lane_positions<G>(LAYF)) != 0;
             const bool full = !LANES_PRUNED && (tile_first + tile_offset<NT, C>((1 << (NT - PRUNE)) - 1, p.sl) < m) &&
                               ((p.out_stride & 3) == 0);
             float* dst = p.out + vec * p.out_stride;
@@ -905,7 +985,7 @@ spinner_tile_kernel(TileParams p)
                 // Code word ((e >> 8) << 2) | (e & 3) holds, in bit (e >> 2) & 63, whether coordinate e
                 // is negative.  Lanes hold index bits 2..7, so the wave-wide comparison mask of one
                 // register is one whole word; lane j then stores the word of register j.
-                static_assert(G::LB == 6 && C >= NT && std::is_same<T, float>::value && RF <= 64,
+                static_assert(G::LB == 6 && (!G::WIDE || LAYF == 0) && C >= NT && std::is_same<T, float>::value && RF <= 64,
                               "sign codes: fp32 contiguous tiles with a whole wave per 256 coordinates");
                 // The compare is written out with an explicit scalar destination: through the VCC alias
                 // (what the compiler would pick) a lane write right behind it reads a stale mask, and

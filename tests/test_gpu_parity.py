@@ -315,9 +315,14 @@ def test_sign_word_path_every_fused_size(gpu, oracle, log2n):
     _, ys = oracle.hash(x, ds, return_y=True)
     exact, banded = check_hash_against_projection(h, ys)
     assert exact + banded == batch * L and banded <= 1
-    # the sign-word path and the fp32-diagonal path agree bit for bit on +-1 diagonals
+    # the sign-word path and the fp32-diagonal path agree on +-1 diagonals: bit for bit where both use the
+    # same order of butterflies (n < 2^12), to rounding above that (the sign-word kernels order them differently)
     ref = gpu.b.spinner_apply(xd, dsd[0, 0], dsd[0, 1], dsd[0, 2])
-    assert bool((ref == gpu.b.spinner_apply_signs(xd, signs, triple=0)).all())
+    alt = gpu.b.spinner_apply_signs(xd, signs, triple=0)
+    if log2n < 12:
+        assert bool((ref == alt).all())
+    else:
+        assert rel_l2_per_vector(alt.cpu().numpy(), ref.cpu().numpy().astype(np.float64)).max() <= 2e-6
     assert bool((gpu.b.spinner_hash(xd, dsd) == gpu.b.spinner_hash_signs(xd, signs, L)).all())
 
 
