@@ -12,9 +12,10 @@
 //                                        crossbar swizzle, bpermute) + one FMA;
 //   * bits held by the wave id (NT>12) : an LDS transpose swaps them with
 //                                        register bits, then register stages.
-// The lane id always holds index bits 2..7, so every global and LDS access is a
-// 16-byte-per-lane, fully coalesced access, and diagonals are read with the
-// same addresses as the data.
+// The lane id holds index bits 2..7 (in the second layout of a "wide" geometry:
+// bits 2..5 and two high bits), so every global and LDS access is a 16-byte-per-
+// lane access in runs of 64 (16) lanes, and diagonals are read with the same
+// addresses as the data.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -659,7 +660,7 @@ __device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& 
 // ------------------------------------------------------------------ +-1 diagonals as packed sign words
 // Packed format of one diagonal (n <= 2^14): 64-bit words; element e has its
 // sign bit at bit (e >> 2) & 63 of word ((e >> 8) << 2) | (e & 3).  Because the
-// lane id always holds index bits 2..7, one word is exactly the lane mask "which
+// lane id holds index bits 2..7 (except in layout 1 of a wide geometry), one word is exactly the lane mask "which
 // lanes hold a negated element" of one register, so it is fetched with a scalar
 // load and applied with one v_cndmask (x or -x by lane mask): no vector memory
 // traffic and no registers spent on staging the diagonal.
