@@ -24,8 +24,9 @@ __global__ void __launch_bounds__(256) stream_copy_kernel(const float4* __restri
 
 // One wave per output word: lane l looks at element ((w >> 2) << 8) | (l << 2) | (w & 3)
 // of its diagonal and the wave's ballot of the sign bits is the word.
+// Diagonal dg = 3 * triple + k; a triple's words start triple_words apart.
 __global__ void __launch_bounds__(256) pack_signs_kernel(const float* __restrict__ diag, unsigned long long* __restrict__ out,
-                                                         int n, int W, long long total_words)
+                                                         int n, int W, long long triple_words, long long total_words)
 {
     const long long gw = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -36,7 +37,7 @@ __global__ void __launch_bounds__(256) pack_signs_kernel(const float* __restrict
     bool neg = false;
     if (e < n) neg = (__float_as_uint(diag[dg * n + e]) >> 31) != 0;
     const unsigned long long m = __ballot(neg);
-    if (lane == 0) out[gw] = m;
+    if (lane == 0) out[(dg / 3) * triple_words + (dg % 3) * W + w] = m;
 }
 }  // namespace spinner
 
@@ -223,7 +224,7 @@ size_t spinner_signs_bytes(int n, int L)
 {
     int log2n;
     if (!pow2_in_range(n, &log2n) || L < 1) return 0;
-    if (log2n <= spinner::kFusedMaxLogOther) return (size_t)L * 3 * (size_t)spinner::sign_words_per_diag(n) * 8;
+    if (log2n <= spinner::kFusedMaxLogOther) return (size_t)L * (size_t)spinner::sign_words_per_triple(n, log2n) * 8;
     return (size_t)L * 3 * (size_t)n * sizeof(float);      // plain copy of the diagonals
 }
 
@@ -243,8 +244,10 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     const long long total_words = (long long)L * 3 * W;
     const long long blocks = (total_words + 3) / 4;
     hipLaunchKernelGGL(spinner::pack_signs_kernel, dim3((unsigned)blocks), dim3(256), 0, s, diag_sets,
-                       static_cast<unsigned long long*>(signs), n, W, total_words);
-    const hipError_t e = hipGetLastError();
+                       static_cast<unsigned long long*>(signs), n, W, spinner::sign_words_per_triple(n, log2n), total_words);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && spinner::hash_ar_log2r(log2n))
+        e = spinner::launch_pack_hash_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 
@@ -279,6 +282,7 @@ static int hash_impl(const float* x, int n, long batch, int L, const float* diag
     if (log2n > kFusedMaxLogOther) return SPINNER_ERR_UNSUPPORTED;
     HashParams p;
     p.x = x; p.diag_sets = diag_sets; p.signs = signs; p.out_idx = out_idx; p.batch = batch; p.L = L;
+    p.triple_words = sign_words_per_triple(n, log2n);
     const hipError_t e = launch_hash(log2n, signs != nullptr, p, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }

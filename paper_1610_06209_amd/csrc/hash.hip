@@ -5,9 +5,208 @@
 #define SPINNER_HASH_RMAX 5
 #endif
 namespace spinner {
+
+// ------------------------------------------------------------------ hash kernel with every butterfly between registers
+// Hashing applies L triples to one resident copy of x, so it is bound by the vector ALU, where a butterfly
+// between two registers costs half of one across lanes (DPP forms issue at half rate) and uses no LDS.
+// This kernel therefore keeps two layouts of a vector of 2^NT = 2^(r + LB) elements on 2^LB lanes:
+//   layout A: register j, lane l hold element j + (l << r)                    (registers = index bits 0 .. r-1)
+//   layout B: register j, lane l hold element (l mod 2^r) + (j << r) + ((l >> r) << 2r)   (registers = bits r .. 2r-1)
+// and goes from one to the other through a wave-private LDS buffer once per transform, so that a transform is
+// r register stages, the exchange, r register stages (plus lane stages for the LB - r lane bits both layouts
+// share).  Element e sits at word (e >> r) * (2^r + 4) + (e mod 2^r) (+ a skew per group of 2^r lanes and per
+// vector): layout A accesses it 16 bytes per lane, layout B 4 bytes per lane with consecutive lanes on
+// consecutive words; the padding of 4 words keeps both free of bank conflicts.
+// The lane masks of the sign flips in these layouts are prepared by spinner_pack_signs (pack_hash_words_kernel).
+template <int NT_, int r_>
+struct HashArGeom {
+    static constexpr int NT = NT_, r = r_, R = 1 << r_, LB = NT_ - r_, LANES = 1 << LB, TPW = 64 >> LB;
+    static_assert(LB >= r && LB <= 6 && r >= 2, "two register layouts must cover all but the shared lane bits");
+    static constexpr int WAVES = 4, THREADS = 64 * WAVES, VECS_PER_WG = WAVES * TPW;
+    static constexpr int STRIDE = R + 4;
+    static constexpr int GROUPS = LANES >> r;                          // runs of 2^r lanes per vector
+    static constexpr int VEC_WORDS = LANES * STRIDE + GROUPS * R;      // the skews fit, and vectors of a wave start on different banks
+    static_assert((LANES * STRIDE) % 64 == 0 && GROUPS * R * TPW <= 64, "bank layout of the exchange buffer");
+};
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // orders this wave's LDS writes before its later LDS reads (the buffer is private to the wave)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <typename G>
+__device__ __forceinline__ void hash_ar_stages(float (&v)[G::R])
+{
+    static_for<0, G::r>([&](auto q) { reg_stage<q.value>(v); });
+}
+template <typename G>
+__device__ __forceinline__ void hash_ar_shared_lane_stages(float (&v)[G::R], int l)
+{
+    static_for<G::r, G::LB>([&](auto b) { lane_stage<b.value>(v, ((l >> b.value) & 1) ? -1.0f : 1.0f); });
+}
+template <typename G>
+__device__ __forceinline__ void hash_ar_flip(float (&v)[G::R], const unsigned long long* words)
+{
+    sign_words_t w = (sign_words_t)words;
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) flip_by_mask(v[j], w[j]);
+}
+// v = D x for a diagonal given as lane masks (reads the resident copy, writes the working registers)
+template <typename G>
+__device__ __forceinline__ void hash_ar_flip_from(float (&v)[G::R], const float (&x)[G::R], const unsigned long long* words)
+{
+    sign_words_t w = (sign_words_t)words;
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) asm("v_cndmask_b32_e64 %0, %1, -%1, %2" : "=v"(v[j]) : "v"(x[j]), "s"(w[j]));
+}
+template <typename G>
+__device__ __forceinline__ void hash_ar_a_to_b(float (&v)[G::R], float4* pa, float* pb)
+{
+#pragma unroll
+    for (int k = 0; k < G::R / 4; ++k) pa[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+    wave_lds_fence();
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) v[j] = pb[j * G::STRIDE];
+    wave_lds_fence();
+}
+template <typename G>
+__device__ __forceinline__ void hash_ar_b_to_a(float (&v)[G::R], float4* pa, float* pb)
+{
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) pb[j * G::STRIDE] = v[j];
+    wave_lds_fence();
+#pragma unroll
+    for (int k = 0; k < G::R / 4; ++k) {
+        const float4 t = pa[k];
+        v[4 * k] = t.x; v[4 * k + 1] = t.y; v[4 * k + 2] = t.z; v[4 * k + 3] = t.w;
+    }
+    wave_lds_fence();
+}
+
+template <typename G>
+__global__ void __launch_bounds__(G::THREADS) spinner_hash_ar_kernel(HashParams p)
+{
+    constexpr int R = G::R, r = G::r, n = 1 << G::NT;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int g = lane >> G::LB, l = lane & (G::LANES - 1);
+    const long long vec = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + g;
+    const bool active = vec < p.batch;
+
+    __shared__ float4 lds_store[G::WAVES * G::TPW * G::VEC_WORDS / 4];
+    float* w = reinterpret_cast<float*>(lds_store) + (wave * G::TPW + g) * G::VEC_WORDS;
+    float4* pa = reinterpret_cast<float4*>(w + l * G::STRIDE + (l >> r) * R);
+    float* pb = w + (l & (R - 1)) + ((l >> r) << r) * G::STRIDE + (l >> r) * R;
+
+    // x: coalesced 16-byte loads, then through the buffer into layout A
+    float x0[R];
+    {
+        const float* src = p.x + (active ? vec : 0) * (long long)n;
+#pragma unroll
+        for (int k = 0; k < R / 4; ++k) {
+            const int e = 4 * (k * G::LANES + l);
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (active) t = *reinterpret_cast<const float4*>(src + e);
+            *reinterpret_cast<float4*>(w + (e >> r) * G::STRIDE + (e & (R - 1)) + (e >> (2 * r)) * R) = t;
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int k = 0; k < R / 4; ++k) {
+            const float4 t = pa[k];
+            x0[4 * k] = t.x; x0[4 * k + 1] = t.y; x0[4 * k + 2] = t.z; x0[4 * k + 3] = t.w;
+        }
+        wave_lds_fence();
+    }
+
+    constexpr int W = n / 64 < 4 ? 4 : n / 64;
+    for (int t = 0; t < p.L; ++t) {
+        const unsigned long long* hw = p.signs + (long long)t * p.triple_words + 3 * W;   // [3][2][R]: diagonal, layout
+        float v[R];
+        hash_ar_flip_from<G>(v, x0, hw);            // D1 in layout A
+        hash_ar_stages<G>(v);
+        hash_ar_a_to_b<G>(v, pa, pb);
+        hash_ar_stages<G>(v);
+        hash_ar_shared_lane_stages<G>(v, l);
+        hash_ar_flip<G>(v, hw + 3 * R);             // D2 in layout B
+        hash_ar_stages<G>(v);
+        hash_ar_b_to_a<G>(v, pa, pb);
+        hash_ar_stages<G>(v);
+        hash_ar_shared_lane_stages<G>(v, l);
+        hash_ar_flip<G>(v, hw + 4 * R);             // D3 in layout A
+        hash_ar_stages<G>(v);
+        hash_ar_a_to_b<G>(v, pa, pb);
+        hash_ar_stages<G>(v);
+        hash_ar_shared_lane_stages<G>(v, l);
+
+        // layout B: register j holds element ebase + (j << r); increasing j is increasing index, strict '>' keeps the lowest
+        const int ebase = (l & (R - 1)) + ((l >> r) << (2 * r));
+        float best = v[0];
+        int best_i = ebase;
+#pragma unroll
+        for (int j = 1; j < R; ++j) {
+            const bool take = __builtin_fabsf(v[j]) > __builtin_fabsf(best);
+            best = take ? v[j] : best;
+            best_i = take ? (ebase + (j << r)) : best_i;
+        }
+        static_for<0, G::LB>([&](auto b) {
+            const float ov = lane_xor<(1 << b.value)>(best);
+            const int oi = lane_xor_i<(1 << b.value)>(best_i);
+            const float fa = __builtin_fabsf(ov), fb = __builtin_fabsf(best);
+            const bool take = (fa > fb) || (fa == fb && oi < best_i);
+            best = take ? ov : best;
+            best_i = take ? oi : best_i;
+        });
+        if (active && l == 0) p.out_idx[vec * p.L + t] = best_i + ((best < 0.0f) ? n : 0);
+    }
+}
+
+// Lane masks of the sign flips in the two layouts above, behind the sign words of each triple:
+// word [k][0][j] (layout A): bit l of each vector's lane group = sign of d_k[j + (l << r)];
+// word [k][1][j] (layout B): sign of d_k[(l mod 2^r) + (j << r) + ((l >> r) << 2r)].
+__global__ void __launch_bounds__(256) pack_hash_words_kernel(const float* __restrict__ diag, unsigned long long* __restrict__ out,
+                                                              int log2n, int r, long long triple_words, long long std_words, long long total)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int R = 1 << r, LB = log2n - r;
+    const int j = (int)(i % R);
+    const int lay = (int)((i / R) % 2);
+    const long long dg = i / (2 * R);               // 3 * triple + k
+    const float* d = diag + (dg << log2n);
+    unsigned long long m = 0;
+    for (int l = 0; l < (1 << LB); ++l) {
+        const int e = lay == 0 ? j + (l << r) : (l & (R - 1)) + (j << r) + ((l >> r) << (2 * r));
+        m |= (unsigned long long)(__float_as_uint(d[e]) >> 31) << l;
+    }
+    for (int sft = 1 << LB; sft < 64; sft <<= 1) m |= m << sft;     // one copy per vector of the wave
+    out[(dg / 3) * triple_words + std_words + ((dg % 3) * 2 + lay) * R + j] = m;
+}
+
+hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s)
+{
+    const int r = hash_ar_log2r(log2n);
+    if (!r) return hipSuccess;
+    const int n = 1 << log2n;
+    const long long total = (long long)L * 3 * 2 * (1 << r);
+    hipLaunchKernelGGL(pack_hash_words_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, diag_sets, signs, log2n, r,
+                       sign_words_per_triple(n, log2n), 3 * sign_words_per_diag(n), total);
+    return hipGetLastError();
+}
+
 template <int NT, bool SIGNS>
 static hipError_t launch_hash_nt(const HashParams& p, hipStream_t s)
 {
+    if constexpr (SIGNS && hash_ar_log2r(NT) != 0) {
+        using GA = HashArGeom<NT, hash_ar_log2r(NT)>;
+        const long long blocks = (p.batch + GA::VECS_PER_WG - 1) / GA::VECS_PER_WG;
+        if (blocks <= 0) return hipSuccess;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+        hipLaunchKernelGGL((spinner_hash_ar_kernel<GA>), dim3((unsigned)blocks), dim3(GA::THREADS), 0, s, p);
+        return hipGetLastError();
+    }
     using G = TileGeom<NT, clamp_rmax(NT, SPINNER_HASH_RMAX)>;
     const long long blocks = (p.batch + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;

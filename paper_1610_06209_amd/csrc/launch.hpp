@@ -109,6 +109,20 @@ hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const 
 
 // sign words per diagonal in the packed format (n <= 2^14)
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
+// Sizes whose hash kernel keeps every butterfly between registers (hash.hip) take, behind the three diagonals'
+// sign words of a triple, the lane masks of that kernel's two layouts: [3 diagonals][2 layouts][2^r words].
+#ifndef SPINNER_HASH_AR_SIZES     // bit N set: n = 2^N is hashed by that kernel (tuning experiments)
+#define SPINNER_HASH_AR_SIZES 0x500
+#endif
+constexpr int hash_ar_log2r(int log2n)      // values per thread (log2); 0: size not covered
+{
+    return (log2n >= 8 && log2n <= 11 && ((SPINNER_HASH_AR_SIZES >> log2n) & 1)) ? (log2n >= 10 ? 5 : 4) : 0;
+}
+inline long long sign_words_per_triple(int n, int log2n)
+{
+    return 3 * sign_words_per_diag(n) + (hash_ar_log2r(log2n) ? 6LL << hash_ar_log2r(log2n) : 0);
+}
+hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
 
 // adaptive layer (forward with saved activations, backward); the parameter structs are in layer_kernels.hpp
 struct LayerForwardParams;

@@ -1055,7 +1055,8 @@ spinner_tile_kernel(TileParams p)
 struct HashParams {
     const float* x;
     const float* diag_sets;   // [L][3][n] fp32 diagonals, or null when sign words are used
-    const unsigned long long* signs;   // [L][3][words] packed sign words, or null
+    const unsigned long long* signs;   // packed sign words of L triples, or null
+    long long triple_words;   // 64-bit words from one triple's sign words to the next
     int* out_idx;             // [batch][L]
     long long batch;
     int L;
@@ -1105,7 +1106,7 @@ spinner_hash_kernel(HashParams p)
     for (int l = 0; l < p.L; ++l) {
         const float* d = p.diag_sets + (long long)l * 3 * n;
         constexpr int W = n / 64 < 4 ? 4 : n / 64;              // sign words per diagonal
-        const unsigned long long* sw = p.signs + (long long)l * 3 * W;
+        const unsigned long long* sw = p.signs + (long long)l * p.triple_words;
         float v[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) v[j] = x0[j];

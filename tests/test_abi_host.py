@@ -86,8 +86,12 @@ def test_hash_rejects_bad_arguments_before_launch(b):
 
 
 def test_sign_word_entry_points_reject_bad_arguments(b):
-    assert b.spinner_signs_bytes(1024, 1) == 3 * 16 * 8
+    assert b.spinner_signs_bytes(2048, 1) == 3 * 32 * 8
+    # n = 1024 also carries the lane masks of its hash kernel's two layouts: [3][2][32] words per triple
+    assert b.spinner_signs_bytes(1024, 1) == 3 * 16 * 8 + 3 * 2 * 32 * 8
+    assert b.spinner_signs_bytes(1024, 5) == 5 * b.spinner_signs_bytes(1024, 1)
     assert b.spinner_signs_bytes(64, 2) == 2 * 3 * 4 * 8
+    assert b.spinner_signs_bytes(256, 1) == 3 * 4 * 8 + 3 * 2 * 16 * 8
     assert b.spinner_signs_bytes(1 << 16, 1) == 3 * (1 << 16) * 4
     assert b.spinner_signs_bytes(1000, 1) == 0 and b.spinner_signs_bytes(1024, 0) == 0
     pk = b.lib.spinner_pack_signs
