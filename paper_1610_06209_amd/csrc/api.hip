@@ -224,7 +224,7 @@ size_t spinner_signs_bytes(int n, int L)
 {
     int log2n;
     if (!pow2_in_range(n, &log2n) || L < 1) return 0;
-    if (log2n <= spinner::kFusedMaxLogOther) return (size_t)L * (size_t)spinner::sign_words_per_triple(n, log2n) * 8;
+    if (log2n <= spinner::kSignWordsMaxLog) return (size_t)L * (size_t)spinner::sign_words_per_triple(n, log2n) * 8;
     return (size_t)L * 3 * (size_t)n * sizeof(float);      // plain copy of the diagonals
 }
 
@@ -236,7 +236,7 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     if (!diag_sets || !signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (log2n > spinner::kFusedMaxLogOther) {
+    if (log2n > spinner::kSignWordsMaxLog) {
         const hipError_t e = hipMemcpyAsync(signs, diag_sets, spinner_signs_bytes(n, L), hipMemcpyDeviceToDevice, s);
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);
     }
@@ -248,6 +248,10 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && spinner::hash_ar_log2r(log2n))
         e = spinner::launch_pack_hash_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
+    if (e == hipSuccess && log2n > spinner::kFusedMaxLogOther)      // fp32 copy of each triple behind its sign words
+        e = hipMemcpy2DAsync(static_cast<unsigned long long*>(signs) + 3 * W, (size_t)spinner::sign_words_per_triple(n, log2n) * 8,
+                             diag_sets, (size_t)3 * n * sizeof(float), (size_t)3 * n * sizeof(float), (size_t)L,
+                             hipMemcpyDeviceToDevice, s);
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 
@@ -259,8 +263,10 @@ int spinner_apply_signs(const float* x, int n, long batch, const void* signs, in
     if (rc != SPINNER_OK || batch == 0) return rc;
     if (!signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > spinner::kFusedMaxLogOther) {
-        const float* d = static_cast<const float*>(signs);
+    if (log2n > fused_max_log(epilogue)) {      // four passes: fp32 diagonals (the whole buffer, or what follows the sign words)
+        const float* d = log2n > spinner::kSignWordsMaxLog
+                             ? static_cast<const float*>(signs)
+                             : reinterpret_cast<const float*>(static_cast<const unsigned long long*>(signs) + 3 * spinner::sign_words_per_diag(n));
         return apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, epilogue, scale, out, workspace,
                           stream);
     }
@@ -353,7 +359,7 @@ int spinner_sign_codes_signs(const float* x, int n, long batch, const void* sign
 {
     if (batch > 0 && !signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (n > (1 << spinner::kFusedMaxLogOther)) {     // the packed form is a plain copy of the diagonals at these sizes
+    if (n > (1 << spinner::kSignWordsMaxLog)) {     // the packed form is a plain copy of the diagonals at these sizes
         const float* d = static_cast<const float*>(signs);
         return codes_impl(x, n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, codes, workspace, stream);
     }

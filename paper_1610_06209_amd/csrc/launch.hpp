@@ -107,7 +107,8 @@ hipError_t launch_pack_codes(const float* y, long long y_stride, unsigned long l
 hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const unsigned long long* b, long long nb, int m,
                                float* out, hipStream_t s);
 
-// sign words per diagonal in the packed format (n <= 2^14)
+// sign words per diagonal in the packed format (n <= 2^16, the range of the fused plain kernels)
+constexpr int kSignWordsMaxLog = kFusedMaxLogPlain;
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
 // Sizes whose hash kernel keeps every butterfly between registers (hash.hip) take, behind the three diagonals'
 // sign words of a triple, the lane masks of that kernel's two layouts: [3 diagonals][2 layouts][2^r words].
@@ -118,9 +119,11 @@ constexpr int hash_ar_log2r(int log2n)      // values per thread (log2); 0: size
 {
     return (log2n >= 8 && log2n <= 11 && ((SPINNER_HASH_AR_SIZES >> log2n) & 1)) ? (log2n >= 10 ? 5 : 4) : 0;
 }
+// n = 2^15, 2^16: the feature map runs in four passes there and needs the fp32 diagonals, which follow the sign words.
 inline long long sign_words_per_triple(int n, int log2n)
 {
-    return 3 * sign_words_per_diag(n) + (hash_ar_log2r(log2n) ? 6LL << hash_ar_log2r(log2n) : 0);
+    return 3 * sign_words_per_diag(n) + (hash_ar_log2r(log2n) ? 6LL << hash_ar_log2r(log2n) : 0) +
+           (log2n > kFusedMaxLogOther ? 3LL * n / 2 : 0);
 }
 hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
 

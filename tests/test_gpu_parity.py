@@ -326,13 +326,27 @@ def test_sign_word_path_every_fused_size(gpu, oracle, log2n):
     assert bool((gpu.b.spinner_hash(xd, dsd) == gpu.b.spinner_hash_signs(xd, signs, L)).all())
 
 
-def test_sign_word_path_above_fused_range(gpu, oracle):
-    n = 1 << 15
-    x, d = _rng_case(n, 2, 31)
+@pytest.mark.parametrize("log2n", [15, 16, 17])
+def test_sign_word_path_above_the_feature_and_hash_range(gpu, oracle, log2n):
+    # n = 2^15, 2^16: sign words for the fused plain kernel, followed by the fp32 diagonals for the four-pass
+    # feature map; n = 2^17: a plain copy of the diagonals.  Two triples, so that the per-triple stride is used.
+    n = 1 << log2n
+    w = W.Workload("s", "apply", n, 2, n, "none", 1.0, 2, "normal", 8100 + log2n, 2)
+    x = W.make_x_numpy(w)
+    ds = W.diag_sets(w)
     xd = _to(gpu, x)
-    signs = gpu.b.spinner_pack_signs(_to(gpu, d[None]))
-    got = gpu.b.spinner_apply_signs(xd, signs).cpu().numpy()
-    want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
+    signs = gpu.b.spinner_pack_signs(_to(gpu, ds))
+    assert signs.numel() == gpu.b.spinner_signs_bytes(n, 2) == 2 * gpu.b.spinner_signs_bytes(n, 1)
+    for t in range(2):
+        got = gpu.b.spinner_apply_signs(xd, signs, triple=t).cpu().numpy()
+        want = oracle.apply(x, ds[t, 0], ds[t, 1], ds[t, 2], n, "none", 1.0)
+        assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, t
+    m = 512
+    got = gpu.b.spinner_apply_signs(xd, signs, m, "cossin", 2.0, triple=1).cpu().numpy()
+    want = oracle.apply(x, ds[1, 0], ds[1, 1], ds[1, 2], m, "cossin", 2.0)
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+    got = gpu.b.spinner_apply_signs(xd, signs, m, "none", 3.0, triple=1).cpu().numpy()      # pruned last round
+    want = oracle.apply(x, ds[1, 0], ds[1, 1], ds[1, 2], m, "none", 3.0)
     assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
 
 
