@@ -246,7 +246,7 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     hipLaunchKernelGGL(spinner::pack_signs_kernel, dim3((unsigned)blocks), dim3(256), 0, s, diag_sets,
                        static_cast<unsigned long long*>(signs), n, W, spinner::sign_words_per_triple(n, log2n), total_words);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && spinner::hash_ar_log2r(log2n))
+    if (e == hipSuccess && spinner::ar_log2r(log2n))
         e = spinner::launch_pack_hash_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
     if (e == hipSuccess && log2n > spinner::kFusedMaxLogOther)      // fp32 copy of each triple behind its sign words
         e = hipMemcpy2DAsync(static_cast<unsigned long long*>(signs) + 3 * W, (size_t)spinner::sign_words_per_triple(n, log2n) * 8,

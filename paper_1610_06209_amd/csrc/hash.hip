@@ -1,41 +1,11 @@
 // Cross-polytope hash kernels, n = 2^4 .. 2^14.
 #include "launch.hpp"
+#include "allreg.hpp"
 #ifndef SPINNER_HASH_RMAX      // values per thread (log2) of the hash kernels: 32 values leave room for four waves per
                                // SIMD beside the resident copy of x (measured 16 % faster than 64 at n = 1024, L = 16)
 #define SPINNER_HASH_RMAX 5
 #endif
 namespace spinner {
-
-// ------------------------------------------------------------------ hash kernel with every butterfly between registers
-// Hashing applies L triples to one resident copy of x, so it is bound by the vector ALU, where a butterfly
-// between two registers costs half of one across lanes (DPP forms issue at half rate) and uses no LDS.
-// This kernel therefore keeps two layouts of a vector of 2^NT = 2^(r + LB) elements on 2^LB lanes:
-//   layout A: register j, lane l hold element j + (l << r)                    (registers = index bits 0 .. r-1)
-//   layout B: register j, lane l hold element (l mod 2^r) + (j << r) + ((l >> r) << 2r)   (registers = bits r .. 2r-1)
-// and goes from one to the other through a wave-private LDS buffer once per transform, so that a transform is
-// r register stages, the exchange, r register stages (plus lane stages for the LB - r lane bits both layouts
-// share).  Element e sits at word (e >> r) * (2^r + 4) + (e mod 2^r) (+ a skew per group of 2^r lanes and per
-// vector): layout A accesses it 16 bytes per lane, layout B 4 bytes per lane with consecutive lanes on
-// consecutive words; the padding of 4 words keeps both free of bank conflicts.
-// The lane masks of the sign flips in these layouts are prepared by spinner_pack_signs (pack_hash_words_kernel).
-template <int NT_, int r_>
-struct HashArGeom {
-    static constexpr int NT = NT_, r = r_, R = 1 << r_, LB = NT_ - r_, LANES = 1 << LB, TPW = 64 >> LB;
-    static_assert(LB >= r && LB <= 6 && r >= 2, "two register layouts must cover all but the shared lane bits");
-    static constexpr int WAVES = 4, THREADS = 64 * WAVES, VECS_PER_WG = WAVES * TPW;
-    static constexpr int STRIDE = R + 4;
-    static constexpr int GROUPS = LANES >> r;                          // runs of 2^r lanes per vector
-    static constexpr int VEC_WORDS = LANES * STRIDE + GROUPS * R;      // the skews fit, and vectors of a wave start on different banks
-    static_assert((LANES * STRIDE) % 64 == 0 && GROUPS * R * TPW <= 64, "bank layout of the exchange buffer");
-};
-
-__device__ __forceinline__ void wave_lds_fence()
-{
-    // orders this wave's LDS writes before its later LDS reads (the buffer is private to the wave)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
 
 template <typename G>
 __device__ __forceinline__ void hash_ar_stages(float (&v)[G::R])
@@ -187,7 +157,7 @@ __global__ void __launch_bounds__(256) pack_hash_words_kernel(const float* __res
 
 hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s)
 {
-    const int r = hash_ar_log2r(log2n);
+    const int r = ar_log2r(log2n);
     if (!r) return hipSuccess;
     const int n = 1 << log2n;
     const long long total = (long long)L * 3 * 2 * (1 << r);

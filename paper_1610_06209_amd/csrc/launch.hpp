@@ -119,10 +119,19 @@ constexpr int hash_ar_log2r(int log2n)      // values per thread (log2); 0: size
 {
     return (log2n >= 8 && log2n <= 11 && ((SPINNER_HASH_AR_SIZES >> log2n) & 1)) ? (log2n >= 10 ? 5 : 4) : 0;
 }
+// The fp64 feature map has such a kernel too (fused_cossin.hip), for n = 2^(2r), and reads the same lane masks.
+#ifndef SPINNER_FEATURE_AR_SIZES  // bit N set: the sign-word feature map of n = 2^N runs on that kernel (tuning experiments)
+#define SPINNER_FEATURE_AR_SIZES 0x1000
+#endif
+constexpr int feature_ar_log2r(int log2n)
+{
+    return (log2n >= 8 && log2n <= 12 && !(log2n & 1) && ((SPINNER_FEATURE_AR_SIZES >> log2n) & 1)) ? log2n / 2 : 0;
+}
+constexpr int ar_log2r(int log2n) { return hash_ar_log2r(log2n) ? hash_ar_log2r(log2n) : feature_ar_log2r(log2n); }
 // n = 2^15, 2^16: the feature map runs in four passes there and needs the fp32 diagonals, which follow the sign words.
 inline long long sign_words_per_triple(int n, int log2n)
 {
-    return 3 * sign_words_per_diag(n) + (hash_ar_log2r(log2n) ? 6LL << hash_ar_log2r(log2n) : 0) +
+    return 3 * sign_words_per_diag(n) + (ar_log2r(log2n) ? 6LL << ar_log2r(log2n) : 0) +
            (log2n > kFusedMaxLogOther ? 3LL * n / 2 : 0);
 }
 hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);

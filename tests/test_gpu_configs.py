@@ -95,6 +95,15 @@ def test_cfg3_rff_n4096(gpu, oracle):
     step = 16384
     for s in range(0, w.batch, step):                       # ||features|| = 1 on the whole batch
         assert bool(((_norms(f[s:s + step]) - 1).abs() < 2e-6).all())
+    # the form the benchmark times: +-1 diagonals as packed sign words (a kernel of its own at this size)
+    del f
+    signs = gpu.b.spinner_pack_signs(dsd)
+    f = gpu.b.spinner_apply_signs(x, signs, w.m, w.epilogue, w.scale)
+    got = f[gpu.torch.from_numpy(rows).to(gpu.dev)].cpu().numpy()
+    err = rel_l2_per_vector(got, want)
+    assert err.max() <= REL_L2_TOL, err.max()
+    for s in range(0, w.batch, step):
+        assert bool(((_norms(f[s:s + step]) - 1).abs() < 2e-6).all())
 
 
 def test_cfg4_jl_n16384(gpu, oracle):

@@ -326,6 +326,21 @@ def test_sign_word_path_every_fused_size(gpu, oracle, log2n):
     assert bool((gpu.b.spinner_hash(xd, dsd) == gpu.b.spinner_hash_signs(xd, signs, L)).all())
 
 
+@pytest.mark.parametrize("m,scale,batch", [(4096, 64.0, 7), (1000, 48.0, 5), (64, 64.0, 2), (1, 64.0, 3)])
+def test_features_from_sign_words_n4096(gpu, oracle, m, scale, batch):
+    # n = 4096 with sign words runs the feature kernel that keeps every butterfly between registers:
+    # odd batches (a workgroup's last wave has no vector), row limits inside and at the edge of a 64-lane run
+    n = 4096
+    x, d = _rng_case(n, batch, 31 * m + batch)
+    ds = np.stack([d, W.rademacher_diagonals(n, 3, 77 + m)])
+    signs = gpu.b.spinner_pack_signs(_to(gpu, ds))
+    for t in range(2):
+        got = gpu.b.spinner_apply_signs(_to(gpu, x), signs, m, "cossin", scale, triple=t).cpu().numpy()
+        want = oracle.apply(x, ds[t, 0], ds[t, 1], ds[t, 2], m, "cossin", scale)
+        assert got.shape == (batch, 2 * m)
+        assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (m, t)
+
+
 @pytest.mark.parametrize("log2n", [15, 16, 17])
 def test_sign_word_path_above_the_feature_and_hash_range(gpu, oracle, log2n):
     # n = 2^15, 2^16: sign words for the fused plain kernel, followed by the fp32 diagonals for the four-pass
