@@ -81,25 +81,30 @@ spinner_feature_ar_kernel(TileParams p)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int g = lane >> G::LB, l = lane & (G::LANES - 1);
-    const long long vec = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + g;
-    const bool active = vec < p.batch;
+    const long long wvec = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW;     // first vector of this wave (wave-uniform)
     // a wave with no vector at all leaves (the exchange buffer is private to the wave: no barrier waits for it)
-    if (((long long)blockIdx.x * G::WAVES + wave) * G::TPW >= p.batch) return;
+    if (wvec >= p.batch) return;
 
     __shared__ float4 lds_store[G::WAVES * G::TPW * G::VEC_WORDS / 4];
     float* w = reinterpret_cast<float*>(lds_store) + (wave * G::TPW + g) * G::VEC_WORDS;
     float4* pa = ar_ptr_a<G>(w, l);
     float* pb = ar_ptr_b<G>(w, l);
+    constexpr int W = n / 64 < 4 ? 4 : n / 64;      // sign words per diagonal
+    const unsigned long long* hw = p.sw[0] + 3 * W; // lane masks behind the triple's sign words: [3 diagonals][2 layouts][R]
+    const int ebase = ar_base_b<G>(l);              // layout B: register j holds coordinate ebase + (j << r)
+    const long long so = p.sin_off;
 
-    double v[R];
     {
-        const float* src = p.x + (active ? vec : 0) * p.in_stride;
+        const long long vec = wvec + g;
+        const bool active = vec < p.batch;
+        double v[R];
+        // x: coalesced 16-byte loads, then through the buffer into layout A
+        const float* src = p.x + (active ? vec : 0) * p.in_stride + 4 * l;
 #pragma unroll
         for (int k = 0; k < R / 4; ++k) {
-            const int e = 4 * (k * G::LANES + l);
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (active) t = load4<true>(src + e);
-            *reinterpret_cast<float4*>(w + ar_word_of<G>(e)) = t;
+            if (G::TPW == 1 || active) t = load4<true>(src + 4 * k * G::LANES);
+            *reinterpret_cast<float4*>(w + ar_word_of<G>(4 * (k * G::LANES + l))) = t;
         }
         wave_lds_fence();
 #pragma unroll
@@ -108,57 +113,55 @@ spinner_feature_ar_kernel(TileParams p)
             v[4 * k] = (double)t.x; v[4 * k + 1] = (double)t.y; v[4 * k + 2] = (double)t.z; v[4 * k + 3] = (double)t.w;
         }
         wave_lds_fence();
-    }
 
-    // lane masks behind the triple's sign words: [3 diagonals][2 layouts][R]
-    constexpr int W = n / 64 < 4 ? 4 : n / 64;      // sign words per diagonal
-    const unsigned long long* hw = p.sw[0] + 3 * W;
-    feat_ar_flip<G>(v, hw);                 // D1 in layout A
-    ar_stages<G>(v);
-    feat_ar_a_to_b<G>(v, pa, pb);
-    ar_stages<G>(v);
-    feat_ar_flip<G>(v, hw + 3 * R);         // D2 in layout B
-    ar_stages<G>(v);
-    feat_ar_b_to_a<G>(v, pa, pb);
-    ar_stages<G>(v);
-    feat_ar_flip<G>(v, hw + 4 * R);         // D3 in layout A
-    ar_stages<G>(v);
-    feat_ar_a_to_b<G>(v, pa, pb);
-    ar_stages<G>(v);
+        feat_ar_flip<G>(v, hw);                 // D1 in layout A
+        ar_stages<G>(v);
+        feat_ar_a_to_b<G>(v, pa, pb);
+        ar_stages<G>(v);
+        feat_ar_flip<G>(v, hw + 3 * R);         // D2 in layout B
+        ar_stages<G>(v);
+        feat_ar_b_to_a<G>(v, pa, pb);
+        ar_stages<G>(v);
+        feat_ar_flip<G>(v, hw + 4 * R);         // D3 in layout A
+        ar_stages<G>(v);
+        feat_ar_a_to_b<G>(v, pa, pb);
+        ar_stages<G>(v);
 
-    // layout B: register j holds coordinate ebase + (j << r)
-    const int ebase = ar_base_b<G>(l);
-    const long long so = p.sin_off;
-    float* dst = p.out + (active ? vec : 0) * p.out_stride + ebase;
-    if (p.m == n) {                         // every coordinate is kept: straight-line stores
+        float* dst = p.out + (active ? vec : 0) * p.out_stride + ebase;
+        if (p.m == n) {                         // every coordinate is kept: straight-line stores
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            float sn, cs;
-            feature_sincos(v[j], p, 0.0f, sn, cs);
-            if (G::TPW == 1 || active) {
-                __builtin_nontemporal_store(cs * p.inv_sqrt_m, dst + (j << r));
-                __builtin_nontemporal_store(sn * p.inv_sqrt_m, dst + so + (j << r));
+            for (int j = 0; j < R; ++j) {
+                float sn, cs;
+                feature_sincos(v[j], p, 0.0f, sn, cs);
+                if (G::TPW == 1 || active) {
+                    __builtin_nontemporal_store(cs * p.inv_sqrt_m, dst + (j << r));
+                    __builtin_nontemporal_store(sn * p.inv_sqrt_m, dst + so + (j << r));
+                }
             }
-        }
-    } else {
-        const int m = active ? p.m : 0;
+        } else {
+            const int m = active ? p.m : 0;
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            float sn, cs;
-            feature_sincos(v[j], p, 0.0f, sn, cs);
-            if (ebase + (j << r) < m) {
-                __builtin_nontemporal_store(cs * p.inv_sqrt_m, dst + (j << r));
-                __builtin_nontemporal_store(sn * p.inv_sqrt_m, dst + so + (j << r));
+            for (int j = 0; j < R; ++j) {
+                float sn, cs;
+                feature_sincos(v[j], p, 0.0f, sn, cs);
+                if (ebase + (j << r) < m) {
+                    __builtin_nontemporal_store(cs * p.inv_sqrt_m, dst + (j << r));
+                    __builtin_nontemporal_store(sn * p.inv_sqrt_m, dst + so + (j << r));
+                }
             }
         }
     }
 }
 
+#ifndef SPINNER_FEAT_AR_WAVES       // waves per workgroup (each wave owns its vectors and its exchange buffer)
+#define SPINNER_FEAT_AR_WAVES 1
+#endif
+
 template <int NT>
 static hipError_t launch_cossin_signs(const TileParams& p, long long tiles, hipStream_t s)
 {
     if constexpr (feature_ar_log2r(NT) != 0) {
-        using GA = HashArGeom<NT, feature_ar_log2r(NT), 2>;
+        using GA = HashArGeom<NT, feature_ar_log2r(NT), SPINNER_FEAT_AR_WAVES>;
         const long long blocks = (tiles + GA::VECS_PER_WG - 1) / GA::VECS_PER_WG;
         if (blocks <= 0) return hipSuccess;
         if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;

@@ -52,6 +52,9 @@
 #ifndef SPINNER_DPP_MASKS            // lane masks (of 1, 2, 8) whose butterflies use the one-instruction DPP form; the
 #define SPINNER_DPP_MASKS 0xB        // others go through the LDS crossbar (tuning experiments)
 #endif
+#ifndef SPINNER_EXPERIMENT_PRIO      // tuning experiments: bit 0 raises the wave priority while a tile's loads are issued, bit 1 from the
+#define SPINNER_EXPERIMENT_PRIO 0    // last exchange to the end of the stores
+#endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -912,6 +915,9 @@ spinner_tile_kernel(TileParams p)
 
         T v[R];
         {
+#if SPINNER_EXPERIMENT_PRIO & 1
+            __builtin_amdgcn_s_setprio(3);
+#endif
             const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(G::layout_after(0)), p.sl);
 #pragma unroll
             for (int jh = 0; jh < R / 4; ++jh) {
@@ -919,21 +925,26 @@ spinner_tile_kernel(TileParams p)
                 if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
                 v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
             }
+#if SPINNER_EXPERIMENT_PRIO & 1
+            __builtin_amdgcn_s_setprio(0);
+#endif
         }
 
         // steps (layout alternates only when a tile spans several waves)
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
-        if (p.m < 0)      // never true: keeps the code but skips it (memory-shape experiment)
+        // never true: keeps the code but skips it (memory-shape experiment).  Not for pruned kernels: their
+        // stores rely on the last step's bookkeeping of which waves and registers still hold outputs.
+        if (PRUNE > 0 || p.m < 0)
 #endif
         spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
-        if (p.m < 0)
+        if (PRUNE > 0 || p.m < 0)
 #endif
         if constexpr (NSTEPS > 1)
             spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
         bool wave_live = true;
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
-        if (p.m < 0)
+        if (PRUNE > 0 || p.m < 0)
 #endif
         if constexpr (NSTEPS > 2) {
             if constexpr (PRUNE > 0)
@@ -946,6 +957,9 @@ spinner_tile_kernel(TileParams p)
 
         constexpr int LAYF = G::layout_after(NSTEPS);
         const int ebase = c.base_index(LAYF);
+#if SPINNER_EXPERIMENT_PRIO & 2
+        __builtin_amdgcn_s_setprio(3);
+#endif
         if (active && wave_live) {
             const long long m = p.m;
             // held values carry the tracked lane sign after an odd number of transforms
