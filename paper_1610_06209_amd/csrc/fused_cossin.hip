@@ -73,7 +73,7 @@ __device__ __forceinline__ void feat_ar_b_to_a(double (&v)[G::R], float4* pa, fl
 }
 
 template <typename G>
-__global__ void __launch_bounds__(G::THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(G::THREADS) __attribute__((amdgpu_waves_per_eu(G::r >= 6 ? 2 : 4)))
 spinner_feature_ar_kernel(TileParams p)
 {
     static_assert(G::LB == G::r, "no lane bit is shared by the two layouts");
