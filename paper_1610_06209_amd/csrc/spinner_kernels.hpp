@@ -42,7 +42,7 @@
 #endif
 #ifndef SPINNER_EXPERIMENT_KNOCKOUT   // timing experiments only (results are wrong): bit 0 drops the lane stages that
 #define SPINNER_EXPERIMENT_KNOCKOUT 0 // cross the LDS crossbar, 1 the DPP lane stages, 2 the register stages, 3 the LDS
-#endif                                // traffic of the transposes (barriers stay), 4 the diagonals
+#endif                                // traffic of the transposes (barriers stay), 4 the diagonals, 5 the lane-swap stages
 #ifndef SPINNER_LANE_SWAPS           // 1: in tiles that span several waves, lane bits 4 and 5 are transformed by swapping
 #define SPINNER_LANE_SWAPS 1         //    lane halves with register pairs (vector ALU) instead of LDS-crossbar exchanges
 #endif
@@ -447,7 +447,7 @@ __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c
             }
         }
     });
-    if constexpr (SWAP) {
+    if constexpr (SWAP && !(SPINNER_EXPERIMENT_KNOCKOUT & 32)) {
         lane_swap_stage<4, 2>(v);
         lane_swap_stage<5, 3>(v);
     }
@@ -572,10 +572,11 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
 #pragma unroll
                 for (int jh = 0; jh < NW / 4; ++jh) {
                     const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
-                    lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
+                    if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 8))
+                        lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
                 }
                 __syncthreads();
-                if (reads) {
+                if (reads && !(SPINNER_EXPERIMENT_KNOCKOUT & 8)) {
 #pragma unroll
                     for (int jh = 0; jh < NR / 4; ++jh) {
                         const int e = et | G::reg_index(TO, jh * 4);
