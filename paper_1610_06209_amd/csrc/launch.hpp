@@ -22,7 +22,6 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 #endif
 struct NotWide { static constexpr int wide = 0, start = 0; };
 template <typename T, int NT> struct Tuning : NotWide { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0, trips = 0; };
-#ifndef SPINNER_RMAX_F32
 #ifndef SPINNER_RMAX_F64_N12
 #define SPINNER_RMAX_F64_N12 4
 #endif
@@ -66,15 +65,6 @@ using ContigGeomFor = GeomFrom<ContigTuning<T, NT>, NT>;
 template <typename T, int NT> struct PrunedTuning : Tuning<T, NT> {};
 template <typename T, int NT>
 using PrunedGeomFor = GeomFrom<PrunedTuning<T, NT>, NT>;
-#else   // uniform override used by tuning sweeps
-template <typename T, int NT> struct PrunedTuning { static constexpr int rmax = clamp_rmax(NT, SPINNER_RMAX_F32), waves = SPINNER_WAVES_PER_WG, min_waves = 0, trips = 0, wide = 0, start = 0; };
-template <typename T, int NT> struct Tuning : PrunedTuning<T, NT> {};
-template <typename T, int NT>
-using PrunedGeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
-template <typename T, int NT>
-using GeomFor = TileGeom<NT, std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : clamp_rmax(NT, SPINNER_RMAX_F32), SPINNER_WAVES_PER_WG>;
-template <typename T, int NT> using ContigGeomFor = GeomFor<T, NT>;
-#endif
 
 template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
