@@ -81,63 +81,122 @@ hipError_t launch_pack_codes(const float* y, long long y_stride, unsigned long l
     return hipGetLastError();
 }
 
-// out[i][j] = 1 - popcount(a_i xor b_j) / m.  A workgroup of 16 x 16 threads owns a block of
-// 64 x 64 pairs (4 x 4 per thread) and walks the code words in chunks of 32 staged in LDS
-// (rows padded by one word so that the 16 rows a wave reads at once fall into different banks).
-constexpr int kGramTile = 64, kGramChunk = 32;
+// out[i][j] = 1 - popcount(a_i xor b_j) / m.  With the code bits as 0 / 1 numbers,
+//     popcount(a xor b) = |a| + |b| - 2 <a, b>,
+// and the table of inner products <a_i, b_j> is a dense contraction over the m code bits: it runs on the matrix
+// pipe as an int8 product (v_mfma_i32_32x32x32_i8, exact in int32).  A workgroup of four waves owns 128 x 128 pairs
+// (each wave 64 x 64 = 2 x 2 tiles) and walks the code words in chunks of 16 staged in LDS (rows padded by one
+// word: the 32 rows a wave reads at once fall on different banks).  The bits are spread into bytes in registers:
+// of a 32-bit half word w, lane group g = lane / 32 supplies the four dwords (w >> (4 g + q)) & 0x01010101,
+// q = 0..3, i.e. bits 4 g + q + 8 t in byte t.  Which bit lands in which of the 32 k-slots of the instruction
+// does not matter, as long as both operands are spread the same way.  The row weights |a_i|, |b_j| are counted
+// on the way (v_bcnt), |a_i| goes through LDS to the lanes that hold row i of the result.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+#ifndef SPINNER_GRAM_U            // 32-column tiles per wave (2: 128 x 128 pairs per workgroup; 4: 128 x 256, measured 25 % slower)
+#define SPINNER_GRAM_U 2
+#endif
+constexpr int kGramRows = 128, kGramU = SPINNER_GRAM_U, kGramCols = 64 * kGramU, kGramChunk = 16;
 __global__ void __launch_bounds__(256) hamming_gram_kernel(const unsigned long long* __restrict__ a, long long na,
                                                            const unsigned long long* __restrict__ b, long long nb,
                                                            int words, float inv_m, float* __restrict__ out)
 {
-    __shared__ unsigned long long sa[kGramTile][kGramChunk + 1];
-    __shared__ unsigned long long sb[kGramTile][kGramChunk + 1];
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const long long i0 = (long long)blockIdx.y * kGramTile, j0 = (long long)blockIdx.x * kGramTile;
-    int dh[4][4];
+    __shared__ unsigned long long sa[kGramRows][kGramChunk + 1];
+    __shared__ unsigned long long sb[kGramCols][kGramChunk + 1];
+    __shared__ int weight_a[kGramRows];
+    constexpr int U = kGramU;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wr = wave >> 1, wc = wave & 1, g = lane >> 5, l32 = lane & 31;
+    const long long i0 = (long long)blockIdx.y * kGramRows, j0 = (long long)blockIdx.x * kGramCols;
+    intx16 acc[2][U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int w = 0; w < 4; ++w) dh[u][w] = 0;
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][u][v] = 0;
+    int wa[2] = {0, 0}, wb[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) wb[u] = 0;
 
+    // staging: rows x 16 words per operand, 256 threads: thread handles word (idx & 15) of row (idx >> 4), idx = t * 256 + tid
+    constexpr int TA = kGramRows / 16, TB = kGramCols / 16;
+    const int srow = threadIdx.x >> 4, scol = threadIdx.x & 15;
+    unsigned long long pa[TA], pb[TB];
+    auto fetch = [&](int k0) {
+        const bool in_k = k0 + scol < words;
+#pragma unroll
+        for (int t = 0; t < TA; ++t) pa[t] = (in_k && i0 + t * 16 + srow < na) ? a[(i0 + t * 16 + srow) * words + k0 + scol] : 0ull;
+#pragma unroll
+        for (int t = 0; t < TB; ++t) pb[t] = (in_k && j0 + t * 16 + srow < nb) ? b[(j0 + t * 16 + srow) * words + k0 + scol] : 0ull;
+    };
     for (int k0 = 0; k0 < words; k0 += kGramChunk) {
-        // 64 rows x 32 words per operand, 256 threads: 8 words per thread and operand
+        fetch(k0);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int idx = t * 256 + threadIdx.x;
-            const int row = idx >> 5, col = idx & 31;
-            const bool in_k = k0 + col < words;
-            sa[row][col] = (in_k && i0 + row < na) ? a[(i0 + row) * words + k0 + col] : 0ull;
-            sb[row][col] = (in_k && j0 + row < nb) ? b[(j0 + row) * words + k0 + col] : 0ull;
-        }
+        for (int t = 0; t < TA; ++t) sa[t * 16 + srow][scol] = pa[t];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) sb[t * 16 + srow][scol] = pb[t];
         __syncthreads();
-#pragma unroll 4
+#pragma unroll 2
         for (int k = 0; k < kGramChunk; ++k) {
-            unsigned long long ra[4], rb[4];
+            unsigned long long ra[2], rb[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { ra[u] = sa[ty * 4 + u][k]; rb[u] = sb[tx + 16 * u][k]; }
+            for (int t = 0; t < 2; ++t) {
+                ra[t] = sa[wr * 64 + t * 32 + l32][k];
+                wa[t] += __popcll(ra[t]);
+            }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < U; ++u) {
+                rb[u] = sb[wc * 32 * U + u * 32 + l32][k];
+                wb[u] += __popcll(rb[u]);
+            }
 #pragma unroll
-                for (int w = 0; w < 4; ++w) dh[u][w] += __popcll(ra[u] ^ rb[w]);
+            for (int half = 0; half < 2; ++half) {
+                intx4 fa[2], fb[U];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const unsigned x = (unsigned)(ra[t] >> (32 * half)) >> (4 * g);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) fa[t][q] = (int)((x >> q) & 0x01010101u);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const unsigned x = (unsigned)(rb[u] >> (32 * half)) >> (4 * g);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) fb[u][q] = (int)((x >> q) & 0x01010101u);
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) acc[t][u] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[t], fb[u], acc[t][u], 0, 0, 0);
+            }
         }
         __syncthreads();
     }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const long long i = i0 + ty * 4 + u;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const long long j = j0 + tx + 16 * w;
-            if (i < na && j < nb) out[i * nb + j] = 1.0f - (float)dh[u][w] * inv_m;
-        }
+    if (wc == 0 && g == 0) {
+        weight_a[wr * 64 + l32] = wa[0];
+        weight_a[wr * 64 + 32 + l32] = wa[1];
     }
+    __syncthreads();
+    // result register v of lane l holds row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rl = wr * 64 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const long long i = i0 + rl, j = j0 + wc * 32 * U + u * 32 + l32;
+                const int dh = weight_a[rl] + wb[u] - 2 * acc[t][u][v];
+                if (i < na && j < nb) out[i * nb + j] = 1.0f - (float)dh * inv_m;
+            }
 }
 
 hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const unsigned long long* b, long long nb, int m,
                                float* out, hipStream_t s)
 {
     if (na <= 0 || nb <= 0) return hipSuccess;
-    const long long gx = (nb + kGramTile - 1) / kGramTile, gy = (na + kGramTile - 1) / kGramTile;
+    const long long gx = (nb + kGramCols - 1) / kGramCols, gy = (na + kGramRows - 1) / kGramRows;
     if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(hamming_gram_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, a, na, b, nb, m / 64,
                        1.0f / (float)m, out);

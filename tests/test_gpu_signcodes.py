@@ -149,6 +149,10 @@ def test_angular_gram_is_exact_on_its_codes(gpu, oracle, na, nb, m):
     rng = np.random.default_rng(na * 1000 + nb)
     ca = rng.integers(-2**63, 2**63 - 1, (na, m // 64), dtype=np.int64)
     cb = rng.integers(-2**63, 2**63 - 1, (nb, m // 64), dtype=np.int64)
+    ca[0] = -1                                                         # extreme row weights: all bits set, none set
+    if na > 1:
+        ca[1] = 0
+    cb[nb - 1] = -1
     cb[: min(na, nb)] = ca[: min(na, nb)]                              # some identical rows: estimate exactly 1
     got = gpu.b.spinner_angular_gram(_to(gpu, ca), _to(gpu, cb), m)
     gpu.torch.cuda.synchronize()
