@@ -374,7 +374,7 @@ int spinner_angular_gram(const void* codes_a, long na, const void* codes_b, long
     if (na == 0 || nb == 0) return SPINNER_OK;
     if (!codes_a || !codes_b || !out) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(codes_a) || !aligned16(codes_b) || !aligned16(out)) return SPINNER_ERR_ALIGNMENT;
-    if ((na + 63) / 64 > 65535) return SPINNER_ERR_BAD_BATCH;
+    if ((na + 127) / 128 > 65535) return SPINNER_ERR_BAD_BATCH;
     const hipError_t e = spinner::launch_hamming_gram(static_cast<const unsigned long long*>(codes_a), na,
                                                       static_cast<const unsigned long long*>(codes_b), nb, m, out,
                                                       static_cast<hipStream_t>(stream));
