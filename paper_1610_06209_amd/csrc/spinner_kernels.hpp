@@ -55,6 +55,9 @@
 #ifndef SPINNER_EXPERIMENT_PRIO      // tuning experiments: bit 0 raises the wave priority while a tile's loads are issued, bit 1 from the
 #define SPINNER_EXPERIMENT_PRIO 0    // last exchange to the end of the stores
 #endif
+#ifndef SPINNER_MASK_PREFETCH        // lane masks of the next step's sign flips fetched before the current step's exchange
+#define SPINNER_MASK_PREFETCH 16     // (each takes two scalar registers)
+#endif
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -681,31 +684,32 @@ __device__ __forceinline__ void flip_by_mask(double& x, unsigned long long mask)
     x = __hiloint2double(hi, __double2loint(x));
 }
 
-template <typename G, int LAY, typename T>
-__device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, const unsigned long long* words)
+// index bits held by the (uniform) wave id in layout LAY
+template <typename G, int LAY>
+__device__ __forceinline__ int wave_index_bits(const ThreadCtx<G>& c)
 {
-    sign_words_t w = (sign_words_t)words;
-    int ew = 0;                                   // index bits held by the (uniform) wave id
+    int ew = 0;
     for (int b = 0; b < G::WB; ++b) ew |= ((c.wv >> b) & 1) << G::wave_pos(LAY, b);
+    return ew;
+}
+
+// lane mask "which lanes hold a negated element" of register j in layout LAY
+template <typename G, int LAY>
+__device__ __forceinline__ unsigned long long sign_mask(sign_words_t w, int ew, int j)
+{
     if constexpr (G::WIDE && LAY == 1) {
         // lanes hold index bits 2..5 and two high bits: the lane mask of a register is put together from
         // the 16-bit fields (bits 2..5; bits 6, 7 are register bits here) of four words of the packed format
+        const int e = ew | G::reg_index(1, j);
+        unsigned long long m = 0;
 #pragma unroll
-        for (int j = 0; j < G::R; ++j) {
-            const int e = ew | G::reg_index(1, j);
-            unsigned long long m = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int ek = e | ((k & 1) << G::lane_pos(1, 4)) | ((k >> 1) << G::lane_pos(1, 5));
-                const unsigned long long wk = w[((ek >> 8) << 2) | (ek & 3)];
-                m |= ((wk >> (((ek >> 6) & 3) << 4)) & 0xFFFFull) << (16 * k);
-            }
-            flip_by_mask(v[j], m);
+        for (int k = 0; k < 4; ++k) {
+            const int ek = e | ((k & 1) << G::lane_pos(1, 4)) | ((k >> 1) << G::lane_pos(1, 5));
+            const unsigned long long wk = w[((ek >> 8) << 2) | (ek & 3)];
+            m |= ((wk >> (((ek >> 6) & 3) << 4)) & 0xFFFFull) << (16 * k);
         }
-        return;
-    }
-#pragma unroll
-    for (int j = 0; j < G::R; ++j) {
+        return m;
+    } else {
         const int e = ew | G::reg_index(LAY, j);  // lane bits (2 .. 2+LB-1) are zero here
         unsigned long long m = w[((e >> 8) << 2) | (e & 3)];
         if constexpr (G::LB < 6) {
@@ -715,7 +719,35 @@ __device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, c
 #pragma unroll
             for (int sft = span; sft < 64; sft <<= 1) m |= m << sft;
         }
-        flip_by_mask(v[j], m);
+        return m;
+    }
+}
+
+// Lane masks of the first N registers, fetched ahead of their use: the scalar loads of a step's masks would
+// otherwise start only after the exchange that precedes the step, with nothing to hide their latency behind.
+template <int N>
+struct SignMasks { unsigned long long m[N > 0 ? N : 1]; };
+
+template <typename G, int LAY, int N>
+__device__ __forceinline__ void fetch_sign_masks(SignMasks<N>& pm, const ThreadCtx<G>& c, const unsigned long long* words)
+{
+    sign_words_t w = (sign_words_t)words;
+    const int ew = wave_index_bits<G, LAY>(c);
+#pragma unroll
+    for (int j = 0; j < N; ++j) pm.m[j] = sign_mask<G, LAY>(w, ew, j);
+}
+
+// NPF: the masks of registers 0 .. NPF-1 come from `pm` instead of from memory
+template <typename G, int LAY, int NPF = 0, typename T>
+__device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, const unsigned long long* words,
+                                          const SignMasks<NPF>* pm = nullptr)
+{
+    sign_words_t w = (sign_words_t)words;
+    const int ew = wave_index_bits<G, LAY>(c);
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) {
+        if (j < NPF) flip_by_mask(v[j], pm->m[j]);
+        else flip_by_mask(v[j], sign_mask<G, LAY>(w, ew, j));
     }
 }
 
@@ -723,12 +755,19 @@ __device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, c
 // layout when the tile spans several waves.  Every index bit >= CB is
 // transformed exactly once: register and lane bits of LAY before the transpose,
 // the bits LAY keeps in the wave id after it.
-template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, bool NEGATE, bool SIGNS, typename T>
+// NPF > 0: `pm` holds the first NPF lane masks of this step's sign flips unless this is the first step, and, with
+// PF_NEXT, receives those of the next step (packed words at next_words) before this step's exchange.
+template <typename G, int C, int CB, int LAY, bool HAS_DIAG, bool FIRST_TRANSPOSE, bool NEGATE, bool SIGNS, typename T, int NPF = 0,
+          bool PF_NEXT = false>
 __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c,
-                                             const float* dtile, const unsigned long long* words, int sl, float4* lds)
+                                             const float* dtile, const unsigned long long* words, int sl, float4* lds,
+                                             SignMasks<NPF>* pm = nullptr, const unsigned long long* next_words = nullptr)
 {
     if constexpr (HAS_DIAG && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) {
-        if constexpr (SIGNS) sign_flip<G, LAY>(v, c, words);
+        if constexpr (SIGNS) {
+            if constexpr (NPF > 0 && !FIRST_TRANSPOSE) sign_flip<G, LAY, NPF>(v, c, words, pm);
+            else sign_flip<G, LAY>(v, c, words);
+        }
         else diag_multiply<G, C, LAY>(v, c, dtile, sl);
     }
 #ifndef SPINNER_LANE_SWAPS_F64
@@ -736,6 +775,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 #endif
     constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(LAY, 4);
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
+    if constexpr (NPF > 0 && PF_NEXT && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) fetch_sign_masks<G, (G::WB > 0 ? 1 - LAY : LAY)>(*pm, c, next_words);
     if constexpr (G::WB > 0) {
         if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
         else transpose<G, LAY, !FIRST_TRANSPOSE, SWAP>(v, c, lds);
@@ -816,15 +856,15 @@ __device__ __forceinline__ void pruned_reg_stages(T (&v)[G::R])
 // The last (diagonal, transform) step with the P highest index bits pruned.  Returns,
 // through wave_live, whether this wave still holds outputs; pruned_final_regs() tells
 // how many leading registers do.
-template <typename G, int C, int CB, int LAY, bool NEGATE, bool SIGNS, int P>
+template <typename G, int C, int CB, int LAY, bool NEGATE, bool SIGNS, int P, int NPF = 0>
 __device__ __forceinline__ void spinner_step_pruned(float (&v)[G::R], const ThreadCtx<G>& c, const float* dtile,
                                                     const unsigned long long* words, int sl, float4* lds,
-                                                    bool& wave_live)
+                                                    bool& wave_live, const SignMasks<NPF>* pm = nullptr)
 {
     static_assert(C >= G::NT && CB == 0, "pruning is for whole-vector tiles");
     constexpr unsigned PM = prune_positions<G>(P);
     constexpr unsigned REGS = reg_positions<G>(LAY);
-    if constexpr (SIGNS) sign_flip<G, LAY>(v, c, words);
+    if constexpr (SIGNS) sign_flip<G, LAY, NPF>(v, c, words, pm);
     else diag_multiply<G, C, LAY>(v, c, dtile, sl);
     pruned_reg_stages<G, LAY, REGS, PM, 0u>(v);
     constexpr unsigned DONE1 = PM & REGS;
@@ -931,27 +971,31 @@ spinner_tile_kernel(TileParams p)
 #endif
         }
 
+        // lane masks of the next step's sign flips travel in scalar registers across the exchange (see SignMasks)
+        // (measured: 1.4 % at n = 2^14, nothing elsewhere; only tiles of several waves with 64 values per thread use it)
+        constexpr int NPF = (SIGNS && G::WB > 0 && R == 64 && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) ? SPINNER_MASK_PREFETCH : 0;
+        SignMasks<NPF> pm;
         // steps (layout alternates only when a tile spans several waves)
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
         // never true: keeps the code but skips it (memory-shape experiment).  Not for pruned kernels: their
         // stores rely on the last step's bookkeeping of which waves and registers still hold outputs.
         if (PRUNE > 0 || p.m < 0)
 #endif
-        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds);
+        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS, T, NPF, (NSTEPS > 1)>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds, &pm, p.sw[1]);
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
         if (PRUNE > 0 || p.m < 0)
 #endif
         if constexpr (NSTEPS > 1)
-            spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds);
+            spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS, T, NPF, (NSTEPS > 2)>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds, &pm, p.sw[2]);
         bool wave_live = true;
 #ifdef SPINNER_EXPERIMENT_NOCOMPUTE
         if (PRUNE > 0 || p.m < 0)
 #endif
         if constexpr (NSTEPS > 2) {
             if constexpr (PRUNE > 0)
-                spinner_step_pruned<G, C, CB, G::layout_after(2), false, SIGNS, PRUNE>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds, wave_live);
+                spinner_step_pruned<G, C, CB, G::layout_after(2), false, SIGNS, PRUNE, NPF>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds, wave_live, &pm);
             else
-                spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds);
+                spinner_step<G, C, CB, G::layout_after(2), true, false, false, SIGNS, T, NPF, false>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds, &pm);
         }
         static_assert(PRUNE == 0 || (NSTEPS == 3 && std::is_same<T, float>::value), "pruning: fused fp32 kernels only");
         constexpr int RF = PRUNE > 0 ? pruned_final_regs<G>(G::layout_after(2), PRUNE) : R;   // registers that hold outputs
