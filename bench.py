@@ -181,9 +181,10 @@ def measure_gram(torch, b, dev, rows, m, steps, warmup):
     return res
 
 
-def measure_layer(torch, b, dev, n, batch, steps, warmup):
+def measure_layer(torch, b, dev, n, batch, steps, warmup, graph=False):
     """Adaptive layer: forward (keeps two activations) + backward (dx and the three diagonal gradients).
-    Algorithmic bytes per element: forward 4 read + 12 written, backward 16 read + 4 written."""
+    Algorithmic bytes per element: forward 4 read + 12 written, backward 16 read + 4 written.
+    graph=True also times the step as a captured HIP graph of 20 forward + backward pairs (launch-bound sizes)."""
     g = torch.Generator(device=dev)
     g.manual_seed(1610 + n)
     x = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
@@ -203,8 +204,9 @@ def measure_layer(torch, b, dev, n, batch, steps, warmup):
     _, b_ms = time_calls(torch, bwd, steps, warmup)
     wall_ms, _ = time_calls(torch, lambda: (fwd(), bwd()), steps, warmup)
     el = batch * n
+    graph_ms = time_graph(torch, lambda: (fwd(), bwd()), 20, 10) if graph else None
     res = {"workload": "adaptive_layer_n%d_b%d" % (n, batch), "forward_ms": round(f_ms, 4), "backward_ms": round(b_ms, 4),
-           "step_us_wall": round(wall_ms * 1e3, 2),
+           "step_us_wall": round(wall_ms * 1e3, 2), "step_us_graph": None if graph_ms is None else round(graph_ms * 1e3, 2),
            "forward_GBs": round(16.0 * el / (f_ms * 1e-3) / 1e9, 1), "backward_GBs": round(20.0 * el / (b_ms * 1e-3) / 1e9, 1)}
     del x, dy, d, y, dx, saved, dd, ws
     torch.cuda.empty_cache()
@@ -436,11 +438,11 @@ def main():
         # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
         tbl = []
         for k in range(4, 13):
-            r = measure_layer(torch, b, dev, 1 << k, 1024, 20, 5)
-            tbl.append({"h": 1 << k, "step_us_wall": r["step_us_wall"],
+            r = measure_layer(torch, b, dev, 1 << k, 1024, 20, 5, graph=True)
+            tbl.append({"h": 1 << k, "step_us_wall": r["step_us_wall"], "step_us_graph": r["step_us_graph"],
                         "kernels_us": round((r["forward_ms"] + r["backward_ms"]) * 1e3, 2)})
-        log("[bench] adaptive layer, batch 1024, h=2^4..2^12, forward+backward us per step, wall (kernels): " +
-            " ".join("%.1f (%.1f)" % (t["step_us_wall"], t["kernels_us"]) for t in tbl))
+        log("[bench] adaptive layer, batch 1024, h=2^4..2^12, forward+backward us per step, eager wall / captured graph: " +
+            " ".join("%.1f/%.1f" % (t["step_us_wall"], t["step_us_graph"]) for t in tbl))
         nxt.append({"workload": "adaptive_layer_table2_sizes_b1024", "rows": tbl})
         extras["next_rows"] = nxt
 

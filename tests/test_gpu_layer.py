@@ -123,3 +123,40 @@ def test_layer_empty_batch_and_errors(gpu):
     with pytest.raises(b.SpinnerError) as e:
         b.spinner_layer_forward(big, dbig, dbig, dbig)
     assert e.value.status == b.SPINNER_ERR_UNSUPPORTED
+
+
+def test_layer_step_as_a_captured_graph(gpu):
+    # a training step at the small hidden sizes is launch-bound and meant to be captured: every replay, with
+    # eager work and synchronisations in between, must give the bits of the eager forward + backward calls
+    t, b = gpu.torch, gpu.b
+    n, batch = 256, 1024
+    x, d, dy = _case(n, batch, 777)
+    xt, dt, dyt = _to(gpu, x), _to(gpu, d), _to(gpu, dy)
+    y0, saved0 = b.spinner_layer_forward(xt, dt[0], dt[1], dt[2], 1.0)
+    dx0, dd0 = b.spinner_layer_backward(dyt, xt, saved0, dt[0], dt[1], dt[2], 1.0)
+    t.cuda.synchronize()
+    y, saved, dx, dd = t.zeros_like(y0), t.zeros_like(saved0), t.zeros_like(dx0), t.zeros_like(dd0)
+    ws = t.empty(max(16, b.spinner_layer_workspace_bytes(n, batch)), dtype=t.uint8, device=gpu.dev)
+
+    def step():
+        b.spinner_layer_forward(xt, dt[0], dt[1], dt[2], 1.0, y=y, saved=saved)
+        b.spinner_layer_backward(dyt, xt, saved, dt[0], dt[1], dt[2], 1.0, dx=dx, dd=dd, workspace=ws)
+
+    side = t.cuda.Stream()
+    side.wait_stream(t.cuda.current_stream())
+    with t.cuda.stream(side):
+        step()
+    t.cuda.current_stream().wait_stream(side)
+    t.cuda.synchronize()
+    graph = t.cuda.CUDAGraph()
+    with t.cuda.graph(graph):
+        for _ in range(3):
+            step()
+    for rep in range(3):
+        for buf in (y, saved, dx, dd):
+            buf.fill_(float(rep))                  # eager work between replays
+        ws.zero_()
+        t.cuda.synchronize()
+        graph.replay()
+        t.cuda.synchronize()
+        assert t.equal(y, y0) and t.equal(dx, dx0) and t.equal(dd, dd0), rep
