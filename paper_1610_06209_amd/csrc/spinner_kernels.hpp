@@ -58,6 +58,9 @@
 #ifndef SPINNER_MASK_PREFETCH        // lane masks of the next step's sign flips fetched before the current step's exchange
 #define SPINNER_MASK_PREFETCH 16     // (each takes two scalar registers)
 #endif
+#ifndef SPINNER_STREAM_PASSES        // four-pass schedule: bit 0 non-temporal loads in the first pass, bit 1 non-temporal stores and
+#define SPINNER_STREAM_PASSES 7      // bit 2 non-temporal loads in the last pass (measured: 1 alone +2-3 % at n = 2^17..2^20,
+#endif                               // all three +0.4 / 4 / 2.4 / 3.4 %; 5 and 4 alone lose)
 #ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
 #define SPINNER_STREAMING 1
 #endif
@@ -922,7 +925,11 @@ spinner_tile_kernel(TileParams p)
     constexpr int NT = G::NT;
     constexpr int R = G::R;
     constexpr int CB = C >= NT ? 0 : C;          // index bits below CB are not transformed
-    constexpr bool STREAM = SPINNER_STREAMING && NSTEPS == 3;   // data touched once: bypass cache retention
+    // data touched once bypass cache retention: x and out of the fused kernels, and, in the four-pass schedule,
+    // x read by the first pass and what the last pass reads and writes (what lies between is read again soon)
+    constexpr bool FIRST_PASS = NSTEPS == 1 && FIRST_DIAG && C >= NT, LAST_PASS = NSTEPS == 1 && !FIRST_DIAG && C < NT;
+    constexpr bool STREAM_LD = SPINNER_STREAMING && (NSTEPS == 3 || ((SPINNER_STREAM_PASSES & 1) && FIRST_PASS) || ((SPINNER_STREAM_PASSES & 4) && LAST_PASS));
+    constexpr bool STREAM = SPINNER_STREAMING && (NSTEPS == 3 || ((SPINNER_STREAM_PASSES & 2) && LAST_PASS));
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -963,7 +970,7 @@ spinner_tile_kernel(TileParams p)
 #pragma unroll
             for (int jh = 0; jh < R / 4; ++jh) {
                 float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (active) t = load4<STREAM>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
+                if (active) t = load4<STREAM_LD>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
                 v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
             }
 #if SPINNER_EXPERIMENT_PRIO & 1
