@@ -163,10 +163,16 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     // three intermediate trips of a slice find most of it in the 256 MB memory-side cache
     // (measured 10-15 % faster than pass-by-pass over the whole batch; smaller slices leave
     // too few tiles per launch).
-    const long long slice_bytes = 192LL << 20;
+    long long slice_bytes = 192LL << 20;
+#ifdef SPINNER_TUNING_HOOKS
+    if (const char* e = getenv("SPINNER_SLICE_MIB")) slice_bytes = (long long)atoi(e) << 20;
+#endif
     long long slice = slice_bytes / (4LL * n);
     if (slice < 8) slice = 8;          // very long vectors: keep enough tiles per launch to fill the chip
     if (slice > batch) slice = batch;
+    // equal slices: a short last slice would run its four launches on a partly empty chip
+    const long long nslices = (batch + slice - 1) / slice;
+    slice = (batch + nslices - 1) / nslices;
     if ((slice << kColRowsLog) > 0x7fffffffLL * 4 || (slice << (nr - kColContigLog)) > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
 
     for (long long b0 = 0; b0 < batch; b0 += slice) {
