@@ -165,6 +165,45 @@ def test_next_angular_n4096_full_size(gpu, oracle):
     assert float((frac - 0.5).abs().max()) < 0.06       # binomial: 4 sigma = 4 * 0.5 / sqrt(4096) = 0.031
 
 
+def test_angular_gram_bench_size(gpu, oracle):
+    # the shape bench.py times: 16384 x 16384 codes of 4096 bits (1 GiB of estimates); a sampled block of rows and
+    # columns against the oracle, exact Hamming distances, and properties of the whole table
+    from helpers import unpack_sign_codes
+
+    t, b = gpu.torch, gpu.b
+    rows, m = 16384, 4096
+    g = t.Generator(device=gpu.dev)
+    g.manual_seed(4096 + rows)
+    codes = t.randint(-2**62, 2**62, (rows, m // 64), dtype=t.int64, device=gpu.dev, generator=g)
+    codes[5] = codes[4]                              # a pair at distance 0 off the diagonal
+    codes[7] = ~codes[6]                             # and one at distance m
+    out = b.spinner_angular_gram(codes, codes, m)
+    t.cuda.synchronize()
+    assert tuple(out.shape) == (rows, rows)
+    ri = W.sample_rows(rows, 48, 11)
+    ci = W.sample_rows(rows, 48, 12)
+    ri[:4] = [4, 5, 6, 7]
+    ci[:4] = [5, 4, 7, 6]
+    got = out[t.from_numpy(ri).to(gpu.dev)][:, t.from_numpy(ci).to(gpu.dev)].cpu().numpy()
+    ba = unpack_sign_codes(codes[t.from_numpy(ri).to(gpu.dev)].cpu().numpy(), m)
+    bb = unpack_sign_codes(codes[t.from_numpy(ci).to(gpu.dev)].cpu().numpy(), m)
+    want = oracle.angular_estimate(ba, bb)
+    assert np.array_equal(np.rint((1.0 - got.astype(np.float64)) * m), np.rint((1.0 - want) * m))
+    assert got[0, 0] == 1.0 and got[1, 1] == 1.0 and got[2, 2] == 0.0 and got[3, 3] == 0.0
+    # whole table: symmetric (a = b), ones on the diagonal, estimates of independent codes near 1/2
+    assert bool((out.diagonal() == 1.0).all())
+    step = 2048
+    for s0 in range(0, rows, step):
+        blk = out[s0:s0 + step]
+        assert t.equal(blk, out[:, s0:s0 + step].t())
+        assert float(blk.min()) >= 0.0 and float(blk.max()) <= 1.0
+    off = out[8:, 8:].double()
+    n_off = off.numel() - off.shape[0]
+    mean = (off.sum() - off.diagonal().sum()) / n_off
+    assert abs(float(mean) - 0.5) < 1e-3             # sd of one estimate 0.5 / sqrt(4096), averaged over 2.7e8 pairs
+    del out, off
+
+
 def test_adaptive_layer_full_size(gpu, oracle):
     # the shape bench.py times: n = 4096, batch 65536; sampled rows for y and dx, all of dd through linearity
     t, b = gpu.torch, gpu.b
