@@ -162,8 +162,8 @@ def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0, 
 
 
 def measure_gram(torch, b, dev, rows, m, steps, warmup):
-    """Hamming Gram matrix of `rows` x `rows` random codes of m bits: pairs/s, and the int8 operations per second of
-    the inner-product table behind it (2 m per pair, on the matrix pipe) against the 5.0 POP/s dense int8 MFMA peak."""
+    """Hamming Gram matrix of `rows` x `rows` random codes of m bits: pairs/s, and the fp4 operations per second of
+    the inner-product table behind it (2 m per pair, on the matrix pipe) against the 10.1 PFLOP/s dense fp4 MFMA peak."""
     codes = torch.randint(-2**62, 2**62, (rows, m // 64), dtype=torch.int64, device=dev)
     out = torch.empty((rows, rows), dtype=torch.float32, device=dev)
     fn = lambda: b.spinner_angular_gram(codes, codes, m, out=out)
@@ -174,8 +174,8 @@ def measure_gram(torch, b, dev, rows, m, steps, warmup):
     pairs = rows * rows
     res = {"workload": "angular_gram_%dx%d_m%d" % (rows, rows, m), "ms": round(ev_ms, 4),
            "pairs_per_s": pairs / (ev_ms * 1e-3),
-           "int8_TOPs": pairs * 2.0 * m / (ev_ms * 1e-3) / 1e12,
-           "int8_mfma_frac": pairs * 2.0 * m / (ev_ms * 1e-3) / 5.0e15}
+           "fp4_TFLOPs": pairs * 2.0 * m / (ev_ms * 1e-3) / 1e12,
+           "fp4_mfma_frac": pairs * 2.0 * m / (ev_ms * 1e-3) / 10.1e15}
     del codes, out
     torch.cuda.empty_cache()
     return res
@@ -419,8 +419,8 @@ def main():
                 name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
                 100 * r["valu_frac_adds_only"]))
         g = measure_gram(torch, b, dev, 16384, 4096, max(3, args.steps // 2), max(2, args.warmup // 2))
-        log("[bench] %s: %.4f ms  %.3e pairs/s  %.2f int8 POP/s (%.1f%% of the dense int8 MFMA peak)" % (
-            g["workload"], g["ms"], g["pairs_per_s"], g["int8_TOPs"] / 1e3, 100 * g["int8_mfma_frac"]))
+        log("[bench] %s: %.4f ms  %.3e pairs/s  %.2f fp4 PFLOP/s (%.1f%% of the dense fp4 MFMA peak)" % (
+            g["workload"], g["ms"], g["pairs_per_s"], g["fp4_TFLOPs"] / 1e3, 100 * g["fp4_mfma_frac"]))
         nxt.append(g)
         lay = measure_layer(torch, b, dev, 4096, 65536, max(3, args.steps // 2), max(2, args.warmup // 2))
         log("[bench] %s: forward %.4f ms (%.0f GB/s), backward %.4f ms (%.0f GB/s)" % (

@@ -84,19 +84,30 @@ hipError_t launch_pack_codes(const float* y, long long y_stride, unsigned long l
 // out[i][j] = 1 - popcount(a_i xor b_j) / m.  With the code bits as 0 / 1 numbers,
 //     popcount(a xor b) = |a| + |b| - 2 <a, b>,
 // and the table of inner products <a_i, b_j> is a dense contraction over the m code bits: it runs on the matrix
-// pipe as an int8 product (v_mfma_i32_32x32x32_i8, exact in int32).  A workgroup of four waves owns 128 x 128 pairs
+// pipe in the narrowest format that holds 0 and 1, fp4 (E2M1, 0x2 = 1.0; v_mfma_scale_f32_32x32x64_f8f6f4 with
+// unit scales; products and fp32 sums of at most 2^24 ones: exact).  A workgroup of four waves owns 128 x 128 pairs
 // (each wave 64 x 64 = 2 x 2 tiles) and walks the code words in chunks of 16 staged in LDS (rows padded by one
-// word: the 32 rows a wave reads at once fall on different banks).  The bits are spread into bytes in registers:
-// of a 32-bit half word w, lane group g = lane / 32 supplies the four dwords (w >> (4 g + q)) & 0x01010101,
-// q = 0..3, i.e. bits 4 g + q + 8 t in byte t.  Which bit lands in which of the 32 k-slots of the instruction
-// does not matter, as long as both operands are spread the same way.  The row weights |a_i|, |b_j| are counted
-// on the way (v_bcnt), |a_i| goes through LDS to the lanes that hold row i of the result.
-typedef int intx4 __attribute__((ext_vector_type(4)));
-typedef int intx16 __attribute__((ext_vector_type(16)));
-#ifndef SPINNER_GRAM_U            // 32-column tiles per wave (2: 128 x 128 pairs per workgroup; 4: 128 x 256, measured 25 % slower)
-#define SPINNER_GRAM_U 2
-#endif
-constexpr int kGramRows = 128, kGramU = SPINNER_GRAM_U, kGramCols = 64 * kGramU, kGramChunk = 16;
+// word: the 2 x 32 half words a wave reads at once fall on 64 different banks).  One instruction consumes a whole
+// 64-bit code word: lane group g = lane / 32 takes half word g and spreads it into nibbles in registers, dword q
+// holding bits q, q + 4, .., q + 28 (each moved to bit 1 of its nibble).  Which bit lands in which of the 64
+// k-slots does not matter, as long as both operands are spread the same way.  The row weights |a_i|, |b_j| are
+// counted on the way (v_bcnt, each lane group its half), |a_i| goes through LDS to the lanes that hold row i of
+// the result.  (Bits as +1 / -1, which need no weights, take one more instruction per dword to spread: slower.)
+typedef int intx8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr int kGramRows = 128, kGramCols = 128, kGramChunk = 16;
+
+// the 32 bits of w as 32 fp4 numbers (0 or 1.0) in four dwords
+__device__ __forceinline__ intx8 spread_bits_fp4(unsigned w)
+{
+    intx8 f = {0, 0, 0, 0, 0, 0, 0, 0};
+    f[0] = (int)((w << 1) & 0x22222222u);
+    f[1] = (int)(w & 0x22222222u);
+    f[2] = (int)((w >> 1) & 0x22222222u);
+    f[3] = (int)((w >> 2) & 0x22222222u);
+    return f;
+}
+
 __global__ void __launch_bounds__(256) hamming_gram_kernel(const unsigned long long* __restrict__ a, long long na,
                                                            const unsigned long long* __restrict__ b, long long nb,
                                                            int words, float inv_m, float* __restrict__ out)
@@ -104,74 +115,67 @@ __global__ void __launch_bounds__(256) hamming_gram_kernel(const unsigned long l
     __shared__ unsigned long long sa[kGramRows][kGramChunk + 1];
     __shared__ unsigned long long sb[kGramCols][kGramChunk + 1];
     __shared__ int weight_a[kGramRows];
-    constexpr int U = kGramU;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wr = wave >> 1, wc = wave & 1, g = lane >> 5, l32 = lane & 31;
     const long long i0 = (long long)blockIdx.y * kGramRows, j0 = (long long)blockIdx.x * kGramCols;
-    intx16 acc[2][U];
+    floatx16 acc[2][2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[t][u][v] = 0;
-    int wa[2] = {0, 0}, wb[U];
+            for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.0f;
+    int wa[2] = {0, 0}, wb[2] = {0, 0};
+    const int one = 0x7f7f7f7f;                      // scale exponents (E8M0): 2^0
+    // this lane's half words: row (.. + l32) of each tile, 32-bit half g of word k
+    const unsigned* ha[2];
+    const unsigned* hb[2];
 #pragma unroll
-    for (int u = 0; u < U; ++u) wb[u] = 0;
+    for (int t = 0; t < 2; ++t) {
+        ha[t] = reinterpret_cast<const unsigned*>(&sa[wr * 64 + t * 32 + l32][0]) + g;
+        hb[t] = reinterpret_cast<const unsigned*>(&sb[wc * 64 + t * 32 + l32][0]) + g;
+    }
 
-    // staging: rows x 16 words per operand, 256 threads: thread handles word (idx & 15) of row (idx >> 4), idx = t * 256 + tid
-    constexpr int TA = kGramRows / 16, TB = kGramCols / 16;
+    // staging: 128 rows x 16 words per operand, 256 threads: 8 words per thread and operand
     const int srow = threadIdx.x >> 4, scol = threadIdx.x & 15;
-    unsigned long long pa[TA], pb[TB];
-    auto fetch = [&](int k0) {
+    for (int k0 = 0; k0 < words; k0 += kGramChunk) {
+        unsigned long long pa[8], pb[8];
         const bool in_k = k0 + scol < words;
 #pragma unroll
-        for (int t = 0; t < TA; ++t) pa[t] = (in_k && i0 + t * 16 + srow < na) ? a[(i0 + t * 16 + srow) * words + k0 + scol] : 0ull;
+        for (int t = 0; t < 8; ++t) {
+            pa[t] = (in_k && i0 + t * 16 + srow < na) ? a[(i0 + t * 16 + srow) * words + k0 + scol] : 0ull;
+            pb[t] = (in_k && j0 + t * 16 + srow < nb) ? b[(j0 + t * 16 + srow) * words + k0 + scol] : 0ull;
+        }
 #pragma unroll
-        for (int t = 0; t < TB; ++t) pb[t] = (in_k && j0 + t * 16 + srow < nb) ? b[(j0 + t * 16 + srow) * words + k0 + scol] : 0ull;
-    };
-    for (int k0 = 0; k0 < words; k0 += kGramChunk) {
-        fetch(k0);
-#pragma unroll
-        for (int t = 0; t < TA; ++t) sa[t * 16 + srow][scol] = pa[t];
-#pragma unroll
-        for (int t = 0; t < TB; ++t) sb[t * 16 + srow][scol] = pb[t];
-        __syncthreads();
-#pragma unroll 2
-        for (int k = 0; k < kGramChunk; ++k) {
-            unsigned long long ra[2], rb[U];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                ra[t] = sa[wr * 64 + t * 32 + l32][k];
-                wa[t] += __popcll(ra[t]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                rb[u] = sb[wc * 32 * U + u * 32 + l32][k];
-                wb[u] += __popcll(rb[u]);
-            }
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                intx4 fa[2], fb[U];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const unsigned x = (unsigned)(ra[t] >> (32 * half)) >> (4 * g);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) fa[t][q] = (int)((x >> q) & 0x01010101u);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const unsigned x = (unsigned)(rb[u] >> (32 * half)) >> (4 * g);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) fb[u][q] = (int)((x >> q) & 0x01010101u);
-                }
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int u = 0; u < U; ++u) acc[t][u] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[t], fb[u], acc[t][u], 0, 0, 0);
-            }
+        for (int t = 0; t < 8; ++t) {
+            sa[t * 16 + srow][scol] = pa[t];
+            sb[t * 16 + srow][scol] = pb[t];
         }
         __syncthreads();
+#pragma unroll 4
+        for (int k = 0; k < kGramChunk; ++k) {
+            intx8 fa[2], fb[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const unsigned xa = ha[t][2 * k], xb = hb[t][2 * k];
+                wa[t] += __popc(xa);
+                wb[t] += __popc(xb);
+                fa[t] = spread_bits_fp4(xa);
+                fb[t] = spread_bits_fp4(xb);
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+                    acc[t][u] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[t], fb[u], acc[t][u], 4, 4, 0, one, 0, one);
+        }
+        __syncthreads();
+    }
+    // a row's weight is the sum of what the two lane groups counted
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        wa[t] += lane_xor_i<32>(wa[t]);
+        wb[t] += lane_xor_i<32>(wb[t]);
     }
     if (wc == 0 && g == 0) {
         weight_a[wr * 64 + l32] = wa[0];
@@ -182,12 +186,12 @@ __global__ void __launch_bounds__(256) hamming_gram_kernel(const unsigned long l
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int rl = wr * 64 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                const long long i = i0 + rl, j = j0 + wc * 32 * U + u * 32 + l32;
-                const int dh = weight_a[rl] + wb[u] - 2 * acc[t][u][v];
+                const long long i = i0 + rl, j = j0 + wc * 64 + u * 32 + l32;
+                const int dh = weight_a[rl] + wb[u] - 2 * (int)acc[t][u][v];
                 if (i < na && j < nb) out[i * nb + j] = 1.0f - (float)dh * inv_m;
             }
 }
