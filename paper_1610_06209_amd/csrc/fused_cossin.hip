@@ -72,7 +72,41 @@ __device__ __forceinline__ void feat_ar_b_to_a(double (&v)[G::R], float4* pa, fl
     wave_lds_fence();
 }
 
+// fp32 diagonals for the same kernel.  In layout A a thread's entries are 2^r consecutive floats: the diagonal goes
+// through the exchange buffer like x (coalesced 16-byte loads, 16-byte reads in layout A).  In layout B register j of
+// consecutive lanes wants consecutive entries: 4-byte loads, 64 lanes on 256 consecutive bytes (the diagonal is
+// cache-resident).
 template <typename G>
+__device__ __forceinline__ void feat_ar_diag_a(double (&v)[G::R], const float* d, float* w, float4* pa, int l)
+{
+#pragma unroll
+    for (int k = 0; k < G::R / 4; ++k)
+        *reinterpret_cast<float4*>(w + ar_word_of<G>(4 * (k * G::LANES + l))) = *reinterpret_cast<const float4*>(d + 4 * (k * G::LANES + l));
+    wave_lds_fence();
+#pragma unroll
+    for (int k = 0; k < G::R / 4; ++k) {
+        const float4 t = pa[k];
+        v[4 * k] *= (double)t.x; v[4 * k + 1] *= (double)t.y; v[4 * k + 2] *= (double)t.z; v[4 * k + 3] *= (double)t.w;
+    }
+    wave_lds_fence();
+}
+template <typename G>
+__device__ __forceinline__ void feat_ar_diag_b(double (&v)[G::R], const float* d, int ebase)
+{
+    // a few at a time: with all 2^r entries in flight at once the register allocator runs out
+    constexpr int CH = G::R < 16 ? G::R : 16;
+#pragma unroll
+    for (int j0 = 0; j0 < G::R; j0 += CH) {
+        float t[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) t[j] = d[ebase + ((j0 + j) << G::r)];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) v[j0 + j] *= (double)t[j];
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <typename G, bool SIGNS>
 __global__ void __launch_bounds__(G::THREADS) __attribute__((amdgpu_waves_per_eu(G::r >= 6 ? 2 : 4)))
 spinner_feature_ar_kernel(TileParams p)
 {
@@ -114,15 +148,18 @@ spinner_feature_ar_kernel(TileParams p)
         }
         wave_lds_fence();
 
-        feat_ar_flip<G>(v, hw);                 // D1 in layout A
+        if constexpr (SIGNS) feat_ar_flip<G>(v, hw);                 // D1 in layout A
+        else feat_ar_diag_a<G>(v, p.d[0], w, pa, l);
         ar_stages<G>(v);
         feat_ar_a_to_b<G>(v, pa, pb);
         ar_stages<G>(v);
-        feat_ar_flip<G>(v, hw + 3 * R);         // D2 in layout B
+        if constexpr (SIGNS) feat_ar_flip<G>(v, hw + 3 * R);         // D2 in layout B
+        else feat_ar_diag_b<G>(v, p.d[1], ebase);
         ar_stages<G>(v);
         feat_ar_b_to_a<G>(v, pa, pb);
         ar_stages<G>(v);
-        feat_ar_flip<G>(v, hw + 4 * R);         // D3 in layout A
+        if constexpr (SIGNS) feat_ar_flip<G>(v, hw + 4 * R);         // D3 in layout A
+        else feat_ar_diag_a<G>(v, p.d[2], w, pa, l);
         ar_stages<G>(v);
         feat_ar_a_to_b<G>(v, pa, pb);
         ar_stages<G>(v);
@@ -157,22 +194,24 @@ spinner_feature_ar_kernel(TileParams p)
 #define SPINNER_FEAT_AR_WAVES 1
 #endif
 
-template <int NT>
-static hipError_t launch_cossin_signs(const TileParams& p, long long tiles, hipStream_t s)
+#ifndef SPINNER_FEAT_AR_FP32        // 0: with fp32 diagonals the feature map of these sizes stays on the tile kernel (tuning experiments)
+#define SPINNER_FEAT_AR_FP32 1
+#endif
+template <int NT, bool SIGNS>
+static hipError_t launch_cossin(const TileParams& p, long long tiles, hipStream_t s)
 {
-    if constexpr (feature_ar_log2r(NT) != 0) {
+    if constexpr (feature_ar_log2r(NT) != 0 && (SIGNS || SPINNER_FEAT_AR_FP32)) {
         using GA = HashArGeom<NT, feature_ar_log2r(NT), SPINNER_FEAT_AR_WAVES>;
         const long long blocks = (tiles + GA::VECS_PER_WG - 1) / GA::VECS_PER_WG;
         if (blocks <= 0) return hipSuccess;
         if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-        hipLaunchKernelGGL((spinner_feature_ar_kernel<GA>), dim3((unsigned)blocks), dim3(GA::THREADS), 0, s, p);
+        hipLaunchKernelGGL((spinner_feature_ar_kernel<GA, SIGNS>), dim3((unsigned)blocks), dim3(GA::THREADS), 0, s, p);
         return hipGetLastError();
     }
-    return launch_tile<double, NT, NT, 3, true, EPI_STORE_COSSIN, true>(p, tiles, s);
+    return launch_tile<double, NT, NT, 3, true, EPI_STORE_COSSIN, SIGNS>(p, tiles, s);
 }
 
-#define CASE(NT) case NT: return signs ? launch_cossin_signs<NT>(p, tiles, s) \
-                                       : launch_tile<double, NT, NT, 3, true, EPI_STORE_COSSIN, false>(p, tiles, s);
+#define CASE(NT) case NT: return signs ? launch_cossin<NT, true>(p, tiles, s) : launch_cossin<NT, false>(p, tiles, s);
 hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (log2n) {

@@ -339,6 +339,15 @@ def test_features_from_sign_words_n4096(gpu, oracle, m, scale, batch):
         want = oracle.apply(x, ds[t, 0], ds[t, 1], ds[t, 2], m, "cossin", scale)
         assert got.shape == (batch, 2 * m)
         assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (m, t)
+        # the same kernel takes fp32 diagonals (multiplied, not flipped)
+        got = _run_apply(gpu, x, ds[t], m, "cossin", scale)
+        assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (m, t, "fp32 diagonals")
+    # diagonals that are not +-1: Gaussian third diagonal (the H D_g H D2 H D1 member), scaled first and second
+    rng = np.random.default_rng(5 * m + batch)
+    dg = np.stack([d[0] * np.float32(0.75), d[1] * np.float32(-1.5), rng.standard_normal(n).astype(np.float32)])
+    got = _run_apply(gpu, x, dg, m, "cossin", scale / 2)
+    want = oracle.apply(x, dg[0], dg[1], dg[2], m, "cossin", scale / 2)
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (m, "general diagonals")
 
 
 @pytest.mark.parametrize("log2n", [15, 16, 17])
