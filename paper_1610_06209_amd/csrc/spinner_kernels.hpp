@@ -40,9 +40,6 @@
 #ifndef SPINNER_SYNC_AFTER_READ      // 1: the barrier that protects the LDS buffer from the next writers sits right
 #define SPINNER_SYNC_AFTER_READ 1    //    after the reads (waves are still in step there) instead of before the next writes
 #endif
-#ifndef SPINNER_EXPERIMENT_KNOCKOUT   // timing experiments only (results are wrong): bit 0 drops the lane stages that
-#define SPINNER_EXPERIMENT_KNOCKOUT 0 // cross the LDS crossbar, 1 the DPP lane stages, 2 the register stages, 3 the LDS
-#endif                                // traffic of the transposes (barriers stay), 4 the diagonals, 5 the lane-swap stages
 #ifndef SPINNER_LANE_SWAPS           // 1: in tiles that span several waves, lane bits 4 and 5 are transformed by swapping
 #define SPINNER_LANE_SWAPS 1         //    lane halves with register pairs (vector ALU) instead of LDS-crossbar exchanges
 #endif
@@ -51,9 +48,6 @@
 #endif
 #ifndef SPINNER_DPP_MASKS            // lane masks (of 1, 2, 8) whose butterflies use the one-instruction DPP form; the
 #define SPINNER_DPP_MASKS 0xB        // others go through the LDS crossbar (tuning experiments)
-#endif
-#ifndef SPINNER_EXPERIMENT_PRIO      // tuning experiments: bit 0 raises the wave priority while a tile's loads are issued, bit 1 from the
-#define SPINNER_EXPERIMENT_PRIO 0    // last exchange to the end of the stores
 #endif
 #ifndef SPINNER_MASK_PREFETCH        // lane masks of the next step's sign flips fetched before the current step's exchange
 #define SPINNER_MASK_PREFETCH 16     // (each takes two scalar registers)
@@ -440,20 +434,19 @@ __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c
     static_assert(!G::WIDE || CB == 0, "wide exchanges are for contiguous tiles");
     static_assert(!SWAP || CB <= G::lane_pos(LAY, 4), "lane swaps: lane bits 4 and 5 must be among the transformed ones");
     static_for<0, G::r>([&](auto q) {
-        if constexpr (G::reg_pos(LAY, q.value) >= CB && !(SPINNER_EXPERIMENT_KNOCKOUT & 4))
+        if constexpr (G::reg_pos(LAY, q.value) >= CB)
             reg_stage<q.value>(v);
     });
     static_for<0, G::LANE_STAGES>([&](auto b) {
         if constexpr (G::lane_pos(LAY, b.value) >= CB && !(SWAP && b.value >= 4)) {
             if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) {
-                if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 2))
-                    lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
-            } else if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 1)) {
+                lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
+            } else {
                 lane_stage<b.value>(v, c.sg[b.value]);
             }
         }
     });
-    if constexpr (SWAP && !(SPINNER_EXPERIMENT_KNOCKOUT & 32)) {
+    if constexpr (SWAP) {
         lane_swap_stage<4, 2>(v);
         lane_swap_stage<5, 3>(v);
     }
@@ -520,12 +513,11 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
 #pragma unroll
         for (int jh = 0; jh < NW / 4; ++jh) {
             const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
-            if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 8))
-                lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
+            lds[e >> 2] = make_float4(v[jh * 4], v[jh * 4 + 1], v[jh * 4 + 2], v[jh * 4 + 3]);
         }
         __syncthreads();
         const int et = c.base_index(TO);
-        if (reads && !(SPINNER_EXPERIMENT_KNOCKOUT & 8)) {
+        if (reads) {
 #pragma unroll
             for (int jh = 0; jh < NR / 4; ++jh) {
                 const int e = et | G::reg_index(TO, jh * 4);
@@ -578,11 +570,10 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
 #pragma unroll
                 for (int jh = 0; jh < NW / 4; ++jh) {
                     const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
-                    if constexpr (!(SPINNER_EXPERIMENT_KNOCKOUT & 8))
-                        lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
+                    lds2[e >> 2] = make_float2(v[jh * 4 + 2 * h], v[jh * 4 + 2 * h + 1]);
                 }
                 __syncthreads();
-                if (reads && !(SPINNER_EXPERIMENT_KNOCKOUT & 8)) {
+                if (reads) {
 #pragma unroll
                     for (int jh = 0; jh < NR / 4; ++jh) {
                         const int e = et | G::reg_index(TO, jh * 4);
@@ -658,11 +649,7 @@ __device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& 
     const float* base = dtile + tile_offset<NT, C>(c.base_index(LAY), sl);
 #pragma unroll
     for (int jh = 0; jh < G::R / 4; ++jh) {
-#ifdef SPINNER_EXPERIMENT_NODIAG
-        const float4 t = make_float4(sl + 1.0f, sl + 1.0f, sl + 1.0f, sl + 1.0f);
-#else
         const float4 t = *reinterpret_cast<const float4*>(base + tile_offset<NT, C>(G::reg_index(LAY, jh * 4), sl));
-#endif
         v[jh * 4] *= (T)t.x; v[jh * 4 + 1] *= (T)t.y; v[jh * 4 + 2] *= (T)t.z; v[jh * 4 + 3] *= (T)t.w;
     }
 }
@@ -766,7 +753,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
                                              const float* dtile, const unsigned long long* words, int sl, float4* lds,
                                              SignMasks<NPF>* pm = nullptr, const unsigned long long* next_words = nullptr)
 {
-    if constexpr (HAS_DIAG && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) {
+    if constexpr (HAS_DIAG) {
         if constexpr (SIGNS) {
             if constexpr (NPF > 0 && !FIRST_TRANSPOSE) sign_flip<G, LAY, NPF>(v, c, words, pm);
             else sign_flip<G, LAY>(v, c, words);
@@ -778,7 +765,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 #endif
     constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(LAY, 4);
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
-    if constexpr (NPF > 0 && PF_NEXT && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) fetch_sign_masks<G, (G::WB > 0 ? 1 - LAY : LAY)>(*pm, c, next_words);
+    if constexpr (NPF > 0 && PF_NEXT) fetch_sign_masks<G, (G::WB > 0 ? 1 - LAY : LAY)>(*pm, c, next_words);
     if constexpr (G::WB > 0) {
         if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
         else transpose<G, LAY, !FIRST_TRANSPOSE, SWAP>(v, c, lds);
@@ -963,9 +950,6 @@ spinner_tile_kernel(TileParams p)
 
         T v[R];
         {
-#if SPINNER_EXPERIMENT_PRIO & 1
-            __builtin_amdgcn_s_setprio(3);
-#endif
             const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(G::layout_after(0)), p.sl);
 #pragma unroll
             for (int jh = 0; jh < R / 4; ++jh) {
@@ -973,31 +957,17 @@ spinner_tile_kernel(TileParams p)
                 if (active) t = load4<STREAM_LD>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
                 v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
             }
-#if SPINNER_EXPERIMENT_PRIO & 1
-            __builtin_amdgcn_s_setprio(0);
-#endif
         }
 
         // lane masks of the next step's sign flips travel in scalar registers across the exchange (see SignMasks)
         // (measured: 1.4 % at n = 2^14, nothing elsewhere; only tiles of several waves with 64 values per thread use it)
-        constexpr int NPF = (SIGNS && G::WB > 0 && R == 64 && !(SPINNER_EXPERIMENT_KNOCKOUT & 16)) ? SPINNER_MASK_PREFETCH : 0;
+        constexpr int NPF = (SIGNS && G::WB > 0 && R == 64) ? SPINNER_MASK_PREFETCH : 0;
         SignMasks<NPF> pm;
         // steps (layout alternates only when a tile spans several waves)
-#ifdef SPINNER_EXPERIMENT_NOCOMPUTE
-        // never true: keeps the code but skips it (memory-shape experiment).  Not for pruned kernels: their
-        // stores rely on the last step's bookkeeping of which waves and registers still hold outputs.
-        if (PRUNE > 0 || p.m < 0)
-#endif
         spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS, T, NPF, (NSTEPS > 1)>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds, &pm, p.sw[1]);
-#ifdef SPINNER_EXPERIMENT_NOCOMPUTE
-        if (PRUNE > 0 || p.m < 0)
-#endif
         if constexpr (NSTEPS > 1)
             spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS, T, NPF, (NSTEPS > 2)>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds, &pm, p.sw[2]);
         bool wave_live = true;
-#ifdef SPINNER_EXPERIMENT_NOCOMPUTE
-        if (PRUNE > 0 || p.m < 0)
-#endif
         if constexpr (NSTEPS > 2) {
             if constexpr (PRUNE > 0)
                 spinner_step_pruned<G, C, CB, G::layout_after(2), false, SIGNS, PRUNE, NPF>(v, c, p.d[2] + tile_first, p.sw[2], p.sl, lds, wave_live, &pm);
@@ -1009,9 +979,6 @@ spinner_tile_kernel(TileParams p)
 
         constexpr int LAYF = G::layout_after(NSTEPS);
         const int ebase = c.base_index(LAYF);
-#if SPINNER_EXPERIMENT_PRIO & 2
-        __builtin_amdgcn_s_setprio(3);
-#endif
         if (active && wave_live) {
             const long long m = p.m;
             // held values carry the tracked lane sign after an odd number of transforms
