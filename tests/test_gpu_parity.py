@@ -451,3 +451,49 @@ def test_stacked_blocks_errors(gpu):
     assert e.value.status == b.SPINNER_ERR_BAD_M
     assert tuple(b.spinner_apply_blocks(x, ds[:1], 30, "none", 1.0).shape) == (2, 30)
     assert tuple(b.spinner_apply_blocks(x[:0], ds, 32, "cossin", 1.0).shape) == (0, 128)
+
+
+# ------------------------------------------------------------------ seeded random shapes
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        log2n = int(rng.integers(4, 15))
+        n = 1 << log2n
+        batch = int(rng.integers(1, 70 if log2n <= 11 else (20 if log2n <= 13 else 7)))
+        kind = rng.integers(0, 4)
+        if kind == 0:
+            m = n
+        elif kind == 1:
+            m = int(rng.integers(1, n + 1))                        # any row limit, odd ones included
+        elif kind == 2:
+            m = max(1, n >> int(rng.integers(4, log2n + 1)))       # at or below n / 16: the pruned last round
+        else:
+            m = min(n, (n >> 4) + int(rng.integers(1, 9)))         # just above the pruning threshold
+        cases.append((log2n, batch, m, ("none", "cossin")[int(rng.integers(0, 2))], ("fp32", "signs")[int(rng.integers(0, 2))],
+                      int(rng.integers(0, 1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("log2n,batch,m,epilogue,form,seed", _random_cases(36, 20261127))
+def test_random_shapes_against_the_oracle(gpu, oracle, log2n, batch, m, epilogue, form, seed):
+    n = 1 << log2n
+    x, d = _rng_case(n, batch, seed)
+    scale = 1.5 if epilogue == "none" else 2.0 * math.sqrt(n) / 8.0     # features: w of a few radians per unit of |x|
+    if epilogue == "cossin":
+        x *= np.float32(0.125)
+    if form == "signs":
+        signs = gpu.b.spinner_pack_signs(_to(gpu, d[None]))
+        got = gpu.b.spinner_apply_signs(_to(gpu, x), signs, m, epilogue, scale).cpu().numpy()
+    else:
+        got = _run_apply(gpu, x, d, m, epilogue, scale)
+    want = oracle.apply(x, d[0], d[1], d[2], m, epilogue, scale)
+    assert got.shape == want.shape
+    if epilogue == "none":
+        # A few kept coordinates can cancel to next to nothing, and fp32 cannot hold 1e-5 of that: the error is
+        # measured against the kept part's norm or its expected size sqrt(m / n) * scale * |x|, whichever is larger.
+        err = np.linalg.norm(got.astype(np.float64) - want, axis=1)
+        ref = np.maximum(np.linalg.norm(want, axis=1), math.sqrt(m / n) * scale * np.linalg.norm(x.astype(np.float64), axis=1))
+        assert (err / ref).max() <= REL_L2_TOL, (log2n, batch, m, epilogue, form)
+    else:
+        assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (log2n, batch, m, epilogue, form)
