@@ -338,8 +338,8 @@ def main():
     ap.add_argument("--only", action="store_true", help="headline only, and a single JSON line without extras")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over the batch with no "
-              "collective; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path shards over the batch: vectors are independent, "
+              "no collective is involved); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
