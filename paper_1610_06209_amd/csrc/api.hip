@@ -141,6 +141,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         if (signs) {
             const long long W = sign_words_per_diag(n);
             p.sw[0] = signs; p.sw[1] = signs + W; p.sw[2] = signs + 2 * W;
+            p.wide_off = (int)wide_words_offset(n, log2n);      // both blocks hold a diagonal every W words
         }
         p.in_stride = n; p.out_stride = out_stride;
         p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0;
@@ -254,6 +255,8 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && spinner::ar_log2r(log2n))
         e = spinner::launch_pack_hash_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
+    if (e == hipSuccess && spinner::has_wide_words(log2n))
+        e = spinner::launch_pack_wide_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
     if (e == hipSuccess && log2n > spinner::kFusedMaxLogOther)      // fp32 copy of each triple behind its sign words
         e = hipMemcpy2DAsync(static_cast<unsigned long long*>(signs) + 3 * W, (size_t)spinner::sign_words_per_triple(n, log2n) * 8,
                              diag_sets, (size_t)3 * n * sizeof(float), (size_t)3 * n * sizeof(float), (size_t)L,

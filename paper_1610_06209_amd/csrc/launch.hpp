@@ -118,10 +118,18 @@ constexpr int feature_ar_log2r(int log2n)
     return (log2n >= 8 && log2n <= 12 && !(log2n & 1) && ((SPINNER_FEATURE_AR_SIZES >> log2n) & 1)) ? log2n / 2 : 0;
 }
 constexpr int ar_log2r(int log2n) { return hash_ar_log2r(log2n) ? hash_ar_log2r(log2n) : feature_ar_log2r(log2n); }
+// n = 2^12 .. 2^14: the wide geometries flip signs in a layout whose lane masks are no words of the packed format;
+// they follow as a block of their own, [3 diagonals][n / 64 words], word (wave << r) | register (fused_none.hip).
+constexpr bool has_wide_words(int log2n) { return log2n >= 12 && log2n <= 14; }
+inline long long wide_words_offset(int n, int log2n)      // from a triple's first sign word
+{
+    return 3 * sign_words_per_diag(n) + (ar_log2r(log2n) ? 6LL << ar_log2r(log2n) : 0);
+}
+hipError_t launch_pack_wide_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
 // n = 2^15, 2^16: the feature map runs in four passes there and needs the fp32 diagonals, which follow the sign words.
 inline long long sign_words_per_triple(int n, int log2n)
 {
-    return 3 * sign_words_per_diag(n) + (ar_log2r(log2n) ? 6LL << ar_log2r(log2n) : 0) +
+    return wide_words_offset(n, log2n) + (has_wide_words(log2n) ? 3 * sign_words_per_diag(n) : 0) +
            (log2n > kFusedMaxLogOther ? 3LL * n / 2 : 0);
 }
 hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);

@@ -222,6 +222,7 @@ struct TileParams {
     float* out;               // output, row stride out_stride
     const float* d[3];        // diagonals used by step 0, 1, 2 (unused entries may be null)
     const unsigned long long* sw[3];   // packed sign words of the same diagonals (sign-word kernels only)
+    int wide_off;             // words from sw[k] to the lane masks of layout 1 of the same diagonal (wide geometries)
     long long batch;
     long long in_stride;
     long long out_stride;
@@ -254,6 +255,7 @@ template <typename G>
 struct ThreadCtx {
     int lit;        // lane within tile
     int wv;         // wave bits of the tile index held by this thread
+    int wide_off = 0;   // wide geometries: words from a diagonal's sign words to its lane masks of layout 1
     float sg[6];    // +1 / -1 by lane bit: sign of the own value in a lane butterfly
     __device__ __forceinline__ int base_index(int lay) const
     {
@@ -685,20 +687,12 @@ __device__ __forceinline__ int wave_index_bits(const ThreadCtx<G>& c)
 
 // lane mask "which lanes hold a negated element" of register j in layout LAY
 template <typename G, int LAY>
-__device__ __forceinline__ unsigned long long sign_mask(sign_words_t w, int ew, int j)
+__device__ __forceinline__ unsigned long long sign_mask(sign_words_t w, const ThreadCtx<G>& c, int ew, int j)
 {
     if constexpr (G::WIDE && LAY == 1) {
-        // lanes hold index bits 2..5 and two high bits: the lane mask of a register is put together from
-        // the 16-bit fields (bits 2..5; bits 6, 7 are register bits here) of four words of the packed format
-        const int e = ew | G::reg_index(1, j);
-        unsigned long long m = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int ek = e | ((k & 1) << G::lane_pos(1, 4)) | ((k >> 1) << G::lane_pos(1, 5));
-            const unsigned long long wk = w[((ek >> 8) << 2) | (ek & 3)];
-            m |= ((wk >> (((ek >> 6) & 3) << 4)) & 0xFFFFull) << (16 * k);
-        }
-        return m;
+        // lanes hold index bits 2..5 and two high bits: no word of the packed format is this register's lane mask;
+        // spinner_pack_signs leaves the masks of this layout, word (wave << r) | register, wide_off words further on
+        return w[c.wide_off + ((c.wv << G::r) | j)];
     } else {
         const int e = ew | G::reg_index(LAY, j);  // lane bits (2 .. 2+LB-1) are zero here
         unsigned long long m = w[((e >> 8) << 2) | (e & 3)];
@@ -724,7 +718,7 @@ __device__ __forceinline__ void fetch_sign_masks(SignMasks<N>& pm, const ThreadC
     sign_words_t w = (sign_words_t)words;
     const int ew = wave_index_bits<G, LAY>(c);
 #pragma unroll
-    for (int j = 0; j < N; ++j) pm.m[j] = sign_mask<G, LAY>(w, ew, j);
+    for (int j = 0; j < N; ++j) pm.m[j] = sign_mask<G, LAY>(w, c, ew, j);
 }
 
 // NPF: the masks of registers 0 .. NPF-1 come from `pm` instead of from memory
@@ -737,7 +731,7 @@ __device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, c
 #pragma unroll
     for (int j = 0; j < G::R; ++j) {
         if (j < NPF) flip_by_mask(v[j], pm->m[j]);
-        else flip_by_mask(v[j], sign_mask<G, LAY>(w, ew, j));
+        else flip_by_mask(v[j], sign_mask<G, LAY>(w, c, ew, j));
     }
 }
 
@@ -933,6 +927,7 @@ spinner_tile_kernel(TileParams p)
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) c.sg[b] = ((c.lit >> b) & 1) ? -1.0f : 1.0f;
+    c.wide_off = p.wide_off;
 
     const long long total = p.batch << p.tiles_per_vec_log;
 

@@ -90,7 +90,9 @@ def test_sign_word_entry_points_reject_bad_arguments(b):
     # n = 1024 also carries the lane masks of its hash kernel's two layouts: [3][2][32] words per triple
     assert b.spinner_signs_bytes(1024, 1) == 3 * 16 * 8 + 3 * 2 * 32 * 8
     assert b.spinner_signs_bytes(1024, 5) == 5 * b.spinner_signs_bytes(1024, 1)
-    assert b.spinner_signs_bytes(4096, 1) == 3 * 64 * 8 + 3 * 2 * 64 * 8      # lane masks of the all-register feature kernel
+    # sign words, lane masks of the all-register feature kernel, lane masks of the second layout of the wide exchange
+    assert b.spinner_signs_bytes(4096, 1) == 3 * 64 * 8 + 3 * 2 * 64 * 8 + 3 * 64 * 8
+    assert b.spinner_signs_bytes(16384, 2) == 2 * (3 * 256 * 8 + 3 * 256 * 8)
     assert b.spinner_signs_bytes(64, 2) == 2 * 3 * 4 * 8
     assert b.spinner_signs_bytes(256, 1) == 3 * 4 * 8 + 3 * 2 * 16 * 8
     assert b.spinner_signs_bytes(1 << 16, 1) == 3 * 1024 * 8 + 3 * (1 << 16) * 4      # sign words, then the fp32 diagonals
