@@ -49,7 +49,7 @@ using GeomFor = GeomFrom<Tuning<T, NT>, NT>;
 // trade lane bits 4, 5 for register bits (TileGeom's WIDE_; column tiles never do), through half-size LDS buffers:
 // 32 values per thread on two waves at 2^12, 64 values held to 128 registers on two / four waves at 2^13 / 2^14.
 // Measured against the tables above: 2^12 0.374 -> 0.345 ms (the copy kernel's time), 2^13 -8 %, 2^14 -2 to -4 %;
-// no gain for fp64 butterflies or for the pruned last round, which keep the narrow exchanges.
+// no gain for fp64 butterflies, which keep the narrow exchanges.
 #ifndef SPINNER_WIDE_F32         // bit N set: fp32 contiguous tiles of 2^N elements use wide exchanges (tuning experiments)
 #define SPINNER_WIDE_F32 0x7000
 #endif
@@ -71,7 +71,12 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
 {
     // wide exchanges pay with packed sign words only: fp32 diagonals read in layout 1 come in 256-byte runs,
     // which measured 2-5 % slower than the narrow exchange (also for the row passes above 2^16)
-    using G = std::conditional_t<(PRUNE > 0), PrunedGeomFor<T, NT>,
+#ifndef SPINNER_WIDE_PRUNED      // bit N set: the sign-word kernels of 2^N elements with a pruned last round use wide exchanges too
+#define SPINNER_WIDE_PRUNED 0x7000   // (first n/16 rows: 2^12 0.494 -> 0.451 ms, 2^13 0.528 -> 0.490, 2^14 0.545 -> 0.524)
+#endif
+    constexpr bool kWidePruned = PRUNE > 0 && SIGNS && C >= NT && NSTEPS == 3 && EPI == EPI_STORE_NONE && std::is_same<T, float>::value &&
+                                 ((SPINNER_WIDE_PRUNED >> NT) & 1) != 0;
+    using G = std::conditional_t<(PRUNE > 0 && !kWidePruned), PrunedGeomFor<T, NT>,
                                  std::conditional_t<(C >= NT && SIGNS && NSTEPS == 3), ContigGeomFor<T, NT>, GeomFor<T, NT>>>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
