@@ -126,9 +126,10 @@ int spinner_hash(const float *x, int n, long batch, int L,
  *
  * spinner_apply_signs uses the first triple found at `signs`; all other
  * arguments, the output, the workspace rule and the error codes are those of
- * spinner_apply.  For n > 2^16 the packed form is a plain copy of the
- * diagonals and the four-pass path is used unchanged (at n = 2^15 and 2^16
- * the buffer holds both, for the feature map's four-pass path).
+ * spinner_apply.  For n > 2^14 the buffer holds the sign words and, behind
+ * them, a copy of the fp32 diagonals: in the four-pass path the passes over
+ * rows flip signs by the words and the pass over columns multiplies by the
+ * fp32 second diagonal.
  */
 size_t spinner_signs_bytes(int n, int L);
 int spinner_pack_signs(const float *diag_sets, int n, int L, void *signs, void *stream);

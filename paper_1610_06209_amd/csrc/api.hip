@@ -160,6 +160,9 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     const int kColRowsLog = cs.rows_log, kColContigLog = cs.contig_log;
     const int nr = log2n - kColRowsLog;
     float* buf_all = ws ? static_cast<float*>(workspace) : out;
+    // with packed sign words the row passes flip by lane mask (rows long enough to fill a wave); the column pass
+    // multiplies by the fp32 diagonal in any case
+    const bool row_signs = signs != nullptr && nr >= kRowSignsMinLog;
     // The batch is walked in slices of about 192 MiB, all four passes per slice, so that the
     // three intermediate trips of a slice find most of it in the 256 MB memory-side cache
     // (measured 10-15 % faster than pass-by-pass over the whole batch; smaller slices leave
@@ -187,14 +190,16 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         p.x = x + b0 * (long long)n; p.out = buf; p.d[0] = d1; p.d[1] = nullptr; p.d[2] = nullptr;
         p.in_stride = n; p.out_stride = n; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
         p.m = n; p.factor = 1.0f;
-        if ((e = launch_row_first(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
+        if (row_signs) p.sw[0] = signs;
+        if ((e = launch_row_first(nr, row_signs, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
         // P2: cols, D2, cols : buf -> buf
         p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
         if ((e = launch_col_middle(kColRowsLog, kColContigLog, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
         // P3: rows, D3, rows : buf -> buf
         p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
-        if ((e = launch_row_middle(nr, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
+        if (row_signs) p.sw[1] = signs + 2 * sign_words_per_diag(n);
+        if ((e = launch_row_middle(nr, row_signs, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
         // P4: cols, epilogue : buf -> out
         p.out = out + b0 * out_stride; p.d[1] = nullptr; p.out_stride = out_stride;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
@@ -231,8 +236,7 @@ size_t spinner_signs_bytes(int n, int L)
 {
     int log2n;
     if (!pow2_in_range(n, &log2n) || L < 1) return 0;
-    if (log2n <= spinner::kSignWordsMaxLog) return (size_t)L * (size_t)spinner::sign_words_per_triple(n, log2n) * 8;
-    return (size_t)L * 3 * (size_t)n * sizeof(float);      // plain copy of the diagonals
+    return (size_t)L * (size_t)spinner::sign_words_per_triple(n, log2n) * 8;
 }
 
 int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* stream)
@@ -243,10 +247,6 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
     if (!diag_sets || !signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (log2n > spinner::kSignWordsMaxLog) {
-        const hipError_t e = hipMemcpyAsync(signs, diag_sets, spinner_signs_bytes(n, L), hipMemcpyDeviceToDevice, s);
-        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
-    }
     const int W = (int)spinner::sign_words_per_diag(n);
     const long long total_words = (long long)L * 3 * W;
     const long long blocks = (total_words + 3) / 4;
@@ -272,12 +272,10 @@ int spinner_apply_signs(const float* x, int n, long batch, const void* signs, in
     if (rc != SPINNER_OK || batch == 0) return rc;
     if (!signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > fused_max_log(epilogue)) {      // four passes: fp32 diagonals (the whole buffer, or what follows the sign words)
-        const float* d = log2n > spinner::kSignWordsMaxLog
-                             ? static_cast<const float*>(signs)
-                             : reinterpret_cast<const float*>(static_cast<const unsigned long long*>(signs) + 3 * spinner::sign_words_per_diag(n));
-        return apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, epilogue, scale, out, workspace,
-                          stream);
+    if (log2n > fused_max_log(epilogue)) {      // four passes: sign words for the row passes, the fp32 diagonals behind them
+        const unsigned long long* w = static_cast<const unsigned long long*>(signs);
+        const float* d = reinterpret_cast<const float*>(w + 3 * spinner::sign_words_per_diag(n));
+        return apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, w, m, epilogue, scale, out, workspace, stream);
     }
     return apply_impl(x, n, log2n, batch, nullptr, nullptr, nullptr, static_cast<const unsigned long long*>(signs), m,
                       epilogue, scale, out, workspace, stream);
@@ -348,7 +346,7 @@ static int codes_impl(const float* x, int n, long batch, const float* d1, const 
     if (!workspace) return SPINNER_ERR_WORKSPACE;
     if (!aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
     float* y = static_cast<float*>(workspace);
-    const int rc = apply_impl(x, n, log2n, batch, d1, d2, d3, nullptr, n, SPINNER_EPI_NONE, 1.0f, y, nullptr, stream);
+    const int rc = apply_impl(x, n, log2n, batch, d1, d2, d3, signs, n, SPINNER_EPI_NONE, 1.0f, y, nullptr, stream);
     if (rc != SPINNER_OK) return rc;
     const hipError_t e = spinner::launch_pack_codes(y, n, static_cast<unsigned long long*>(codes), m, batch,
                                                     static_cast<hipStream_t>(stream));
@@ -368,9 +366,10 @@ int spinner_sign_codes_signs(const float* x, int n, long batch, const void* sign
 {
     if (batch > 0 && !signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (n > (1 << spinner::kSignWordsMaxLog)) {     // the packed form is a plain copy of the diagonals at these sizes
-        const float* d = static_cast<const float*>(signs);
-        return codes_impl(x, n, batch, d, d + n, d + 2 * (size_t)n, nullptr, m, codes, workspace, stream);
+    if (n > (1 << spinner::kFusedMaxLogPlain)) {     // four passes: the fp32 diagonals follow the sign words
+        const unsigned long long* w = static_cast<const unsigned long long*>(signs);
+        const float* d = reinterpret_cast<const float*>(w + 3 * spinner::sign_words_per_diag(n));
+        return codes_impl(x, n, batch, d, d + n, d + 2 * (size_t)n, w, m, codes, workspace, stream);
     }
     return codes_impl(x, n, batch, nullptr, nullptr, nullptr, static_cast<const unsigned long long*>(signs), m, codes,
                       workspace, stream);
@@ -614,7 +613,7 @@ int spinner_struct_apply(const float* x, int n, long batch, int kind, const void
     p.batch = batch; p.in_stride = n; p.out_stride = n;
     p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0; p.m = n;
     p.factor = (float)(1.0 / sqrt((double)n));
-    hipError_t e = spinner::launch_row_first(log2n, p, batch, s);
+    hipError_t e = spinner::launch_row_first(log2n, false, p, batch, s);
     if (e != hipSuccess) return hip_fail(e);
     const int lp = struct_log2p(kind, log2n);
     const float2* spec = static_cast<const float2*>(spectrum);

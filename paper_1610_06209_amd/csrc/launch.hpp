@@ -61,6 +61,10 @@ template <typename T, int NT>
 using ContigTuning = std::conditional_t<std::is_same<T, float>::value && ((SPINNER_WIDE_F32 >> NT) & 1) != 0, WideF32<NT>, Tuning<T, NT>>;
 template <typename T, int NT>
 using ContigGeomFor = GeomFrom<ContigTuning<T, NT>, NT>;
+// Row passes of the four-pass schedule that flip signs by packed words need one tile per wave (a wave's scalar
+// loads fetch the words of one tile): 2^11-element rows then take 32 values per thread instead of 64.
+struct RowSigns11 : NotWide { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
+constexpr int kRowSignsMinLog = 9;      // shorter rows share a wave: those passes multiply by the fp32 diagonals
 // geometry of the kernels whose last round is pruned (a separate table so that it can be tuned apart)
 template <typename T, int NT> struct PrunedTuning : Tuning<T, NT> {};
 template <typename T, int NT>
@@ -77,7 +81,8 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
     constexpr bool kWidePruned = PRUNE > 0 && SIGNS && C >= NT && NSTEPS == 3 && EPI == EPI_STORE_NONE && std::is_same<T, float>::value &&
                                  ((SPINNER_WIDE_PRUNED >> NT) & 1) != 0;
     using G = std::conditional_t<(PRUNE > 0 && !kWidePruned), PrunedGeomFor<T, NT>,
-                                 std::conditional_t<(C >= NT && SIGNS && NSTEPS == 3), ContigGeomFor<T, NT>, GeomFor<T, NT>>>;
+                                 std::conditional_t<(C >= NT && SIGNS && NSTEPS == 3), ContigGeomFor<T, NT>,
+                                                    std::conditional_t<(SIGNS && NSTEPS < 3 && NT == 11), GeomFrom<RowSigns11, NT>, GeomFor<T, NT>>>>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
@@ -90,8 +95,9 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
 hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s);
 constexpr int kPruneBits = 4;   // the pruned variant drops the 4 highest index bits in the last round (m <= n/16)
 hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
-hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
-hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
+// signs: the diagonal of the pass comes as packed words p.sw[] (rows of at least 2^kRowSignsMinLog elements), not as p.d[]
+hipError_t launch_row_first(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
+hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
 hipError_t launch_col_middle(int rows_log, int contig_log, const TileParams& p, long long tiles, hipStream_t s);          // cols, D2, cols
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
@@ -102,8 +108,7 @@ hipError_t launch_pack_codes(const float* y, long long y_stride, unsigned long l
 hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const unsigned long long* b, long long nb, int m,
                                float* out, hipStream_t s);
 
-// sign words per diagonal in the packed format (n <= 2^16, the range of the fused plain kernels)
-constexpr int kSignWordsMaxLog = kFusedMaxLogPlain;
+// sign words per diagonal in the packed format
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
 // Sizes whose hash kernel keeps every butterfly between registers (hash.hip) take, behind the three diagonals'
 // sign words of a triple, the lane masks of that kernel's two layouts: [3 diagonals][2 layouts][2^r words].
@@ -131,7 +136,8 @@ inline long long wide_words_offset(int n, int log2n)      // from a triple's fir
     return 3 * sign_words_per_diag(n) + (ar_log2r(log2n) ? 6LL << ar_log2r(log2n) : 0);
 }
 hipError_t launch_pack_wide_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
-// n = 2^15, 2^16: the feature map runs in four passes there and needs the fp32 diagonals, which follow the sign words.
+// n > 2^14: the four-pass schedule multiplies by the second diagonal in column tiles, whose lanes hold no run of
+// the packed format: the fp32 diagonals follow the sign words.
 inline long long sign_words_per_triple(int n, int log2n)
 {
     return wide_words_offset(n, log2n) + (has_wide_words(log2n) ? 3 * sign_words_per_diag(n) : 0) +

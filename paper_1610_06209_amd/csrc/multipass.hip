@@ -6,8 +6,12 @@
 // equals H D3 H D2 H D1 with four trips through HBM instead of six.
 #include "launch.hpp"
 namespace spinner {
-#define ROWCASE(NT, STEPS, FD) case NT: return launch_tile<float, NT, NT, STEPS, FD, EPI_STORE_NONE>(p, tiles, s);
-hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStream_t s)
+#define ROWCASE(NT, STEPS, FD)                                                                                        \
+    case NT:                                                                                                          \
+        if constexpr (NT >= kRowSignsMinLog) { if (signs) return launch_tile<float, NT, NT, STEPS, FD, EPI_STORE_NONE, true>(p, tiles, s); } \
+        else if (signs) return hipErrorInvalidValue;                                                                  \
+        return launch_tile<float, NT, NT, STEPS, FD, EPI_STORE_NONE>(p, tiles, s);
+hipError_t launch_row_first(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (nt) {
         ROWCASE(5, 1, true) ROWCASE(6, 1, true) ROWCASE(7, 1, true) ROWCASE(8, 1, true) ROWCASE(9, 1, true)
@@ -15,7 +19,7 @@ hipError_t launch_row_first(int nt, const TileParams& p, long long tiles, hipStr
     default: return hipErrorInvalidValue;
     }
 }
-hipError_t launch_row_middle(int nt, const TileParams& p, long long tiles, hipStream_t s)
+hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s)
 {
     switch (nt) {
         ROWCASE(5, 2, false) ROWCASE(6, 2, false) ROWCASE(7, 2, false) ROWCASE(8, 2, false) ROWCASE(9, 2, false)

@@ -903,6 +903,8 @@ __attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_W
 spinner_tile_kernel(TileParams p)
 {
     static_assert(!SIGNS || C >= G::NT, "sign words describe contiguous tiles only");
+    // a pass over row tiles of longer vectors reads the words of its own tile: one tile per wave
+    static_assert(!SIGNS || NSTEPS == 3 || G::LB == 6, "sign words of a row pass: a wave holds one tile");
     constexpr int NT = G::NT;
     constexpr int R = G::R;
     constexpr int CB = C >= NT ? 0 : C;          // index bits below CB are not transformed
@@ -920,6 +922,10 @@ spinner_tile_kernel(TileParams p)
         tile = blockIdx.x;
         c.lit = lane;
         c.wv = __builtin_amdgcn_readfirstlane(wave);
+    } else if constexpr (SIGNS && NSTEPS < 3) {
+        tile = (long long)blockIdx.x * G::WAVES + __builtin_amdgcn_readfirstlane(wave);      // wave-uniform: it places the sign words
+        c.lit = lane;
+        c.wv = 0;
     } else {
         tile = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + (lane >> G::LB);
         c.lit = lane & ((1 << G::LB) - 1);
@@ -958,10 +964,14 @@ spinner_tile_kernel(TileParams p)
         // (measured: 1.4 % at n = 2^14, nothing elsewhere; only tiles of several waves with 64 values per thread use it)
         constexpr int NPF = (SIGNS && G::WB > 0 && R == 64) ? SPINNER_MASK_PREFETCH : 0;
         SignMasks<NPF> pm;
+        // packed words of this tile's part of the diagonals (a row tile of a longer vector starts 64 elements per word in)
+        const unsigned long long* sw0 = p.sw[0];
+        const unsigned long long* sw1 = p.sw[1];
+        if constexpr (SIGNS && NSTEPS < 3) { sw0 += tile_first >> 6; sw1 += tile_first >> 6; }
         // steps (layout alternates only when a tile spans several waves)
-        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS, T, NPF, (NSTEPS > 1)>(v, c, p.d[0] + tile_first, p.sw[0], p.sl, lds, &pm, p.sw[1]);
+        spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS, T, NPF, (NSTEPS > 1)>(v, c, p.d[0] + tile_first, sw0, p.sl, lds, &pm, sw1);
         if constexpr (NSTEPS > 1)
-            spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS, T, NPF, (NSTEPS > 2)>(v, c, p.d[1] + tile_first, p.sw[1], p.sl, lds, &pm, p.sw[2]);
+            spinner_step<G, C, CB, G::layout_after(1), true, false, true, SIGNS, T, NPF, (NSTEPS > 2)>(v, c, p.d[1] + tile_first, sw1, p.sl, lds, &pm, p.sw[2]);
         bool wave_live = true;
         if constexpr (NSTEPS > 2) {
             if constexpr (PRUNE > 0)

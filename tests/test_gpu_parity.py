@@ -350,12 +350,15 @@ def test_features_from_sign_words_n4096(gpu, oracle, m, scale, batch):
     assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL, (m, "general diagonals")
 
 
-@pytest.mark.parametrize("log2n", [15, 16, 17])
+@pytest.mark.parametrize("log2n", [15, 16, 17, 18, 19, 20, 21, 22])
 def test_sign_word_path_above_the_feature_and_hash_range(gpu, oracle, log2n):
-    # n = 2^15, 2^16: sign words for the fused plain kernel, followed by the fp32 diagonals for the four-pass
-    # feature map; n = 2^17: a plain copy of the diagonals.  Two triples, so that the per-triple stride is used.
+    # Above 2^14 the packed form is sign words followed by the fp32 diagonals.  n = 2^15, 2^16: the words serve the fused
+    # plain kernel; in the four-pass schedule (features from 2^15, everything from 2^17) the row passes flip by the
+    # words of their own tile once a row fills a wave (rows of 2^9 .. 2^14 elements here, each with its own kernel
+    # geometry) and the column pass multiplies by the fp32 diagonal.  Two triples, so that the per-triple stride is
+    # used; three vectors, so that the tiles of one row index are an odd count.
     n = 1 << log2n
-    w = W.Workload("s", "apply", n, 2, n, "none", 1.0, 2, "normal", 8100 + log2n, 2)
+    w = W.Workload("s", "apply", n, 3, n, "none", 1.0, 2, "normal", 8100 + log2n, 3)
     x = W.make_x_numpy(w)
     ds = W.diag_sets(w)
     xd = _to(gpu, x)
