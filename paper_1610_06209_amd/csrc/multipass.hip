@@ -1,7 +1,7 @@
-// Passes of the four-pass schedule for n > 2^14.  The vector is viewed as a
-// 2^R x 2^(N-R) row-major matrix (R = 8 up to n = 2^20, else 10); H_n = H_rows (x)
+// Passes of the four-pass schedule for n above the fused range.  The vector is viewed as a
+// 2^R x 2^(N-R) row-major matrix (R = 7 up to n = 2^21, then 8, 9, 10: col_shape_for); H_n = H_rows (x)
 // H_cols acts as a transform along rows (contiguous tiles) and along columns
-// (tiles of all 2^R rows x 16 contiguous columns).  Row and column transforms commute and a diagonal is elementwise, so
+// (tiles of all 2^R rows x 32 or 16 contiguous columns).  Row and column transforms commute and a diagonal is elementwise, so
 //   P1: D1, rows   P2: cols, D2, cols   P3: rows, D3, rows   P4: cols, epilogue
 // equals H D3 H D2 H D1 with four trips through HBM instead of six.
 #include "launch.hpp"
