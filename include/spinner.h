@@ -126,10 +126,10 @@ int spinner_hash(const float *x, int n, long batch, int L,
  *
  * spinner_apply_signs uses the first triple found at `signs`; all other
  * arguments, the output, the workspace rule and the error codes are those of
- * spinner_apply.  For n > 2^14 the buffer holds the sign words and, behind
- * them, a copy of the fp32 diagonals: in the four-pass path the passes over
- * rows flip signs by the words and the pass over columns multiplies by the
- * fp32 second diagonal.
+ * spinner_apply.  For n > 2^14 the buffer also holds the lane masks with
+ * which the four-pass path flips signs in its pass over columns (its passes
+ * over rows use the sign words), and at n = 2^15 a copy of the fp32
+ * diagonals: about n / 2 bytes per triple otherwise.
  */
 size_t spinner_signs_bytes(int n, int L);
 int spinner_pack_signs(const float *diag_sets, int n, int L, void *signs, void *stream);

@@ -160,9 +160,11 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     const int kColRowsLog = cs.rows_log, kColContigLog = cs.contig_log;
     const int nr = log2n - kColRowsLog;
     float* buf_all = ws ? static_cast<float*>(workspace) : out;
-    // with packed sign words the row passes flip by lane mask (rows long enough to fill a wave); the column pass
-    // multiplies by the fp32 diagonal in any case
+    // with packed sign words the passes flip by lane mask: the row passes if a row fills a wave (else they multiply
+    // by the fp32 diagonal), the column pass by the masks prepared for its tiles
     const bool row_signs = signs != nullptr && nr >= kRowSignsMinLog;
+    const bool col_signs = signs != nullptr;
+    if ((!row_signs && (!d1 || !d3)) || (!col_signs && !d2)) return SPINNER_ERR_NULL_PTR;
     // The batch is walked in slices of about 192 MiB, all four passes per slice, so that the
     // three intermediate trips of a slice find most of it in the 256 MB memory-side cache
     // (measured 10-15 % faster than pass-by-pass over the whole batch; smaller slices leave
@@ -190,12 +192,13 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         p.x = x + b0 * (long long)n; p.out = buf; p.d[0] = d1; p.d[1] = nullptr; p.d[2] = nullptr;
         p.in_stride = n; p.out_stride = n; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
         p.m = n; p.factor = 1.0f;
-        if (row_signs) p.sw[0] = signs;
+        p.sw[0] = signs;
         if ((e = launch_row_first(nr, row_signs, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
         // P2: cols, D2, cols : buf -> buf
         p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-        if ((e = launch_col_middle(kColRowsLog, kColContigLog, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
+        if (col_signs) p.sw[1] = signs + col_words_offset(n, log2n);
+        if ((e = launch_col_middle(kColRowsLog, kColContigLog, col_signs, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
         // P3: rows, D3, rows : buf -> buf
         p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
         if (row_signs) p.sw[1] = signs + 2 * sign_words_per_diag(n);
@@ -257,8 +260,12 @@ int spinner_pack_signs(const float* diag_sets, int n, int L, void* signs, void* 
         e = spinner::launch_pack_hash_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
     if (e == hipSuccess && spinner::has_wide_words(log2n))
         e = spinner::launch_pack_wide_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
-    if (e == hipSuccess && log2n > spinner::kFusedMaxLogOther)      // fp32 copy of each triple behind its sign words
-        e = hipMemcpy2DAsync(static_cast<unsigned long long*>(signs) + 3 * W, (size_t)spinner::sign_words_per_triple(n, log2n) * 8,
+    // sizes of the four-pass schedule: lane masks of its column pass, then (short rows only) an fp32 copy of each triple
+    if (e == hipSuccess && log2n > spinner::kFusedMaxLogOther)
+        e = spinner::launch_pack_col_words(diag_sets, log2n, L, static_cast<unsigned long long*>(signs), s);
+    if (e == hipSuccess && spinner::has_fp32_copy(log2n))
+        e = hipMemcpy2DAsync(static_cast<unsigned long long*>(signs) + spinner::fp32_copy_offset(n, log2n),
+                             (size_t)spinner::sign_words_per_triple(n, log2n) * 8,
                              diag_sets, (size_t)3 * n * sizeof(float), (size_t)3 * n * sizeof(float), (size_t)L,
                              hipMemcpyDeviceToDevice, s);
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
@@ -272,9 +279,9 @@ int spinner_apply_signs(const float* x, int n, long batch, const void* signs, in
     if (rc != SPINNER_OK || batch == 0) return rc;
     if (!signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > fused_max_log(epilogue)) {      // four passes: sign words for the row passes, the fp32 diagonals behind them
+    if (log2n > fused_max_log(epilogue) && spinner::has_fp32_copy(log2n)) {      // four passes whose row passes multiply by the fp32 diagonals behind the words
         const unsigned long long* w = static_cast<const unsigned long long*>(signs);
-        const float* d = reinterpret_cast<const float*>(w + 3 * spinner::sign_words_per_diag(n));
+        const float* d = reinterpret_cast<const float*>(w + spinner::fp32_copy_offset(n, log2n));
         return apply_impl(x, n, log2n, batch, d, d + n, d + 2 * (size_t)n, w, m, epilogue, scale, out, workspace, stream);
     }
     return apply_impl(x, n, log2n, batch, nullptr, nullptr, nullptr, static_cast<const unsigned long long*>(signs), m,
@@ -366,11 +373,6 @@ int spinner_sign_codes_signs(const float* x, int n, long batch, const void* sign
 {
     if (batch > 0 && !signs) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (n > (1 << spinner::kFusedMaxLogPlain)) {     // four passes: the fp32 diagonals follow the sign words
-        const unsigned long long* w = static_cast<const unsigned long long*>(signs);
-        const float* d = reinterpret_cast<const float*>(w + 3 * spinner::sign_words_per_diag(n));
-        return codes_impl(x, n, batch, d, d + n, d + 2 * (size_t)n, w, m, codes, workspace, stream);
-    }
     return codes_impl(x, n, batch, nullptr, nullptr, nullptr, static_cast<const unsigned long long*>(signs), m, codes,
                       workspace, stream);
 }

@@ -98,7 +98,8 @@ hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long 
 // signs: the diagonal of the pass comes as packed words p.sw[] (rows of at least 2^kRowSignsMinLog elements), not as p.d[]
 hipError_t launch_row_first(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
 hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
-hipError_t launch_col_middle(int rows_log, int contig_log, const TileParams& p, long long tiles, hipStream_t s);          // cols, D2, cols
+// signs: the pass flips by the lane masks p.sw[1] that launch_pack_col_words prepared for its tiles
+hipError_t launch_col_middle(int rows_log, int contig_log, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // cols, D2, cols
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
 // sign codes (angular-kernel features): fused kernels for n = 2^8 .. 2^16, packing of an fp32 projection, Gram matrix
@@ -136,13 +137,36 @@ inline long long wide_words_offset(int n, int log2n)      // from a triple's fir
     return 3 * sign_words_per_diag(n) + (ar_log2r(log2n) ? 6LL << ar_log2r(log2n) : 0);
 }
 hipError_t launch_pack_wide_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
-// n > 2^14: the four-pass schedule multiplies by the second diagonal in column tiles, whose lanes hold no run of
-// the packed format: the fp32 diagonals follow the sign words.
+// Shape of the column tiles of the four-pass schedule: 2^rows_log rows (all rows of the
+// matrix view) by 2^contig_log contiguous columns.  Up to n = 2^21 the matrix view has
+// 2^7 rows and a column tile is 128 rows x 32 columns (128-byte segments, 2^12 elements:
+// one wave, no LDS, no barriers); larger n take more rows so that a row (a contiguous
+// tile of n / rows elements) still fits on chip.  128-byte segments measured 25-30 %
+// faster than 64-byte ones.
+struct ColShape { int rows_log, contig_log; };
+inline ColShape col_shape_for(int log2n)
+{
+    // rows_log grows only as far as needed to keep a row (n / rows elements) within 2^14
+    ColShape cs = log2n <= 21 ? ColShape{7, 5} : (log2n == 22 ? ColShape{8, 5} : (log2n == 23 ? ColShape{9, 5} : ColShape{10, 4}));
+#ifdef SPINNER_TUNING_HOOKS
+    if (const char* e = getenv("SPINNER_COL_SHAPE")) { cs.rows_log = e[0] - '0'; if (e[1] >= '0' && e[1] <= '9') { cs.rows_log = cs.rows_log * 10 + (e[1] - '0'); e++; } cs.contig_log = e[2] - '0'; }
+#endif
+    return cs;
+}
+
+// n > 2^14 (sizes that the four-pass schedule serves): that schedule multiplies by the second diagonal in column
+// tiles, whose lanes hold no run of the packed format; the lane masks of that pass follow the three diagonals' words
+// (n / 64 words, multipass.hip), and then, where the rows of the matrix view are too short for the row passes to flip
+// by sign words (n = 2^15), the fp32 diagonals.
+inline long long col_words_offset(int n, int log2n) { return wide_words_offset(n, log2n); }
+inline long long fp32_copy_offset(int n, int log2n) { return col_words_offset(n, log2n) + sign_words_per_diag(n); }
+inline bool has_fp32_copy(int log2n) { return log2n > kFusedMaxLogOther && log2n - col_shape_for(log2n).rows_log < kRowSignsMinLog; }
 inline long long sign_words_per_triple(int n, int log2n)
 {
-    return wide_words_offset(n, log2n) + (has_wide_words(log2n) ? 3 * sign_words_per_diag(n) : 0) +
-           (log2n > kFusedMaxLogOther ? 3LL * n / 2 : 0);
+    if (log2n > kFusedMaxLogOther) return fp32_copy_offset(n, log2n) + (has_fp32_copy(log2n) ? 3LL * n / 2 : 0);
+    return wide_words_offset(n, log2n) + (has_wide_words(log2n) ? 3 * sign_words_per_diag(n) : 0);
 }
+hipError_t launch_pack_col_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
 hipError_t launch_pack_hash_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s);
 
 // adaptive layer (forward with saved activations, backward); the parameter structs are in layer_kernels.hpp
@@ -164,22 +188,5 @@ hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* sla
 hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, hipStream_t s);
 hipError_t launch_struct_conv(const float* t, const float* d2, const float2* spec, const float2* tw, float* out, long long batch,
                               int n, int log2p, int m, int reverse, float factor, hipStream_t s);
-
-// Shape of the column tiles of the four-pass schedule: 2^rows_log rows (all rows of the
-// matrix view) by 2^contig_log contiguous columns.  Up to n = 2^21 the matrix view has
-// 2^7 rows and a column tile is 128 rows x 32 columns (128-byte segments, 2^12 elements:
-// one wave, no LDS, no barriers); larger n take more rows so that a row (a contiguous
-// tile of n / rows elements) still fits on chip.  128-byte segments measured 25-30 %
-// faster than 64-byte ones.
-struct ColShape { int rows_log, contig_log; };
-inline ColShape col_shape_for(int log2n)
-{
-    // rows_log grows only as far as needed to keep a row (n / rows elements) within 2^14
-    ColShape cs = log2n <= 21 ? ColShape{7, 5} : (log2n == 22 ? ColShape{8, 5} : (log2n == 23 ? ColShape{9, 5} : ColShape{10, 4}));
-#ifdef SPINNER_TUNING_HOOKS
-    if (const char* e = getenv("SPINNER_COL_SHAPE")) { cs.rows_log = e[0] - '0'; if (e[1] >= '0' && e[1] <= '9') { cs.rows_log = cs.rows_log * 10 + (e[1] - '0'); e++; } cs.contig_log = e[2] - '0'; }
-#endif
-    return cs;
-}
 
 }  // namespace spinner

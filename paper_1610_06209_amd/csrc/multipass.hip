@@ -29,17 +29,66 @@ hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long 
 }
 #undef ROWCASE
 #define COLCASE(NT, C, STEPS, EPI) if (rows_log + contig_log == NT && contig_log == C) return launch_tile<float, NT, C, STEPS, false, EPI>(p, tiles, s);
-hipError_t launch_col_middle(int rows_log, int contig_log, const TileParams& p, long long tiles, hipStream_t s)
+#define COLMID(NT, C)                                                                                     \
+    if (rows_log + contig_log == NT && contig_log == C)                                                   \
+        return signs ? launch_tile<float, NT, C, 2, false, EPI_STORE_NONE, true>(p, tiles, s)             \
+                     : launch_tile<float, NT, C, 2, false, EPI_STORE_NONE>(p, tiles, s);
+hipError_t launch_col_middle(int rows_log, int contig_log, bool signs, const TileParams& p, long long tiles, hipStream_t s)
 {
-    COLCASE(12, 5, 2, EPI_STORE_NONE)
-    COLCASE(13, 5, 2, EPI_STORE_NONE)
-    COLCASE(14, 5, 2, EPI_STORE_NONE)
-    COLCASE(14, 4, 2, EPI_STORE_NONE)
+    COLMID(12, 5) COLMID(13, 5) COLMID(14, 5) COLMID(14, 4)
 #ifdef SPINNER_TUNING_HOOKS
-    COLCASE(12, 4, 2, EPI_STORE_NONE) COLCASE(12, 6, 2, EPI_STORE_NONE) COLCASE(13, 6, 2, EPI_STORE_NONE)
+    COLMID(12, 4) COLMID(12, 6) COLMID(13, 6)
 #endif
     return hipErrorInvalidValue;
 }
+#undef COLMID
+
+// Lane masks of the second diagonal for that pass, one 64-bit word per register of a wave: the tile of columns
+// [q 2^C, (q + 1) 2^C) has its 2^NT / 64 words at q 2^NT / 64, word (wave << r) | register, and bit l of a word is
+// the sign of the entry that lane l of that wave holds in that register in layout 1, where the pass multiplies.
+// One wave per word; the word is the wave's ballot.
+template <typename G, int C>
+__global__ void __launch_bounds__(256) pack_col_words_kernel(const float* __restrict__ diag_sets, unsigned long long* __restrict__ signs,
+                                                             long long n, int sl, long long triple_words, long long offset,
+                                                             long long total_words)
+{
+    static_assert(G::WB > 0 && G::LB == 6 && !G::WIDE && C < G::NT, "column tile held by several waves");
+    const long long gw = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (gw >= total_words) return;
+    const long long W = n >> 6;
+    const long long triple = gw / W, w = gw - triple * W;
+    const long long q = w >> (G::NT - 6);
+    const int wj = (int)(w & ((1 << (G::NT - 6)) - 1));
+    const int wv = wj >> G::r, j = wj & (G::R - 1);
+    int e = G::reg_index(1, j) | (lane << 2);
+    for (int b = 0; b < G::WB; ++b) e |= ((wv >> b) & 1) << G::wave_pos(1, b);
+    const long long idx = (q << C) + tile_offset<G::NT, C>(e, sl);
+    const bool neg = (__float_as_uint(diag_sets[(triple * 3 + 1) * n + idx]) >> 31) != 0;
+    const unsigned long long m = __ballot(neg);
+    if (lane == 0) signs[triple * triple_words + offset + w] = m;
+}
+
+#define COLPACK(NT, C)                                                                                                     \
+    if (cs.rows_log + cs.contig_log == NT && cs.contig_log == C) {                                                         \
+        hipLaunchKernelGGL((pack_col_words_kernel<GeomFor<float, NT>, C>), dim3((unsigned)blocks), dim3(256), 0, s, diag_sets, signs, \
+                           n, log2n - cs.rows_log, sign_words_per_triple((int)n, log2n), col_words_offset((int)n, log2n), total); \
+        return hipGetLastError();                                                                                          \
+    }
+hipError_t launch_pack_col_words(const float* diag_sets, int log2n, int L, unsigned long long* signs, hipStream_t s)
+{
+    const ColShape cs = col_shape_for(log2n);
+    const long long n = 1LL << log2n;
+    const long long total = (long long)L * (n >> 6);
+    const long long blocks = (total + 3) / 4;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    COLPACK(12, 5) COLPACK(13, 5) COLPACK(14, 5) COLPACK(14, 4)
+#ifdef SPINNER_TUNING_HOOKS
+    COLPACK(12, 4) COLPACK(12, 6) COLPACK(13, 6)
+#endif
+    return hipErrorInvalidValue;
+}
+#undef COLPACK
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s)
 {
     if (epi == EPI_STORE_COSSIN) {

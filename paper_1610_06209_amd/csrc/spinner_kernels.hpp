@@ -686,10 +686,14 @@ __device__ __forceinline__ int wave_index_bits(const ThreadCtx<G>& c)
 }
 
 // lane mask "which lanes hold a negated element" of register j in layout LAY
-template <typename G, int LAY>
+// DIRECT: `w` holds this tile's masks as they are used, word (wave << r) | register (column tiles of the four-pass
+// schedule, whose lanes hold no run of the packed format)
+template <typename G, int LAY, bool DIRECT = false>
 __device__ __forceinline__ unsigned long long sign_mask(sign_words_t w, const ThreadCtx<G>& c, int ew, int j)
 {
-    if constexpr (G::WIDE && LAY == 1) {
+    if constexpr (DIRECT) {
+        return w[(c.wv << G::r) | j];
+    } else if constexpr (G::WIDE && LAY == 1) {
         // lanes hold index bits 2..5 and two high bits: no word of the packed format is this register's lane mask;
         // spinner_pack_signs leaves the masks of this layout, word (wave << r) | register, wide_off words further on
         return w[c.wide_off + ((c.wv << G::r) | j)];
@@ -712,17 +716,17 @@ __device__ __forceinline__ unsigned long long sign_mask(sign_words_t w, const Th
 template <int N>
 struct SignMasks { unsigned long long m[N > 0 ? N : 1]; };
 
-template <typename G, int LAY, int N>
+template <typename G, int LAY, int N, bool DIRECT = false>
 __device__ __forceinline__ void fetch_sign_masks(SignMasks<N>& pm, const ThreadCtx<G>& c, const unsigned long long* words)
 {
     sign_words_t w = (sign_words_t)words;
     const int ew = wave_index_bits<G, LAY>(c);
 #pragma unroll
-    for (int j = 0; j < N; ++j) pm.m[j] = sign_mask<G, LAY>(w, c, ew, j);
+    for (int j = 0; j < N; ++j) pm.m[j] = sign_mask<G, LAY, DIRECT>(w, c, ew, j);
 }
 
 // NPF: the masks of registers 0 .. NPF-1 come from `pm` instead of from memory
-template <typename G, int LAY, int NPF = 0, typename T>
+template <typename G, int LAY, int NPF = 0, bool DIRECT = false, typename T>
 __device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, const unsigned long long* words,
                                           const SignMasks<NPF>* pm = nullptr)
 {
@@ -731,7 +735,7 @@ __device__ __forceinline__ void sign_flip(T (&v)[G::R], const ThreadCtx<G>& c, c
 #pragma unroll
     for (int j = 0; j < G::R; ++j) {
         if (j < NPF) flip_by_mask(v[j], pm->m[j]);
-        else flip_by_mask(v[j], sign_mask<G, LAY>(w, c, ew, j));
+        else flip_by_mask(v[j], sign_mask<G, LAY, DIRECT>(w, c, ew, j));
     }
 }
 
@@ -747,10 +751,11 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
                                              const float* dtile, const unsigned long long* words, int sl, float4* lds,
                                              SignMasks<NPF>* pm = nullptr, const unsigned long long* next_words = nullptr)
 {
+    constexpr bool DIRECT = SIGNS && C < G::NT;      // column tiles bring their lane masks as they are used
     if constexpr (HAS_DIAG) {
         if constexpr (SIGNS) {
-            if constexpr (NPF > 0 && !FIRST_TRANSPOSE) sign_flip<G, LAY, NPF>(v, c, words, pm);
-            else sign_flip<G, LAY>(v, c, words);
+            if constexpr (NPF > 0 && !FIRST_TRANSPOSE) sign_flip<G, LAY, NPF, DIRECT>(v, c, words, pm);
+            else sign_flip<G, LAY, 0, DIRECT>(v, c, words);
         }
         else diag_multiply<G, C, LAY>(v, c, dtile, sl);
     }
@@ -759,7 +764,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
 #endif
     constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(LAY, 4);
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
-    if constexpr (NPF > 0 && PF_NEXT) fetch_sign_masks<G, (G::WB > 0 ? 1 - LAY : LAY)>(*pm, c, next_words);
+    if constexpr (NPF > 0 && PF_NEXT) fetch_sign_masks<G, (G::WB > 0 ? 1 - LAY : LAY), NPF, DIRECT>(*pm, c, next_words);
     if constexpr (G::WB > 0) {
         if constexpr (std::is_same<T, float>::value) transpose<G, LAY, !FIRST_TRANSPOSE, 0, 0, SWAP>(v, c, lds);
         else transpose<G, LAY, !FIRST_TRANSPOSE, SWAP>(v, c, lds);
@@ -902,9 +907,11 @@ __global__ void __launch_bounds__(G::THREADS)
 __attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_WAVES ? G::MIN_WAVES : (G::WB ? SPINNER_MIN_WAVES_MULTI : SPINNER_MIN_WAVES_PER_EU))))
 spinner_tile_kernel(TileParams p)
 {
-    static_assert(!SIGNS || C >= G::NT, "sign words describe contiguous tiles only");
-    // a pass over row tiles of longer vectors reads the words of its own tile: one tile per wave
-    static_assert(!SIGNS || NSTEPS == 3 || G::LB == 6, "sign words of a row pass: a wave holds one tile");
+    // packed sign words describe contiguous tiles; the column pass that applies the second diagonal takes lane masks
+    // prepared for its layout (see sign_mask)
+    static_assert(!SIGNS || C >= G::NT || (NSTEPS == 2 && !FIRST_DIAG && G::WB > 0), "sign words and column tiles");
+    // a pass over tiles of longer vectors reads the words of its own tile: one tile per wave
+    static_assert(!SIGNS || NSTEPS == 3 || G::LB == 6, "sign words of a pass: a wave holds one tile");
     constexpr int NT = G::NT;
     constexpr int R = G::R;
     constexpr int CB = C >= NT ? 0 : C;          // index bits below CB are not transformed
@@ -964,10 +971,10 @@ spinner_tile_kernel(TileParams p)
         // (measured: 1.4 % at n = 2^14, nothing elsewhere; only tiles of several waves with 64 values per thread use it)
         constexpr int NPF = (SIGNS && G::WB > 0 && R == 64) ? SPINNER_MASK_PREFETCH : 0;
         SignMasks<NPF> pm;
-        // packed words of this tile's part of the diagonals (a row tile of a longer vector starts 64 elements per word in)
+        // words of this tile's part of the diagonals (tile q of a longer vector: 2^NT / 64 words per tile)
         const unsigned long long* sw0 = p.sw[0];
         const unsigned long long* sw1 = p.sw[1];
-        if constexpr (SIGNS && NSTEPS < 3) { sw0 += tile_first >> 6; sw1 += tile_first >> 6; }
+        if constexpr (SIGNS && NSTEPS < 3) { sw0 += q << (NT - 6); sw1 += q << (NT - 6); }
         // steps (layout alternates only when a tile spans several waves)
         spinner_step<G, C, CB, G::layout_after(0), FIRST_DIAG, true, false, SIGNS, T, NPF, (NSTEPS > 1)>(v, c, p.d[0] + tile_first, sw0, p.sl, lds, &pm, sw1);
         if constexpr (NSTEPS > 1)

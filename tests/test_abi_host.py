@@ -95,9 +95,11 @@ def test_sign_word_entry_points_reject_bad_arguments(b):
     assert b.spinner_signs_bytes(16384, 2) == 2 * (3 * 256 * 8 + 3 * 256 * 8)
     assert b.spinner_signs_bytes(64, 2) == 2 * 3 * 4 * 8
     assert b.spinner_signs_bytes(256, 1) == 3 * 4 * 8 + 3 * 2 * 16 * 8
-    assert b.spinner_signs_bytes(1 << 16, 1) == 3 * 1024 * 8 + 3 * (1 << 16) * 4      # sign words, then the fp32 diagonals
-    assert b.spinner_signs_bytes(1 << 17, 1) == 3 * 2048 * 8 + 3 * (1 << 17) * 4
-    assert b.spinner_signs_bytes(1 << 24, 2) == 2 * (3 * (1 << 18) * 8 + 3 * (1 << 24) * 4)
+    # above 2^14: sign words, lane masks of the four-pass schedule's column pass; at 2^15 also the fp32 diagonals
+    assert b.spinner_signs_bytes(1 << 15, 1) == 4 * 512 * 8 + 3 * (1 << 15) * 4
+    assert b.spinner_signs_bytes(1 << 16, 1) == 4 * 1024 * 8
+    assert b.spinner_signs_bytes(1 << 17, 1) == 4 * 2048 * 8
+    assert b.spinner_signs_bytes(1 << 24, 2) == 2 * 4 * (1 << 18) * 8
     assert b.spinner_signs_bytes(1000, 1) == 0 and b.spinner_signs_bytes(1024, 0) == 0
     pk = b.lib.spinner_pack_signs
     assert pk(64, 1000, 1, 64, None) == b.SPINNER_ERR_BAD_N
