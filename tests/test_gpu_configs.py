@@ -63,6 +63,10 @@ def test_cfg1_plain_n256(gpu, oracle):
     err = rel_l2_per_vector(y.cpu().numpy()[rows], want)
     assert err.max() <= REL_L2_TOL, err.max()
     assert bool(((_norms(y) / _norms(x) - 1).abs() < 1e-5).all())          # isometry, whole batch
+    # the form the benchmark times: +-1 diagonals as packed sign words
+    ys = gpu.b.spinner_apply_signs(x, gpu.b.spinner_pack_signs(dsd), w.m, w.epilogue, w.scale)
+    assert rel_l2_per_vector(ys.cpu().numpy()[rows], want).max() <= REL_L2_TOL
+    assert bool(((_norms(ys) / _norms(x) - 1).abs() < 1e-5).all())
 
 
 def test_cfg2_lsh_n1024(gpu, oracle):
@@ -82,6 +86,13 @@ def test_cfg2_lsh_n1024(gpu, oracle):
     chi2 = float(((counts - expect) ** 2 / expect).sum())
     assert chi2 < 2 * w.n + 8 * math.sqrt(4 * w.n)          # mean 2n-1, std sqrt(2(2n-1))
     assert float((h[:, 0] == h[:, 1]).double().mean()) < 5.0 / (2 * w.n)
+    # the form the benchmark times: packed sign words (a kernel of its own at this size); sampled rows against the
+    # oracle, and the whole batch against the fp32-diagonal kernel (they may part only where two coordinates tie)
+    hs = gpu.b.spinner_hash_signs(x, gpu.b.spinner_pack_signs(dsd), w.L)
+    exact, banded = check_hash_against_projection(hs.cpu().numpy()[rows], ys)
+    assert exact + banded == len(rows) * w.L
+    assert banded <= 2
+    assert float((hs != h).double().mean()) < 1e-3
 
 
 def test_cfg3_rff_n4096(gpu, oracle):
@@ -113,6 +124,11 @@ def test_cfg4_jl_n16384(gpu, oracle):
     want = oracle.apply(xs, ds[0, 0], ds[0, 1], ds[0, 2], w.m, "none", w.scale)
     err = rel_l2_per_vector(f.cpu().numpy()[rows], want)
     assert err.max() <= REL_L2_TOL, err.max()
+    # the form the benchmark times: packed sign words (wide exchanges, pruned last round)
+    fs = gpu.b.spinner_apply_signs(x, gpu.b.spinner_pack_signs(dsd), w.m, w.epilogue, w.scale)
+    assert rel_l2_per_vector(fs.cpu().numpy()[rows], want).max() <= REL_L2_TOL
+    assert float(((fs - f).double().norm(dim=1) / f.double().norm(dim=1)).max()) <= REL_L2_TOL
+    del fs
     # pairwise distances of 1000 seeded pairs, on the full-batch GPU output
     rng = np.random.default_rng(4)
     i = rng.integers(0, w.batch, 1000)
@@ -137,6 +153,10 @@ def test_cfg5_large_n2p20(gpu, oracle):
     # stays below log(n)/sqrt(n); the full spinner output is balanced as well
     ymax = (y.abs().max(dim=1).values.double() / _norms(x)).max()
     assert float(ymax) <= math.log(w.n) / math.sqrt(w.n)
+    # the form the benchmark times: packed sign words in all three diagonal passes, several slices
+    ys = gpu.b.spinner_apply_signs(x, gpu.b.spinner_pack_signs(dsd), w.m, w.epilogue, w.scale)
+    assert rel_l2_per_vector(ys.cpu().numpy()[rows], want).max() <= REL_L2_TOL
+    assert float(((ys - y).double().norm(dim=1) / _norms(y)).max()) <= REL_L2_TOL
 
 
 # ------------------------------------------------------------------ the rows beyond the five configurations, at the sizes bench.py times
