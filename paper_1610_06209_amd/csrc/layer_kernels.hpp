@@ -9,6 +9,9 @@
 // Backward, with t1 = H_u dy, t2 = H_u D3 t1, t3 = H_u D2 t2 and c = scale n^{-3/2}:
 //   dD3 = c sum_b t1 * saved2,  dD2 = c sum_b t2 * saved1,  dD1 = c sum_b t3 * x,  dx = c D1 t3.
 #pragma once
+#ifndef SPINNER_LAYER_BWD_WAVES     // waves per SIMD that the backward kernel of tiles of several waves, 16 values per thread, is compiled for
+#define SPINNER_LAYER_BWD_WAVES 3
+#endif
 #include "layer_params.hpp"
 #include "spinner_kernels.hpp"
 
@@ -49,6 +52,14 @@ __device__ __forceinline__ void tile_mac(float (&acc)[G::R], const float (&g)[G:
         acc[jh * 4 + 2] = __builtin_fmaf(g[jh * 4 + 2], t.z, acc[jh * 4 + 2]);
         acc[jh * 4 + 3] = __builtin_fmaf(g[jh * 4 + 3], t.w, acc[jh * 4 + 3]);
     }
+}
+
+// acc += g * t for a tile already in registers
+template <int R>
+__device__ __forceinline__ void tile_fma(float (&acc)[R], const float (&g)[R], const float (&t)[R])
+{
+#pragma unroll
+    for (int j = 0; j < R; ++j) acc[j] = __builtin_fmaf(g[j], t[j], acc[j]);
 }
 
 template <typename G>
@@ -98,12 +109,19 @@ __global__ void __launch_bounds__(G::THREADS) layer_forward_kernel(LayerForwardP
 // Slot s (one tile position of one workgroup) handles vectors s, s + slots, s + 2 slots, ... and
 // keeps its three per-coordinate sums in registers; they are written once at the end.
 template <typename G>
-__global__ void __launch_bounds__(G::THREADS) layer_backward_kernel(LayerBackwardParams p)
+__global__ void __launch_bounds__(G::THREADS) __attribute__((amdgpu_waves_per_eu((G::R == 16 && G::WB > 0) ? SPINNER_LAYER_BWD_WAVES : (G::R == 32 ? 2 : 1))))
+layer_backward_kernel(LayerBackwardParams p)
 {
     constexpr int NT = G::NT;
     constexpr int n = 1 << NT;
     constexpr int R = G::R;
     constexpr int L1 = G::layout_after(1), L2 = G::layout_after(2), L3 = G::layout_after(3);
+#ifndef SPINNER_LAYER_PREFETCH      // 0: the backward kernel loads nothing ahead (tuning experiments)
+#define SPINNER_LAYER_PREFETCH 1
+#endif
+    // (tiles of several waves, n = 2^11 .. 2^14: measured -7 % at n = 2^12, -29 % at 2^13, -20 % at 2^14; with fewer
+    // values per thread nothing is gained, with 16 on one wave the registers for it are not there)
+    constexpr bool PREFETCH = (R == 16 || R == 32) && G::WB > 0 && SPINNER_LAYER_PREFETCH != 0;
     ThreadCtx<G> c;
     long long slot;
     layer_ctx(c, slot);
@@ -123,13 +141,31 @@ __global__ void __launch_bounds__(G::THREADS) layer_backward_kernel(LayerBackwar
         const long long off = (active ? vec : 0) * (long long)n;
         float g[R];
         tile_load<G, G::layout_after(0)>(g, c, p.dy + off, active);
-        spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
-        if (active) tile_mac<G, L1>(acc3, g, c, p.saved2 + off);
-        spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
-        if (active) tile_mac<G, L2>(acc2, g, c, p.saved1 + off);
-        spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
+        if constexpr (PREFETCH) {
+            // each saved tile is asked for one transform ahead of its use (the scheduling barriers keep the loads
+            // where they are written: left alone, the compiler moves each next to its use to save registers)
+            float ta[R];
+            tile_load<G, L1>(ta, c, p.saved2 + off, active);
+            __builtin_amdgcn_sched_barrier(0);
+            spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
+            tile_fma<R>(acc3, g, ta);
+            tile_load<G, L2>(ta, c, p.saved1 + off, active);
+            __builtin_amdgcn_sched_barrier(0);
+            spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
+            tile_fma<R>(acc2, g, ta);
+            tile_load<G, L3>(ta, c, p.x + off, active);
+            __builtin_amdgcn_sched_barrier(0);
+            spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
+            tile_fma<R>(acc1, g, ta);
+        } else {
+            spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
+            if (active) tile_mac<G, L1>(acc3, g, c, p.saved2 + off);
+            spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
+            if (active) tile_mac<G, L2>(acc2, g, c, p.saved1 + off);
+            spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
+            if (active) tile_mac<G, L3>(acc1, g, c, p.x + off);
+        }
         if (active) {
-            tile_mac<G, L3>(acc1, g, c, p.x + off);
             // dx = factor * D1 t3
             const float* d1 = p.d[0] + c.base_index(L3);
             float* dst = p.dx + off + c.base_index(L3);

@@ -76,7 +76,7 @@ def test_layer_forward_backward_every_size(gpu, oracle, log2n):
     _check(oracle, x, d, dy, scale, y, dx, dd)
 
 
-@pytest.mark.parametrize("n,batch", [(64, 70000), (256, 20000), (2048, 2300), (4096, 1100)])
+@pytest.mark.parametrize("n,batch", [(64, 70000), (256, 20000), (2048, 2300), (4096, 1100), (8192, 700), (16384, 600)])
 def test_layer_backward_many_vectors_per_slot(gpu, oracle, n, batch):
     # more vectors than resident tile slots: every slot accumulates several vectors, the last round is ragged
     x, d, dy = _case(n, batch, 6100 + n)
