@@ -136,8 +136,7 @@ spinner_feature_ar_kernel(TileParams p)
         const float* src = p.x + (active ? vec : 0) * p.in_stride + 4 * l;
 #pragma unroll
         for (int k = 0; k < R / 4; ++k) {
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (G::TPW == 1 || active) t = load4<true>(src + 4 * k * G::LANES);
+            const float4 t = load4<true>(src + 4 * k * G::LANES);      // a vector past the end reads the first one
             *reinterpret_cast<float4*>(w + ar_word_of<G>(4 * (k * G::LANES + l))) = t;
         }
         wave_lds_fence();

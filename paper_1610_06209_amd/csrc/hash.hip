@@ -78,8 +78,7 @@ __global__ void __launch_bounds__(G::THREADS) spinner_hash_ar_kernel(HashParams 
 #pragma unroll
         for (int k = 0; k < R / 4; ++k) {
             const int e = 4 * (k * G::LANES + l);
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (active) t = *reinterpret_cast<const float4*>(src + e);
+            const float4 t = *reinterpret_cast<const float4*>(src + e);      // a vector past the end reads the first one (nothing is stored for it)
             *reinterpret_cast<float4*>(w + (e >> r) * G::STRIDE + (e & (R - 1)) + (e >> (2 * r)) * R) = t;
         }
         wave_lds_fence();

@@ -17,14 +17,15 @@
 
 namespace spinner {
 
+// `base` must be readable also for a tile past the end of the batch (the callers pass the first vector then and
+// store nothing): loads under a condition end up in a branch each, with waits where the branches join
 template <typename G, int LAY>
-__device__ __forceinline__ void tile_load(float (&v)[G::R], const ThreadCtx<G>& c, const float* base, bool active)
+__device__ __forceinline__ void tile_load(float (&v)[G::R], const ThreadCtx<G>& c, const float* base)
 {
     const float* src = base + c.base_index(LAY);
 #pragma unroll
     for (int jh = 0; jh < G::R / 4; ++jh) {
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (active) t = *reinterpret_cast<const float4*>(src + G::reg_index(LAY, jh * 4));
+        const float4 t = *reinterpret_cast<const float4*>(src + G::reg_index(LAY, jh * 4));
         v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
     }
 }
@@ -97,7 +98,7 @@ __global__ void __launch_bounds__(G::THREADS) layer_forward_kernel(LayerForwardP
     const float sgn = tracked_sign<G, 0, float>(c);
 
     float v[G::R];
-    tile_load<G, G::layout_after(0)>(v, c, p.x + off, active);
+    tile_load<G, G::layout_after(0)>(v, c, p.x + off);
     spinner_step<G, NT, 0, G::layout_after(0), true, true, false, false>(v, c, p.d[0], nullptr, 0, lds);
     if (active) tile_store<G, G::layout_after(1)>(v, c, p.saved1 + off, sgn);
     spinner_step<G, NT, 0, G::layout_after(1), true, false, true, false>(v, c, p.d[1], nullptr, 0, lds);
@@ -140,23 +141,23 @@ layer_backward_kernel(LayerBackwardParams p)
         const bool active = vec < p.batch;
         const long long off = (active ? vec : 0) * (long long)n;
         float g[R];
-        tile_load<G, G::layout_after(0)>(g, c, p.dy + off, active);
+        tile_load<G, G::layout_after(0)>(g, c, p.dy + off);
         if constexpr (PREFETCH) {
             // each saved tile is asked for one transform ahead of its use (the scheduling barriers keep the loads
             // where they are written: left alone, the compiler moves each next to its use to save registers)
             float ta[R];
-            tile_load<G, L1>(ta, c, p.saved2 + off, active);
+            tile_load<G, L1>(ta, c, p.saved2 + off);
             __builtin_amdgcn_sched_barrier(0);
             spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
-            tile_fma<R>(acc3, g, ta);
-            tile_load<G, L2>(ta, c, p.saved1 + off, active);
+            if (active) tile_fma<R>(acc3, g, ta);
+            tile_load<G, L2>(ta, c, p.saved1 + off);
             __builtin_amdgcn_sched_barrier(0);
             spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
-            tile_fma<R>(acc2, g, ta);
-            tile_load<G, L3>(ta, c, p.x + off, active);
+            if (active) tile_fma<R>(acc2, g, ta);
+            tile_load<G, L3>(ta, c, p.x + off);
             __builtin_amdgcn_sched_barrier(0);
             spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
-            tile_fma<R>(acc1, g, ta);
+            if (active) tile_fma<R>(acc1, g, ta);
         } else {
             spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
             if (active) tile_mac<G, L1>(acc3, g, c, p.saved2 + off);

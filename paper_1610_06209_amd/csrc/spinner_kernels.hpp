@@ -961,8 +961,9 @@ spinner_tile_kernel(TileParams p)
             const float* src = p.x + vec * p.in_stride + tile_first + tile_offset<NT, C>(c.base_index(G::layout_after(0)), p.sl);
 #pragma unroll
             for (int jh = 0; jh < R / 4; ++jh) {
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (active) t = load4<STREAM_LD>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
+                // no test of `active` here: a tile past the end reads the first tile of the first vector (vec = q = 0)
+                // and stores nothing; loads under a condition end up in a branch each, with waits where they join
+                const float4 t = load4<STREAM_LD>(src + tile_offset<NT, C>(G::reg_index(G::layout_after(0), jh * 4), p.sl));
                 v[jh * 4] = (T)t.x; v[jh * 4 + 1] = (T)t.y; v[jh * 4 + 2] = (T)t.z; v[jh * 4 + 3] = (T)t.w;
             }
         }
@@ -1142,8 +1143,7 @@ spinner_hash_kernel(HashParams p)
         const float* src = p.x + (active ? vec : 0) * (long long)n + c.base_index(0);
 #pragma unroll
         for (int jh = 0; jh < R / 4; ++jh) {
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (active) t = *reinterpret_cast<const float4*>(src + G::reg_index(0, jh * 4));
+            const float4 t = *reinterpret_cast<const float4*>(src + G::reg_index(0, jh * 4));   // a vector past the end reads the first one
             x0[jh * 4] = t.x; x0[jh * 4 + 1] = t.y; x0[jh * 4 + 2] = t.z; x0[jh * 4 + 3] = t.w;
         }
     }

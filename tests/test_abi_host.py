@@ -152,7 +152,12 @@ def test_layer_entry_points_host_side(b):
     assert b.spinner_layer_saved_bytes(1 << 15, 10) == 0 and b.spinner_layer_saved_bytes(1000, 10) == 0
     # one partial row of 3 n floats per tile slot: small batches take one slot per vector (rounded up to whole workgroups)
     assert b.spinner_layer_workspace_bytes(4096, 8) == 8 * 3 * 4096 * 4
-    assert b.spinner_layer_workspace_bytes(4096, 1 << 20) == 1024 * 3 * 4096 * 4
+    # large batches: as many slots as tiles are resident on the chip (four workgroups per compute unit, or what the
+    # backward kernel of that size is compiled for)
+    assert b.spinner_layer_workspace_bytes(1024, 1 << 20) == 4096 * 3 * 1024 * 4
+    assert b.spinner_layer_workspace_bytes(2048, 1 << 20) == 1536 * 3 * 2048 * 4
+    assert b.spinner_layer_workspace_bytes(4096, 1 << 20) == 768 * 3 * 4096 * 4
+    assert b.spinner_layer_workspace_bytes(8192, 1 << 20) == 512 * 3 * 8192 * 4
     assert b.spinner_layer_workspace_bytes(16, 1 << 20) == 8192 * 3 * 16 * 4          # bounded number of partial rows
     assert b.spinner_layer_workspace_bytes(1 << 15, 8) == 0
     f = b.lib.spinner_layer_forward
