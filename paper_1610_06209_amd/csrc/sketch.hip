@@ -4,25 +4,38 @@
 namespace spinner {
 
 // dst[c][r] = src[r][c] * (row_scale ? row_scale[r] : 1), src is [rows][cols] row-major.
-// 64 x 64 tiles through LDS (row padded by one word), both sides coalesced.
+// 64 x 64 tiles through LDS (row padded by one word), both sides coalesced.  All sixteen loads of a thread are
+// issued before the first is used: rows and columns past the end are clamped to the last one (and not stored), so
+// that no load sits under a condition.
+template <bool SCALED>
 __global__ void __launch_bounds__(256) transpose_scale_kernel(const float* __restrict__ src, long long rows, long long cols,
                                                               const float* __restrict__ row_scale, float* __restrict__ dst)
 {
     __shared__ float tile[64][65];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const long long r0 = (long long)blockIdx.y * 64, c0 = (long long)blockIdx.x * 64;
+    const long long cc = c0 + tx < cols ? c0 + tx : cols - 1;
+    float v[16], w[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        const long long r = r0 + ty + 4 * k, c = c0 + tx;
-        float v = 0.f;
-        if (r < rows && c < cols) v = src[r * cols + c] * (row_scale ? row_scale[r] : 1.0f);
-        tile[ty + 4 * k][tx] = v;
+        const long long r = r0 + ty + 4 * k;
+        const long long rr = r < rows ? r : rows - 1;
+        v[k] = src[rr * cols + cc];
+        w[k] = SCALED ? row_scale[rr] : 1.0f;
     }
-    __syncthreads();
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const long long c = c0 + ty + 4 * k, r = r0 + tx;
-        if (r < rows && c < cols) dst[c * rows + r] = tile[tx][ty + 4 * k];
+    for (int k = 0; k < 16; ++k) tile[ty + 4 * k][tx] = SCALED ? v[k] * w[k] : v[k];
+    __syncthreads();
+    const long long r = r0 + tx;
+    if (r0 + 64 <= rows && c0 + 64 <= cols) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) dst[(c0 + ty + 4 * k) * rows + r] = tile[tx][ty + 4 * k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const long long c = c0 + ty + 4 * k;
+            if (r < rows && c < cols) dst[c * rows + r] = tile[tx][ty + 4 * k];
+        }
     }
 }
 
@@ -32,7 +45,10 @@ hipError_t launch_transpose_scale(const float* src, long long rows, long long co
     if (rows <= 0 || cols <= 0) return hipSuccess;
     const long long gx = (cols + 63) / 64, gy = (rows + 63) / 64;
     if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(transpose_scale_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, src, rows, cols, row_scale, dst);
+    if (row_scale)
+        hipLaunchKernelGGL(transpose_scale_kernel<true>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, src, rows, cols, row_scale, dst);
+    else
+        hipLaunchKernelGGL(transpose_scale_kernel<false>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, src, rows, cols, row_scale, dst);
     return hipGetLastError();
 }
 
@@ -62,17 +78,39 @@ __global__ void __launch_bounds__(256) sketch_gram_kernel(const float* __restric
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    for (int k0 = k_begin; k0 < m; k0 += kGramK) {
-        // 16 rows x 128 columns per operand, 256 threads: 8 values per thread and operand
+    // 16 rows x 128 columns per operand, 256 threads: 8 values per thread and operand.  A chunk is loaded into
+    // registers while the chunk before it is multiplied (addresses clamped to the last row / column, what lies
+    // outside set to zero afterwards: no load under a condition).
+    float ra[8], rb[8];
+    auto load_chunk = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int idx = q * 256 + threadIdx.x;
+            const int kk = idx >> 7, col = idx & 127;
+            const int row = k0 + kk < m ? k0 + kk : m - 1;
+            const int ca = a0 + col < d ? a0 + col : d - 1, cb = b0 + col < d ? b0 + col : d - 1;
+            ra[q] = B[(long long)row * d + ca];
+            rb[q] = B[(long long)row * d + cb];
+        }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const int idx = q * 256 + threadIdx.x;
             const int kk = idx >> 7, col = idx & 127;
             const bool row_ok = k0 + kk < m;
-            sa[kk][col] = (row_ok && a0 + col < d) ? B[(long long)(k0 + kk) * d + a0 + col] : 0.f;
-            sb[kk][col] = (row_ok && b0 + col < d) ? B[(long long)(k0 + kk) * d + b0 + col] : 0.f;
+            if (!(row_ok && a0 + col < d)) ra[q] = 0.f;
+            if (!(row_ok && b0 + col < d)) rb[q] = 0.f;
+        }
+    };
+    if (k_begin < m) load_chunk(k_begin);
+    for (int k0 = k_begin; k0 < m; k0 += kGramK) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int idx = q * 256 + threadIdx.x;
+            sa[idx >> 7][idx & 127] = ra[q];
+            sb[idx >> 7][idx & 127] = rb[q];
         }
         __syncthreads();
+        if (k0 + kGramK < m) load_chunk(k0 + kGramK);
 #pragma unroll
         for (int kk = 0; kk < kGramK; kk += 2) {
             float fa[2], fb[2];
@@ -107,7 +145,12 @@ __global__ void __launch_bounds__(256) gram_reduce_kernel(const float* __restric
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= len) return;
     float s = 0.f;
-    for (int k = 0; k < count; ++k) s += slabs[k * len + i];
+    int k = 0;
+    for (; k + 3 < count; k += 4) {         // four loads in flight; the order of the additions stays fixed
+        const float a0 = slabs[k * len + i], a1 = slabs[(k + 1) * len + i], a2 = slabs[(k + 2) * len + i], a3 = slabs[(k + 3) * len + i];
+        s += a0; s += a1; s += a2; s += a3;
+    }
+    for (; k < count; ++k) s += slabs[k * len + i];
     G[i] = s;
 }
 
@@ -115,7 +158,10 @@ __global__ void __launch_bounds__(256) gram_reduce_kernel(const float* __restric
 int sketch_gram_slabs(int m, int d)
 {
     const long long tiles = (long long)((d + kGramBlock - 1) / kGramBlock) * ((d + kGramBlock - 1) / kGramBlock);
-    long long ks = (512 + tiles - 1) / tiles;
+#ifndef SPINNER_GRAM_WGS       // workgroups aimed at when the sum over k is split (tuning experiments)
+#define SPINNER_GRAM_WGS 256
+#endif
+    long long ks = (SPINNER_GRAM_WGS + tiles - 1) / tiles;
     if (ks > (m + 63) / 64) ks = (m + 63) / 64;
     if (ks > 64) ks = 64;
     return ks < 1 ? 1 : (int)ks;
