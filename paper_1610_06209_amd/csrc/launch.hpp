@@ -74,7 +74,7 @@ template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool 
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
     // wide exchanges pay with packed sign words only: fp32 diagonals read in layout 1 come in 256-byte runs,
-    // which measured 2-5 % slower than the narrow exchange (also for the row passes above 2^16)
+    // which measured 2-5 % slower than the narrow exchange (also for the row passes of the four-pass schedule)
 #ifndef SPINNER_WIDE_PRUNED      // bit N set: the sign-word kernels of 2^N elements with a pruned last round use wide exchanges too
 #define SPINNER_WIDE_PRUNED 0x7000   // (first n/16 rows: 2^12 0.494 -> 0.451 ms, 2^13 0.528 -> 0.490, 2^14 0.545 -> 0.524)
 #endif

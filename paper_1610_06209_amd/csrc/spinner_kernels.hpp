@@ -657,9 +657,9 @@ __device__ __forceinline__ void diag_multiply(T (&v)[G::R], const ThreadCtx<G>& 
 }
 
 // ------------------------------------------------------------------ +-1 diagonals as packed sign words
-// Packed format of one diagonal (n <= 2^14): 64-bit words; element e has its
+// Packed format of one diagonal (any n; n / 64 words, at least 4): 64-bit words; element e has its
 // sign bit at bit (e >> 2) & 63 of word ((e >> 8) << 2) | (e & 3).  Because the
-// lane id holds index bits 2..7 (except in layout 1 of a wide geometry), one word is exactly the lane mask "which
+// lane id holds index bits 2..7 (except in layout 1 of a wide geometry and in column tiles), one word is exactly the lane mask "which
 // lanes hold a negated element" of one register, so it is fetched with a scalar
 // load and applied with one v_cndmask (x or -x by lane mask): no vector memory
 // traffic and no registers spent on staging the diagonal.
