@@ -277,6 +277,15 @@ def test_multipass_largest_sizes_by_properties(gpu, log2n):
     z = gpu.b.spinner_apply(yr, one, d[2], d[1])
     err = ((z * d[0]).double() - xr.double()).norm(dim=1) / nx
     assert float(err.max()) < 1e-5, float(err.max())
+    # the same through packed sign words (row passes by the words of their tile, column pass by its lane masks, each
+    # with the tile geometry of this size): equal to the fp32-diagonal result up to rounding, and inverted the same way
+    signs = gpu.b.spinner_pack_signs(d[None].contiguous())
+    ys = gpu.b.spinner_apply_signs(xr, signs)
+    assert float(((ys.double() - yr.double()).norm(dim=1) / ny).max()) < 1e-6
+    back = gpu.b.spinner_pack_signs(t.stack([one, d[2], d[1]])[None].contiguous())
+    zs = gpu.b.spinner_apply_signs(ys, back)
+    err = ((zs * d[0]).double() - xr.double()).norm(dim=1) / nx
+    assert float(err.max()) < 1e-5, float(err.max())
 
 
 def test_multipass_truncated_and_features(gpu, oracle):
