@@ -324,6 +324,47 @@ def cpu_fast_single_thread(W, w):
             "sample": "%d vectors of %s (n=%d), %.2f s wall" % (sample, w.name, w.n, dt)}
 
 
+def measure_next_rows(torch, b, W, dev, args):
+    """The rows beyond the five configurations: sign codes and their Gram estimate, adaptive layer, Newton sketch,
+    G_struct members, and the layer at the hidden sizes of the paper's MLP timing table."""
+    nxt = []
+    for name, w in W.NEXT.items():
+        r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
+        nxt.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
+                    "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
+                    "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
+        log("[bench] %s: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)  butterfly adds at %.1f%% of VALU peak" % (
+            name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
+            100 * r["valu_frac_adds_only"]))
+    g = measure_gram(torch, b, dev, 16384, 4096, max(3, args.steps // 2), max(2, args.warmup // 2))
+    log("[bench] %s: %.4f ms  %.3e pairs/s  %.2f fp4 PFLOP/s (%.1f%% of the dense fp4 MFMA peak)" % (
+        g["workload"], g["ms"], g["pairs_per_s"], g["fp4_TFLOPs"] / 1e3, 100 * g["fp4_mfma_frac"]))
+    nxt.append(g)
+    lay = measure_layer(torch, b, dev, 4096, 65536, max(3, args.steps // 2), max(2, args.warmup // 2))
+    log("[bench] %s: forward %.4f ms (%.0f GB/s), backward %.4f ms (%.0f GB/s)" % (
+        lay["workload"], lay["forward_ms"], lay["forward_GBs"], lay["backward_ms"], lay["backward_GBs"]))
+    nxt.append(lay)
+    skt = measure_sketch(torch, b, W, dev, 1 << 16, 512, 2048, 10, 3)
+    log("[bench] %s: sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
+        skt["workload"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
+    nxt.append(skt)
+    for kind in ("circulant", "toeplitz"):
+        st = measure_struct(torch, b, dev, kind, 4096, 16384, 5, 2)
+        log("[bench] %s: %.4f ms  %.3e vec/s  (%.0f GB/s counting 8 B per element)" % (
+            st["workload"], st["ms"], st["vectors_per_s"], st["GBs_of_8B_per_element"]))
+        nxt.append(st)
+    # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
+    tbl = []
+    for k in range(4, 13):
+        r = measure_layer(torch, b, dev, 1 << k, 1024, 20, 5, graph=True)
+        tbl.append({"h": 1 << k, "step_us_wall": r["step_us_wall"], "step_us_graph": r["step_us_graph"],
+                    "kernels_us": round((r["forward_ms"] + r["backward_ms"]) * 1e3, 2)})
+    log("[bench] adaptive layer, batch 1024, h=2^4..2^12, forward+backward us per step, eager wall / captured graph: " +
+        " ".join("%.1f/%.1f" % (t["step_us_wall"], t["step_us_graph"]) for t in tbl))
+    nxt.append({"workload": "adaptive_layer_table2_sizes_b1024", "rows": tbl})
+    return nxt
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -336,6 +377,8 @@ def main():
                          "(spinner_*_signs) or fp32 arrays (spinner_apply / spinner_hash)")
     ap.add_argument("--quick", action="store_true", help="headline only: no sweep, no configs, no CPU baseline")
     ap.add_argument("--only", action="store_true", help="headline only, and a single JSON line without extras")
+    ap.add_argument("--next-only", action="store_true",
+                    help="only the rows beyond the five configurations (for profiling them); prints their JSON and exits")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over the batch: vectors are independent, "
@@ -362,6 +405,9 @@ def main():
             return W.sweep_workload(int(name[len("sweep_plain_n2p"):]))
         raise SystemExit("unknown workload %r" % name)
 
+    if args.next_only:
+        print(json.dumps({"next_rows": measure_next_rows(torch, b, W, dev, args)}), flush=True)
+        return
     head = resolve(args.workload)
     copy_gbs = round(copy_ceiling(torch, b, dev, 10, 3), 1)
     log("[bench] plain copy kernel (1 GiB read + 1 GiB write): %.0f GB/s" % copy_gbs)
@@ -409,41 +455,7 @@ def main():
                 name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
                 100 * r["valu_frac_adds_only"]))
         extras["configs"] = cfgs
-        nxt = []
-        for name, w in W.NEXT.items():
-            r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
-            nxt.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
-                        "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
-                        "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
-            log("[bench] %s: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)  butterfly adds at %.1f%% of VALU peak" % (
-                name, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
-                100 * r["valu_frac_adds_only"]))
-        g = measure_gram(torch, b, dev, 16384, 4096, max(3, args.steps // 2), max(2, args.warmup // 2))
-        log("[bench] %s: %.4f ms  %.3e pairs/s  %.2f fp4 PFLOP/s (%.1f%% of the dense fp4 MFMA peak)" % (
-            g["workload"], g["ms"], g["pairs_per_s"], g["fp4_TFLOPs"] / 1e3, 100 * g["fp4_mfma_frac"]))
-        nxt.append(g)
-        lay = measure_layer(torch, b, dev, 4096, 65536, max(3, args.steps // 2), max(2, args.warmup // 2))
-        log("[bench] %s: forward %.4f ms (%.0f GB/s), backward %.4f ms (%.0f GB/s)" % (
-            lay["workload"], lay["forward_ms"], lay["forward_GBs"], lay["backward_ms"], lay["backward_GBs"]))
-        nxt.append(lay)
-        skt = measure_sketch(torch, b, W, dev, 1 << 16, 512, 2048, 10, 3)
-        log("[bench] %s: sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
-            skt["workload"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
-        nxt.append(skt)
-        for kind in ("circulant", "toeplitz"):
-            st = measure_struct(torch, b, dev, kind, 4096, 16384, 5, 2)
-            log("[bench] %s: %.4f ms  %.3e vec/s  (%.0f GB/s counting 8 B per element)" % (
-                st["workload"], st["ms"], st["vectors_per_s"], st["GBs_of_8B_per_element"]))
-            nxt.append(st)
-        # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
-        tbl = []
-        for k in range(4, 13):
-            r = measure_layer(torch, b, dev, 1 << k, 1024, 20, 5, graph=True)
-            tbl.append({"h": 1 << k, "step_us_wall": r["step_us_wall"], "step_us_graph": r["step_us_graph"],
-                        "kernels_us": round((r["forward_ms"] + r["backward_ms"]) * 1e3, 2)})
-        log("[bench] adaptive layer, batch 1024, h=2^4..2^12, forward+backward us per step, eager wall / captured graph: " +
-            " ".join("%.1f/%.1f" % (t["step_us_wall"], t["step_us_graph"]) for t in tbl))
-        nxt.append({"workload": "adaptive_layer_table2_sizes_b1024", "rows": tbl})
+        nxt = measure_next_rows(torch, b, W, dev, args)
         extras["next_rows"] = nxt
 
     traffic = MEASURED_TRAFFIC_BYTES.get(head.name)
