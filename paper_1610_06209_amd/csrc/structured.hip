@@ -22,72 +22,147 @@ __device__ __forceinline__ float2 cmul_conj(float2 a, float2 b) { return make_fl
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
 
-// forward transform, decimation in frequency: natural order in, bit-reversed order out.  Two radix-2 stages
-// (index bits s and s-1) are done per trip through LDS on four points held in registers; a last single
-// stage is left when the number of stages is odd.  The stage on bit s pairs points 2^s apart and multiplies
-// the difference by exp(-2 pi i j / 2^(s+1)), j the offset inside the lower half.
-__device__ __forceinline__ void fft_forward(float2* X, const float2* __restrict__ tw, int log2p)
+// Point i of a transform sits at X[pad(i)]: one unused slot after every 16 points keeps the strided accesses of the
+// passes below on different LDS banks.
+__device__ __forceinline__ int pad(int i) { return i + (i >> 4); }
+inline size_t fft_lds_bytes(int log2p) { return (((size_t)1 << log2p) + ((size_t)1 << log2p) / 16) * sizeof(float2); }
+
+// A radix-2 stage on index bit s pairs points 2^s apart; with o the offset of the lower point inside its group of
+// 2^s, the twiddle is exp(-2 pi i o / 2^(s+1)): the forward transform (decimation in frequency) multiplies the
+// difference by it after the butterfly, the inverse (decimation in time) multiplies the upper point by its conjugate
+// before the butterfly.  Four stages (bits top .. top-3) run on sixteen points k * 2^(top-3) + j, k = 0 .. 15, held
+// in registers, one trip through LDS for the four; their twiddles are a base factor per stage (a function of j,
+// read from the table) times a constant power of exp(-2 pi i / 16).
+struct Twiddles16 { float2 a[8], b[4], c[2], d; };     // stages on bits top, top-1, top-2, top-3
+
+__device__ __forceinline__ void twiddles16(Twiddles16& t, const float2* __restrict__ tw, int j, int top, int log2p)
 {
-    int s = log2p - 1;
-    for (; s >= 1; s -= 2) {
-        const int q = 1 << (s - 1);                         // quarter of the 2^(s+1)-point group
-        for (int b = threadIdx.x; b < (1 << (log2p - 2)); b += blockDim.x) {
-            const int j = b & (q - 1);
-            const int i0 = ((b >> (s - 1)) << (s + 1)) | j;
-            const float2 a0 = X[i0], a1 = X[i0 + q], a2 = X[i0 + 2 * q], a3 = X[i0 + 3 * q];
-            const int sh = log2p - 1 - s;
-            const float2 b0 = cadd(a0, a2), b2 = cmul(csub(a0, a2), tw[j << sh]);
-            const float2 b1 = cadd(a1, a3), b3 = cmul(csub(a1, a3), tw[(j + q) << sh]);
-            const float2 w = tw[j << (sh + 1)];
-            X[i0] = cadd(b0, b1);
-            X[i0 + q] = cmul(csub(b0, b1), w);
-            X[i0 + 2 * q] = cadd(b2, b3);
-            X[i0 + 3 * q] = cmul(csub(b2, b3), w);
-        }
-        __syncthreads();
-    }
-    if (s == 0) {                                           // bit 0: twiddle 1
-        for (int b = threadIdx.x; b < (1 << (log2p - 1)); b += blockDim.x) {
-            const float2 a = X[2 * b], c = X[2 * b + 1];
-            X[2 * b] = cadd(a, c);
-            X[2 * b + 1] = csub(a, c);
-        }
-        __syncthreads();
+    const int sh = log2p - 1 - top;
+    const float2 b1 = tw[j << sh], b2 = tw[j << (sh + 1)], b3 = tw[j << (sh + 2)], b4 = tw[j << (sh + 3)];
+    constexpr float c1 = 0.92387953251128674f, s1 = 0.38268343236508977f, h = 0.70710678118654752f;
+    t.a[0] = b1;
+    t.a[1] = cmul(b1, make_float2(c1, -s1));
+    t.a[2] = cmul(b1, make_float2(h, -h));
+    t.a[3] = cmul(b1, make_float2(s1, -c1));
+    t.a[4] = make_float2(b1.y, -b1.x);                      // times -i
+    t.a[5] = cmul(b1, make_float2(-s1, -c1));
+    t.a[6] = cmul(b1, make_float2(-h, -h));
+    t.a[7] = cmul(b1, make_float2(-c1, -s1));
+    t.b[0] = b2;
+    t.b[1] = cmul(b2, make_float2(h, -h));
+    t.b[2] = make_float2(b2.y, -b2.x);
+    t.b[3] = cmul(b2, make_float2(-h, -h));
+    t.c[0] = b3;
+    t.c[1] = make_float2(b3.y, -b3.x);
+    t.d = b4;
+}
+
+template <bool INVERSE>
+__device__ __forceinline__ void butterfly(float2& lo, float2& hi, float2 w)
+{
+    if constexpr (INVERSE) {
+        const float2 t = cmul_conj(hi, w);
+        hi = csub(lo, t);
+        lo = cadd(lo, t);
+    } else {
+        const float2 d = csub(lo, hi);
+        lo = cadd(lo, hi);
+        hi = cmul(d, w);
     }
 }
 
-// inverse transform (unnormalised), decimation in time: bit-reversed order in, natural order out; the
-// mirror image of fft_forward with conjugate twiddles (bit 0 first when the number of stages is odd).
+// the four stages on bits top .. top-3 (forward: in that order; inverse: from bit top-3 up)
+template <bool INVERSE>
+__device__ __forceinline__ void fft_trip16(float2* X, const float2* __restrict__ tw, int top, int log2p)
+{
+    const int qb = top - 3, q = 1 << qb;
+    for (int b = threadIdx.x; b < (1 << (log2p - 4)); b += blockDim.x) {
+        const int j = b & (q - 1);
+        const int i0 = ((b >> qb) << (top + 1)) | j;
+        float2 v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = X[pad(i0 + (k << qb))];
+        Twiddles16 t;
+        twiddles16(t, tw, j, top, log2p);
+        if constexpr (!INVERSE) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) butterfly<false>(v[k], v[k + 8], t.a[k]);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) if (!(k & 4)) butterfly<false>(v[k], v[k + 4], t.b[k & 3]);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) if (!(k & 2)) butterfly<false>(v[k], v[k + 2], t.c[k & 1]);
+#pragma unroll
+            for (int k = 0; k < 16; k += 2) butterfly<false>(v[k], v[k + 1], t.d);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; k += 2) butterfly<true>(v[k], v[k + 1], t.d);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) if (!(k & 2)) butterfly<true>(v[k], v[k + 2], t.c[k & 1]);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) if (!(k & 4)) butterfly<true>(v[k], v[k + 4], t.b[k & 3]);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) butterfly<true>(v[k], v[k + 8], t.a[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) X[pad(i0 + (k << qb))] = v[k];
+    }
+    __syncthreads();
+}
+
+// two stages (bits s and s-1) on four points, and a single stage on bit 0: what is left below the radix-16 trips
+template <bool INVERSE>
+__device__ __forceinline__ void fft_trip4(float2* X, const float2* __restrict__ tw, int s, int log2p)
+{
+    const int q = 1 << (s - 1);
+    const int sh = log2p - 1 - s;
+    for (int b = threadIdx.x; b < (1 << (log2p - 2)); b += blockDim.x) {
+        const int j = b & (q - 1);
+        const int i0 = ((b >> (s - 1)) << (s + 1)) | j;
+        float2 a0 = X[pad(i0)], a1 = X[pad(i0 + q)], a2 = X[pad(i0 + 2 * q)], a3 = X[pad(i0 + 3 * q)];
+        const float2 w0 = tw[j << sh], w1 = tw[(j + q) << sh], wl = tw[j << (sh + 1)];
+        if constexpr (!INVERSE) {
+            butterfly<false>(a0, a2, w0);
+            butterfly<false>(a1, a3, w1);
+            butterfly<false>(a0, a1, wl);
+            butterfly<false>(a2, a3, wl);
+        } else {
+            butterfly<true>(a0, a1, wl);
+            butterfly<true>(a2, a3, wl);
+            butterfly<true>(a0, a2, w0);
+            butterfly<true>(a1, a3, w1);
+        }
+        X[pad(i0)] = a0; X[pad(i0 + q)] = a1; X[pad(i0 + 2 * q)] = a2; X[pad(i0 + 3 * q)] = a3;
+    }
+    __syncthreads();
+}
+__device__ __forceinline__ void fft_bit0(float2* X, int log2p)      // twiddle 1 in both directions
+{
+    for (int b = threadIdx.x; b < (1 << (log2p - 1)); b += blockDim.x) {
+        const float2 a = X[pad(2 * b)], c = X[pad(2 * b + 1)];
+        X[pad(2 * b)] = cadd(a, c);
+        X[pad(2 * b + 1)] = csub(a, c);
+    }
+    __syncthreads();
+}
+
+// forward transform, decimation in frequency: natural order in, bit-reversed order out, in place
+__device__ __forceinline__ void fft_forward(float2* X, const float2* __restrict__ tw, int log2p)
+{
+    int s = log2p - 1;
+    for (; s >= 3; s -= 4) fft_trip16<false>(X, tw, s, log2p);
+    if (s >= 1) { fft_trip4<false>(X, tw, s, log2p); s -= 2; }
+    if (s == 0) fft_bit0(X, log2p);
+}
+
+// inverse transform (unnormalised), decimation in time: bit-reversed order in, natural order out; the mirror
+// image of fft_forward with conjugate twiddles
 __device__ __forceinline__ void fft_inverse(float2* X, const float2* __restrict__ tw, int log2p)
 {
+    const int low = log2p & 3;          // stages below the radix-16 trips
     int s = 0;
-    if (log2p & 1) {
-        for (int b = threadIdx.x; b < (1 << (log2p - 1)); b += blockDim.x) {
-            const float2 a = X[2 * b], c = X[2 * b + 1];
-            X[2 * b] = cadd(a, c);
-            X[2 * b + 1] = csub(a, c);
-        }
-        __syncthreads();
-        s = 1;
-    }
-    for (; s + 1 < log2p; s += 2) {                         // bits s and s+1
-        const int q = 1 << s;
-        for (int b = threadIdx.x; b < (1 << (log2p - 2)); b += blockDim.x) {
-            const int j = b & (q - 1);
-            const int i0 = ((b >> s) << (s + 2)) | j;
-            const float2 a0 = X[i0], a1 = X[i0 + q], a2 = X[i0 + 2 * q], a3 = X[i0 + 3 * q];
-            const int sh = log2p - 1 - s;
-            const float2 w = tw[j << sh];
-            const float2 t1 = cmul_conj(a1, w), t3 = cmul_conj(a3, w);
-            const float2 b0 = cadd(a0, t1), b1 = csub(a0, t1), b2 = cadd(a2, t3), b3 = csub(a2, t3);
-            const float2 u2 = cmul_conj(b2, tw[j << (sh - 1)]), u3 = cmul_conj(b3, tw[(j + q) << (sh - 1)]);
-            X[i0] = cadd(b0, u2);
-            X[i0 + 2 * q] = csub(b0, u2);
-            X[i0 + q] = cadd(b1, u3);
-            X[i0 + 3 * q] = csub(b1, u3);
-        }
-        __syncthreads();
-    }
+    if (low & 1) { fft_bit0(X, log2p); s = 1; }
+    if (low & 2) { fft_trip4<true>(X, tw, s + 1, log2p); s += 2; }
+    for (; s + 3 < log2p; s += 4) fft_trip16<true>(X, tw, s + 3, log2p);
 }
 
 __global__ void __launch_bounds__(512) struct_conv_kernel(StructParams p)
@@ -104,15 +179,15 @@ __global__ void __launch_bounds__(512) struct_conv_kernel(StructParams p)
             re = p.t[v0 * p.n + si] * dd;
             if (two) im = p.t[v1 * p.n + si] * dd;
         }
-        X[i] = make_float2(re, im);
+        X[pad(i)] = make_float2(re, im);
     }
     __syncthreads();
     fft_forward(X, p.tw, p.log2p);
-    for (int i = threadIdx.x; i < P; i += blockDim.x) X[i] = cmul(X[i], p.spec[i]);
+    for (int i = threadIdx.x; i < P; i += blockDim.x) X[pad(i)] = cmul(X[pad(i)], p.spec[i]);
     __syncthreads();
     fft_inverse(X, p.tw, p.log2p);
     for (int i = threadIdx.x; i < p.m; i += blockDim.x) {
-        const float2 r = X[i];
+        const float2 r = X[pad(i)];
         p.out[v0 * p.m + i] = r.x * p.factor;
         if (two) p.out[v1 * p.m + i] = r.y * p.factor;
     }
@@ -152,11 +227,11 @@ __global__ void __launch_bounds__(512) struct_spectrum_kernel(const float* __res
             else if (kind == 2) v = params[n - 1 + q];
             else v = params[2 * n - 2 - (n - 1 + q)];
         }
-        X[k] = make_float2(v, 0.f);
+        X[pad(k)] = make_float2(v, 0.f);
     }
     __syncthreads();
     fft_forward(X, tw, log2p);
-    for (int k = threadIdx.x; k < P; k += blockDim.x) spec[k] = X[k];
+    for (int k = threadIdx.x; k < P; k += blockDim.x) spec[k] = X[pad(k)];
 }
 
 static hipError_t allow_lds(const void* kernel, size_t bytes)
@@ -170,7 +245,7 @@ hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p
     hipLaunchKernelGGL(struct_twiddle_kernel, dim3((P / 2 + 255) / 256), dim3(256), 0, s, tw, P / 2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds = (size_t)P * sizeof(float2);
+    const size_t lds = fft_lds_bytes(log2p);
     if ((e = allow_lds(reinterpret_cast<const void*>(struct_spectrum_kernel), lds)) != hipSuccess) return e;
     hipLaunchKernelGGL(struct_spectrum_kernel, dim3(1), dim3(512), lds, s, params, kind, n, log2p, tw, spec);
     return hipGetLastError();
@@ -182,11 +257,13 @@ hipError_t launch_struct_conv(const float* t, const float* d2, const float2* spe
     if (batch <= 0) return hipSuccess;
     const long long blocks = (batch + 1) / 2;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const size_t lds = ((size_t)1 << log2p) * sizeof(float2);
+    const size_t lds = fft_lds_bytes(log2p);
     hipError_t e = allow_lds(reinterpret_cast<const void*>(struct_conv_kernel), lds);
     if (e != hipSuccess) return e;
     StructParams p{t, d2, spec, tw, out, batch, n, log2p, m, reverse, factor};
-    hipLaunchKernelGGL(struct_conv_kernel, dim3((unsigned)blocks), dim3(512), lds, s, p);
+    // one thread per sixteen points of the transform
+    const int threads = (1 << log2p) / 16 < 64 ? 64 : ((1 << log2p) / 16 > 512 ? 512 : (1 << log2p) / 16);
+    hipLaunchKernelGGL(struct_conv_kernel, dim3((unsigned)blocks), dim3(threads), lds, s, p);
     return hipGetLastError();
 }
 }  // namespace spinner
