@@ -71,9 +71,11 @@ __device__ __forceinline__ void butterfly(float2& lo, float2& hi, float2 w)
     }
 }
 
-// the four stages on bits top .. top-3 (forward: in that order; inverse: from bit top-3 up)
-template <bool INVERSE>
-__device__ __forceinline__ void fft_trip16(float2* X, const float2* __restrict__ tw, int top, int log2p)
+// the four stages on bits top .. top-3 (forward: in that order; inverse: from bit top-3 up).  load(i) brings point i,
+// store(i, v) takes it: LDS by default; the first forward trip reads the vectors and the last inverse trip writes the
+// result straight from / to global memory, and a trip next to the spectrum product multiplies on its way
+template <bool INVERSE, typename Load, typename Store>
+__device__ __forceinline__ void fft_trip16(const float2* __restrict__ tw, int top, int log2p, Load load, Store store)
 {
     const int qb = top - 3, q = 1 << qb;
     for (int b = threadIdx.x; b < (1 << (log2p - 4)); b += blockDim.x) {
@@ -81,7 +83,7 @@ __device__ __forceinline__ void fft_trip16(float2* X, const float2* __restrict__
         const int i0 = ((b >> qb) << (top + 1)) | j;
         float2 v[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = X[pad(i0 + (k << qb))];
+        for (int k = 0; k < 16; ++k) v[k] = load(i0 + (k << qb));
         Twiddles16 t;
         twiddles16(t, tw, j, top, log2p);
         if constexpr (!INVERSE) {
@@ -104,7 +106,43 @@ __device__ __forceinline__ void fft_trip16(float2* X, const float2* __restrict__
             for (int k = 0; k < 8; ++k) butterfly<true>(v[k], v[k + 8], t.a[k]);
         }
 #pragma unroll
-        for (int k = 0; k < 16; ++k) X[pad(i0 + (k << qb))] = v[k];
+        for (int k = 0; k < 16; ++k) store(i0 + (k << qb), v[k]);
+    }
+    __syncthreads();
+}
+template <bool INVERSE>
+__device__ __forceinline__ void fft_trip16(float2* X, const float2* __restrict__ tw, int top, int log2p)
+{
+    fft_trip16<INVERSE>(tw, top, log2p, [&](int i) { return X[pad(i)]; }, [&](int i, float2 v) { X[pad(i)] = v; });
+}
+
+// The stages on the LOW lowest bits (LOW = log2p mod 4, what the radix-16 trips leave) act on 2^LOW neighbouring
+// points with constant twiddles (powers of exp(-2 pi i / 8)): forward stages, product with the spectrum and inverse
+// stages are one pass over registers.
+template <int LOW>
+__device__ __forceinline__ void fft_middle(float2* X, const float2* __restrict__ spec, int log2p)
+{
+    constexpr int M = 1 << LOW;
+    constexpr float h = 0.70710678118654752f;
+    const float2 w8[4] = {make_float2(1.f, 0.f), make_float2(h, -h), make_float2(0.f, -1.f), make_float2(-h, -h)};
+    for (int b = threadIdx.x; b < (1 << (log2p - LOW)); b += blockDim.x) {
+        float2 v[M];
+#pragma unroll
+        for (int k = 0; k < M; ++k) v[k] = X[pad(b * M + k)];
+#pragma unroll
+        for (int st = LOW - 1; st >= 0; --st)
+#pragma unroll
+            for (int k = 0; k < M; ++k)
+                if (!(k & (1 << st))) butterfly<false>(v[k], v[k + (1 << st)], w8[(k & ((1 << st) - 1)) * (4 >> st)]);
+#pragma unroll
+        for (int k = 0; k < M; ++k) v[k] = cmul(v[k], spec[b * M + k]);
+#pragma unroll
+        for (int st = 0; st < LOW; ++st)
+#pragma unroll
+            for (int k = 0; k < M; ++k)
+                if (!(k & (1 << st))) butterfly<true>(v[k], v[k + (1 << st)], w8[(k & ((1 << st) - 1)) * (4 >> st)]);
+#pragma unroll
+        for (int k = 0; k < M; ++k) X[pad(b * M + k)] = v[k];
     }
     __syncthreads();
 }
@@ -145,7 +183,8 @@ __device__ __forceinline__ void fft_bit0(float2* X, int log2p)      // twiddle 1
     __syncthreads();
 }
 
-// forward transform, decimation in frequency: natural order in, bit-reversed order out, in place
+// forward transform, decimation in frequency: natural order in, bit-reversed order out, in place (used for the
+// spectrum of the generator; the convolution kernel runs the same stages, fused with its loads and stores)
 __device__ __forceinline__ void fft_forward(float2* X, const float2* __restrict__ tw, int log2p)
 {
     int s = log2p - 1;
@@ -154,43 +193,47 @@ __device__ __forceinline__ void fft_forward(float2* X, const float2* __restrict_
     if (s == 0) fft_bit0(X, log2p);
 }
 
-// inverse transform (unnormalised), decimation in time: bit-reversed order in, natural order out; the mirror
-// image of fft_forward with conjugate twiddles
-__device__ __forceinline__ void fft_inverse(float2* X, const float2* __restrict__ tw, int log2p)
-{
-    const int low = log2p & 3;          // stages below the radix-16 trips
-    int s = 0;
-    if (low & 1) { fft_bit0(X, log2p); s = 1; }
-    if (low & 2) { fft_trip4<true>(X, tw, s + 1, log2p); s += 2; }
-    for (; s + 3 < log2p; s += 4) fft_trip16<true>(X, tw, s + 3, log2p);
-}
-
+// forward transform of two vectors (real and imaginary part), product with the spectrum, inverse transform: the
+// first forward trip reads the vectors from global memory, the last inverse trip writes the result there
 __global__ void __launch_bounds__(512) struct_conv_kernel(StructParams p)
 {
     extern __shared__ float2 X[];
-    const int P = 1 << p.log2p;
+    const int L = p.log2p;
     const long long v0 = 2LL * blockIdx.x, v1 = v0 + 1;
     const bool two = v1 < p.batch;
-    for (int i = threadIdx.x; i < P; i += blockDim.x) {
-        float re = 0.f, im = 0.f;
-        if (i < p.n) {
-            const int si = p.reverse ? p.n - 1 - i : i;
-            const float dd = p.d2[si];
-            re = p.t[v0 * p.n + si] * dd;
-            if (two) im = p.t[v1 * p.n + si] * dd;
+    const float* __restrict__ t0 = p.t + v0 * p.n;
+    const float* __restrict__ t1 = p.t + (two ? v1 : v0) * p.n;      // a lone last vector is read twice, its copy dropped
+    auto from_global = [&](int i) {
+        // zero padding up to P; indices clamped so that no load sits under a condition
+        const int ic = i < p.n ? i : p.n - 1;
+        const int si = p.reverse ? p.n - 1 - ic : ic;
+        const float dd = p.d2[si];
+        float re = t0[si] * dd, im = t1[si] * dd;
+        if (i >= p.n) { re = 0.f; im = 0.f; }
+        return make_float2(re, im);
+    };
+    auto to_lds = [&](int i, float2 v) { X[pad(i)] = v; };
+    auto from_lds = [&](int i) { return X[pad(i)]; };
+    auto to_global = [&](int i, float2 r) {
+        if (i < p.m) {
+            p.out[v0 * p.m + i] = r.x * p.factor;
+            if (two) p.out[v1 * p.m + i] = r.y * p.factor;
         }
-        X[pad(i)] = make_float2(re, im);
+    };
+    const int low = L & 3;
+    // forward: bits L-1 .. low in radix-16 trips (the last one multiplies by the spectrum when no bits are left)
+    int s = L - 1;
+    fft_trip16<false>(p.tw, s, L, from_global, to_lds);
+    for (s -= 4; s >= 3; s -= 4) {
+        if (low == 0 && s == 3) fft_trip16<false>(p.tw, s, L, from_lds, [&](int i, float2 v) { X[pad(i)] = cmul(v, p.spec[i]); });
+        else fft_trip16<false>(X, p.tw, s, L);
     }
-    __syncthreads();
-    fft_forward(X, p.tw, p.log2p);
-    for (int i = threadIdx.x; i < P; i += blockDim.x) X[pad(i)] = cmul(X[pad(i)], p.spec[i]);
-    __syncthreads();
-    fft_inverse(X, p.tw, p.log2p);
-    for (int i = threadIdx.x; i < p.m; i += blockDim.x) {
-        const float2 r = X[pad(i)];
-        p.out[v0 * p.m + i] = r.x * p.factor;
-        if (two) p.out[v1 * p.m + i] = r.y * p.factor;
-    }
+    if (low == 1) fft_middle<1>(X, p.spec, L);
+    else if (low == 2) fft_middle<2>(X, p.spec, L);
+    else if (low == 3) fft_middle<3>(X, p.spec, L);
+    // inverse: bits low .. L-1
+    for (s = low; s + 7 < L; s += 4) fft_trip16<true>(X, p.tw, s + 3, L);
+    fft_trip16<true>(p.tw, s + 3, L, from_lds, to_global);
 }
 
 // tw[k] = exp(-2 pi i k / P), formed in fp64

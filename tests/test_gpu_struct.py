@@ -56,7 +56,7 @@ def _run(g, kind, x, d, params, m, scale):
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("log2n", [5, 6, 8, 10, 12, 13])
+@pytest.mark.parametrize("log2n", [5, 6, 7, 8, 9, 10, 11, 12, 13])
 def test_struct_members_match_oracle(gpu, oracle, kind, log2n):
     n = 1 << log2n
     batch = 7 if log2n >= 12 else 33                     # odd: the last pair of vectors is half empty
