@@ -243,7 +243,7 @@ def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup):
 
 
 def measure_struct(torch, b, dev, kind, n, batch, steps, warmup):
-    """G_struct D2 H D1 member: one tile-kernel pass (H D1 x) plus the LDS-resident FFT convolution."""
+    """G_struct D2 H D1 member: Hadamard stages and FFT convolution of two vectors in LDS, one kernel."""
     g = torch.Generator(device=dev)
     g.manual_seed(1610 + n)
     x = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
@@ -251,15 +251,14 @@ def measure_struct(torch, b, dev, kind, n, batch, steps, warmup):
     params = torch.randn(int(b.lib.spinner_struct_params(b.STRUCT_KINDS[kind], n)), generator=g, device=dev, dtype=torch.float32)
     spec = b.spinner_struct_prepare(kind, params, n)
     out = torch.empty((batch, n), dtype=torch.float32, device=dev)
-    ws = torch.empty(batch * n * 4, dtype=torch.uint8, device=dev)
-    fn = lambda: b.spinner_struct_apply(x, kind, spec, d[0], d[1], n, 1.0, out=out, workspace=ws)
+    fn = lambda: b.spinner_struct_apply(x, kind, spec, d[0], d[1], n, 1.0, out=out)
     for _ in range(5):
         fn()
     torch.cuda.synchronize()
     _, ms = time_calls(torch, fn, steps, warmup)
     res = {"workload": "struct_%s_n%d_b%d" % (kind, n, batch), "ms": round(ms, 4), "vectors_per_s": batch / (ms * 1e-3),
            "GBs_of_8B_per_element": round(8.0 * batch * n / (ms * 1e-3) / 1e9, 1)}
-    del x, d, params, spec, out, ws
+    del x, d, params, spec, out
     torch.cuda.empty_cache()
     return res
 

@@ -280,8 +280,8 @@ int spinner_sketch_gram(const float *B, int m, int d, float *G, void *workspace,
  * spinner_struct_spectrum_bytes(kind, n) bytes) once, off the clock, as the paper
  * prepares all parameters in advance.  spinner_struct_apply computes
  *     out[batch][m] = scale * (first m rows of G_struct D2 H D1 x)
- * with H the normalised Hadamard matrix; workspace: batch * n * 4 bytes of device
- * scratch (H D1 x).  The product with G_struct is an O(n log n) FFT convolution.
+ * with H the normalised Hadamard matrix, in one kernel that needs no scratch
+ * memory.  The product with G_struct is an O(n log n) FFT convolution.
  * n = 2^5 .. 2^14 for the circulant, .. 2^13 for the others (SPINNER_ERR_UNSUPPORTED
  * outside); an unknown kind gives SPINNER_ERR_BAD_EPILOGUE.
  */
@@ -291,7 +291,7 @@ size_t spinner_struct_spectrum_bytes(int kind, int n);
 int spinner_struct_prepare(int kind, const float *params, int n, void *spectrum, void *stream);
 int spinner_struct_apply(const float *x, int n, long batch, int kind, const void *spectrum,
                          const float *d1, const float *d2, int m, float scale,
-                         float *out, void *workspace, void *stream);
+                         float *out, void *stream);
 
 /*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the

@@ -115,7 +115,7 @@ lib.spinner_struct_prepare.restype = ctypes.c_int
 lib.spinner_struct_prepare.argtypes = [ctypes.c_int, _vp, ctypes.c_int, _vp, _vp]
 lib.spinner_struct_apply.restype = ctypes.c_int
 lib.spinner_struct_apply.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp, ctypes.c_int, ctypes.c_float,
-                                     _vp, _vp, _vp]
+                                     _vp, _vp]
 STRUCT_KINDS = {"circulant": 0, "skew_circulant": 1, "toeplitz": 2, "hankel": 3}
 
 
@@ -580,7 +580,7 @@ def spinner_struct_prepare(kind, params, n, stream=None):
     return spec
 
 
-def spinner_struct_apply(x, kind, spectrum, d1, d2, m=None, scale=1.0, out=None, workspace=None, stream=None):
+def spinner_struct_apply(x, kind, spectrum, d1, d2, m=None, scale=1.0, out=None, stream=None):
     """out [batch][m] = scale * (first m rows of G_struct D2 H D1 x)."""
     import torch
 
@@ -595,12 +595,8 @@ def spinner_struct_apply(x, kind, spectrum, d1, d2, m=None, scale=1.0, out=None,
         _check_tensor(out, "out", torch.float32)
         if out.numel() != batch * m:
             raise ValueError("out has the wrong size")
-    if workspace is None:
-        workspace = torch.empty(max(16, batch * n * 4), dtype=torch.uint8, device=x.device)
-    if workspace.numel() * workspace.element_size() < batch * n * 4:
-        raise ValueError("workspace too small")
     rc = lib.spinner_struct_apply(x.data_ptr(), n, batch, k, spectrum.data_ptr(), d1.data_ptr(), d2.data_ptr(), m,
-                                  ctypes.c_float(scale), out.data_ptr(), workspace.data_ptr(), _stream_handle(stream))
+                                  ctypes.c_float(scale), out.data_ptr(), _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out

@@ -594,7 +594,7 @@ int spinner_struct_prepare(int kind, const float* params, int n, void* spectrum,
 }
 
 int spinner_struct_apply(const float* x, int n, long batch, int kind, const void* spectrum, const float* d1, const float* d2,
-                         int m, float scale, float* out, void* workspace, void* stream)
+                         int m, float scale, float* out, void* stream)
 {
     int log2n;
     const int rc = check_struct(kind, n, &log2n);
@@ -603,25 +603,14 @@ int spinner_struct_apply(const float* x, int n, long batch, int kind, const void
     if (batch < 0 || batch > 0x7fffffffL || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
     if (batch == 0) return SPINNER_OK;
     if (!x || !spectrum || !d1 || !d2 || !out) return SPINNER_ERR_NULL_PTR;
-    if (!workspace) return SPINNER_ERR_WORKSPACE;
-    if (!aligned16(x) || !aligned16(spectrum) || !aligned16(d1) || !aligned16(d2) || !aligned16(out) || !aligned16(workspace))
-        return SPINNER_ERR_ALIGNMENT;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    // t = H D1 x (one diagonal, one normalised transform) into the workspace
-    spinner::TileParams p;
-    memset(&p, 0, sizeof(p));
-    float* t = static_cast<float*>(workspace);
-    p.x = x; p.out = t; p.d[0] = d1;
-    p.batch = batch; p.in_stride = n; p.out_stride = n;
-    p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0; p.m = n;
-    p.factor = (float)(1.0 / sqrt((double)n));
-    hipError_t e = spinner::launch_row_first(log2n, false, p, batch, s);
-    if (e != hipSuccess) return hip_fail(e);
+    if (!aligned16(x) || !aligned16(spectrum) || !aligned16(d1) || !aligned16(d2) || !aligned16(out)) return SPINNER_ERR_ALIGNMENT;
     const int lp = struct_log2p(kind, log2n);
     const float2* spec = static_cast<const float2*>(spectrum);
-    e = spinner::launch_struct_conv(t, d2, spec, spec + ((size_t)1 << lp), out, batch, n, lp, m,
-                                    kind == SPINNER_STRUCT_HANKEL ? 1 : 0,
-                                    (float)((double)scale / (double)((size_t)1 << lp)), s);
+    // the Hadamard stages and both transforms of the convolution run unnormalised: 1 / sqrt(n) and 1 / P go into the last scale
+    const double factor = (double)scale / ((double)((size_t)1 << lp) * sqrt((double)n));
+    const hipError_t e = spinner::launch_struct_conv(x, d1, d2, spec, spec + ((size_t)1 << lp), out, batch, n, log2n, lp, m,
+                                                     kind == SPINNER_STRUCT_HANKEL ? 1 : 0, (float)factor,
+                                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 

@@ -186,7 +186,7 @@ hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* sla
 
 // G_struct D2 H D1 members: spectrum of the structured block, FFT convolution (structured.hip)
 hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, hipStream_t s);
-hipError_t launch_struct_conv(const float* t, const float* d2, const float2* spec, const float2* tw, float* out, long long batch,
-                              int n, int log2p, int m, int reverse, float factor, hipStream_t s);
+hipError_t launch_struct_conv(const float* x, const float* d1, const float* d2, const float2* spec, const float2* tw, float* out,
+                              long long batch, int n, int log2n, int log2p, int m, int reverse, float factor, hipStream_t s);
 
 }  // namespace spinner

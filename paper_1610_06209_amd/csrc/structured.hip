@@ -1,19 +1,22 @@
 // The G_struct D2 H D1 members of the family: third block a circulant, skew-circulant, Toeplitz or Hankel
-// matrix given by its generating vector.  H D1 x comes from the tile kernels; the product with G_struct is a
-// cyclic convolution of length P (n for a circulant, 2n otherwise) done by a complex FFT held in LDS.  Two
-// real vectors share one complex transform (the generator is real, so real and imaginary part stay apart).
+// matrix given by its generating vector.  One workgroup holds two vectors in LDS as the real and imaginary
+// parts of complex points (the generator is real, so the two stay apart): H D1 x by Walsh-Hadamard stages on
+// those points, then the product with G_struct as a cyclic convolution of length P (n for a circulant, 2n
+// otherwise) by a complex FFT in the same buffer.
 #include "launch.hpp"
 namespace spinner {
 
 struct StructParams {
-    const float* t;        // [batch][n]: H D1 x
+    const float* x;        // [batch][n]
+    const float* d1;       // [n]
     const float* d2;       // [n]
     const float2* spec;    // [P] spectrum of the convolution kernel, in the order the forward transform leaves it
     const float2* tw;      // [P/2] exp(-2 pi i k / P)
     float* out;            // [batch][m]
     long long batch;
     int n, log2p, m, reverse;
-    float factor;          // scale / P
+    float factor;          // scale / (P sqrt(n)): both transforms are left unnormalised on the way
+    int log2n;
 };
 
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) { return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x); }
@@ -193,27 +196,70 @@ __device__ __forceinline__ void fft_forward(float2* X, const float2* __restrict_
     if (s == 0) fft_bit0(X, log2p);
 }
 
-// forward transform of two vectors (real and imaginary part), product with the spectrum, inverse transform: the
-// first forward trip reads the vectors from global memory, the last inverse trip writes the result there
+// Walsh-Hadamard stages on the BITS index bits top .. top-BITS+1 of the 2^log2n points in LDS, 2^BITS points per
+// thread in registers (one trip through LDS for all of them)
+template <int BITS, typename Load>
+__device__ __forceinline__ void wht_trip(float2* X, int top, int log2n, Load load)
+{
+    constexpr int M = 1 << BITS;
+    const int qb = top - (BITS - 1), q = 1 << qb;
+    for (int b = threadIdx.x; b < (1 << (log2n - BITS)); b += blockDim.x) {
+        const int j = b & (q - 1);
+        const int i0 = ((b >> qb) << (top + 1)) | j;
+        float2 v[M];
+#pragma unroll
+        for (int k = 0; k < M; ++k) v[k] = load(i0 + (k << qb));
+#pragma unroll
+        for (int st = 0; st < BITS; ++st)
+#pragma unroll
+            for (int k = 0; k < M; ++k)
+                if (!(k & (1 << st))) {
+                    const float2 a = v[k], c = v[k + (1 << st)];
+                    v[k] = cadd(a, c);
+                    v[k + (1 << st)] = csub(a, c);
+                }
+#pragma unroll
+        for (int k = 0; k < M; ++k) X[pad(i0 + (k << qb))] = v[k];
+    }
+    __syncthreads();
+}
+
+// H D1 x of two vectors, times D2 (reversed for a Hankel block), zero-padded to P; forward transform, product with
+// the spectrum, inverse transform.  The first trip of the Hadamard stages reads x from global memory, the last
+// inverse trip writes the result there; everything between stays in LDS.
 __global__ void __launch_bounds__(512) struct_conv_kernel(StructParams p)
 {
     extern __shared__ float2 X[];
-    const int L = p.log2p;
+    const int L = p.log2p, N = p.log2n;
     const long long v0 = 2LL * blockIdx.x, v1 = v0 + 1;
     const bool two = v1 < p.batch;
-    const float* __restrict__ t0 = p.t + v0 * p.n;
-    const float* __restrict__ t1 = p.t + (two ? v1 : v0) * p.n;      // a lone last vector is read twice, its copy dropped
-    auto from_global = [&](int i) {
-        // zero padding up to P; indices clamped so that no load sits under a condition
-        const int ic = i < p.n ? i : p.n - 1;
-        const int si = p.reverse ? p.n - 1 - ic : ic;
-        const float dd = p.d2[si];
-        float re = t0[si] * dd, im = t1[si] * dd;
-        if (i >= p.n) { re = 0.f; im = 0.f; }
-        return make_float2(re, im);
-    };
-    auto to_lds = [&](int i, float2 v) { X[pad(i)] = v; };
+    const float* __restrict__ x0 = p.x + v0 * p.n;
+    const float* __restrict__ x1 = p.x + (two ? v1 : v0) * p.n;      // a lone last vector is read twice, its copy dropped
     auto from_lds = [&](int i) { return X[pad(i)]; };
+    auto to_lds = [&](int i, float2 v) { X[pad(i)] = v; };
+
+    // t = H_u D1 x on the points 0 .. n-1 (H_u the +-1 matrix): four bits per trip, then what is left
+    int top = N - 1;
+    wht_trip<4>(X, top, N, [&](int i) { const float d = p.d1[i]; return make_float2(x0[i] * d, x1[i] * d); });
+    for (top -= 4; top >= 3; top -= 4) wht_trip<4>(X, top, N, from_lds);
+    if (top == 2) wht_trip<3>(X, 2, N, from_lds);
+    else if (top == 1) wht_trip<2>(X, 1, N, from_lds);
+    else if (top == 0) wht_trip<1>(X, 0, N, from_lds);
+    if (p.reverse) {                                                  // Hankel: G acts on the reversed vector
+        for (int i = threadIdx.x; i < p.n / 2; i += blockDim.x) {
+            const float2 a = X[pad(i)], c = X[pad(p.n - 1 - i)];
+            X[pad(i)] = c;
+            X[pad(p.n - 1 - i)] = a;
+        }
+        __syncthreads();
+    }
+    // every point is read and written by the same thread in a trip, so the transforms run in place
+    auto padded_times_d2 = [&](int i) {
+        const int ic = i < p.n ? i : p.n - 1;                         // clamped: no load under a condition
+        const float dd = p.d2[p.reverse ? p.n - 1 - ic : ic];
+        const float2 t = X[pad(ic)];
+        return i < p.n ? make_float2(t.x * dd, t.y * dd) : make_float2(0.f, 0.f);
+    };
     auto to_global = [&](int i, float2 r) {
         if (i < p.m) {
             p.out[v0 * p.m + i] = r.x * p.factor;
@@ -223,7 +269,7 @@ __global__ void __launch_bounds__(512) struct_conv_kernel(StructParams p)
     const int low = L & 3;
     // forward: bits L-1 .. low in radix-16 trips (the last one multiplies by the spectrum when no bits are left)
     int s = L - 1;
-    fft_trip16<false>(p.tw, s, L, from_global, to_lds);
+    fft_trip16<false>(p.tw, s, L, padded_times_d2, to_lds);
     for (s -= 4; s >= 3; s -= 4) {
         if (low == 0 && s == 3) fft_trip16<false>(p.tw, s, L, from_lds, [&](int i, float2 v) { X[pad(i)] = cmul(v, p.spec[i]); });
         else fft_trip16<false>(X, p.tw, s, L);
@@ -294,8 +340,8 @@ hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p
     return hipGetLastError();
 }
 
-hipError_t launch_struct_conv(const float* t, const float* d2, const float2* spec, const float2* tw, float* out, long long batch,
-                              int n, int log2p, int m, int reverse, float factor, hipStream_t s)
+hipError_t launch_struct_conv(const float* x, const float* d1, const float* d2, const float2* spec, const float2* tw, float* out,
+                              long long batch, int n, int log2n, int log2p, int m, int reverse, float factor, hipStream_t s)
 {
     if (batch <= 0) return hipSuccess;
     const long long blocks = (batch + 1) / 2;
@@ -303,7 +349,7 @@ hipError_t launch_struct_conv(const float* t, const float* d2, const float2* spe
     const size_t lds = fft_lds_bytes(log2p);
     hipError_t e = allow_lds(reinterpret_cast<const void*>(struct_conv_kernel), lds);
     if (e != hipSuccess) return e;
-    StructParams p{t, d2, spec, tw, out, batch, n, log2p, m, reverse, factor};
+    StructParams p{x, d1, d2, spec, tw, out, batch, n, log2p, m, reverse, factor, log2n};
     // one thread per sixteen points of the transform
     const int threads = (1 << log2p) / 16 < 64 ? 64 : ((1 << log2p) / 16 > 512 ? 512 : (1 << log2p) / 16);
     hipLaunchKernelGGL(struct_conv_kernel, dim3((unsigned)blocks), dim3(threads), lds, s, p);

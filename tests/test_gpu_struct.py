@@ -100,10 +100,10 @@ def test_struct_argument_errors(gpu):
     import ctypes
     one = ctypes.c_float(1.0)
     f = b.lib.spinner_struct_apply
-    assert f(64, 1024, 4, 9, 64, 64, 64, 1024, one, 64, 64, None) == b.SPINNER_ERR_BAD_EPILOGUE
-    assert f(64, 1000, 4, 0, 64, 64, 64, 1000, one, 64, 64, None) == b.SPINNER_ERR_BAD_N
-    assert f(64, 1 << 14, 4, 2, 64, 64, 64, 16, one, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
-    assert f(64, 1024, 4, 0, 64, 64, 64, 2000, one, 64, 64, None) == b.SPINNER_ERR_BAD_M
-    assert f(64, 1024, 4, 0, 64, 64, 64, 1024, one, 64, None, None) == b.SPINNER_ERR_WORKSPACE
-    assert f(64, 1024, 4, 0, None, 64, 64, 1024, one, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
-    assert f(None, 1024, 0, 0, None, None, None, 1024, one, None, None, None) == b.SPINNER_OK
+    assert f(64, 1024, 4, 9, 64, 64, 64, 1024, one, 64, None) == b.SPINNER_ERR_BAD_EPILOGUE
+    assert f(64, 1000, 4, 0, 64, 64, 64, 1000, one, 64, None) == b.SPINNER_ERR_BAD_N
+    assert f(64, 1 << 14, 4, 2, 64, 64, 64, 16, one, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert f(64, 1024, 4, 0, 64, 64, 64, 2000, one, 64, None) == b.SPINNER_ERR_BAD_M
+    assert f(64, 1024, 4, 0, 64, 64, 64, 1024, one, 72, None) == b.SPINNER_ERR_ALIGNMENT
+    assert f(64, 1024, 4, 0, None, 64, 64, 1024, one, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert f(None, 1024, 0, 0, None, None, None, 1024, one, None, None) == b.SPINNER_OK
