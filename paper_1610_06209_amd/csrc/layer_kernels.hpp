@@ -171,11 +171,25 @@ layer_backward_kernel(LayerBackwardParams p)
             const float* d1 = p.d[0] + c.base_index(L3);
             float* dst = p.dx + off + c.base_index(L3);
             const float f = p.factor * sgn;
+            if constexpr (R >= 32) {
+                // all of D1's entries are asked for before the first product is stored: the scheduling barrier keeps the
+                // compiler from pairing each load with its store, one load in flight at a time (n = 2^14: 1.305 -> 1.137 ms;
+                // with 16 values per thread the pairing measured 3 % faster at n = 2^11 and is left alone)
+                float4 t[R / 4];
 #pragma unroll
-            for (int jh = 0; jh < R / 4; ++jh) {
-                const float4 t = *reinterpret_cast<const float4*>(d1 + G::reg_index(L3, jh * 4));
-                *reinterpret_cast<float4*>(dst + G::reg_index(L3, jh * 4)) =
-                    make_float4(g[jh * 4] * f * t.x, g[jh * 4 + 1] * f * t.y, g[jh * 4 + 2] * f * t.z, g[jh * 4 + 3] * f * t.w);
+                for (int jh = 0; jh < R / 4; ++jh) t[jh] = *reinterpret_cast<const float4*>(d1 + G::reg_index(L3, jh * 4));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int jh = 0; jh < R / 4; ++jh)
+                    *reinterpret_cast<float4*>(dst + G::reg_index(L3, jh * 4)) =
+                        make_float4(g[jh * 4] * f * t[jh].x, g[jh * 4 + 1] * f * t[jh].y, g[jh * 4 + 2] * f * t[jh].z, g[jh * 4 + 3] * f * t[jh].w);
+            } else {
+#pragma unroll
+                for (int jh = 0; jh < R / 4; ++jh) {
+                    const float4 t = *reinterpret_cast<const float4*>(d1 + G::reg_index(L3, jh * 4));
+                    *reinterpret_cast<float4*>(dst + G::reg_index(L3, jh * 4)) =
+                        make_float4(g[jh * 4] * f * t.x, g[jh * 4 + 1] * f * t.y, g[jh * 4 + 2] * f * t.z, g[jh * 4 + 3] * f * t.w);
+                }
             }
         }
     }
