@@ -55,6 +55,22 @@ __device__ __forceinline__ void tile_mac(float (&acc)[G::R], const float (&g)[G:
     }
 }
 
+// v *= (tile of the diagonal d in layout LAY); GROUPED: all loads are issued before the first product (a scheduling
+// barrier keeps them together where the compiler would otherwise wait for each by itself)
+template <typename G, int LAY, bool GROUPED>
+__device__ __forceinline__ void tile_scale(float (&v)[G::R], const ThreadCtx<G>& c, const float* d)
+{
+    const float* src = d + c.base_index(LAY);
+    float4 t[G::R / 4];
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) t[jh] = *reinterpret_cast<const float4*>(src + G::reg_index(LAY, jh * 4));
+    if constexpr (GROUPED) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int jh = 0; jh < G::R / 4; ++jh) {
+        v[jh * 4] *= t[jh].x; v[jh * 4 + 1] *= t[jh].y; v[jh * 4 + 2] *= t[jh].z; v[jh * 4 + 3] *= t[jh].w;
+    }
+}
+
 // acc += g * t for a tile already in registers
 template <int R>
 __device__ __forceinline__ void tile_fma(float (&acc)[R], const float (&g)[R], const float (&t)[R])
@@ -117,6 +133,9 @@ layer_backward_kernel(LayerBackwardParams p)
     constexpr int n = 1 << NT;
     constexpr int R = G::R;
     constexpr int L1 = G::layout_after(1), L2 = G::layout_after(2), L3 = G::layout_after(3);
+#ifndef SPINNER_LAYER_GROUPED_DIAG  // 1: with 32 values per thread the backward kernel loads a diagonal's entries together (tuning experiments)
+#define SPINNER_LAYER_GROUPED_DIAG 1
+#endif
 #ifndef SPINNER_LAYER_PREFETCH      // 0: the backward kernel loads nothing ahead (tuning experiments)
 #define SPINNER_LAYER_PREFETCH 1
 #endif
@@ -152,11 +171,21 @@ layer_backward_kernel(LayerBackwardParams p)
             if (active) tile_fma<R>(acc3, g, ta);
             tile_load<G, L2>(ta, c, p.saved1 + off);
             __builtin_amdgcn_sched_barrier(0);
-            spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
+            if constexpr (SPINNER_LAYER_GROUPED_DIAG && R >= 32) {
+                tile_scale<G, L1, true>(g, c, p.d[2]);
+                spinner_step<G, NT, 0, L1, false, false, true, false>(g, c, nullptr, nullptr, 0, lds);
+            } else {
+                spinner_step<G, NT, 0, L1, true, false, true, false>(g, c, p.d[2], nullptr, 0, lds);
+            }
             if (active) tile_fma<R>(acc2, g, ta);
             tile_load<G, L3>(ta, c, p.x + off);
             __builtin_amdgcn_sched_barrier(0);
-            spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
+            if constexpr (SPINNER_LAYER_GROUPED_DIAG && R >= 32) {
+                tile_scale<G, L2, true>(g, c, p.d[1]);
+                spinner_step<G, NT, 0, L2, false, false, false, false>(g, c, nullptr, nullptr, 0, lds);
+            } else {
+                spinner_step<G, NT, 0, L2, true, false, false, false>(g, c, p.d[1], nullptr, 0, lds);
+            }
             if (active) tile_fma<R>(acc1, g, ta);
         } else {
             spinner_step<G, NT, 0, G::layout_after(0), false, true, false, false>(g, c, nullptr, nullptr, 0, lds);
