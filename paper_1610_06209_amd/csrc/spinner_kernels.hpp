@@ -173,7 +173,10 @@ struct TileGeom {
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
     // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
     // (tiles above 2^14 elements always take as many trips as keep the buffer at 64 KiB)
-    static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : (((SPINNER_LDS_HALVES == 2 || TRIPS_ == 2) && WB >= 1) ? 2 : 1);
+#ifndef SPINNER_N16_TRIPS      // trips per exchange of a tile of 2^16 elements: 4 (64 KiB buffer) or 2 (128 KiB of the 160 KiB)
+#define SPINNER_N16_TRIPS 4
+#endif
+    static constexpr int LDS_HALVES = NT_ == 16 ? SPINNER_N16_TRIPS : NT_ > 14 ? (1 << (NT_ - 14)) : (((SPINNER_LDS_HALVES == 2 || TRIPS_ == 2) && WB >= 1) ? 2 : 1);
     static constexpr int LDS_FLOAT4 = WB > 0 ? ((1 << NT_) / 4) / LDS_HALVES : 1;
     static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
