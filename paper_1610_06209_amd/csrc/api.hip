@@ -199,7 +199,8 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         // P2: cols, D2, cols : buf -> buf
         p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-        p.vec_major = 0;
+        // neighbouring column tiles of one vector read neighbouring 128-byte segments of the same rows
+        p.vec_major = col_signs ? 1 : 0;
         if (col_signs) p.sw[1] = signs + col_words_offset(n, log2n);
         if ((e = launch_col_middle(kColRowsLog, kColContigLog, col_signs, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
         // P3: rows, D3, rows : buf -> buf
@@ -210,7 +211,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         // P4: cols, epilogue : buf -> out
         p.out = out + b0 * out_stride; p.d[1] = nullptr; p.out_stride = out_stride;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-        p.m = m; p.factor = (float)factor_d; p.vec_major = 0;
+        p.m = m; p.factor = (float)factor_d; p.vec_major = 1;      // no diagonal in this pass
         if ((e = launch_col_last(kColRowsLog, kColContigLog, epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
     }
     return SPINNER_OK;
