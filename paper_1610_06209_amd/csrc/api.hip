@@ -193,25 +193,20 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         p.in_stride = n; p.out_stride = n; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
         p.m = n; p.factor = 1.0f;
         p.sw[0] = signs;
-        // with sign words nothing is gained from neighbours sharing a diagonal block: consecutive tiles are consecutive in memory
-        p.vec_major = row_signs ? 1 : 0;
         if ((e = launch_row_first(nr, row_signs, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
         // P2: cols, D2, cols : buf -> buf
         p.x = buf; p.out = buf; p.d[0] = nullptr; p.d[1] = d2;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-        // neighbouring column tiles of one vector read neighbouring 128-byte segments of the same rows
-        p.vec_major = col_signs ? 1 : 0;
         if (col_signs) p.sw[1] = signs + col_words_offset(n, log2n);
         if ((e = launch_col_middle(kColRowsLog, kColContigLog, col_signs, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
         // P3: rows, D3, rows : buf -> buf
         p.d[1] = d3; p.tiles_per_vec_log = kColRowsLog; p.tb = nr; p.sl = 0;
-        p.vec_major = row_signs ? 1 : 0;
         if (row_signs) p.sw[1] = signs + 2 * sign_words_per_diag(n);
         if ((e = launch_row_middle(nr, row_signs, p, row_tiles, s)) != hipSuccess) return hip_fail(e);
         // P4: cols, epilogue : buf -> out
         p.out = out + b0 * out_stride; p.d[1] = nullptr; p.out_stride = out_stride;
         p.tiles_per_vec_log = nr - kColContigLog; p.tb = kColContigLog; p.sl = nr;
-        p.m = m; p.factor = (float)factor_d; p.vec_major = 1;      // no diagonal in this pass
+        p.m = m; p.factor = (float)factor_d;
         if ((e = launch_col_last(kColRowsLog, kColContigLog, epi, p, col_tiles, s)) != hipSuccess) return hip_fail(e);
     }
     return SPINNER_OK;

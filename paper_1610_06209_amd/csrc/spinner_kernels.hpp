@@ -230,7 +230,6 @@ struct TileParams {
     long long in_stride;
     long long out_stride;
     int tiles_per_vec_log;    // log2(tiles per vector)
-    int vec_major;            // tile number = vector * tiles per vector + tile of the vector (else: tile of the vector * batch + vector)
     int tb;                   // tile number -> first element: q << tb
     int sl;                   // log2(row stride) of a column tile (ignored for contiguous tiles)
     int m;                    // coordinates kept by the epilogue
@@ -955,9 +954,10 @@ spinner_tile_kernel(TileParams p)
         const bool active = tile < total;
         long long vec = 0, q = 0;
         if (active) {
+            // tiles are numbered vector by vector: consecutive row tiles are consecutive memory, consecutive column
+            // tiles read neighbouring segments of the same rows
             if (p.tiles_per_vec_log == 0) { vec = tile; }
-            else if (p.vec_major) { vec = tile >> p.tiles_per_vec_log; q = tile - (vec << p.tiles_per_vec_log); }   // neighbours are contiguous in memory
-            else { q = tile / p.batch; vec = tile - q * p.batch; }   // neighbours share the diagonal block
+            else { vec = tile >> p.tiles_per_vec_log; q = tile - (vec << p.tiles_per_vec_log); }
         }
         const long long tile_first = q << p.tb;      // first element of the tile inside its vector
 
