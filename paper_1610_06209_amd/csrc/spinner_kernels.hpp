@@ -956,7 +956,7 @@ spinner_tile_kernel(TileParams p)
         if (active) {
             // tiles are numbered vector by vector: consecutive row tiles are consecutive memory, consecutive column
             // tiles read neighbouring segments of the same rows
-            if (p.tiles_per_vec_log == 0) { vec = tile; }
+            if constexpr (NSTEPS == 3) { vec = tile; }      // all three rounds on chip: the tile is a whole vector
             else { vec = tile >> p.tiles_per_vec_log; q = tile - (vec << p.tiles_per_vec_log); }
         }
         const long long tile_first = q << p.tb;      // first element of the tile inside its vector
