@@ -28,14 +28,22 @@ HBM_PEAK_GBS = 8000.0
 # of the two of a fused multiply-add); packed fp32 forms are not used
 VALU_PEAK_GOPS = 256 * 4 * 32 * 2.4
 
-# HBM bytes per launch read from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# each scaled by what the same counter reads for spinner_stream_copy of known size); see
-# profiles/.  None where no counter run has been made for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/spinner_tile_kernel_f32_n4096_sweep_plain_n2p12.md:
-    # (FETCH_SIZE 524393.5 KiB x 2.0000) + (WRITE_SIZE 1051652.9 KiB x 1.0000), scale factors from the copy kernel
-    "sweep_plain_n2p12": 2150830972,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def measured_traffic_bytes(workload, diagonals):
+    """HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
+    the same counter reads for spinner_stream_copy of known size): the row of profiles/hbm_traffic.md for this
+    workload and diagonal form, or None where no counter run has been made."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 7 and cells[0] == workload and cells[1] == diagonals:
+                    return int(cells[6].replace(" ", ""))
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -143,6 +151,7 @@ def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0, 
     wall_ms, ev_ms = time_calls(torch, fn, steps, warmup)
     graph_ms = time_graph(torch, fn, 20, 10) if graph else None
     alg = W.algorithmic_bytes_per_vector(w) * w.batch
+    sched = W.schedule_bytes_per_vector(w) * w.batch
     ops = W.adds_per_vector(w) * w.batch
     res = {
         "workload": w.name, "n": w.n, "batch": w.batch, "m": w.m, "epilogue": w.epilogue, "L": w.L,
@@ -152,6 +161,10 @@ def measure(torch, b, W, w, dev, steps, warmup, diagonals="signs", ramp_ms=0.0, 
         "algorithmic_bytes": alg,
         "achieved_GBs": alg / (ev_ms * 1e-3) / 1e9,
         "hbm_frac": alg / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        # what the kernels themselves read and write (memory-side cache + HBM): differs from the algorithmic
+        # bytes only above the fused range, where the four-pass schedule moves a vector four times
+        "schedule_bytes": sched,
+        "schedule_GBs": sched / (ev_ms * 1e-3) / 1e9,
         "butterfly_adds_Gops": ops / (ev_ms * 1e-3) / 1e9,
         "valu_frac_adds_only": ops / (ev_ms * 1e-3) / 1e9 / VALU_PEAK_GOPS,
         "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
@@ -429,14 +442,29 @@ def main():
             w = W.sweep_workload(k)
             r = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), args.diagonals, ramp_ms=60.0)
             rf = measure(torch, b, W, w, dev, max(3, args.steps // 2), max(2, args.warmup // 2), "fp32", ramp_ms=60.0)
-            sweep.append({"log2n": k, "batch": w.batch, "ms": round(r["kernel_ms"], 4),
-                          "vectors_per_s": round(r["vectors_per_s"], 1), "GBs": round(r["achieved_GBs"], 1),
-                          "hbm_frac": round(r["hbm_frac"], 4), "frac_of_copy": round(r["achieved_GBs"] / copy_gbs, 4),
-                          "fp32_diag_GBs": round(rf["achieved_GBs"], 1)})
-            log("[bench] sweep n=2^%d batch=%d: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)   [fp32 diagonals: %.0f GB/s]" % (
+            row = {"log2n": k, "batch": w.batch, "ms": round(r["kernel_ms"], 4),
+                   "vectors_per_s": round(r["vectors_per_s"], 1), "GBs": round(r["achieved_GBs"], 1),
+                   "hbm_frac": round(r["hbm_frac"], 4), "frac_of_copy": round(r["achieved_GBs"] / copy_gbs, 4),
+                   "fp32_diag_ms": round(rf["kernel_ms"], 4), "fp32_diag_GBs": round(rf["achieved_GBs"], 1),
+                   "fp32_diag_hbm_frac": round(rf["hbm_frac"], 4),
+                   "traffic": measured_traffic_bytes(w.name, args.diagonals)}
+            if r["schedule_bytes"] != r["algorithmic_bytes"]:
+                # four passes: 32 B per element go through the memory-side cache and HBM together
+                row["schedule_GBs_cache_and_hbm"] = round(r["schedule_GBs"], 1)
+                row["fp32_diag_schedule_GBs_cache_and_hbm"] = round(rf["schedule_GBs"], 1)
+            sweep.append(row)
+            log("[bench] sweep n=2^%d batch=%d: %.4f ms  %.3e vec/s  %.0f GB/s (%.1f%%)   [fp32 diagonals: %.0f GB/s (%.1f%%)]%s" % (
                 k, w.batch, r["kernel_ms"], r["vectors_per_s"], r["achieved_GBs"], 100 * r["hbm_frac"],
-                rf["achieved_GBs"]))
+                rf["achieved_GBs"], 100 * rf["hbm_frac"],
+                "" if r["schedule_bytes"] == r["algorithmic_bytes"] else
+                "   four passes move %.0f GB/s through cache + HBM" % r["schedule_GBs"]))
         extras["sweep"] = sweep
+        target = [t for t in sweep if 10 <= t["log2n"] <= 14]
+        ws = min(target, key=lambda t: t["hbm_frac"])
+        wf = min(target, key=lambda t: t["fp32_diag_hbm_frac"])
+        extras["min_frac_2p10_2p14"] = {args.diagonals: {"frac": ws["hbm_frac"], "log2n": ws["log2n"]},
+                                        "fp32": {"frac": wf["fp32_diag_hbm_frac"], "log2n": wf["log2n"]}}
+        log("[bench] lowest fraction of the HBM peak over n = 2^10 .. 2^14: %s" % json.dumps(extras["min_frac_2p10_2p14"]))
         cfgs = []
         for name in W.CONFIG_ORDER:
             w = W.CONFIGS[name]
@@ -446,7 +474,10 @@ def main():
             cfgs.append({"workload": name, "ms": round(r["kernel_ms"], 4), "vectors_per_s": round(r["vectors_per_s"], 1),
                          "GBs": round(r["achieved_GBs"], 1), "hbm_frac": round(r["hbm_frac"], 4),
                          "frac_of_copy": round(r["achieved_GBs"] / copy_gbs, 4),
-                         "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4)})
+                         "valu_frac_adds_only": round(r["valu_frac_adds_only"], 4),
+                         "traffic": measured_traffic_bytes(name, args.diagonals)})
+            if r["schedule_bytes"] != r["algorithmic_bytes"]:
+                cfgs[-1]["schedule_GBs_cache_and_hbm"] = round(r["schedule_GBs"], 1)
             if r["graph_ms_per_step"] is not None:
                 cfgs[-1]["graph_ms_per_step"] = r["graph_ms_per_step"]
                 log("[bench] %s as a HIP graph of 20 steps: %.5f ms per step" % (name, r["graph_ms_per_step"]))
@@ -457,7 +488,7 @@ def main():
         nxt = measure_next_rows(torch, b, W, dev, args)
         extras["next_rows"] = nxt
 
-    traffic = MEASURED_TRAFFIC_BYTES.get(head.name)
+    traffic = measured_traffic_bytes(head.name, args.diagonals)
     alu_bound = head.kind in ("hash", "codes")
     line = {
         "metric": "HD3HD2HD1 vectors/s + achieved HBM GB/s vs peak, fp32, n=2^10..2^20",
@@ -488,6 +519,9 @@ def main():
             "algorithmic_bytes": hres["algorithmic_bytes"],
         },
     }
+    if "min_frac_2p10_2p14" in extras:
+        # the target is stated for every n = 2^10 .. 2^14: the headline size is one of them, this is the worst
+        line["roofline"]["min_frac_2p10_2p14"] = extras.pop("min_frac_2p10_2p14")
     if not (args.quick or args.only):
         line["cpu_baseline"] = cpu_baseline(W, head)
         log("[bench] cpu oracle: %.1f vectors/s on %d cores (%s)" % (

@@ -84,6 +84,16 @@ typedef enum {
  * transform rounds.  Above it the call makes four passes over HBM using the
  * Kronecker structure H_{ab} = H_a (x) H_b of the Sylvester matrix; intermediate
  * passes run in place in `out` when m == n, else in `workspace`.
+ *
+ * Accuracy: outputs of SPINNER_EPI_NONE carry the rounding of 3 log2 n fp32
+ * butterfly stages (relative L2 error of a few 1e-7 per vector).  The fused
+ * feature kernels (SPINNER_EPI_COSSIN, n <= 2^14) run their butterflies and the
+ * reduction of w in fp64, so the unit-norm feature vector is good to 1e-5
+ * relative at any scale.  Above 2^14 the four passes are fp32: each angle w
+ * then carries an error of about 3.4e-8 * sqrt(3 log2 n) * rms(w) radians,
+ * which is also the relative L2 error of the feature vector, i.e. at most
+ * max(1e-5, 5e-7 * rms(w)); with scale = sqrt(n) / sigma that exceeds 1e-5
+ * once |x| / sigma is above about 40.
  */
 int spinner_apply(const float *x, int n, long batch,
                   const float *d1, const float *d2, const float *d3,
@@ -188,7 +198,7 @@ int spinner_apply_blocks(const float *x, int n, long batch, int L,
  *
  * spinner_angular_gram computes out[i][j] = 1 - d_H(a_i, b_j) / m (fp32,
  * row-major [na][nb]) for two sets of codes of the same m; the Hamming
- * distances are exact integers.  na is limited to 64 * 65535 rows per call.
+ * distances are exact integers.  na is limited to 128 * 65535 rows per call.
  */
 size_t spinner_code_bytes(int m);
 size_t spinner_codes_workspace_bytes(int n, long batch);

@@ -224,11 +224,15 @@ def layer_backward(x, d1, d2, d3, dy, scale: float = 1.0):
 def sketch(A, w, d1, d2, d3, m: int, scale: float, nthreads: int = 0) -> np.ndarray:
     """B = S diag(w) A, fp64 [m][d], for A fp32 [n][d], row weights w fp32 [n] (None: all ones) and
     S = scale * (first m rows of H D3 H D2 H D1).  The spinner acts on each column of diag(w) A."""
-    A = np.asarray(A, dtype=np.float32)
+    A = np.asarray(A, dtype=np.float64)
     if w is not None:
-        A = (A * np.asarray(w, dtype=np.float32)[:, None]).astype(np.float32)     # the product the fp32 path forms
+        A = A * np.asarray(w, dtype=np.float64)[:, None]                           # diag(w) A, no intermediate rounding
     cols = np.ascontiguousarray(A.T)                                               # [d][n]: one vector per column
-    y = spinner(cols, d1, d2, d3, nthreads=nthreads)
+    ka = default_kron_a(cols.shape[1])
+    d1, d2, d3 = (np.asarray(d, dtype=np.float64) for d in (d1, d2, d3))
+    t = hadamard_apply(cols * d1, ka)                                              # H D1 (diag(w) a) for every column a
+    t = hadamard_apply(t * d2, ka)
+    y = hadamard_apply(t * d3, ka)
     return float(scale) * np.ascontiguousarray(y[:, :m].T)
 
 

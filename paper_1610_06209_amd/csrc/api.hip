@@ -329,7 +329,8 @@ size_t spinner_codes_workspace_bytes(int n, long batch)
 
 int spinner_code_position(int coordinate, int* word, int* bit)
 {
-    if (coordinate < 0 || !word || !bit) return SPINNER_ERR_NULL_PTR;
+    if (!word || !bit) return SPINNER_ERR_NULL_PTR;
+    if (coordinate < 0) return SPINNER_ERR_BAD_M;
     *word = ((coordinate >> 8) << 2) | (coordinate & 3);
     *bit = (coordinate >> 2) & 63;
     return SPINNER_OK;

@@ -1190,7 +1190,7 @@ spinner_hash_kernel(HashParams p)
         if constexpr (G::WB > 0) {
             if (lane == 0) { red_val[wave] = best; red_idx[wave] = best_i; }
             __syncthreads();
-            if (threadIdx.x == 0) {
+            if (active && threadIdx.x == 0) {
                 for (int w = 1; w < G::WAVES; ++w) {
                     const float ov = red_val[w];
                     const int oi = red_idx[w];

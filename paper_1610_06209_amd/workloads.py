@@ -193,20 +193,40 @@ def fused_max_n(epilogue: str) -> int:
 
 
 def algorithmic_bytes_per_vector(w: Workload) -> int:
-    """Bytes the method must move per vector: x once, the epilogue's output once
-    (diagonals are shared by the batch and amortise to zero).  For n above the
-    largest fused size the four-pass schedule moves the vector four times."""
+    """Bytes the method must move per vector at any n: x once, the epilogue's output once
+    (diagonals are shared by the batch and amortise to zero)."""
     n = w.n
     if w.kind == "hash":
         return 4 * n + 4 * w.L
     if w.kind == "codes":                       # one bit per kept coordinate leaves the chip
-        return 4 * n + w.m // 8 if n <= fused_max_n("none") else 4 * 8 * n + 4 * w.m + w.m // 8
+        return 4 * n + w.m // 8
     out = 8 * w.m if w.epilogue == "cossin" else 4 * w.m
-    if n > fused_max_n(w.epilogue):
-        return 4 * 8 * n if w.m == n else 3 * 8 * n + 4 * n + out
     return 4 * n + out
 
 
+def schedule_bytes_per_vector(w: Workload) -> int:
+    """Bytes the kernels themselves read and write per vector, memory-side cache and HBM together.  The same as
+    the algorithmic bytes while one fused kernel serves n; above that the four-pass schedule moves the vector four
+    times (three of the trips are meant to stay in the memory-side cache), and sign codes take a fifth read."""
+    n = w.n
+    if w.kind == "hash" or n <= fused_max_n("none" if w.kind == "codes" else w.epilogue):
+        return algorithmic_bytes_per_vector(w)
+    if w.kind == "codes":
+        return 4 * 8 * n + 4 * n + w.m // 8
+    out = 8 * w.m if w.epilogue == "cossin" else 4 * w.m
+    return 3 * 8 * n + 4 * n + out
+
+
+PRUNE_BITS = 4      # the kernels drop the four highest index bits of the last round when m <= n / 16
+
+
 def adds_per_vector(w: Workload) -> int:
-    """fp32 additions of the unpruned butterfly network (3 rounds, per triple)."""
-    return 3 * int(math.log2(w.n)) * w.n * w.L
+    """fp32 additions of the butterfly network per vector (3 rounds, per triple).  When at most n/16 leading
+    coordinates are kept, the last round only forms the sums on its four highest index bits
+    (n/2 + n/4 + n/8 + n/16 additions) and log2(n) - 4 full stages on the n/16 values that are left."""
+    N = int(math.log2(w.n))
+    full = N * w.n
+    if w.kind == "apply" and w.epilogue == "none" and 8 <= N <= 14 and w.m <= (w.n >> PRUNE_BITS):
+        last = (w.n - (w.n >> PRUNE_BITS)) + (N - PRUNE_BITS) * (w.n >> PRUNE_BITS)
+        return (2 * full + last) * w.L
+    return 3 * full * w.L

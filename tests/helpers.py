@@ -12,6 +12,19 @@ def rel_l2_per_vector(got: np.ndarray, want: np.ndarray) -> np.ndarray:
     return num / np.where(den == 0, 1.0, den)
 
 
+def rel_l2_first_m(got: np.ndarray, want: np.ndarray, x: np.ndarray, n: int, m: int, scale: float) -> np.ndarray:
+    """Error of a first-m-rows output per vector.  With m > 8 coordinates kept this is the plain rule
+    (error norm over the norm of the kept part).  A handful of kept coordinates can cancel to next to
+    nothing, and fp32 cannot hold 1e-5 of that: for m <= 8 the error is measured against the kept part's
+    norm or its expected size sqrt(m / n) * scale * |x| (the spinner is an isometry), whichever is larger."""
+    if m > 8:
+        return rel_l2_per_vector(got, want)
+    num = np.linalg.norm(got.astype(np.float64) - want, axis=-1)
+    ref = np.maximum(np.linalg.norm(want, axis=-1),
+                     np.sqrt(m / n) * scale * np.linalg.norm(x.astype(np.float64), axis=-1))
+    return num / np.where(ref == 0, 1.0, ref)
+
+
 def check_hash_against_projection(idx_gpu: np.ndarray, y: np.ndarray, band: float = HASH_BAND):
     """idx_gpu int32 [batch][L]; y fp64 [L][batch][n] (the oracle's projections).
 

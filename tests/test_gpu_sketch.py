@@ -82,7 +82,7 @@ def test_full_sketch_gives_the_exact_hessian(gpu):
     B = gpu.b.spinner_sketch(_to(gpu, A), _to(gpu, w), _to(gpu, dg[0]), _to(gpu, dg[1]), _to(gpu, dg[2]), n, 1.0)
     G = gpu.b.spinner_sketch_gram(B)
     gpu.torch.cuda.synchronize()
-    WA = (A * w[:, None]).astype(np.float32).astype(np.float64)
+    WA = A.astype(np.float64) * w.astype(np.float64)[:, None]
     want = WA.T @ WA
     assert np.linalg.norm(G.cpu().numpy() - want) <= 1e-5 * np.linalg.norm(want)
 

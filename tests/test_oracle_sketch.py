@@ -20,7 +20,7 @@ def test_sketch_is_the_dense_matrix_product(oracle):
     dg = _rademacher(rng, (3, n))
     H = scipy.linalg.hadamard(n) / math.sqrt(n)
     S = scale * (H @ np.diag(dg[2]) @ H @ np.diag(dg[1]) @ H @ np.diag(dg[0]))[:m]
-    WA = (A * w[:, None]).astype(np.float32).astype(np.float64)
+    WA = A.astype(np.float64) * w.astype(np.float64)[:, None]
     B = oracle.sketch(A, w, dg[0], dg[1], dg[2], m, scale)
     assert B.shape == (m, d)
     assert np.allclose(B, S @ WA, atol=1e-12)
@@ -35,7 +35,7 @@ def test_full_sketch_reproduces_the_hessian_exactly(oracle):
     A, w = W.newton_sketch_problem(n, d, 11)
     dg = W.rademacher_diagonals(n, 3, 12)
     B = oracle.sketch(A, w, dg[0], dg[1], dg[2], n, 1.0)
-    WA = (A * w[:, None]).astype(np.float32).astype(np.float64)
+    WA = A.astype(np.float64) * w.astype(np.float64)[:, None]
     assert np.allclose(oracle.sketched_gram(B), WA.T @ WA, rtol=1e-11, atol=1e-11)
 
 
@@ -43,7 +43,7 @@ def test_sketched_hessian_is_unbiased_and_close(oracle):
     # scale sqrt(n/m): E[S^T S] = I over the random diagonals; the error of one sketch shrinks like sqrt(d/m)
     n, d, m = 1024, 8, 256
     A, w = W.newton_sketch_problem(n, d, 21)
-    WA = (A * w[:, None]).astype(np.float32).astype(np.float64)
+    WA = A.astype(np.float64) * w.astype(np.float64)[:, None]
     exact = WA.T @ WA
     mean = np.zeros_like(exact)
     errs = []
