@@ -47,7 +47,8 @@ enum {
     SPINNER_ERR_HIP          = -7,  /* a kernel launch failed; see spinner_strerror         */
     SPINNER_ERR_BAD_L        = -8,  /* L < 1                                                */
     SPINNER_ERR_ALIGNMENT    = -9,  /* a data pointer is not 16-byte aligned                */
-    SPINNER_ERR_UNSUPPORTED  = -10  /* combination not built (e.g. hashing with n > 2^14)   */
+    SPINNER_ERR_UNSUPPORTED  = -10, /* combination not built (e.g. hashing with n > 2^14)   */
+    SPINNER_ERR_SCRATCH_LIMIT = -11 /* needs more scratch than the built-in buffer of an allocation-free entry point */
 };
 
 typedef enum {
@@ -275,6 +276,24 @@ int spinner_sketch(const float *A, int n, int d, const float *w,
                    int m, float scale, float *B, void *workspace, void *stream);
 size_t spinner_sketch_gram_workspace_bytes(int m, int d);
 int spinner_sketch_gram(const float *B, int m, int d, float *G, void *workspace, void *stream);
+
+/*
+ * spinner_sketch_gram for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the
+ * slabs of the split sum go to a buffer built into the library (a file-scope
+ * device array of spinner_sketch_gram_static_limit() = 16 MiB that each GPU the
+ * library runs on holds until the process ends).  The call allocates and frees
+ * nothing.  Problems with spinner_sketch_gram_workspace_bytes(m, d) above the
+ * limit return SPINNER_ERR_SCRATCH_LIMIT and enqueue nothing (every d <= 256
+ * and the d = 512 of the paper's experiment fit; d > 1920 needs no scratch at
+ * all).  All calls on one GPU share the one buffer: calls that may
+ * overlap in time on the same GPU (different streams, different threads) race;
+ * calls on one stream are safe.  Nothing in the buffer has to be cleared
+ * between calls.
+ */
+size_t spinner_sketch_gram_static_limit(void);
+int spinner_sketch_gram_static(const float *B, int m, int d, float *G, void *stream);
 
 /*
  * The G_struct D2 H D1 members of the family (Lemma 1 and the remark after it; Theorem 3;

@@ -25,6 +25,7 @@ SPINNER_ERR_HIP = -7
 SPINNER_ERR_BAD_L = -8
 SPINNER_ERR_ALIGNMENT = -9
 SPINNER_ERR_UNSUPPORTED = -10
+SPINNER_ERR_SCRATCH_LIMIT = -11
 
 SPINNER_EPI_NONE = 0
 SPINNER_EPI_COSSIN = 1
@@ -36,7 +37,8 @@ EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_
            "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram",
            "spinner_layer_saved_bytes", "spinner_layer_workspace_bytes", "spinner_layer_forward",
            "spinner_layer_backward", "spinner_sketch_workspace_bytes", "spinner_sketch", "spinner_sketch_gram",
-           "spinner_sketch_gram_workspace_bytes", "spinner_blocks_workspace_bytes", "spinner_apply_blocks",
+           "spinner_sketch_gram_workspace_bytes", "spinner_sketch_gram_static", "spinner_sketch_gram_static_limit",
+           "spinner_blocks_workspace_bytes", "spinner_apply_blocks",
            "spinner_struct_params", "spinner_struct_spectrum_bytes", "spinner_struct_prepare", "spinner_struct_apply"]
 
 if not os.path.exists(LIB_PATH):
@@ -102,6 +104,10 @@ lib.spinner_sketch_gram.restype = ctypes.c_int
 lib.spinner_sketch_gram.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp]
 lib.spinner_sketch_gram_workspace_bytes.restype = ctypes.c_size_t
 lib.spinner_sketch_gram_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
+lib.spinner_sketch_gram_static.restype = ctypes.c_int
+lib.spinner_sketch_gram_static.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp]
+lib.spinner_sketch_gram_static_limit.restype = ctypes.c_size_t
+lib.spinner_sketch_gram_static_limit.argtypes = []
 lib.spinner_blocks_workspace_bytes.restype = ctypes.c_size_t
 lib.spinner_blocks_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_long, ctypes.c_int, ctypes.c_int]
 lib.spinner_apply_blocks.restype = ctypes.c_int
@@ -496,6 +502,25 @@ def spinner_sketch(A, w, d1, d2, d3, m, scale=1.0, out=None, workspace=None, str
     rc = lib.spinner_sketch(A.data_ptr(), n, d, w.data_ptr() if w is not None else None, d1.data_ptr(), d2.data_ptr(),
                             d3.data_ptr(), int(m), ctypes.c_float(scale), out.data_ptr(), workspace.data_ptr(),
                             _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out
+
+
+def spinner_sketch_gram_static_limit() -> int:
+    return int(lib.spinner_sketch_gram_static_limit())
+
+
+def spinner_sketch_gram_static(B, out, stream=None):
+    """G = B^T B into the caller's `out` [d][d]; the call allocates nothing (the library's built-in scratch)."""
+    import torch
+
+    _check_tensor(B, "B", torch.float32)
+    _check_tensor(out, "out", torch.float32)
+    m, d = B.shape
+    if out.numel() != d * d:
+        raise ValueError("out has the wrong size")
+    rc = lib.spinner_sketch_gram_static(B.data_ptr(), m, d, out.data_ptr(), _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out

@@ -91,6 +91,7 @@ const char* spinner_strerror(int status)
     case SPINNER_ERR_BAD_L: return "L must be >= 1";
     case SPINNER_ERR_ALIGNMENT: return "data pointers must be 16-byte aligned";
     case SPINNER_ERR_UNSUPPORTED: return "combination not supported";
+    case SPINNER_ERR_SCRATCH_LIMIT: return "problem needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }
@@ -519,6 +520,23 @@ int spinner_sketch_gram(const float* B, int m, int d, float* G, void* workspace,
     if (!aligned16(B) || !aligned16(G) || !aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
     const hipError_t e = spinner::launch_sketch_gram(B, m, d, G, static_cast<float*>(workspace),
                                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+size_t spinner_sketch_gram_static_limit(void) { return spinner::kGramStaticScratchBytes; }
+
+int spinner_sketch_gram_static(const float* B, int m, int d, float* G, void* stream)
+{
+    if (m < 0 || d < 0) return SPINNER_ERR_BAD_BATCH;
+    if (m == 0 || d == 0) return SPINNER_OK;
+    if (!B || !G) return SPINNER_ERR_NULL_PTR;
+    if (!aligned16(B) || !aligned16(G)) return SPINNER_ERR_ALIGNMENT;
+    if (spinner_sketch_gram_workspace_bytes(m, d) > spinner::kGramStaticScratchBytes) return SPINNER_ERR_SCRATCH_LIMIT;
+    float* slabs = nullptr;
+    hipError_t e = spinner::gram_static_scratch_ptr(&slabs);
+    if (e != hipSuccess) return hip_fail(e);
+    // every slab entry the reduction reads is written by the first kernel of this call: nothing has to start at zero
+    e = spinner::launch_sketch_gram(B, m, d, G, slabs, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 

@@ -183,6 +183,10 @@ hipError_t launch_transpose_scale(const float* src, long long rows, long long co
                                   hipStream_t s);
 int sketch_gram_slabs(int m, int d);      // d x d slabs of scratch the Gram kernel needs (1: none)
 hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* slabs, hipStream_t s);
+// scratch of spinner_sketch_gram_static: a file-scope device array in sketch.hip; gram_static_scratch_ptr gives its
+// address on the current device (looked up on the first call per device, no allocation)
+constexpr size_t kGramStaticScratchBytes = (size_t)16 << 20;
+hipError_t gram_static_scratch_ptr(float** ptr);
 
 // G_struct D2 H D1 members: spectrum of the structured block, FFT convolution (structured.hip)
 hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, hipStream_t s);

@@ -1,5 +1,7 @@
 // Newton-sketch helpers: transposition with optional row weights (the sketch acts on the columns
 // of a row-major data matrix) and the Gram matrix B^T B on the fp32 matrix pipe.
+#include <mutex>
+
 #include "launch.hpp"
 namespace spinner {
 
@@ -165,6 +167,33 @@ int sketch_gram_slabs(int m, int d)
     if (ks > (m + 63) / 64) ks = (m + 63) / 64;
     if (ks > 64) ks = 64;
     return ks < 1 ? 1 : (int)ks;
+}
+
+// Scratch of the entry point that allocates nothing: the slabs of the split sum live in a file-scope device array.
+// Every GPU the library runs on holds its own copy at its own address; in host code the array's name is only a
+// handle, so its device address is asked for once per device (hipGetSymbolAddress with that device current) and
+// kept, and that pointer - never the name - is what reaches the kernels.
+static __device__ __align__(256) unsigned char gram_static_scratch[kGramStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static float* g_scratch_ptr[kMaxDevices];     // device address of gram_static_scratch on each device, once known
+
+hipError_t gram_static_scratch_ptr(float** ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(gram_static_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<float*>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* slabs, hipStream_t s)

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(b):
 def test_version_and_messages(b):
     assert b.spinner_version() >= 100
     assert b.spinner_strerror(0) == "success"
-    for code in range(-10, 0):
+    for code in range(-11, 0):
         msg = b.spinner_strerror(code)
         assert msg and msg != "unknown status"
     assert b.spinner_strerror(-99) == "unknown status"
