@@ -112,6 +112,13 @@ def make_runner(torch, b, W, w, dev, diagonals):
         else:
             def fn():
                 b.spinner_hash(x, ds, out_idx=out)
+    elif w.kind == "blocks":
+        # stacked independent blocks: fp32 diagonals [L][3][n], one call
+        width = (2 if w.epilogue == "cossin" else 1) * w.L * w.m
+        out = torch.empty((w.batch, width), dtype=torch.float32, device=dev)
+
+        def fn():
+            b.spinner_apply_blocks(x, ds, w.m, w.epilogue, w.scale, out=out)
     elif w.kind == "codes":
         out = torch.empty((w.batch, w.m // 64), dtype=torch.int64, device=dev)
         need = b.spinner_codes_workspace_bytes(w.n, w.batch)

@@ -162,7 +162,10 @@ int spinner_hash_signs(const float *x, int n, long batch, int L,
  *                              triple l in columns [l m, (l+1) m) of either block
  *   diag_sets  in   device fp32 [L][3][n], order d1, d2, d3 within a triple
  *   workspace  in   spinner_blocks_workspace_bytes(n, batch, m, epilogue) bytes
- * For L > 1, m must be a multiple of 4.  x is read once per block.  Otherwise as
+ * For L > 1, m must be a multiple of 4.  Up to n = 2^14 the L blocks come from one
+ * kernel launch that reads x once and keeps it in registers while the triples are
+ * applied one after the other (the feature blocks in fp64 as in spinner_apply); above
+ * that size every block runs the four-pass path and reads x again.  Otherwise as
  * spinner_apply (which is the case L = 1).
  */
 size_t spinner_blocks_workspace_bytes(int n, long batch, int m, int epilogue);

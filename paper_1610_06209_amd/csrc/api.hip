@@ -561,6 +561,23 @@ int spinner_apply_blocks(const float* x, int n, long batch, int L, const float* 
     if (!diag_sets) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(diag_sets)) return SPINNER_ERR_ALIGNMENT;
     if (spinner_blocks_workspace_bytes(n, batch, m, epilogue) && !workspace) return SPINNER_ERR_WORKSPACE;
+    if (L > 1 && log2n <= spinner::kBlocksMaxLog) {
+        // one launch: x is read once and stays in registers while the L triples are applied
+        if (batch > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
+        const double factor_d = (double)scale / ((double)n * sqrt((double)n));
+        spinner::TileParams p;
+        memset(&p, 0, sizeof(p));
+        p.x = x; p.out = out; p.batch = batch; p.m = m;
+        p.in_stride = n;
+        p.out_stride = (epilogue == SPINNER_EPI_COSSIN ? 2LL : 1LL) * m * L;
+        p.factor = (float)factor_d;
+        p.factor_rev = factor_d / 6.283185307179586476925286766559;
+        p.inv_sqrt_m = (float)(1.0 / sqrt((double)m * L));
+        p.sin_off = (long long)m * L;
+        const hipError_t e = spinner::launch_blocks(log2n, epilogue == SPINNER_EPI_COSSIN, p, diag_sets, L,
+                                                    static_cast<hipStream_t>(stream));
+        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+    }
     for (int l = 0; l < L; ++l) {
         const float* d = diag_sets + (size_t)l * 3 * n;
         // block l owns columns [l m, (l + 1) m) of the cos part (and of the sin part, L m further on)

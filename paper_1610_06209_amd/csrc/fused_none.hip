@@ -3,12 +3,18 @@
 // round pruned to the rows that are kept (m <= n / 16).
 #include "launch.hpp"
 namespace spinner {
-#define CASE(NT) case NT: return signs ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true>(p, tiles, s) \
-                                       : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false>(p, tiles, s);
+// whole: every tile lies inside the kept rows and output rows are 16-byte aligned: kernels without row-limit tests
+#define CASE(NT) case NT: return signs ? (whole ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true, 0, false>(p, tiles, s)  \
+                                                : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true>(p, tiles, s))            \
+                                       : (whole ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false, 0, false>(p, tiles, s) \
+                                                : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false>(p, tiles, s));
+#define RCASE(NT) case NT: return signs ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true>(p, tiles, s) \
+                                        : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false>(p, tiles, s);
 #define PCASE(NT) case NT: return signs ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true, kPruneBits>(p, tiles, s) \
                                         : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false, kPruneBits>(p, tiles, s);
 hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s)
 {
+    const bool whole = p.m == (1 << log2n) && (p.out_stride & 3) == 0;
     if (prune >= kPruneBits) {
         switch (log2n) {
             PCASE(8) PCASE(9) PCASE(10) PCASE(11) PCASE(12) PCASE(13) PCASE(14)
@@ -17,11 +23,13 @@ hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams&
     }
     switch (log2n) {
         CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14)
-        CASE(15) CASE(16)
+        // 2^15, 2^16: the kernels without row-limit tests measured no faster with sign words and 2-6 % slower with fp32 diagonals
+        RCASE(15) RCASE(16)
     default: return hipErrorInvalidValue;
     }
 }
 #undef CASE
+#undef RCASE
 #undef PCASE
 
 // Lane masks of the sign flips in layout 1 of the wide geometries (n = 2^12 .. 2^14), behind the other words of

@@ -17,7 +17,7 @@ using GeomCodeFrom = TileGeom<NT, clamp_rmax(NT, (TU::rmax < NT - 6 ? (TU::rmax 
 #ifndef SPINNER_CODE_WIDE
 #define SPINNER_CODE_WIDE 0x7000
 #endif
-template <int NT> struct CodeWide { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = 1; };
+template <int NT> struct CodeWide { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = 1, chunk = SPINNER_LANE_CHUNK; };
 template <int NT, bool PRUNED>
 using GeomCode = std::conditional_t<PRUNED, GeomCodeFrom<PrunedTuning<float, NT>, NT>,
                                     std::conditional_t<((SPINNER_CODE_WIDE >> NT) & 1) != 0, GeomFrom<CodeWide<NT>, NT>, GeomCodeFrom<Tuning<float, NT>, NT>>>;

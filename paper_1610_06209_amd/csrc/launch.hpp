@@ -20,7 +20,7 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 #ifndef SPINNER_RMAX_F64
 #define SPINNER_RMAX_F64 5
 #endif
-struct NotWide { static constexpr int wide = 0, start = 0; };
+struct NotWide { static constexpr int wide = 0, start = 0, chunk = SPINNER_LANE_CHUNK; };
 template <typename T, int NT> struct Tuning : NotWide { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0, trips = 0; };
 #ifndef SPINNER_RMAX_F64_N12
 #define SPINNER_RMAX_F64_N12 4
@@ -42,7 +42,7 @@ template <> struct Tuning<float, 14> : NotWide { static constexpr int rmax = 6, 
 template <> struct Tuning<float, 15> : NotWide { static constexpr int rmax = 6, waves = 4, min_waves = 4, trips = 0; };   // 8 waves per tile; 128 registers let two tiles share a compute unit
 template <> struct Tuning<float, 16> : NotWide { static constexpr int rmax = 6, waves = 4, min_waves = 0, trips = 0; };   // 16 waves per tile
 template <typename TU, int NT>
-using GeomFrom = TileGeom<NT, TU::rmax, TU::waves, TU::min_waves, TU::trips, TU::wide, TU::start>;   // wide, start: see WideF32 below
+using GeomFrom = TileGeom<NT, TU::rmax, TU::waves, TU::min_waves, TU::trips, TU::wide, TU::start, TU::chunk>;   // wide, start: see WideF32 below
 template <typename T, int NT>
 using GeomFor = GeomFrom<Tuning<T, NT>, NT>;
 // Fused fp32 kernels with packed sign words for vectors of 2^12 .. 2^14 elements use exchanges that also
@@ -56,7 +56,7 @@ using GeomFor = GeomFrom<Tuning<T, NT>, NT>;
 #ifndef SPINNER_WIDE_START       // layout in which the wide kernels load their tile
 #define SPINNER_WIDE_START 0
 #endif
-template <int NT> struct WideF32 { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = SPINNER_WIDE_START; };
+template <int NT> struct WideF32 { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = SPINNER_WIDE_START, chunk = SPINNER_LANE_CHUNK; };
 template <typename T, int NT>
 using ContigTuning = std::conditional_t<std::is_same<T, float>::value && ((SPINNER_WIDE_F32 >> NT) & 1) != 0, WideF32<NT>, Tuning<T, NT>>;
 template <typename T, int NT>
@@ -65,12 +65,20 @@ using ContigGeomFor = GeomFrom<ContigTuning<T, NT>, NT>;
 // loads fetch the words of one tile): 2^11-element rows then take 32 values per thread instead of 64.
 struct RowSigns11 : NotWide { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 0; };
 constexpr int kRowSignsMinLog = 9;      // shorter rows share a wave: those passes multiply by the fp32 diagonals
+// Fused three-round kernels with fp32 diagonals at n = 2^13, 2^14: 32 values per thread (four / eight waves per tile)
+// and half-size exchange buffers.  With 64 values the diagonal loads of the second and third round do not fit the
+// 128 registers beside the data (the 2^14 kernel spilled); measured in one run: 2^14 0.518 -> 0.483 ms, 2^13 0.438 -> 0.431.
+template <int NT> struct FusedF32DiagTuning : Tuning<float, NT> {};
+template <> struct FusedF32DiagTuning<13> : NotWide { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 2; };
+// eight waves per tile: crossbar lane stages in batches of eight registers keep the kernel at 64 registers (four tiles
+// per compute unit instead of three; 0.479 -> 0.447 ms)
+template <> struct FusedF32DiagTuning<14> { static constexpr int rmax = 5, waves = 4, min_waves = 0, trips = 2, wide = 0, start = 0, chunk = 8; };
 // geometry of the kernels whose last round is pruned (a separate table so that it can be tuned apart)
 template <typename T, int NT> struct PrunedTuning : Tuning<T, NT> {};
 template <typename T, int NT>
 using PrunedGeomFor = GeomFrom<PrunedTuning<T, NT>, NT>;
 
-template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0>
+template <typename T, int NT, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS = false, int PRUNE = 0, bool RAGGED = true>
 inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStream_t stream)
 {
     // wide exchanges pay with packed sign words only: fp32 diagonals read in layout 1 come in 256-byte runs,
@@ -80,13 +88,15 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
 #endif
     constexpr bool kWidePruned = PRUNE > 0 && SIGNS && C >= NT && NSTEPS == 3 && EPI == EPI_STORE_NONE && std::is_same<T, float>::value &&
                                  ((SPINNER_WIDE_PRUNED >> NT) & 1) != 0;
+    constexpr bool kFusedF32Diag = PRUNE == 0 && !SIGNS && C >= NT && NSTEPS == 3 && EPI == EPI_STORE_NONE && std::is_same<T, float>::value;
     using G = std::conditional_t<(PRUNE > 0 && !kWidePruned), PrunedGeomFor<T, NT>,
                                  std::conditional_t<(C >= NT && SIGNS && NSTEPS == 3), ContigGeomFor<T, NT>,
-                                                    std::conditional_t<(SIGNS && NSTEPS < 3 && NT == 11), GeomFrom<RowSigns11, NT>, GeomFor<T, NT>>>>;
+                                                    std::conditional_t<(SIGNS && NSTEPS < 3 && NT == 11), GeomFrom<RowSigns11, NT>,
+                                                                       std::conditional_t<kFusedF32Diag, GeomFrom<FusedF32DiagTuning<NT>, NT>, GeomFor<T, NT>>>>>;
     const long long blocks = (total_tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, PRUNE>), dim3((unsigned)blocks),
+    hipLaunchKernelGGL((spinner_tile_kernel<T, G, C, NSTEPS, FIRST_DIAG, EPI, SIGNS, PRUNE, RAGGED>), dim3((unsigned)blocks),
                        dim3(G::THREADS), 0, stream, p);
     return hipGetLastError();
 }
@@ -108,6 +118,11 @@ hipError_t launch_fused_signbits(int log2n, bool signs, int prune, const TilePar
 hipError_t launch_pack_codes(const float* y, long long y_stride, unsigned long long* codes, int m, long long batch, hipStream_t s);
 hipError_t launch_hamming_gram(const unsigned long long* a, long long na, const unsigned long long* b, long long nb, int m,
                                float* out, hipStream_t s);
+
+// stacked blocks in one launch (blocks.hip): L fp32 triples [L][3][n] applied to a resident copy of x, n <= 2^kBlocksMaxLog;
+// p as for one block (out_stride = the whole row, sin_off = L m, inv_sqrt_m = 1 / sqrt(L m))
+constexpr int kBlocksMaxLog = 14;
+hipError_t launch_blocks(int log2n, bool cossin, const TileParams& p, const float* diag_sets, int L, hipStream_t s);
 
 // sign words per diagonal in the packed format
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }

@@ -157,9 +157,13 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //        lane bits 4, 5 never need a cross-lane butterfly.  Accesses stay 16 bytes per lane in runs of 16 lanes.
 // START_: layout in which a kernel loads its tile (1: a three-round kernel ends in layout 0, where the lanes
 //        hold index bits 2..7 again, which the sign-code epilogue needs)
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0, int TRIPS_ = 0, int WIDE_ = 0, int START_ = 0>
+// CHUNK_: registers exchanged per batch in the lane stages that go through the LDS crossbar (the exchanged copies of one
+//        batch are alive at once, so a smaller batch lowers the register count; 0: all registers at once)
+template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0, int TRIPS_ = 0, int WIDE_ = 0, int START_ = 0,
+          int CHUNK_ = SPINNER_LANE_CHUNK>
 struct TileGeom {
     static constexpr int MIN_WAVES = MINW_;
+    static constexpr int LANE_CHUNK = CHUNK_;
     static constexpr int NT = NT_;
     static_assert(WAVES_1 == 1 || WAVES_1 == 2 || WAVES_1 == 4 || WAVES_1 == 8, "waves per workgroup");
     static_assert(NT >= 4 && NT <= 16, "tile of 2^4 .. 2^16 elements");
@@ -296,14 +300,13 @@ __device__ __forceinline__ void reg_stage(T (&v)[R])
 
 // Exact lane butterfly: the lane with the mask bit clear gets own + partner,
 // the other one partner - own.
-template <int B, int RL = 0, typename T, int RR>
+template <int B, int RL = 0, int CHUNK = SPINNER_LANE_CHUNK, typename T, int RR>
 __device__ __forceinline__ void lane_stage(T (&v)[RR], float sign_own)
 {
     constexpr int R = RL ? RL : RR;
-#if SPINNER_LANE_CHUNK > 0
     // exchange and combine a few registers at a time so that the exchanged copies of
     // only one chunk are alive at once (register pressure decides occupancy here)
-    constexpr int CH = SPINNER_LANE_CHUNK < R ? SPINNER_LANE_CHUNK : R;
+    constexpr int CH = (CHUNK > 0 && CHUNK < R) ? CHUNK : R;
 #pragma unroll
     for (int j0 = 0; j0 < R; j0 += CH) {
         T t[CH];
@@ -313,11 +316,6 @@ __device__ __forceinline__ void lane_stage(T (&v)[RR], float sign_own)
         for (int j = 0; j < CH; ++j) v[j0 + j] = fused_mul_add(v[j0 + j], (T)sign_own, t[j]);
         if (CH < R) __builtin_amdgcn_sched_barrier(0);
     }
-#else
-#pragma unroll
-    for (int j = 0; j < R; ++j)
-        v[j] = fused_mul_add(v[j], (T)sign_own, lane_xor<(1 << B)>(v[j]));
-#endif
 }
 
 // One-instruction lane butterfly for the masks a DPP control can express
@@ -447,7 +445,7 @@ __device__ __forceinline__ void local_stages(T (&v)[G::R], const ThreadCtx<G>& c
             if constexpr (lane_mask_uses_fmac_dpp<T, G::R>(1 << b.value)) {
                 lane_stage_fmac_dpp<b.value>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
             } else {
-                lane_stage<b.value>(v, c.sg[b.value]);
+                lane_stage<b.value, 0, G::LANE_CHUNK>(v, c.sg[b.value]);
             }
         }
     });
@@ -865,7 +863,7 @@ __device__ __forceinline__ void spinner_step_pruned(float (&v)[G::R], const Thre
         if constexpr (lane_mask_uses_fmac_dpp<float, G::R>(1 << b.value))
             lane_stage_fmac_dpp<b.value, RL1>(v, NEGATE ? -c.sg[b.value] : c.sg[b.value]);
         else
-            lane_stage<b.value, RL1>(v, c.sg[b.value]);
+            lane_stage<b.value, RL1, G::LANE_CHUNK>(v, c.sg[b.value]);
     });
     wave_live = true;
     if constexpr (G::WB > 0) {
@@ -905,7 +903,11 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE, EPI_STORE_COSSIN (applied with p.factor, limit p.m) or EPI_STORE_SIGNBITS
 //         (p.out holds 64-bit code words, p.out_stride counts words, p.m is a multiple of 256)
-template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, int PRUNE = 0>
+// RAGGED  false: the caller guarantees that every tile lies entirely inside the kept range [0, m) and that output rows
+//         are 16-byte aligned (EPI_STORE_NONE only); the kernel then has no per-store row-limit test at all.  With the
+//         tests compiled in, the compiler forms their predicates before the rounds and carries them through the
+//         whole kernel (dozens of scalar register pairs, spilled to vector-register lanes and read back at the end).
+template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, int PRUNE = 0, bool RAGGED = true>
 __global__ void __launch_bounds__(G::THREADS)
 __attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_WAVES ? G::MIN_WAVES : (G::WB ? SPINNER_MIN_WAVES_MULTI : SPINNER_MIN_WAVES_PER_EU))))
 spinner_tile_kernel(TileParams p)
@@ -1005,8 +1007,9 @@ spinner_tile_kernel(TileParams p)
             // whole tile inside the kept range and rows 16-byte aligned: no per-store checks
             // (with a pruned last round, lanes whose pruned bits are set hold nothing to store)
             constexpr bool LANES_PRUNED = PRUNE > 0 && (prune_positions<G>(PRUNE) & lane_positions<G>(LAYF)) != 0;
-            const bool full = !LANES_PRUNED && (tile_first + tile_offset<NT, C>((1 << (NT - PRUNE)) - 1, p.sl) < m) &&
-                              ((p.out_stride & 3) == 0);
+            static_assert(RAGGED || (EPI == EPI_STORE_NONE && !LANES_PRUNED), "kernels without row-limit tests: plain stores of whole tiles");
+            const bool full = !RAGGED || (!LANES_PRUNED && (tile_first + tile_offset<NT, C>((1 << (NT - PRUNE)) - 1, p.sl) < m) &&
+                                          ((p.out_stride & 3) == 0));
             float* dst = p.out + vec * p.out_stride;
             if constexpr (EPI == EPI_STORE_NONE) {
                 if (full) {

@@ -66,6 +66,9 @@ NEXT = {
     # Angular-kernel sign codes (Section 5) on the shape of the random-feature configuration.
     "next_angular_n4096": Workload("next_angular_n4096", "codes", 4096, 131072, 4096, "signbits", 1.0, 1,
                                    "mixture64", BASE_SEED + 6, 128),
+    # k = 4 n random features from four stacked independent blocks (Section 3.2, Section 5), on the mixture of cfg3.
+    "next_blocks_n4096_L4": Workload("next_blocks_n4096_L4", "blocks", 4096, 32768, 4096, "cossin", 64.0, 4,
+                                     "mixture64", BASE_SEED + 7, 64),
 }
 
 
@@ -201,6 +204,8 @@ def algorithmic_bytes_per_vector(w: Workload) -> int:
     if w.kind == "codes":                       # one bit per kept coordinate leaves the chip
         return 4 * n + w.m // 8
     out = 8 * w.m if w.epilogue == "cossin" else 4 * w.m
+    if w.kind == "blocks":                      # x once, L blocks of output
+        return 4 * n + out * w.L
     return 4 * n + out
 
 
@@ -209,7 +214,7 @@ def schedule_bytes_per_vector(w: Workload) -> int:
     the algorithmic bytes while one fused kernel serves n; above that the four-pass schedule moves the vector four
     times (three of the trips are meant to stay in the memory-side cache), and sign codes take a fifth read."""
     n = w.n
-    if w.kind == "hash" or n <= fused_max_n("none" if w.kind == "codes" else w.epilogue):
+    if w.kind in ("hash", "blocks") or n <= fused_max_n("none" if w.kind == "codes" else w.epilogue):
         return algorithmic_bytes_per_vector(w)
     if w.kind == "codes":
         return 4 * 8 * n + 4 * n + w.m // 8
