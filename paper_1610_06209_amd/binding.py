@@ -11,8 +11,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# SPINNER_LIB lets a tuning run point the binding at another build of the same library
-LIB_PATH = os.environ.get("SPINNER_LIB") or os.path.join(_HERE, "libspinner.so")
+LIB_PATH = os.path.join(_HERE, "libspinner.so")
 
 SPINNER_OK = 0
 SPINNER_ERR_BAD_N = -1

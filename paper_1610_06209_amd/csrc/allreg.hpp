@@ -29,15 +29,12 @@ struct HashArGeom {
     static_assert(WAVES * TPW * VEC_WORDS * 4 <= 65536, "exchange buffers of a workgroup");
 };
 
-#ifndef SPINNER_AR_FENCE_SCOPE     // tuning experiments: scope of the fences between the two sides of an exchange
-#define SPINNER_AR_FENCE_SCOPE "workgroup"
-#endif
 __device__ __forceinline__ void wave_lds_fence()
 {
     // orders this wave's LDS writes before its later LDS reads (the buffer is private to the wave)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, SPINNER_AR_FENCE_SCOPE, "local");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, SPINNER_AR_FENCE_SCOPE, "local");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // Where a thread finds its elements in the wave's exchange buffer `w` (start of its vector's words):

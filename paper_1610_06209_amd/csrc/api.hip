@@ -170,10 +170,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     // three intermediate trips of a slice find it in the 256 MB memory-side cache (measured
     // 20 % faster than pass-by-pass over the whole batch; slices of 340 MiB are already as slow
     // as that, smaller ones lose 1 % at 224 MiB, 2 % at 192, 6 % at 128).
-    long long slice_bytes = 256LL << 20;
-#ifdef SPINNER_TUNING_HOOKS
-    if (const char* e = getenv("SPINNER_SLICE_MIB")) slice_bytes = (long long)atoi(e) << 20;
-#endif
+    const long long slice_bytes = 256LL << 20;
     long long slice = slice_bytes / (4LL * n);
     if (slice < 8) slice = 8;          // very long vectors: keep enough tiles per launch to fill the chip
     if (slice > batch) slice = batch;

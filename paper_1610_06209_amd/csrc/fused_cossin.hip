@@ -189,18 +189,13 @@ spinner_feature_ar_kernel(TileParams p)
     }
 }
 
-#ifndef SPINNER_FEAT_AR_WAVES       // waves per workgroup (each wave owns its vectors and its exchange buffer)
-#define SPINNER_FEAT_AR_WAVES 1
-#endif
-
-#ifndef SPINNER_FEAT_AR_FP32        // 0: with fp32 diagonals the feature map of these sizes stays on the tile kernel (tuning experiments)
-#define SPINNER_FEAT_AR_FP32 1
-#endif
+// one wave per workgroup (each wave owns its vectors and its exchange buffer): measured 3-4 % faster than two
+constexpr int kFeatureArWaves = 1;
 template <int NT, bool SIGNS>
 static hipError_t launch_cossin(const TileParams& p, long long tiles, hipStream_t s)
 {
-    if constexpr (feature_ar_log2r(NT) != 0 && (SIGNS || SPINNER_FEAT_AR_FP32)) {
-        using GA = HashArGeom<NT, feature_ar_log2r(NT), SPINNER_FEAT_AR_WAVES>;
+    if constexpr (feature_ar_log2r(NT) != 0) {
+        using GA = HashArGeom<NT, feature_ar_log2r(NT), kFeatureArWaves>;
         const long long blocks = (tiles + GA::VECS_PER_WG - 1) / GA::VECS_PER_WG;
         if (blocks <= 0) return hipSuccess;
         if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;

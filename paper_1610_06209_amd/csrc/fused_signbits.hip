@@ -6,21 +6,15 @@
 namespace spinner {
 // The epilogue needs a whole wave per 256 coordinates (six lane bits per tile), so the
 // values per thread are capped at n / 64.
-#ifndef SPINNER_CODE_RMAX       // tuning experiments: cap on the values per thread (log2) of the sign-code kernels
-#define SPINNER_CODE_RMAX 6
-#endif
 template <typename TU, int NT>
-using GeomCodeFrom = TileGeom<NT, clamp_rmax(NT, (TU::rmax < NT - 6 ? (TU::rmax < SPINNER_CODE_RMAX ? TU::rmax : SPINNER_CODE_RMAX) : NT - 6)),
+using GeomCodeFrom = TileGeom<NT, clamp_rmax(NT, (TU::rmax < NT - 6 ? TU::rmax : NT - 6)),
                               TU::waves, TU::min_waves, TU::trips>;
 // Without pruning, n = 2^12 .. 2^14 take the wide exchanges of the plain kernels, loading in layout 1 so that
 // the three rounds end in layout 0, where a wave's lanes hold index bits 2..7 (one code word per register).
-#ifndef SPINNER_CODE_WIDE
-#define SPINNER_CODE_WIDE 0x7000
-#endif
-template <int NT> struct CodeWide { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = 1, chunk = SPINNER_LANE_CHUNK; };
+template <int NT> struct CodeWide { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = 1, chunk = kLaneChunk; };
 template <int NT, bool PRUNED>
 using GeomCode = std::conditional_t<PRUNED, GeomCodeFrom<PrunedTuning<float, NT>, NT>,
-                                    std::conditional_t<((SPINNER_CODE_WIDE >> NT) & 1) != 0, GeomFrom<CodeWide<NT>, NT>, GeomCodeFrom<Tuning<float, NT>, NT>>>;
+                                    std::conditional_t<has_wide_words(NT), GeomFrom<CodeWide<NT>, NT>, GeomCodeFrom<Tuning<float, NT>, NT>>>;
 
 template <int NT, bool SIGNS, int PRUNE>
 static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStream_t stream)

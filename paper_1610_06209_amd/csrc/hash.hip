@@ -1,11 +1,10 @@
 // Cross-polytope hash kernels, n = 2^4 .. 2^14.
 #include "launch.hpp"
 #include "allreg.hpp"
-#ifndef SPINNER_HASH_RMAX      // values per thread (log2) of the hash kernels: 32 values leave room for four waves per
-                               // SIMD beside the resident copy of x (measured 16 % faster than 64 at n = 1024, L = 16)
-#define SPINNER_HASH_RMAX 5
-#endif
 namespace spinner {
+// values per thread (log2) of the hash kernels: 32 values leave room for four waves per SIMD beside the resident
+// copy of x (measured 16 % faster than 64 at n = 1024, L = 16)
+constexpr int kHashRmax = 5;
 
 template <typename G>
 __device__ __forceinline__ void hash_ar_stages(float (&v)[G::R])
@@ -176,7 +175,7 @@ static hipError_t launch_hash_nt(const HashParams& p, hipStream_t s)
         hipLaunchKernelGGL((spinner_hash_ar_kernel<GA>), dim3((unsigned)blocks), dim3(GA::THREADS), 0, s, p);
         return hipGetLastError();
     }
-    using G = TileGeom<NT, clamp_rmax(NT, SPINNER_HASH_RMAX)>;
+    using G = TileGeom<NT, clamp_rmax(NT, kHashRmax)>;
     const long long blocks = (p.batch + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;

@@ -1,8 +1,6 @@
 // Host-side launch helpers shared by the translation units that instantiate
 // the kernels (split only to compile them in parallel).
 #pragma once
-#include <stdlib.h>
-
 #include "spinner_kernels.hpp"
 
 namespace spinner {
@@ -16,16 +14,10 @@ constexpr int kFusedMaxLogOther = 14;     // fp64 feature map, hash
 // Registers per thread (2^rmax values) and waves per workgroup for each tile
 // size, from timing sweeps on MI355X: fewer registers per thread buy occupancy
 // (more waves to hide HBM latency) at the price of more lane / LDS stages.
-// fp64 butterflies keep 32 values per thread (64 registers).
-#ifndef SPINNER_RMAX_F64
-#define SPINNER_RMAX_F64 5
-#endif
-struct NotWide { static constexpr int wide = 0, start = 0, chunk = SPINNER_LANE_CHUNK; };
-template <typename T, int NT> struct Tuning : NotWide { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, SPINNER_RMAX_F64) : 6, waves = 4, min_waves = 0, trips = 0; };
-#ifndef SPINNER_RMAX_F64_N12
-#define SPINNER_RMAX_F64_N12 4
-#endif
-template <> struct Tuning<double, 12> : NotWide { static constexpr int rmax = SPINNER_RMAX_F64_N12, waves = 4, min_waves = 0, trips = 0; };
+// fp64 butterflies keep 32 values per thread (64 registers), 16 at n = 2^12.
+struct NotWide { static constexpr int wide = 0, start = 0, chunk = kLaneChunk; };
+template <typename T, int NT> struct Tuning : NotWide { static constexpr int rmax = std::is_same<T, double>::value ? clamp_rmax(NT, 5) : 6, waves = 4, min_waves = 0, trips = 0; };
+template <> struct Tuning<double, 12> : NotWide { static constexpr int rmax = 4, waves = 4, min_waves = 0, trips = 0; };
 template <> struct Tuning<float, 4> : NotWide { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
 template <> struct Tuning<float, 5> : NotWide { static constexpr int rmax = 2, waves = 4, min_waves = 0, trips = 0; };
 template <> struct Tuning<float, 6> : NotWide { static constexpr int rmax = 3, waves = 4, min_waves = 0, trips = 0; };
@@ -50,15 +42,10 @@ using GeomFor = GeomFrom<Tuning<T, NT>, NT>;
 // 32 values per thread on two waves at 2^12, 64 values held to 128 registers on two / four waves at 2^13 / 2^14.
 // Measured against the tables above: 2^12 0.374 -> 0.345 ms (the copy kernel's time), 2^13 -8 %, 2^14 -2 to -4 %;
 // no gain for fp64 butterflies, which keep the narrow exchanges.
-#ifndef SPINNER_WIDE_F32         // bit N set: fp32 contiguous tiles of 2^N elements use wide exchanges (tuning experiments)
-#define SPINNER_WIDE_F32 0x7000
-#endif
-#ifndef SPINNER_WIDE_START       // layout in which the wide kernels load their tile
-#define SPINNER_WIDE_START 0
-#endif
-template <int NT> struct WideF32 { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = SPINNER_WIDE_START, chunk = SPINNER_LANE_CHUNK; };
+constexpr bool has_wide_words(int log2n) { return log2n >= 12 && log2n <= 14; }      // sizes of the wide geometries
+template <int NT> struct WideF32 { static constexpr int rmax = NT >= 13 ? 6 : 5, waves = 4, min_waves = NT >= 13 ? 4 : 0, trips = 2, wide = 1, start = 0, chunk = kLaneChunk; };
 template <typename T, int NT>
-using ContigTuning = std::conditional_t<std::is_same<T, float>::value && ((SPINNER_WIDE_F32 >> NT) & 1) != 0, WideF32<NT>, Tuning<T, NT>>;
+using ContigTuning = std::conditional_t<std::is_same<T, float>::value && has_wide_words(NT), WideF32<NT>, Tuning<T, NT>>;
 template <typename T, int NT>
 using ContigGeomFor = GeomFrom<ContigTuning<T, NT>, NT>;
 // Row passes of the four-pass schedule that flip signs by packed words need one tile per wave (a wave's scalar
@@ -83,11 +70,10 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
 {
     // wide exchanges pay with packed sign words only: fp32 diagonals read in layout 1 come in 256-byte runs,
     // which measured 2-5 % slower than the narrow exchange (also for the row passes of the four-pass schedule)
-#ifndef SPINNER_WIDE_PRUNED      // bit N set: the sign-word kernels of 2^N elements with a pruned last round use wide exchanges too
-#define SPINNER_WIDE_PRUNED 0x7000   // (first n/16 rows: 2^12 0.494 -> 0.451 ms, 2^13 0.528 -> 0.490, 2^14 0.545 -> 0.524)
-#endif
+    // the sign-word kernels with a pruned last round use the wide exchanges too
+    // (first n/16 rows: 2^12 0.494 -> 0.451 ms, 2^13 0.528 -> 0.490, 2^14 0.545 -> 0.524)
     constexpr bool kWidePruned = PRUNE > 0 && SIGNS && C >= NT && NSTEPS == 3 && EPI == EPI_STORE_NONE && std::is_same<T, float>::value &&
-                                 ((SPINNER_WIDE_PRUNED >> NT) & 1) != 0;
+                                 has_wide_words(NT);
     constexpr bool kFusedF32Diag = PRUNE == 0 && !SIGNS && C >= NT && NSTEPS == 3 && EPI == EPI_STORE_NONE && std::is_same<T, float>::value;
     using G = std::conditional_t<(PRUNE > 0 && !kWidePruned), PrunedGeomFor<T, NT>,
                                  std::conditional_t<(C >= NT && SIGNS && NSTEPS == 3), ContigGeomFor<T, NT>,
@@ -128,25 +114,15 @@ hipError_t launch_blocks(int log2n, bool cossin, const TileParams& p, const floa
 inline long long sign_words_per_diag(int n) { return n / 64 < 4 ? 4 : n / 64; }
 // Sizes whose hash kernel keeps every butterfly between registers (hash.hip) take, behind the three diagonals'
 // sign words of a triple, the lane masks of that kernel's two layouts: [3 diagonals][2 layouts][2^r words].
-#ifndef SPINNER_HASH_AR_SIZES     // bit N set: n = 2^N is hashed by that kernel (tuning experiments)
-#define SPINNER_HASH_AR_SIZES 0x500
-#endif
-constexpr int hash_ar_log2r(int log2n)      // values per thread (log2); 0: size not covered
+constexpr int hash_ar_log2r(int log2n)      // values per thread (log2) at n = 2^8 and 2^10; 0: size not covered
 {
-    return (log2n >= 8 && log2n <= 11 && ((SPINNER_HASH_AR_SIZES >> log2n) & 1)) ? (log2n >= 10 ? 5 : 4) : 0;
+    return log2n == 8 ? 4 : (log2n == 10 ? 5 : 0);
 }
 // The fp64 feature map has such a kernel too (fused_cossin.hip), for n = 2^(2r), and reads the same lane masks.
-#ifndef SPINNER_FEATURE_AR_SIZES  // bit N set: the sign-word feature map of n = 2^N runs on that kernel (tuning experiments)
-#define SPINNER_FEATURE_AR_SIZES 0x1000
-#endif
-constexpr int feature_ar_log2r(int log2n)
-{
-    return (log2n >= 8 && log2n <= 12 && !(log2n & 1) && ((SPINNER_FEATURE_AR_SIZES >> log2n) & 1)) ? log2n / 2 : 0;
-}
+constexpr int feature_ar_log2r(int log2n) { return log2n == 12 ? 6 : 0; }
 constexpr int ar_log2r(int log2n) { return hash_ar_log2r(log2n) ? hash_ar_log2r(log2n) : feature_ar_log2r(log2n); }
 // n = 2^12 .. 2^14: the wide geometries flip signs in a layout whose lane masks are no words of the packed format;
 // they follow as a block of their own, [3 diagonals][n / 64 words], word (wave << r) | register (fused_none.hip).
-constexpr bool has_wide_words(int log2n) { return log2n >= 12 && log2n <= 14; }
 inline long long wide_words_offset(int n, int log2n)      // from a triple's first sign word
 {
     return 3 * sign_words_per_diag(n) + (ar_log2r(log2n) ? 6LL << ar_log2r(log2n) : 0);
@@ -162,11 +138,7 @@ struct ColShape { int rows_log, contig_log; };
 inline ColShape col_shape_for(int log2n)
 {
     // rows_log grows only as far as needed to keep a row (n / rows elements) within 2^14
-    ColShape cs = log2n <= 21 ? ColShape{7, 5} : (log2n == 22 ? ColShape{8, 5} : (log2n == 23 ? ColShape{9, 5} : ColShape{10, 4}));
-#ifdef SPINNER_TUNING_HOOKS
-    if (const char* e = getenv("SPINNER_COL_SHAPE")) { cs.rows_log = e[0] - '0'; if (e[1] >= '0' && e[1] <= '9') { cs.rows_log = cs.rows_log * 10 + (e[1] - '0'); e++; } cs.contig_log = e[2] - '0'; }
-#endif
-    return cs;
+    return log2n <= 21 ? ColShape{7, 5} : (log2n == 22 ? ColShape{8, 5} : (log2n == 23 ? ColShape{9, 5} : ColShape{10, 4}));
 }
 
 // n > 2^14 (sizes that the four-pass schedule serves): that schedule multiplies by the second diagonal in column

@@ -53,10 +53,8 @@ static long long slots_nt(long long batch)
     using G = LayerGeom<NT>;
     // four workgroups for each of the 256 compute units (as many as the kernel's registers let a compute unit hold
     // where it is compiled for a given number of waves per SIMD), fewer when the batch is small
-#ifndef SPINNER_LAYER_WGS32     // workgroups of the backward kernels with 32 values per thread (two waves per SIMD: 512 are resident)
-#define SPINNER_LAYER_WGS32 512
-#endif
-    long long wgs = (G::R == 16 && G::WB > 0) ? 256 * 4 * SPINNER_LAYER_BWD_WAVES / G::WAVES : (G::R == 32 ? SPINNER_LAYER_WGS32 : 1024);
+    // (32 values per thread: two waves per SIMD, 512 workgroups are resident)
+    long long wgs = (G::R == 16 && G::WB > 0) ? 256 * 4 * kLayerBackwardWaves / G::WAVES : (G::R == 32 ? 512 : 1024);
     const long long need = (batch + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (wgs > need) wgs = need;
     // small vectors put many tiles into one workgroup: keep the number of partial rows bounded

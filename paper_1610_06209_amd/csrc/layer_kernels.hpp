@@ -9,13 +9,12 @@
 // Backward, with t1 = H_u dy, t2 = H_u D3 t1, t3 = H_u D2 t2 and c = scale n^{-3/2}:
 //   dD3 = c sum_b t1 * saved2,  dD2 = c sum_b t2 * saved1,  dD1 = c sum_b t3 * x,  dx = c D1 t3.
 #pragma once
-#ifndef SPINNER_LAYER_BWD_WAVES     // waves per SIMD that the backward kernel of tiles of several waves, 16 values per thread, is compiled for
-#define SPINNER_LAYER_BWD_WAVES 3
-#endif
 #include "layer_params.hpp"
 #include "spinner_kernels.hpp"
 
 namespace spinner {
+// waves per SIMD that the backward kernel of tiles of several waves, 16 values per thread, is compiled for
+constexpr int kLayerBackwardWaves = 3;
 
 // `base` must be readable also for a tile past the end of the batch (the callers pass the first vector then and
 // store nothing): loads under a condition end up in a branch each, with waits where the branches join
@@ -126,22 +125,18 @@ __global__ void __launch_bounds__(G::THREADS) layer_forward_kernel(LayerForwardP
 // Slot s (one tile position of one workgroup) handles vectors s, s + slots, s + 2 slots, ... and
 // keeps its three per-coordinate sums in registers; they are written once at the end.
 template <typename G>
-__global__ void __launch_bounds__(G::THREADS) __attribute__((amdgpu_waves_per_eu((G::R == 16 && G::WB > 0) ? SPINNER_LAYER_BWD_WAVES : (G::R == 32 ? 2 : 1))))
+__global__ void __launch_bounds__(G::THREADS) __attribute__((amdgpu_waves_per_eu((G::R == 16 && G::WB > 0) ? kLayerBackwardWaves : (G::R == 32 ? 2 : 1))))
 layer_backward_kernel(LayerBackwardParams p)
 {
     constexpr int NT = G::NT;
     constexpr int n = 1 << NT;
     constexpr int R = G::R;
     constexpr int L1 = G::layout_after(1), L2 = G::layout_after(2), L3 = G::layout_after(3);
-#ifndef SPINNER_LAYER_GROUPED_DIAG  // 1: with 32 values per thread the backward kernel loads a diagonal's entries together (tuning experiments)
-#define SPINNER_LAYER_GROUPED_DIAG 1
-#endif
-#ifndef SPINNER_LAYER_PREFETCH      // 0: the backward kernel loads nothing ahead (tuning experiments)
-#define SPINNER_LAYER_PREFETCH 1
-#endif
+    // with 32 values per thread the loads of a diagonal are issued together, ahead of its products
+    constexpr bool GROUPED_DIAG = R >= 32;
     // (tiles of several waves, n = 2^11 .. 2^14: measured -7 % at n = 2^12, -29 % at 2^13, -20 % at 2^14; with fewer
     // values per thread nothing is gained, with 16 on one wave the registers for it are not there)
-    constexpr bool PREFETCH = (R == 16 || R == 32) && G::WB > 0 && SPINNER_LAYER_PREFETCH != 0;
+    constexpr bool PREFETCH = (R == 16 || R == 32) && G::WB > 0;
     ThreadCtx<G> c;
     long long slot;
     layer_ctx(c, slot);
@@ -171,7 +166,7 @@ layer_backward_kernel(LayerBackwardParams p)
             if (active) tile_fma<R>(acc3, g, ta);
             tile_load<G, L2>(ta, c, p.saved1 + off);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (SPINNER_LAYER_GROUPED_DIAG && R >= 32) {
+            if constexpr (GROUPED_DIAG) {
                 tile_scale<G, L1, true>(g, c, p.d[2]);
                 spinner_step<G, NT, 0, L1, false, false, true, false>(g, c, nullptr, nullptr, 0, lds);
             } else {
@@ -180,7 +175,7 @@ layer_backward_kernel(LayerBackwardParams p)
             if (active) tile_fma<R>(acc2, g, ta);
             tile_load<G, L3>(ta, c, p.x + off);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (SPINNER_LAYER_GROUPED_DIAG && R >= 32) {
+            if constexpr (GROUPED_DIAG) {
                 tile_scale<G, L2, true>(g, c, p.d[1]);
                 spinner_step<G, NT, 0, L2, false, false, false, false>(g, c, nullptr, nullptr, 0, lds);
             } else {

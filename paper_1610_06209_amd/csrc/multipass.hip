@@ -36,9 +36,6 @@ hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long 
 hipError_t launch_col_middle(int rows_log, int contig_log, bool signs, const TileParams& p, long long tiles, hipStream_t s)
 {
     COLMID(12, 5) COLMID(13, 5) COLMID(14, 5) COLMID(14, 4)
-#ifdef SPINNER_TUNING_HOOKS
-    COLMID(12, 4) COLMID(12, 6) COLMID(13, 6)
-#endif
     return hipErrorInvalidValue;
 }
 #undef COLMID
@@ -83,9 +80,6 @@ hipError_t launch_pack_col_words(const float* diag_sets, int log2n, int L, unsig
     const long long blocks = (total + 3) / 4;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     COLPACK(12, 5) COLPACK(13, 5) COLPACK(14, 5) COLPACK(14, 4)
-#ifdef SPINNER_TUNING_HOOKS
-    COLPACK(12, 4) COLPACK(12, 6) COLPACK(13, 6)
-#endif
     return hipErrorInvalidValue;
 }
 #undef COLPACK
@@ -102,9 +96,6 @@ hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TilePara
     COLCASE(13, 5, 1, EPI_STORE_NONE)
     COLCASE(14, 5, 1, EPI_STORE_NONE)
     COLCASE(14, 4, 1, EPI_STORE_NONE)
-#ifdef SPINNER_TUNING_HOOKS
-    COLCASE(12, 4, 1, EPI_STORE_NONE) COLCASE(12, 6, 1, EPI_STORE_NONE) COLCASE(13, 6, 1, EPI_STORE_NONE)
-#endif
     return hipErrorInvalidValue;
 }
 #undef COLCASE

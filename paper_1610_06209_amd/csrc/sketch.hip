@@ -160,10 +160,8 @@ __global__ void __launch_bounds__(256) gram_reduce_kernel(const float* __restric
 int sketch_gram_slabs(int m, int d)
 {
     const long long tiles = (long long)((d + kGramBlock - 1) / kGramBlock) * ((d + kGramBlock - 1) / kGramBlock);
-#ifndef SPINNER_GRAM_WGS       // workgroups aimed at when the sum over k is split (tuning experiments)
-#define SPINNER_GRAM_WGS 256
-#endif
-    long long ks = (SPINNER_GRAM_WGS + tiles - 1) / tiles;
+    constexpr int kGramWorkgroups = 256;      // workgroups aimed at when the sum over k is split (128 .. 1024 measured alike)
+    long long ks = (kGramWorkgroups + tiles - 1) / tiles;
     if (ks > (m + 63) / 64) ks = (m + 63) / 64;
     if (ks > 64) ks = 64;
     return ks < 1 ? 1 : (int)ks;

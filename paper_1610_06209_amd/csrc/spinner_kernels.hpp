@@ -21,45 +21,13 @@
 #include <stdint.h>
 #include <type_traits>
 
-// Tuning knobs (defaults are the measured best on MI355X).
-#ifndef SPINNER_WAVES_PER_WG          // waves per workgroup when a tile fits one wave
-#define SPINNER_WAVES_PER_WG 4
-#endif
-#ifndef SPINNER_MIN_WAVES_PER_EU      // occupancy the register allocator must allow for one-wave tiles
-#define SPINNER_MIN_WAVES_PER_EU 1
-#endif
-#ifndef SPINNER_MIN_WAVES_MULTI       // the same for fp32 tiles that span several waves
-#define SPINNER_MIN_WAVES_MULTI 1
-#endif
-#ifndef SPINNER_LANE_CHUNK            // registers exchanged per batch in swizzle / bpermute stages (0: all at once)
-#define SPINNER_LANE_CHUNK 32
-#endif
-#ifndef SPINNER_LDS_HALVES           // 2: transposes go through an LDS buffer of half a tile, in two trips
-#define SPINNER_LDS_HALVES 1
-#endif
-#ifndef SPINNER_SYNC_AFTER_READ      // 1: the barrier that protects the LDS buffer from the next writers sits right
-#define SPINNER_SYNC_AFTER_READ 1    //    after the reads (waves are still in step there) instead of before the next writes
-#endif
-#ifndef SPINNER_LANE_SWAPS           // 1: in tiles that span several waves, lane bits 4 and 5 are transformed by swapping
-#define SPINNER_LANE_SWAPS 1         //    lane halves with register pairs (vector ALU) instead of LDS-crossbar exchanges
-#endif
-#ifndef SPINNER_MASK4_DPP            // 1: the lane exchange across lane bit 2 uses two bank-masked DPP row shifts instead of ds_swizzle
-#define SPINNER_MASK4_DPP 0
-#endif
-#ifndef SPINNER_DPP_MASKS            // lane masks (of 1, 2, 8) whose butterflies use the one-instruction DPP form; the
-#define SPINNER_DPP_MASKS 0xB        // others go through the LDS crossbar (tuning experiments)
-#endif
-#ifndef SPINNER_MASK_PREFETCH        // lane masks of the next step's sign flips fetched before the current step's exchange
-#define SPINNER_MASK_PREFETCH 16     // (each takes two scalar registers)
-#endif
-#ifndef SPINNER_STREAM_PASSES        // four-pass schedule: bit 0 non-temporal loads in the first pass, bit 1 non-temporal stores and
-#define SPINNER_STREAM_PASSES 7      // bit 2 non-temporal loads in the last pass (measured: 1 alone +2-3 % at n = 2^17..2^20,
-#endif                               // all three +0.4 / 4 / 2.4 / 3.4 %; 5 and 4 alone lose)
-#ifndef SPINNER_STREAMING            // 1: non-temporal loads of x / stores of out in fused kernels
-#define SPINNER_STREAMING 1
-#endif
-
 namespace spinner {
+
+// Fixed choices, each the best of a timing sweep on MI355X.
+constexpr int kWavesPerWorkgroup = 4;     // waves per workgroup when a tile fits one wave
+constexpr int kLaneChunk = 32;            // registers exchanged per batch in the lane stages that cross the LDS crossbar
+constexpr int kMaskPrefetch = 16;         // lane masks of the next step's sign flips fetched before the current step's exchange
+                                          // (each takes two scalar registers)
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -106,15 +74,8 @@ __device__ __forceinline__ float lane_xor(float v)
         t = __builtin_amdgcn_update_dpp(0, s, 0x4E, 0xF, 0xF, true);
     else if constexpr (MASK == 8)   // row_ror:8 (rotation by half a 16-lane row)
         t = __builtin_amdgcn_update_dpp(0, s, 0x128, 0xF, 0xF, true);
-    else if constexpr (MASK == 4) { // swizzle, bit mode: and=0x1f or=0 xor=4
-#if SPINNER_MASK4_DPP
-        // two bank-masked row shifts: banks 1, 3 take the lane four below, banks 0, 2 the lane four above
-        t = __builtin_amdgcn_update_dpp(0, s, 0x114, 0xF, 0xA, false);
-        t = __builtin_amdgcn_update_dpp(t, s, 0x104, 0xF, 0x5, false);
-#else
+    else if constexpr (MASK == 4)   // swizzle, bit mode: and=0x1f or=0 xor=4
         t = __builtin_amdgcn_ds_swizzle(s, (4 << 10) | 0x1F);
-#endif
-    }
     else if constexpr (MASK == 16)  // swizzle, bit mode: xor=16
         t = __builtin_amdgcn_ds_swizzle(s, (16 << 10) | 0x1F);
     else {                          // MASK == 32: crosses the 32-lane halves
@@ -159,8 +120,8 @@ __device__ __forceinline__ double fused_mul_add(double a, double b, double c) { 
 //        hold index bits 2..7 again, which the sign-code epilogue needs)
 // CHUNK_: registers exchanged per batch in the lane stages that go through the LDS crossbar (the exchanged copies of one
 //        batch are alive at once, so a smaller batch lowers the register count; 0: all registers at once)
-template <int NT_, int RMAX = 6, int WAVES_1 = SPINNER_WAVES_PER_WG, int MINW_ = 0, int TRIPS_ = 0, int WIDE_ = 0, int START_ = 0,
-          int CHUNK_ = SPINNER_LANE_CHUNK>
+template <int NT_, int RMAX = 6, int WAVES_1 = kWavesPerWorkgroup, int MINW_ = 0, int TRIPS_ = 0, int WIDE_ = 0, int START_ = 0,
+          int CHUNK_ = kLaneChunk>
 struct TileGeom {
     static constexpr int MIN_WAVES = MINW_;
     static constexpr int LANE_CHUNK = CHUNK_;
@@ -177,10 +138,7 @@ struct TileGeom {
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
     // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
     // (tiles above 2^14 elements always take as many trips as keep the buffer at 64 KiB)
-#ifndef SPINNER_N16_TRIPS      // trips per exchange of a tile of 2^16 elements: 4 (64 KiB buffer) or 2 (128 KiB of the 160 KiB)
-#define SPINNER_N16_TRIPS 4
-#endif
-    static constexpr int LDS_HALVES = NT_ == 16 ? SPINNER_N16_TRIPS : NT_ > 14 ? (1 << (NT_ - 14)) : (((SPINNER_LDS_HALVES == 2 || TRIPS_ == 2) && WB >= 1) ? 2 : 1);
+    static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : ((TRIPS_ == 2 && WB >= 1) ? 2 : 1);
     static constexpr int LDS_FLOAT4 = WB > 0 ? ((1 << NT_) / 4) / LDS_HALVES : 1;
     static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
@@ -206,7 +164,7 @@ struct TileGeom {
     }
     // "Swapped" state of a tile (see lane_swap_stages): physical register bits 2, 3 hold the index
     // bits of lane bits 4, 5 (positions 6, 7) and the lanes hold the index bits of register bits 2, 3.
-    static constexpr bool LANE_SWAPS = SPINNER_LANE_SWAPS != 0 && WB > 0 && LB == 6 && r >= 4 && !WIDE;
+    static constexpr bool LANE_SWAPS = WB > 0 && LB == 6 && r >= 4 && !WIDE;
     static constexpr int reg_index_sw(int lay, int j)
     {
         int e = 0;
@@ -300,7 +258,7 @@ __device__ __forceinline__ void reg_stage(T (&v)[R])
 
 // Exact lane butterfly: the lane with the mask bit clear gets own + partner,
 // the other one partner - own.
-template <int B, int RL = 0, int CHUNK = SPINNER_LANE_CHUNK, typename T, int RR>
+template <int B, int RL = 0, int CHUNK = kLaneChunk, typename T, int RR>
 __device__ __forceinline__ void lane_stage(T (&v)[RR], float sign_own)
 {
     constexpr int R = RL ? RL : RR;
@@ -374,7 +332,7 @@ __device__ __forceinline__ void fmac_dpp_block8(float* a, float coef)
 template <typename T, int R>
 constexpr bool lane_mask_uses_fmac_dpp(int mask)
 {
-    return std::is_same<T, float>::value && R >= 8 && (mask == 1 || mask == 2 || mask == 8) && (SPINNER_DPP_MASKS & mask);
+    return std::is_same<T, float>::value && R >= 8 && (mask == 1 || mask == 2 || mask == 8);
 }
 
 template <int B, int RL = 0, int R>
@@ -511,7 +469,6 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
     static_assert(!SW || (RW == 0 && RR == 0), "pruned rounds do not use lane swaps");
     constexpr int NW = RW ? RW : G::R, NR = RR ? RR : G::R;
     if constexpr (G::LDS_HALVES == 1) {
-        if constexpr (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ) __syncthreads();     // earlier readers of lds are done
         const int ef = SW ? c.base_index_sw(FROM) : c.base_index(FROM);
 #pragma unroll
         for (int jh = 0; jh < NW / 4; ++jh) {
@@ -528,7 +485,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
                 v[jh * 4] = t.x; v[jh * 4 + 1] = t.y; v[jh * 4 + 2] = t.z; v[jh * 4 + 3] = t.w;
             }
         }
-        if constexpr (SPINNER_SYNC_AFTER_READ != 0) __syncthreads();   // buffer free for the next exchange
+        __syncthreads();   // buffer free for the next exchange
     } else {
         static_assert(G::LDS_HALVES <= 2 || (RW == 0 && RR == 0), "pruned rounds exchange in one or two trips");
         // Several trips through an LDS buffer of a half (quarter) of the tile: trip h moves
@@ -549,7 +506,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
             wide_slot_bases<G, TO>(c, et, br);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (h == 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
+                if (h == 1) __syncthreads();
 #pragma unroll
                 for (int jh = 0; jh < NW / 4; ++jh) {
                     const int rj = G::reg_index(FROM, jh * 4);
@@ -569,7 +526,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
             float2* lds2 = reinterpret_cast<float2*>(lds);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (h == 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
+                if (h == 1) __syncthreads();
 #pragma unroll
                 for (int jh = 0; jh < NW / 4; ++jh) {
                     const int e = ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4));
@@ -590,7 +547,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
             float* lds1 = reinterpret_cast<float*>(lds);
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
-                if (h >= 1 || (SYNC_BEFORE && !SPINNER_SYNC_AFTER_READ)) __syncthreads();
+                if (h >= 1) __syncthreads();
 #pragma unroll
                 for (int jh = 0; jh < G::R / 4; ++jh) lds1[(ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4))) >> 2] = v[jh * 4 + h];
                 __syncthreads();
@@ -598,7 +555,7 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
                 for (int jh = 0; jh < G::R / 4; ++jh) v[jh * 4 + h] = lds1[(et | G::reg_index(TO, jh * 4)) >> 2];
             }
         }
-        if constexpr (SPINNER_SYNC_AFTER_READ != 0) __syncthreads();
+        __syncthreads();
     }
 }
 
@@ -760,10 +717,7 @@ __device__ __forceinline__ void spinner_step(T (&v)[G::R], const ThreadCtx<G>& c
         }
         else diag_multiply<G, C, LAY>(v, c, dtile, sl);
     }
-#ifndef SPINNER_LANE_SWAPS_F64
-#define SPINNER_LANE_SWAPS_F64 1
-#endif
-    constexpr bool SWAP = G::LANE_SWAPS && (std::is_same<T, float>::value || SPINNER_LANE_SWAPS_F64) && CB <= G::lane_pos(LAY, 4);
+    constexpr bool SWAP = G::LANE_SWAPS && CB <= G::lane_pos(LAY, 4);
     local_stages<G, CB, LAY, NEGATE, SWAP>(v, c);
     if constexpr (NPF > 0 && PF_NEXT) fetch_sign_masks<G, (G::WB > 0 ? 1 - LAY : LAY), NPF, DIRECT>(*pm, c, next_words);
     if constexpr (G::WB > 0) {
@@ -909,7 +863,7 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 //         whole kernel (dozens of scalar register pairs, spilled to vector-register lanes and read back at the end).
 template <typename T, typename G, int C, int NSTEPS, bool FIRST_DIAG, int EPI, bool SIGNS, int PRUNE = 0, bool RAGGED = true>
 __global__ void __launch_bounds__(G::THREADS)
-__attribute__((amdgpu_waves_per_eu(!std::is_same<T, float>::value ? 1 : G::MIN_WAVES ? G::MIN_WAVES : (G::WB ? SPINNER_MIN_WAVES_MULTI : SPINNER_MIN_WAVES_PER_EU))))
+__attribute__((amdgpu_waves_per_eu(G::MIN_WAVES > 0 && std::is_same<T, float>::value ? G::MIN_WAVES : 1)))
 spinner_tile_kernel(TileParams p)
 {
     // packed sign words describe contiguous tiles; the column pass that applies the second diagonal takes lane masks
@@ -923,8 +877,9 @@ spinner_tile_kernel(TileParams p)
     // data touched once bypass cache retention: x and out of the fused kernels, and, in the four-pass schedule,
     // x read by the first pass and what the last pass reads and writes (what lies between is read again soon)
     constexpr bool FIRST_PASS = NSTEPS == 1 && FIRST_DIAG && C >= NT, LAST_PASS = NSTEPS == 1 && !FIRST_DIAG && C < NT;
-    constexpr bool STREAM_LD = SPINNER_STREAMING && (NSTEPS == 3 || ((SPINNER_STREAM_PASSES & 1) && FIRST_PASS) || ((SPINNER_STREAM_PASSES & 4) && LAST_PASS));
-    constexpr bool STREAM = SPINNER_STREAMING && (NSTEPS == 3 || ((SPINNER_STREAM_PASSES & 2) && LAST_PASS));
+    // (measured on the four-pass schedule: the hint on the first pass alone +2-3 % at n = 2^17 .. 2^20, on the last pass too +0.4 .. 4 %)
+    constexpr bool STREAM_LD = NSTEPS == 3 || FIRST_PASS || LAST_PASS;
+    constexpr bool STREAM = NSTEPS == 3 || LAST_PASS;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -977,7 +932,7 @@ spinner_tile_kernel(TileParams p)
 
         // lane masks of the next step's sign flips travel in scalar registers across the exchange (see SignMasks)
         // (measured: 1.4 % at n = 2^14, nothing elsewhere; only tiles of several waves with 64 values per thread use it)
-        constexpr int NPF = (SIGNS && G::WB > 0 && R == 64) ? SPINNER_MASK_PREFETCH : 0;
+        constexpr int NPF = (SIGNS && G::WB > 0 && R == 64) ? kMaskPrefetch : 0;
         SignMasks<NPF> pm;
         // words of this tile's part of the diagonals (tile q of a longer vector: 2^NT / 64 words per tile)
         const unsigned long long* sw0 = p.sw[0];
