@@ -47,7 +47,7 @@ enum {
     SPINNER_ERR_HIP          = -7,  /* a kernel launch failed; see spinner_strerror         */
     SPINNER_ERR_BAD_L        = -8,  /* L < 1                                                */
     SPINNER_ERR_ALIGNMENT    = -9,  /* a data pointer is not 16-byte aligned                */
-    SPINNER_ERR_UNSUPPORTED  = -10, /* combination not built (e.g. hashing with n > 2^14)   */
+    SPINNER_ERR_UNSUPPORTED  = -10, /* combination not built (e.g. hashing with n > 2^16)   */
     SPINNER_ERR_SCRATCH_LIMIT = -11 /* needs more scratch than the built-in buffer of an allocation-free entry point */
 };
 
@@ -113,7 +113,10 @@ int spinner_apply(const float *x, int n, long batch,
  *   diag_sets  in   device fp32 [L][3][n], order d1, d2, d3 within a triple
  *   out_idx    out  device int32 [batch][L], values in [0, 2n)
  *
- * Supported for n <= 2^14 (SPINNER_ERR_UNSUPPORTED above that).
+ * Supported for n <= 2^16 (SPINNER_ERR_UNSUPPORTED above that: the call has no
+ * workspace for the four-pass path).  Up to n = 2^14 one kernel keeps x in
+ * registers for all L triples; at n = 2^15 and 2^16 a vector fills the
+ * registers of a workgroup and every triple is a launch of its own.
  */
 int spinner_hash(const float *x, int n, long batch, int L,
                  const float *diag_sets, int *out_idx, void *stream);

@@ -297,7 +297,30 @@ static int hash_impl(const float* x, int n, long batch, int L, const float* diag
     if (batch == 0) return SPINNER_OK;
     if (!x || (!diag_sets && !signs) || !out_idx) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(x) || !aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > kFusedMaxLogOther) return SPINNER_ERR_UNSUPPORTED;
+    if (log2n > kFusedMaxLogPlain) return SPINNER_ERR_UNSUPPORTED;
+    if (log2n > kFusedMaxLogOther) {
+        // one launch of the fused plain kernel per triple, the bucket as its epilogue
+        const long long W = sign_words_per_diag(n);
+        for (int l = 0; l < L; ++l) {
+            TileParams p;
+            memset(&p, 0, sizeof(p));
+            p.x = x; p.batch = batch; p.m = n;
+            p.out = reinterpret_cast<float*>(out_idx + l);
+            p.in_stride = n; p.out_stride = L;
+            p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0;
+            p.factor = 1.0f;      // the bucket does not depend on a positive scale
+            if (signs) {
+                const unsigned long long* sw = signs + (long long)l * sign_words_per_triple(n, log2n);
+                p.sw[0] = sw; p.sw[1] = sw + W; p.sw[2] = sw + 2 * W;
+            } else {
+                const float* d = diag_sets + (size_t)l * 3 * n;
+                p.d[0] = d; p.d[1] = d + n; p.d[2] = d + 2 * (size_t)n;
+            }
+            const hipError_t e = launch_hash_tile(log2n, signs != nullptr, p, batch, static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        return SPINNER_OK;
+    }
     HashParams p;
     p.x = x; p.diag_sets = diag_sets; p.signs = signs; p.out_idx = out_idx; p.batch = batch; p.L = L;
     p.triple_words = sign_words_per_triple(n, log2n);

@@ -182,6 +182,20 @@ static hipError_t launch_hash_nt(const HashParams& p, hipStream_t s)
     hipLaunchKernelGGL((spinner_hash_kernel<G, SIGNS>), dim3((unsigned)blocks), dim3(G::THREADS), 0, s, p);
     return hipGetLastError();
 }
+// n = 2^15, 2^16: a vector fills the registers of a whole workgroup, so no copy of x can stay resident beside the
+// working values; each triple is one launch of the fused plain kernel with the bucket as its epilogue (x is read once
+// per triple).  p describes one triple; p.out points at its column of the int32 [batch][L] result, p.out_stride = L.
+hipError_t launch_hash_tile(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s)
+{
+    switch (log2n) {
+    case 15: return signs ? launch_tile<float, 15, 15, 3, true, EPI_STORE_HASH, true>(p, tiles, s)
+                          : launch_tile<float, 15, 15, 3, true, EPI_STORE_HASH, false>(p, tiles, s);
+    case 16: return signs ? launch_tile<float, 16, 16, 3, true, EPI_STORE_HASH, true>(p, tiles, s)
+                          : launch_tile<float, 16, 16, 3, true, EPI_STORE_HASH, false>(p, tiles, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 #define CASE(NT) case NT: return signs ? launch_hash_nt<NT, true>(p, s) : launch_hash_nt<NT, false>(p, s);
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s)
 {

@@ -98,6 +98,7 @@ hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long 
 hipError_t launch_col_middle(int rows_log, int contig_log, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // cols, D2, cols
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
+hipError_t launch_hash_tile(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // n = 2^15, 2^16, one triple
 // sign codes (angular-kernel features): fused kernels for n = 2^8 .. 2^16, packing of an fp32 projection, Gram matrix
 constexpr int kCodeMinLog = 8;
 hipError_t launch_fused_signbits(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s);

@@ -201,7 +201,7 @@ struct TileParams {
     long long sin_off;        // COSSIN only: distance from a cos entry to its sin entry (m for a single block)
 };
 
-enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1, EPI_STORE_SIGNBITS = 2 };
+enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1, EPI_STORE_SIGNBITS = 2, EPI_STORE_HASH = 3 };
 
 // Position of tile element e inside its vector, relative to the tile's base:
 // the low C bits are contiguous, the rest walks rows of 2^sl elements.
@@ -856,7 +856,8 @@ __device__ __forceinline__ void feature_sincos(double y, const TileParams& p, fl
 // NSTEPS  number of (diagonal, transform) steps run on chip (1..3)
 // FIRST_DIAG  whether step 0 multiplies by p.d[0] first
 // EPI     EPI_STORE_NONE, EPI_STORE_COSSIN (applied with p.factor, limit p.m) or EPI_STORE_SIGNBITS
-//         (p.out holds 64-bit code words, p.out_stride counts words, p.m is a multiple of 256)
+//         (p.out holds 64-bit code words, p.out_stride counts words, p.m is a multiple of 256) or EPI_STORE_HASH
+//         (whole-vector tiles; p.out holds int32 buckets, one per vector, p.out_stride apart)
 // RAGGED  false: the caller guarantees that every tile lies entirely inside the kept range [0, m) and that output rows
 //         are 16-byte aligned (EPI_STORE_NONE only); the kernel then has no per-store row-limit test at all.  With the
 //         tests compiled in, the compiler forms their predicates before the rounds and carries them through the
@@ -990,6 +991,47 @@ spinner_tile_kernel(TileParams p)
                             if (i + 3 < m) dst[i + 3] = a3;
                         }
                     }
+                }
+            } else if constexpr (EPI == EPI_STORE_HASH) {
+                // Cross-polytope bucket of the whole vector: argmax of |y_i|, lowest index on exact ties, + n when that
+                // coordinate is negative.  Per thread, then across the lanes, then across the waves through the
+                // exchange buffer (free again: every exchange ends with a barrier).  `active` is uniform over a
+                // workgroup whose tile spans several waves, so every wave reaches the barrier below.
+                static_assert(C >= NT && NSTEPS == 3 && PRUNE == 0 && std::is_same<T, float>::value && G::WB > 0 && G::LB == 6,
+                              "hash epilogue: fused fp32 kernels of tiles that span several waves");
+                float best = v[0];
+                int best_i = ebase | G::reg_index(LAYF, 0);
+#pragma unroll
+                for (int j = 1; j < R; ++j) {
+                    const int ij = ebase | G::reg_index(LAYF, j);
+                    const float fa = __builtin_fabsf(v[j]), fb = __builtin_fabsf(best);
+                    const bool take = (fa > fb) || (fa == fb && ij < best_i);
+                    best = take ? v[j] : best;
+                    best_i = take ? ij : best_i;
+                }
+                best *= lane_factor;      // positive factor times the tracked lane sign
+                static_for<0, 6>([&](auto b) {
+                    const float ov = lane_xor<(1 << b.value)>(best);
+                    const int oi = lane_xor_i<(1 << b.value)>(best_i);
+                    const float fa = __builtin_fabsf(ov), fb = __builtin_fabsf(best);
+                    const bool take = (fa > fb) || (fa == fb && oi < best_i);
+                    best = take ? ov : best;
+                    best_i = take ? oi : best_i;
+                });
+                float* red_val = reinterpret_cast<float*>(lds);
+                int* red_idx = reinterpret_cast<int*>(lds) + G::WAVES;
+                if (lane == 0) { red_val[wave] = best; red_idx[wave] = best_i; }
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    for (int w = 1; w < G::WAVES; ++w) {
+                        const float ov = red_val[w];
+                        const int oi = red_idx[w];
+                        const float fa = __builtin_fabsf(ov), fb = __builtin_fabsf(best);
+                        const bool take = (fa > fb) || (fa == fb && oi < best_i);
+                        best = take ? ov : best;
+                        best_i = take ? oi : best_i;
+                    }
+                    reinterpret_cast<int*>(p.out)[vec * p.out_stride] = best_i + ((best < 0.0f) ? (1 << NT) : 0);
                 }
             } else if constexpr (EPI == EPI_STORE_SIGNBITS) {
                 // Code word ((e >> 8) << 2) | (e & 3) holds, in bit (e >> 2) & 63, whether coordinate e

@@ -81,7 +81,7 @@ def test_hash_rejects_bad_arguments_before_launch(b):
     assert h(None, 1024, 4, 2, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
     assert h(64, 1024, 4, 2, 64, None, None) == b.SPINNER_ERR_NULL_PTR
     assert h(4, 1024, 4, 2, 64, 64, None) == b.SPINNER_ERR_ALIGNMENT
-    assert h(64, 1 << 15, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert h(64, 1 << 17, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
     assert h(None, 1024, 0, 2, None, None, None) == b.SPINNER_OK
 
 
@@ -112,7 +112,7 @@ def test_sign_word_entry_points_reject_bad_arguments(b):
     assert ap(64, 1024, 4, 8, 1024, 0, ctypes.c_float(1.0), 64, None, None) == b.SPINNER_ERR_ALIGNMENT
     hs = b.lib.spinner_hash_signs
     assert hs(64, 1024, 4, 2, None, 64, None) == b.SPINNER_ERR_NULL_PTR
-    assert hs(64, 1 << 15, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert hs(64, 1 << 17, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
 
 
 def test_sign_code_entry_points_host_side(b):

@@ -177,7 +177,7 @@ def test_cos_sin_features(gpu, oracle, n, m, scale):
 
 
 # ------------------------------------------------------------------ hash
-@pytest.mark.parametrize("log2n", list(range(4, 15)))
+@pytest.mark.parametrize("log2n", list(range(4, 17)))
 def test_hash_every_size(gpu, oracle, log2n):
     n = 1 << log2n
     batch = 70 if log2n < 12 else 6
@@ -191,6 +191,11 @@ def test_hash_every_size(gpu, oracle, log2n):
     exact, banded = check_hash_against_projection(got, ys)
     assert exact + banded == batch * L
     assert banded <= 1
+    if log2n > 14:      # one launch per triple: also from packed sign words (the smaller sizes: test_sign_word_path_every_fused_size)
+        signs = gpu.b.spinner_pack_signs(_to(gpu, ds))
+        got = gpu.b.spinner_hash_signs(_to(gpu, x), signs, L).cpu().numpy()
+        exact, banded = check_hash_against_projection(got, ys)
+        assert exact + banded == batch * L and banded <= 1
 
 
 def test_hash_rules_on_constructed_inputs(gpu):
