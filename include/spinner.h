@@ -188,8 +188,11 @@ int spinner_apply_blocks(const float *x, int n, long batch, int L,
  * positive, as in spinner_hash).  The bits are stored in 64-bit words in the
  * order in which the hardware produces them (the comparison mask of one
  * register over one wave): coordinate e lives in bit (e >> 2) & 63 of word
- * ((e >> 8) << 2) | (e & 3) of its row; spinner_code_position returns this
- * pair on the host.  Any fixed order gives the same Hamming distances.
+ * ((e >> 8) << 2) | (e & 3) of its row.  The order is part of this interface
+ * (it will not change between versions); spinner_code_position is the call
+ * that converts a coordinate into its (word, bit) pair on the host, for
+ * consumers that need the sign of one particular coordinate.  Hamming
+ * distances, which is what the estimate uses, are the same in any fixed order.
  *
  *   x, d1..d3  in   as for spinner_apply
  *   m          in   coordinates kept: a multiple of 256, 256 <= m <= n
@@ -209,7 +212,7 @@ int spinner_apply_blocks(const float *x, int n, long batch, int L,
  */
 size_t spinner_code_bytes(int m);
 size_t spinner_codes_workspace_bytes(int n, long batch);
-int spinner_code_position(int coordinate, int *word, int *bit);
+int spinner_code_position(int coordinate, int *word, int *bit);   /* SPINNER_ERR_BAD_M for a negative coordinate */
 int spinner_sign_codes(const float *x, int n, long batch,
                        const float *d1, const float *d2, const float *d3,
                        int m, void *codes, void *workspace, void *stream);
