@@ -150,7 +150,9 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
         // how many of the highest index bits lie entirely above the kept rows
         int prune = 0;
         while (prune < log2n && (long long)m <= ((long long)n >> (prune + 1))) ++prune;
-        const hipError_t e = epilogue == kEpiSignBits ? launch_fused_signbits(log2n, signs != nullptr, prune, p, batch, s)
+        const bool shared_diag = !signs && epilogue == SPINNER_EPI_NONE && m == n && blocks == 1 && has_shared_diag_kernel(log2n);
+        const hipError_t e = shared_diag                ? launch_fused_shared_diag(log2n, p, s)
+                             : epilogue == kEpiSignBits ? launch_fused_signbits(log2n, signs != nullptr, prune, p, batch, s)
                              : epi == EPI_STORE_COSSIN ? launch_fused_cossin(log2n, signs != nullptr, p, batch, s)
                                                        : launch_fused_none(log2n, signs != nullptr, prune, p, batch, s);
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);

@@ -89,6 +89,9 @@ inline hipError_t launch_tile(const TileParams& p, long long total_tiles, hipStr
 
 // implemented in fused_none.hip / fused_cossin.hip / multipass.hip / hash.hip
 hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s);
+// fp32 diagonals, full-width output, n = 2^12, 2^13: a workgroup carries two vectors per diagonal load (fused_shared.hip)
+constexpr bool has_shared_diag_kernel(int log2n) { return log2n == 12 || log2n == 13; }
+hipError_t launch_fused_shared_diag(int log2n, const TileParams& p, hipStream_t s);
 constexpr int kPruneBits = 4;   // the pruned variant drops the 4 highest index bits in the last round (m <= n/16)
 hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);
 // signs: the diagonal of the pass comes as packed words p.sw[] (rows of at least 2^kRowSignsMinLog elements), not as p.d[]

@@ -74,7 +74,7 @@ def test_plain_spinner_every_fused_size(gpu, oracle, log2n):
 
 
 def test_batch_of_one_and_exact_multiple(gpu, oracle):
-    for n, batch in ((256, 1), (256, 64), (1024, 16), (4096, 4)):
+    for n, batch in ((256, 1), (256, 64), (1024, 16), (4096, 4), (4096, 1), (8192, 1), (8192, 2)):
         x, d = _rng_case(n, batch, n + batch)
         got = _run_apply(gpu, x, d, n, "none", 1.0)
         want = oracle.apply(x, d[0], d[1], d[2], n, "none", 1.0)
@@ -124,6 +124,14 @@ def test_in_place_and_non_default_stream(gpu, oracle):
         gpu.b.spinner_apply(xd, dd[0], dd[1], dd[2], out=xd)        # out aliases x
     s.synchronize()
     assert rel_l2_per_vector(xd.cpu().numpy(), want).max() <= REL_L2_TOL
+    # in place where a workgroup carries two vectors through the rounds (fp32 diagonals at n = 2^12, 2^13), odd batch
+    for n2 in (4096, 8192):
+        x, d = _rng_case(n2, 5, 4243 + n2, gaussian_d3=True)
+        want = oracle.apply(x, d[0], d[1], d[2], n2, "none", 0.5)
+        xd = _to(gpu, x)
+        gpu.b.spinner_apply(xd, _to(gpu, d[0]), _to(gpu, d[1]), _to(gpu, d[2]), n2, "none", 0.5, out=xd)
+        t.cuda.synchronize()
+        assert rel_l2_per_vector(xd.cpu().numpy(), want).max() <= REL_L2_TOL
 
 
 # ------------------------------------------------------------------ truncation
