@@ -1,5 +1,5 @@
 // Fused three-round kernels, first-m-rows epilogue, n = 2^4 .. 2^16,
-// with fp32 diagonals or with packed sign words; for n = 2^8 .. 2^15 also with the last
+// with fp32 diagonals or with packed sign words; for n >= 2^8 also with the last
 // round pruned to the rows that are kept (m <= n / 16).
 #include "launch.hpp"
 namespace spinner {
@@ -17,7 +17,7 @@ hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams&
     const bool whole = p.m == (1 << log2n) && (p.out_stride & 3) == 0;
     if (prune >= kPruneBits) {
         switch (log2n) {
-            PCASE(8) PCASE(9) PCASE(10) PCASE(11) PCASE(12) PCASE(13) PCASE(14) PCASE(15)
+            PCASE(8) PCASE(9) PCASE(10) PCASE(11) PCASE(12) PCASE(13) PCASE(14) PCASE(15) PCASE(16)
         default: break;
         }
     }

@@ -487,7 +487,6 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
         }
         __syncthreads();   // buffer free for the next exchange
     } else {
-        static_assert(G::LDS_HALVES <= 2 || (RW == 0 && RR == 0), "pruned rounds exchange in one or two trips");
         // Several trips through an LDS buffer of a half (quarter) of the tile: trip h moves
         // registers 4k+2h, 4k+2h+1 (register 4k+h) of every thread, i.e. the elements with a
         // given value of index bit 1 (bits 1..0): 8 (4) bytes per lane, consecutive lanes on
@@ -549,10 +548,12 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
             for (int h = 0; h < 4; ++h) {
                 if (h >= 1) __syncthreads();
 #pragma unroll
-                for (int jh = 0; jh < G::R / 4; ++jh) lds1[(ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4))) >> 2] = v[jh * 4 + h];
+                for (int jh = 0; jh < NW / 4; ++jh) lds1[(ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4))) >> 2] = v[jh * 4 + h];
                 __syncthreads();
+                if (reads) {
 #pragma unroll
-                for (int jh = 0; jh < G::R / 4; ++jh) v[jh * 4 + h] = lds1[(et | G::reg_index(TO, jh * 4)) >> 2];
+                    for (int jh = 0; jh < NR / 4; ++jh) v[jh * 4 + h] = lds1[(et | G::reg_index(TO, jh * 4)) >> 2];
+                }
             }
         }
         __syncthreads();

@@ -231,7 +231,7 @@ def adds_per_vector(w: Workload) -> int:
     (n/2 + n/4 + n/8 + n/16 additions) and log2(n) - 4 full stages on the n/16 values that are left."""
     N = int(math.log2(w.n))
     full = N * w.n
-    if w.kind == "apply" and w.epilogue == "none" and 8 <= N <= 15 and w.m <= (w.n >> PRUNE_BITS):
+    if w.kind == "apply" and w.epilogue == "none" and 8 <= N <= 16 and w.m <= (w.n >> PRUNE_BITS):
         last = (w.n - (w.n >> PRUNE_BITS)) + (N - PRUNE_BITS) * (w.n >> PRUNE_BITS)
         return (2 * full + last) * w.L
     return 3 * full * w.L

@@ -145,7 +145,7 @@ def test_first_m_rows(gpu, oracle, n, m, scale):
     assert rel_l2_first_m(got, want, x, n, m, scale).max() <= REL_L2_TOL
 
 
-@pytest.mark.parametrize("log2n", list(range(8, 16)))
+@pytest.mark.parametrize("log2n", list(range(8, 17)))
 def test_first_m_rows_with_pruned_last_round(gpu, oracle, log2n):
     # m <= n/16 takes the kernels whose last round only forms the sums it needs on the four
     # highest index bits; both diagonal forms, exact and ragged m.
