@@ -134,6 +134,7 @@ static int apply_impl(const float* x, int n, int log2n, long batch, const float*
     p.inv_sqrt_m = (float)(1.0 / sqrt((double)m * blocks));
     p.sin_off = (long long)m * blocks;
     p.factor_rev = factor_d / 6.283185307179586476925286766559;
+    p.xcd_group_log = -1;
 
     if (log2n <= fused_max_log(epilogue)) {
         if (batch > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
@@ -311,6 +312,7 @@ static int hash_impl(const float* x, int n, long batch, int L, const float* diag
             p.in_stride = n; p.out_stride = L;
             p.tiles_per_vec_log = 0; p.tb = log2n; p.sl = 0;
             p.factor = 1.0f;      // the bucket does not depend on a positive scale
+            p.xcd_group_log = -1;
             if (signs) {
                 const unsigned long long* sw = signs + (long long)l * sign_words_per_triple(n, log2n);
                 p.sw[0] = sw; p.sw[1] = sw + W; p.sw[2] = sw + 2 * W;
@@ -596,6 +598,7 @@ int spinner_apply_blocks(const float* x, int n, long batch, int L, const float* 
         p.factor_rev = factor_d / 6.283185307179586476925286766559;
         p.inv_sqrt_m = (float)(1.0 / sqrt((double)m * L));
         p.sin_off = (long long)m * L;
+        p.xcd_group_log = -1;
         const hipError_t e = spinner::launch_blocks(log2n, epilogue == SPINNER_EPI_COSSIN, p, diag_sets, L,
                                                     static_cast<hipStream_t>(stream));
         return e == hipSuccess ? SPINNER_OK : hip_fail(e);

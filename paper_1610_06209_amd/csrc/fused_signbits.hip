@@ -24,8 +24,10 @@ static hipError_t launch_code_tile(const TileParams& p, long long tiles, hipStre
     const long long blocks = (tiles + G::TILES_PER_WG - 1) / G::TILES_PER_WG;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    TileParams q = p;
+    q.xcd_group_log = SIGNS ? xcd_group_log_for<G>() : -1;
     hipLaunchKernelGGL((spinner_tile_kernel<float, G, NT, 3, true, EPI_STORE_SIGNBITS, SIGNS, PRUNE>),
-                       dim3((unsigned)blocks), dim3(G::THREADS), 0, stream, p);
+                       dim3((unsigned)blocks), dim3(G::THREADS), 0, stream, q);
     return hipGetLastError();
 }
 

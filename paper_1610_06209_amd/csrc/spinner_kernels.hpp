@@ -199,7 +199,23 @@ struct TileParams {
     double factor_rev;        // factor / (2 pi), fp64: w in revolutions for the fp64 feature path
     float inv_sqrt_m;         // COSSIN only: 1 / sqrt(number of features of the whole row)
     long long sin_off;        // COSSIN only: distance from a cos entry to its sin entry (m for a single block)
+    int xcd_group_log;        // tiles that span several waves: log2 of the run of consecutive tiles an XCD takes (see xcd_tile); -1: none
 };
+
+// Workgroups go to the eight XCDs in turn (workgroup b runs on XCD b mod 8).  With tile = b each XCD would touch
+// every eighth tile: pieces of one tile size at eight times that stride, so that for tiles of 32 KiB and more the
+// address bits that pick a tile's place among its seven neighbours are fixed per XCD.  Here each XCD takes runs of
+// 2^group_log consecutive tiles instead: within a chunk of 8 * 2^group_log tiles, XCD k walks tiles
+// [k 2^group_log, (k + 1) 2^group_log).  Tiles beyond the last whole chunk keep tile = b.  group_log < 0: tile = b.
+__device__ __forceinline__ long long xcd_tile(unsigned b, long long total, int group_log)
+{
+    if (group_log < 0) return b;
+    const long long chunk = 8LL << group_log;
+    const long long whole = total - total % chunk;
+    if (b >= whole) return b;
+    const long long cidx = b / chunk, r = b % chunk;
+    return cidx * chunk + ((r & 7) << group_log) + (r >> 3);
+}
 
 enum { EPI_STORE_NONE = 0, EPI_STORE_COSSIN = 1, EPI_STORE_SIGNBITS = 2, EPI_STORE_HASH = 3 };
 
@@ -888,7 +904,7 @@ spinner_tile_kernel(TileParams p)
     ThreadCtx<G> c;
     long long tile;
     if constexpr (G::WB > 0) {
-        tile = blockIdx.x;
+        tile = xcd_tile(blockIdx.x, p.batch << p.tiles_per_vec_log, p.xcd_group_log);
         c.lit = lane;
         c.wv = __builtin_amdgcn_readfirstlane(wave);
     } else if constexpr (SIGNS && NSTEPS < 3) {
@@ -896,7 +912,8 @@ spinner_tile_kernel(TileParams p)
         c.lit = lane;
         c.wv = 0;
     } else {
-        tile = ((long long)blockIdx.x * G::WAVES + wave) * G::TPW + (lane >> G::LB);
+        const long long wg = NSTEPS == 3 ? xcd_tile(blockIdx.x, gridDim.x, p.xcd_group_log) : (long long)blockIdx.x;
+        tile = (wg * G::WAVES + wave) * G::TPW + (lane >> G::LB);
         c.lit = lane & ((1 << G::LB) - 1);
         c.wv = 0;
     }
