@@ -137,8 +137,10 @@ struct TileGeom {
     static_assert(WB <= r - 2, "too few registers per thread for this many waves per tile");
     static constexpr int TPW = 64 >> LB;                     // tiles per wave
     // the LDS exchange buffer holds the whole tile, or half of it (two trips per transpose)
-    // (tiles above 2^14 elements always take as many trips as keep the buffer at 64 KiB)
-    static constexpr int LDS_HALVES = NT_ > 14 ? (1 << (NT_ - 14)) : ((TRIPS_ == 2 && WB >= 1) ? 2 : 1);
+    // (tiles above 2^14 elements always take two trips: 64 KiB at 2^15, where two tiles share a compute unit, and
+    // 128 KiB at 2^16, where one tile fills the registers of a compute unit anyway; four trips through 64 KiB
+    // measured 6 % slower there)
+    static constexpr int LDS_HALVES = NT_ > 14 ? 2 : ((TRIPS_ == 2 && WB >= 1) ? 2 : 1);
     static constexpr int LDS_FLOAT4 = WB > 0 ? ((1 << NT_) / 4) / LDS_HALVES : 1;
     static constexpr int WAVES = WB ? (1 << WB) : WAVES_1;   // waves per workgroup
     static constexpr int THREADS = 64 * WAVES;
@@ -503,10 +505,9 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
         }
         __syncthreads();   // buffer free for the next exchange
     } else {
-        // Several trips through an LDS buffer of a half (quarter) of the tile: trip h moves
-        // registers 4k+2h, 4k+2h+1 (register 4k+h) of every thread, i.e. the elements with a
-        // given value of index bit 1 (bits 1..0): 8 (4) bytes per lane, consecutive lanes on
-        // consecutive addresses.  Each thread receives exactly the register slots it has just
+        // Two trips through an LDS buffer of half the tile: trip h moves registers 4k+2h, 4k+2h+1
+        // of every thread, i.e. the elements with a given value of index bit 1: 8 bytes per lane,
+        // consecutive lanes on consecutive addresses.  Each thread receives exactly the register slots it has just
         // sent, so nothing is overwritten before it is sent.  A smaller footprint lets a CU
         // hold more workgroups, and lets tiles of 2^15 and 2^16 elements fit at all.
         const int ef = SW ? c.base_index_sw(FROM) : c.base_index(FROM);
@@ -537,7 +538,8 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
                     }
                 }
             }
-        } else if constexpr (G::LDS_HALVES == 2) {
+        } else {
+            static_assert(G::LDS_HALVES == 2, "one or two trips");
             float2* lds2 = reinterpret_cast<float2*>(lds);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -555,20 +557,6 @@ __device__ __forceinline__ void transpose(float (&v)[G::R], const ThreadCtx<G>& 
                         const float2 t = lds2[e >> 2];
                         v[jh * 4 + 2 * h] = t.x; v[jh * 4 + 2 * h + 1] = t.y;
                     }
-                }
-            }
-        } else {
-            static_assert(G::LDS_HALVES == 4, "one, two or four trips");
-            float* lds1 = reinterpret_cast<float*>(lds);
-#pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                if (h >= 1) __syncthreads();
-#pragma unroll
-                for (int jh = 0; jh < NW / 4; ++jh) lds1[(ef | (SW ? G::reg_index_sw(FROM, jh * 4) : G::reg_index(FROM, jh * 4))) >> 2] = v[jh * 4 + h];
-                __syncthreads();
-                if (reads) {
-#pragma unroll
-                    for (int jh = 0; jh < NR / 4; ++jh) v[jh * 4 + h] = lds1[(et | G::reg_index(TO, jh * 4)) >> 2];
                 }
             }
         }
