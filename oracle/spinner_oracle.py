@@ -10,6 +10,9 @@ What each function follows:
 
 * ``spinner``            - Section 1 / Section 3 (the HD3HD2HD1 member of the
   family; H is the L2-normalised Hadamard matrix, D_i diagonal).
+* ``spinner_by_products`` - the same product for the largest n, where the plain loops of ``spinner`` take minutes per
+  vector: H_n = H_a (x) H_b is applied as the two dense matrix products H_a T H_b on the a x b view of the vector,
+  with the materialised factors and numpy's fp64 matrix product as the step.
 * ``epilogue_none``      - Section 3.2: an m x n spinner is the first m rows of
   the n x n one; ``scale`` is the caller's extra factor (sqrt(n) in Lemma 1,
   sqrt(n/m) for a norm-preserving embedding).
@@ -155,6 +158,35 @@ def spinner(x: np.ndarray, d1: np.ndarray, d2: np.ndarray, d3: np.ndarray,
     if rc != 0:
         raise ValueError("oracle_spinner: bad arguments or out of memory")
     return y[0] if squeeze else y
+
+
+def spinner_by_products(x: np.ndarray, d1: np.ndarray, d2: np.ndarray, d3: np.ndarray) -> np.ndarray:
+    """y = H D3 H D2 H D1 x in fp64 for each row of fp32 ``x`` [batch][n], n >= 4, for the largest n.
+
+    Section 1 / Section 3, with the Sylvester matrix written as H_n = H_a (x) H_b (a b = n): entry (i, j) of H_n is
+    H_a[ia][ja] H_b[ib][jb] for i = ia b + ib, j = ja b + jb, so H_n t is the matrix H_a T H_b for the row-major a x b
+    view T of t (both factors are symmetric).  The factors are materialised and multiplied with numpy's fp64 matrix
+    product: 2 n (a + b) multiply-adds per round instead of n^2.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    squeeze = x.ndim == 1
+    if squeeze:
+        x = x[None, :]
+    batch, n = x.shape
+    assert _is_pow2(n) and n >= 4
+    log2n = n.bit_length() - 1
+    a = 1 << ((log2n + 1) // 2)
+    b = n // a
+    Ha = hadamard_dense(a).astype(np.float64)
+    Hb = hadamard_dense(b).astype(np.float64)
+    t = x.astype(np.float64)
+    for d in (d1, d2, d3):
+        d = np.asarray(d, dtype=np.float32)
+        if d.shape != (n,):
+            raise ValueError("diagonal must have shape (n,)")
+        t = t * d.astype(np.float64)[None, :]
+        t = (Ha @ t.reshape(batch, a, b) @ Hb).reshape(batch, n) / np.sqrt(float(n))
+    return t[0] if squeeze else t
 
 
 def epilogue_none(y: np.ndarray, m: int, scale: float) -> np.ndarray:

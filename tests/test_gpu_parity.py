@@ -251,6 +251,30 @@ def test_multipass_plain(gpu, oracle, log2n, batch):
     assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
 
 
+@pytest.mark.parametrize("log2n,batch", [(22, 2), (23, 1), (24, 1)])
+def test_multipass_largest_sizes_against_the_oracle(gpu, oracle, log2n, batch):
+    # The plain-loop oracle takes minutes per vector here; its route through two dense matrix products per round
+    # (pinned on the CPU against the plain loops) takes seconds.  Random +-1 first and second diagonals, Gaussian
+    # third diagonal through spinner_apply; +-1 diagonals through both forms, full width and the first rows.
+    n = 1 << log2n
+    x, d = _rng_case(n, batch, 2200 + log2n, gaussian_d3=True)
+    got = _run_apply(gpu, x, d, n, "none", 1.0)
+    want = oracle.spinner_by_products(x, d[0], d[1], d[2])
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+    del got
+    x, d = _rng_case(n, batch, 2300 + log2n)
+    want = oracle.spinner_by_products(x, d[0], d[1], d[2])
+    xd = _to(gpu, x)
+    signs = gpu.b.spinner_pack_signs(_to(gpu, d[None, :, :]))
+    got = gpu.b.spinner_apply_signs(xd, signs).cpu().numpy()
+    assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
+    m = 3000
+    got = gpu.b.spinner_apply_signs(xd, signs, m, "none", 2.0).cpu().numpy()
+    assert rel_l2_first_m(got, 2.0 * want[:, :m], x, n, m, 2.0).max() <= REL_L2_TOL
+    got = _run_apply(gpu, x, d, m, "none", 2.0)
+    assert rel_l2_first_m(got, 2.0 * want[:, :m], x, n, m, 2.0).max() <= REL_L2_TOL
+
+
 @pytest.mark.parametrize("log2n", [19, 22, 23, 24])
 def test_multipass_largest_sizes_by_properties(gpu, log2n):
     # The O(n^2)-per-factor oracle takes minutes per vector here, so these sizes are checked by
