@@ -114,12 +114,28 @@ int spinner_apply(const float *x, int n, long batch,
  *   out_idx    out  device int32 [batch][L], values in [0, 2n)
  *
  * Supported for n <= 2^16 (SPINNER_ERR_UNSUPPORTED above that: the call has no
- * workspace for the four-pass path).  Up to n = 2^14 one kernel keeps x in
- * registers for all L triples; at n = 2^15 and 2^16 a vector fills the
- * registers of a workgroup and every triple is a launch of its own.
+ * workspace for the four-pass path; spinner_hash_ws does).  Up to n = 2^14 one
+ * kernel keeps x in registers for all L triples; at n = 2^15 and 2^16 a vector
+ * fills the registers of a workgroup and every triple is a launch of its own.
  */
 int spinner_hash(const float *x, int n, long batch, int L,
                  const float *diag_sets, int *out_idx, void *stream);
+
+/*
+ * The same hash for every n in [2^4, 2^24].  Above 2^16 each triple runs the
+ * four-pass projection into the workspace and the bucket is taken from there by
+ * two small kernels (same rules: largest |y_i|, lowest index on exact ties, a
+ * zero counts as positive); x is then read once per triple.  Up to 2^16 the
+ * call is spinner_hash and the workspace may be NULL.
+ *
+ *   workspace  in   device scratch of spinner_hash_workspace_bytes(n, batch)
+ *                   bytes (0 for n <= 2^16), 16-byte aligned;
+ *                   SPINNER_ERR_WORKSPACE if it is needed and NULL
+ * spinner_hash_signs_ws is the variant for packed sign words (see below).
+ */
+size_t spinner_hash_workspace_bytes(int n, long batch);
+int spinner_hash_ws(const float *x, int n, long batch, int L,
+                    const float *diag_sets, int *out_idx, void *workspace, void *stream);
 
 /*
  * Random setting, parameters prepared in advance.  In the random setting the
@@ -152,6 +168,8 @@ int spinner_apply_signs(const float *x, int n, long batch, const void *signs,
                         float *out, void *workspace, void *stream);
 int spinner_hash_signs(const float *x, int n, long batch, int L,
                        const void *signs, int *out_idx, void *stream);
+int spinner_hash_signs_ws(const float *x, int n, long batch, int L,
+                          const void *signs, int *out_idx, void *workspace, void *stream);
 
 /*
  * Stacked blocks (Section 3.2: independently constructed m x n spinners stacked

@@ -32,7 +32,7 @@ EPILOGUES = {"none": SPINNER_EPI_NONE, "cossin": SPINNER_EPI_COSSIN}
 
 EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_strerror",
            "spinner_version", "spinner_stream_copy", "spinner_signs_bytes", "spinner_pack_signs",
-           "spinner_apply_signs", "spinner_hash_signs", "spinner_code_bytes", "spinner_codes_workspace_bytes",
+           "spinner_apply_signs", "spinner_hash_signs", "spinner_hash_workspace_bytes", "spinner_hash_ws", "spinner_hash_signs_ws", "spinner_code_bytes", "spinner_codes_workspace_bytes",
            "spinner_code_position", "spinner_sign_codes", "spinner_sign_codes_signs", "spinner_angular_gram",
            "spinner_layer_saved_bytes", "spinner_layer_workspace_bytes", "spinner_layer_forward",
            "spinner_layer_backward", "spinner_sketch_workspace_bytes", "spinner_sketch", "spinner_sketch_gram",
@@ -72,6 +72,12 @@ lib.spinner_apply_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, _vp, ctype
                                     ctypes.c_float, _vp, _vp, _vp]
 lib.spinner_hash_signs.restype = ctypes.c_int
 lib.spinner_hash_signs.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp]
+lib.spinner_hash_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_hash_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_long]
+lib.spinner_hash_ws.restype = ctypes.c_int
+lib.spinner_hash_ws.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp, _vp]
+lib.spinner_hash_signs_ws.restype = ctypes.c_int
+lib.spinner_hash_signs_ws.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp, _vp]
 lib.spinner_stream_copy.restype = ctypes.c_int
 lib.spinner_stream_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
 lib.spinner_code_bytes.restype = ctypes.c_size_t
@@ -214,6 +220,67 @@ def spinner_hash(x, diag_sets, out_idx=None, stream=None):
         if out_idx.numel() != batch * L:
             raise ValueError("out_idx has the wrong size")
     rc = lib.spinner_hash(x.data_ptr(), n, batch, L, diag_sets.data_ptr(), out_idx.data_ptr(), _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out_idx
+
+
+def spinner_hash_workspace_bytes(n: int, batch: int) -> int:
+    return int(lib.spinner_hash_workspace_bytes(int(n), int(batch)))
+
+
+def _hash_workspace(x, n, batch, workspace):
+    import torch
+
+    need = spinner_hash_workspace_bytes(n, batch)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    return workspace
+
+
+def spinner_hash_ws(x, diag_sets, out_idx=None, workspace=None, stream=None):
+    """spinner_hash for every n up to 2^24 (a workspace tensor is made when none is given and one is needed)."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    _check_tensor(diag_sets, "diag_sets", torch.float32)
+    batch, n = x.shape
+    if diag_sets.dim() != 3 or diag_sets.shape[1] != 3 or diag_sets.shape[2] != n:
+        raise ValueError("diag_sets must be [L][3][n]")
+    L = diag_sets.shape[0]
+    if out_idx is None:
+        out_idx = torch.empty((batch, L), dtype=torch.int32, device=x.device)
+    else:
+        _check_tensor(out_idx, "out_idx", torch.int32)
+        if out_idx.numel() != batch * L:
+            raise ValueError("out_idx has the wrong size")
+    workspace = _hash_workspace(x, n, batch, workspace)
+    rc = lib.spinner_hash_ws(x.data_ptr(), n, batch, L, diag_sets.data_ptr(), out_idx.data_ptr(),
+                             workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out_idx
+
+
+def spinner_hash_signs_ws(x, signs, L, out_idx=None, workspace=None, stream=None):
+    """spinner_hash_signs for every n up to 2^24."""
+    import torch
+
+    _check_tensor(x, "x", torch.float32)
+    batch, n = x.shape
+    if signs.numel() < spinner_signs_bytes(n, L):
+        raise ValueError("signs buffer too small")
+    if out_idx is None:
+        out_idx = torch.empty((batch, L), dtype=torch.int32, device=x.device)
+    else:
+        _check_tensor(out_idx, "out_idx", torch.int32)
+        if out_idx.numel() != batch * L:
+            raise ValueError("out_idx has the wrong size")
+    workspace = _hash_workspace(x, n, batch, workspace)
+    rc = lib.spinner_hash_signs_ws(x.data_ptr(), n, batch, L, signs.data_ptr(), out_idx.data_ptr(),
+                                   workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out_idx

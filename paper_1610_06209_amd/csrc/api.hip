@@ -289,8 +289,18 @@ int spinner_apply_signs(const float* x, int n, long batch, const void* signs, in
                       epilogue, scale, out, workspace, stream);
 }
 
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t spinner_hash_workspace_bytes(int n, long batch)
+{
+    int log2n;
+    if (!pow2_in_range(n, &log2n) || batch <= 0 || log2n <= spinner::kFusedMaxLogPlain) return 0;
+    return align256((size_t)batch * (size_t)n * sizeof(float)) + spinner::hash_candidates_bytes(log2n, batch);
+}
+
+// with_workspace: the call has a workspace argument (spinner_hash_ws / spinner_hash_signs_ws), which n > 2^16 needs
 static int hash_impl(const float* x, int n, long batch, int L, const float* diag_sets, const unsigned long long* signs,
-                     int* out_idx, void* stream)
+                     int* out_idx, void* stream, bool with_workspace = false, void* workspace = nullptr)
 {
     using namespace spinner;
     int log2n;
@@ -300,7 +310,24 @@ static int hash_impl(const float* x, int n, long batch, int L, const float* diag
     if (batch == 0) return SPINNER_OK;
     if (!x || (!diag_sets && !signs) || !out_idx) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(x) || !aligned16(diag_sets) || !aligned16(signs)) return SPINNER_ERR_ALIGNMENT;
-    if (log2n > kFusedMaxLogPlain) return SPINNER_ERR_UNSUPPORTED;
+    if (log2n > kFusedMaxLogPlain) {
+        // four passes per triple leave the projection in the workspace; its bucket is taken from there
+        if (!with_workspace) return SPINNER_ERR_UNSUPPORTED;
+        if (!workspace) return SPINNER_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
+        float* y = static_cast<float*>(workspace);
+        void* candidates = static_cast<char*>(workspace) + align256((size_t)batch * (size_t)n * sizeof(float));
+        for (int l = 0; l < L; ++l) {
+            const float* d = diag_sets ? diag_sets + (size_t)l * 3 * n : nullptr;
+            const unsigned long long* sw = signs ? signs + (long long)l * sign_words_per_triple(n, log2n) : nullptr;
+            const int rc = apply_impl(x, n, log2n, batch, d, d ? d + n : nullptr, d ? d + 2 * (size_t)n : nullptr, sw, n,
+                                      SPINNER_EPI_NONE, 1.0f, y, nullptr, stream);
+            if (rc != SPINNER_OK) return rc;
+            const hipError_t e = launch_hash_argmax(y, log2n, batch, candidates, out_idx + l, L, static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        return SPINNER_OK;
+    }
     if (log2n > kFusedMaxLogOther) {
         // one launch of the fused plain kernel per triple, the bucket as its epilogue
         const long long W = sign_words_per_diag(n);
@@ -340,6 +367,16 @@ int spinner_hash(const float* x, int n, long batch, int L, const float* diag_set
 int spinner_hash_signs(const float* x, int n, long batch, int L, const void* signs, int* out_idx, void* stream)
 {
     return hash_impl(x, n, batch, L, nullptr, static_cast<const unsigned long long*>(signs), out_idx, stream);
+}
+
+int spinner_hash_ws(const float* x, int n, long batch, int L, const float* diag_sets, int* out_idx, void* workspace, void* stream)
+{
+    return hash_impl(x, n, batch, L, diag_sets, nullptr, out_idx, stream, true, workspace);
+}
+
+int spinner_hash_signs_ws(const float* x, int n, long batch, int L, const void* signs, int* out_idx, void* workspace, void* stream)
+{
+    return hash_impl(x, n, batch, L, nullptr, static_cast<const unsigned long long*>(signs), out_idx, stream, true, workspace);
 }
 
 // ------------------------------------------------------------------ sign codes (angular kernel)
@@ -491,7 +528,6 @@ int spinner_layer_backward(const float* dy, const float* x, const void* saved, i
 }
 
 // ------------------------------------------------------------------ Newton sketch
-static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 size_t spinner_sketch_workspace_bytes(int n, int d, int m)
 {

@@ -196,6 +196,96 @@ hipError_t launch_hash_tile(int log2n, bool signs, const TileParams& p, long lon
     }
 }
 
+// ------------------------------------------------------------------ buckets of a projection that lies in memory (n > 2^16)
+// Above the fused range the projection y is produced by the four-pass schedule; the bucket of each vector is then
+// taken from y in two steps.  Step 1: a workgroup scans one chunk of 2^kArgmaxChunkLog coordinates of one vector and
+// leaves the chunk's candidate (value, index): largest |y_i|, lowest index on exact ties.  Step 2: one wave per vector
+// picks among the candidates by the same rule and writes index + n when the value is negative.
+constexpr int kArgmaxChunkLog = 16;
+
+__device__ __forceinline__ void argmax_take(float& best, int& best_i, float ov, int oi)
+{
+    const float fa = __builtin_fabsf(ov), fb = __builtin_fabsf(best);
+    const bool take = (fa > fb) || (fa == fb && oi < best_i);
+    best = take ? ov : best;
+    best_i = take ? oi : best_i;
+}
+
+__global__ void __launch_bounds__(256) hash_argmax_chunks_kernel(const float* __restrict__ y, int log2n, float* __restrict__ cand_val,
+                                                                 int* __restrict__ cand_idx)
+{
+    const int chunks_log = log2n - kArgmaxChunkLog;
+    const long long vec = blockIdx.x >> chunks_log;
+    const int chunk = blockIdx.x & ((1 << chunks_log) - 1);
+    const int first = chunk << kArgmaxChunkLog;
+    const float4* src = reinterpret_cast<const float4*>(y + (vec << log2n) + first);
+    float best = 0.0f;
+    int best_i = 0x7fffffff;
+    // a thread meets its coordinates in increasing order, so the strict comparison keeps the lowest index
+    for (int q = threadIdx.x; q < (1 << (kArgmaxChunkLog - 2)); q += 256) {
+        const float4 t = src[q];
+        const int i = first + 4 * q;
+        argmax_take(best, best_i, t.x, i);
+        argmax_take(best, best_i, t.y, i + 1);
+        argmax_take(best, best_i, t.z, i + 2);
+        argmax_take(best, best_i, t.w, i + 3);
+    }
+    static_for<0, 6>([&](auto b) {
+        const float ov = lane_xor<(1 << b.value)>(best);
+        const int oi = lane_xor_i<(1 << b.value)>(best_i);
+        argmax_take(best, best_i, ov, oi);
+    });
+    __shared__ float red_val[4];
+    __shared__ int red_idx[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { red_val[wave] = best; red_idx[wave] = best_i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) argmax_take(best, best_i, red_val[w], red_idx[w]);
+        cand_val[blockIdx.x] = best;
+        cand_idx[blockIdx.x] = best_i;
+    }
+}
+
+__global__ void __launch_bounds__(64) hash_argmax_pick_kernel(const float* __restrict__ cand_val, const int* __restrict__ cand_idx,
+                                                              int log2n, int* __restrict__ out_idx, long long out_stride)
+{
+    const int chunks = 1 << (log2n - kArgmaxChunkLog);
+    const long long vec = blockIdx.x;
+    float best = 0.0f;
+    int best_i = 0x7fffffff;
+    for (int k = threadIdx.x; k < chunks; k += 64) argmax_take(best, best_i, cand_val[vec * chunks + k], cand_idx[vec * chunks + k]);
+    static_for<0, 6>([&](auto b) {
+        const float ov = lane_xor<(1 << b.value)>(best);
+        const int oi = lane_xor_i<(1 << b.value)>(best_i);
+        argmax_take(best, best_i, ov, oi);
+    });
+    if (best_i == 0x7fffffff) best_i = 0;      // no coordinate compared at all (NaN input): bucket 0
+    if (threadIdx.x == 0) out_idx[vec * out_stride] = best_i + ((best < 0.0f) ? (1 << log2n) : 0);
+}
+
+size_t hash_candidates_bytes(int log2n, long long batch)
+{
+    return log2n > kArgmaxChunkLog ? (size_t)batch * ((size_t)1 << (log2n - kArgmaxChunkLog)) * 8 : 0;
+}
+
+// y: fp32 [batch][n]; candidates: hash_candidates_bytes(log2n, batch) bytes of scratch; out_idx[vec * out_stride]
+hipError_t launch_hash_argmax(const float* y, int log2n, long long batch, void* candidates, int* out_idx, long long out_stride,
+                              hipStream_t s)
+{
+    if (log2n <= kArgmaxChunkLog) return hipErrorInvalidValue;
+    if (batch <= 0) return hipSuccess;
+    const long long blocks = batch << (log2n - kArgmaxChunkLog);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    float* cand_val = static_cast<float*>(candidates);
+    int* cand_idx = reinterpret_cast<int*>(cand_val + blocks);
+    hipLaunchKernelGGL(hash_argmax_chunks_kernel, dim3((unsigned)blocks), dim3(256), 0, s, y, log2n, cand_val, cand_idx);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(hash_argmax_pick_kernel, dim3((unsigned)batch), dim3(64), 0, s, cand_val, cand_idx, log2n, out_idx, out_stride);
+    return hipGetLastError();
+}
+
 #define CASE(NT) case NT: return signs ? launch_hash_nt<NT, true>(p, s) : launch_hash_nt<NT, false>(p, s);
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s)
 {

@@ -118,6 +118,10 @@ hipError_t launch_col_middle(int rows_log, int contig_log, bool signs, const Til
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
 hipError_t launch_hash(int log2n, bool signs, const HashParams& p, hipStream_t s);
 hipError_t launch_hash_tile(int log2n, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // n = 2^15, 2^16, one triple
+// n > 2^16: buckets of a projection y [batch][n] that the four-pass schedule left in memory (two small kernels)
+size_t hash_candidates_bytes(int log2n, long long batch);
+hipError_t launch_hash_argmax(const float* y, int log2n, long long batch, void* candidates, int* out_idx, long long out_stride,
+                              hipStream_t s);
 // sign codes (angular-kernel features): fused kernels for n = 2^8 .. 2^16, packing of an fp32 projection, Gram matrix
 constexpr int kCodeMinLog = 8;
 hipError_t launch_fused_signbits(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s);

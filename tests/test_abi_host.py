@@ -83,6 +83,18 @@ def test_hash_rejects_bad_arguments_before_launch(b):
     assert h(4, 1024, 4, 2, 64, 64, None) == b.SPINNER_ERR_ALIGNMENT
     assert h(64, 1 << 17, 4, 2, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
     assert h(None, 1024, 0, 2, None, None, None) == b.SPINNER_OK
+    # the variant with a workspace serves every n; above 2^16 the workspace holds the projection and the candidates
+    hw = b.lib.spinner_hash_ws
+    assert b.spinner_hash_workspace_bytes(1 << 16, 8) == 0 and b.spinner_hash_workspace_bytes(1000, 8) == 0
+    assert b.spinner_hash_workspace_bytes(1 << 17, 3) == 3 * (1 << 17) * 4 + 3 * 2 * 8
+    assert b.spinner_hash_workspace_bytes(1 << 24, 1) == (1 << 26) + 256 * 8
+    assert hw(64, 1 << 17, 4, 2, 64, 64, None, None) == b.SPINNER_ERR_WORKSPACE
+    assert hw(64, 1 << 17, 4, 2, 64, 64, 72, None) == b.SPINNER_ERR_ALIGNMENT
+    assert hw(64, 1 << 17, 4, 0, 64, 64, 64, None) == b.SPINNER_ERR_BAD_L
+    assert hw(64, 1 << 25, 4, 2, 64, 64, 64, None) == b.SPINNER_ERR_BAD_N
+    assert hw(None, 1 << 17, 4, 2, 64, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
+    assert hw(None, 1 << 17, 0, 2, None, None, None, None) == b.SPINNER_OK
+    assert b.lib.spinner_hash_signs_ws(64, 1 << 17, 4, 2, None, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
 
 
 def test_sign_word_entry_points_reject_bad_arguments(b):

@@ -206,6 +206,53 @@ def test_hash_every_size(gpu, oracle, log2n):
         assert exact + banded == batch * L and banded <= 1
 
 
+@pytest.mark.parametrize("log2n,batch,L", [(17, 5, 2), (18, 3, 1), (20, 2, 2), (22, 1, 1)])
+def test_hash_above_the_fused_range(gpu, oracle, log2n, batch, L):
+    # four passes per triple into the workspace, then the bucket from there (spinner_hash_ws); both diagonal forms
+    n = 1 << log2n
+    w = W.Workload("h", "hash", n, batch, n, "hash", 1.0, L, "unit_normal", 600 + log2n, batch)
+    x = W.make_x_numpy(w)
+    ds = W.diag_sets(w)
+    ys = np.stack([oracle.spinner_by_products(x, ds[l, 0], ds[l, 1], ds[l, 2]) for l in range(L)])
+    got = gpu.b.spinner_hash_ws(_to(gpu, x), _to(gpu, ds)).cpu().numpy()
+    assert got.shape == (batch, L) and got.dtype == np.int32
+    exact, banded = check_hash_against_projection(got, ys)
+    assert exact + banded == batch * L and banded <= 1
+    signs = gpu.b.spinner_pack_signs(_to(gpu, ds))
+    got = gpu.b.spinner_hash_signs_ws(_to(gpu, x), signs, L).cpu().numpy()
+    exact, banded = check_hash_against_projection(got, ys)
+    assert exact + banded == batch * L and banded <= 1
+    with pytest.raises(gpu.b.SpinnerError):
+        gpu.b.spinner_hash(_to(gpu, x), _to(gpu, ds))      # the call without a workspace stops at 2^16
+
+
+def test_hash_above_the_fused_range_on_constructed_inputs(gpu):
+    # D = I: x = +-(column j of normalised H) gives y = +-e_j exactly (entries are +-2^-9 at n = 2^18); a tie between
+    # two coordinates that fall into different chunks of the scan goes to the lower index; zero vector -> bucket 0
+    t = gpu.torch
+    n = 1 << 18
+    ones = t.ones((1, 3, n), dtype=t.float32, device=gpu.dev)
+    i = np.arange(n, dtype=np.int64)
+
+    def col(j):
+        v, par = i & j, np.zeros(n, dtype=np.int64)
+        for s in range(18):
+            par ^= (v >> s) & 1
+        return ((1.0 - 2.0 * par) / 512.0).astype(np.float32)
+
+    js = [0, 3, 65535, 65536, 200000, n - 1]
+    x = np.zeros((2 * len(js) + 3, n), dtype=np.float32)
+    for k, j in enumerate(js):
+        x[2 * k] = col(j)
+        x[2 * k + 1] = -col(j)
+    x[-3] = col(70000) + col(5)            # tie across chunks: lowest index
+    x[-2] = -col(262000) - col(131072)     # tie of two negative coordinates
+    got = gpu.b.spinner_hash_ws(_to(gpu, x), ones).cpu().numpy()[:, 0]
+    for k, j in enumerate(js):
+        assert got[2 * k] == j and got[2 * k + 1] == j + n, j
+    assert got[-3] == 5 and got[-2] == 131072 + n and got[-1] == 0
+
+
 def test_hash_rules_on_constructed_inputs(gpu):
     # D = I, x = +-(column j of normalised H)  ->  bucket j / j + n ; zero vector -> bucket 0 ;
     # exact tie -> lowest index.
