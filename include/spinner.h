@@ -255,14 +255,20 @@ int spinner_angular_gram(const void *codes_a, long na, const void *codes_b, long
  *   d1..d3     in   device fp32 [n], arbitrary values
  *   y, dx      out  device fp32 [batch][n]; dx may alias dy
  *   saved      out/in  device, spinner_layer_saved_bytes(n, batch) = 2 * batch * n * 4
- *                   bytes, opaque (unnormalised activations); written by the forward
- *                   call, passed unchanged to the backward call of the same x, d1..d3
+ *                   bytes, opaque; written by the forward call, passed unchanged to
+ *                   the backward call of the same x, d1..d3
  *   dd         out  device fp32 [3][n], overwritten
  *   workspace  in   device scratch of spinner_layer_workspace_bytes(n, batch) bytes
- *                   (per-workgroup partial sums; they are added up in fp64)
+ *                   (partial sums over the batch, added up in fp64 in a fixed order;
+ *                   above 2^14 also two signal buffers of batch * n floats)
  *
- * n = 2^4 .. 2^14 (SPINNER_ERR_UNSUPPORTED above), batch < 2^31.  Same ownership,
- * alignment and error rules as spinner_apply.
+ * n = 2^4 .. 2^24, batch < 2^31.  Up to 2^14 each call is one fused kernel (plus the
+ * reduction of the partial sums).  Above, every one of the three transforms is a pass
+ * over the rows and a pass over the columns of the matrix view of the vector (the
+ * saved activations arise between transforms), the backward pass writes the signal
+ * arriving at each diagonal to the workspace and sums signal times activation over
+ * the batch: six passes forward, six passes and three batch sums backward.  Same
+ * ownership, alignment and error rules as spinner_apply.
  */
 size_t spinner_layer_saved_bytes(int n, long batch);
 size_t spinner_layer_workspace_bytes(int n, long batch);

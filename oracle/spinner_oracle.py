@@ -230,9 +230,10 @@ def layer_forward(x, d1, d2, d3, scale: float = 1.0, nthreads: int = 0):
     b1 = H D1 x and b2 = H D2 b1 (all fp64, [batch][n])."""
     x = np.ascontiguousarray(x, dtype=np.float64)
     d1, d2, d3 = (np.asarray(d, dtype=np.float64) for d in (d1, d2, d3))
-    b1 = hadamard_apply(x * d1)
-    b2 = hadamard_apply(b1 * d2)
-    y = float(scale) * hadamard_apply(b2 * d3)
+    ka = default_kron_a(x.shape[-1])              # dense H_n up to DENSE_MAX_N, its two Kronecker factors above
+    b1 = hadamard_apply(x * d1, ka)
+    b2 = hadamard_apply(b1 * d2, ka)
+    y = float(scale) * hadamard_apply(b2 * d3, ka)
     return y, b1, b2
 
 
@@ -243,11 +244,12 @@ def layer_backward(x, d1, d2, d3, dy, scale: float = 1.0):
     x = np.ascontiguousarray(x, dtype=np.float64)
     dy = np.ascontiguousarray(dy, dtype=np.float64)
     _, b1, b2 = layer_forward(x, d1, d2, d3, scale)
-    g3 = float(scale) * hadamard_apply(dy)        # dL/d(D3 b2): H^T = H
+    ka = default_kron_a(x.shape[-1])
+    g3 = float(scale) * hadamard_apply(dy, ka)    # dL/d(D3 b2): H^T = H
     dd3 = (g3 * b2).sum(axis=0)
-    g2 = hadamard_apply(g3 * d3)                  # dL/d(D2 b1)
+    g2 = hadamard_apply(g3 * d3, ka)              # dL/d(D2 b1)
     dd2 = (g2 * b1).sum(axis=0)
-    g1 = hadamard_apply(g2 * d2)                  # dL/d(D1 x)
+    g1 = hadamard_apply(g2 * d2, ka)              # dL/d(D1 x)
     dd1 = (g1 * x).sum(axis=0)
     dx = g1 * d1
     return dx, np.stack([dd1, dd2, dd3])

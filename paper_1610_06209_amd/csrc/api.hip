@@ -458,22 +458,59 @@ int spinner_angular_gram(const void* codes_a, long na, const void* codes_b, long
 size_t spinner_layer_saved_bytes(int n, long batch)
 {
     int log2n;
-    if (!pow2_in_range(n, &log2n) || log2n > spinner::kLayerMaxLog || batch <= 0) return 0;
+    if (!pow2_in_range(n, &log2n) || batch <= 0) return 0;
     return 2 * (size_t)batch * (size_t)n * sizeof(float);
 }
 
 size_t spinner_layer_workspace_bytes(int n, long batch)
 {
     int log2n;
-    if (!pow2_in_range(n, &log2n) || log2n > spinner::kLayerMaxLog || batch <= 0) return 0;
+    if (!pow2_in_range(n, &log2n) || batch <= 0) return 0;
+    if (log2n > spinner::kLayerMaxLog)      // two signal buffers and the partial rows of the batch sums
+        return 2 * (size_t)batch * (size_t)n * sizeof(float) + (size_t)spinner::layer_large_slabs(log2n, batch) * (size_t)n * sizeof(float);
     return (size_t)spinner::layer_backward_slots(log2n, batch) * 3 * (size_t)n * sizeof(float);
 }
 
 static int check_layer_args(int n, long batch, int* log2n)
 {
     if (!pow2_in_range(n, log2n)) return SPINNER_ERR_BAD_N;
-    if (*log2n > spinner::kLayerMaxLog) return SPINNER_ERR_UNSUPPORTED;
     if (batch < 0 || batch > 0x7fffffffL || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
+    return SPINNER_OK;
+}
+
+// One transform of vectors longer than the fused layer kernels serve: out = factor * H (diag .* in), or factor * H in
+// when diag is null, as a pass over the rows and a pass over the columns of the 2^rows x 2^nr view of each vector
+// (the passes of the four-pass schedule, one transform each).  in == out is allowed.  The batch is walked in slices of
+// 256 MiB so that the second pass finds what the first wrote in the memory-side cache.
+static int large_round(const float* in, const float* diag, float* out, int n, int log2n, long long batch, double factor,
+                       hipStream_t s)
+{
+    using namespace spinner;
+    const ColShape cs = col_shape_for(log2n);
+    const int nr = log2n - cs.rows_log;
+    long long slice = (256LL << 20) / (4LL * n);
+    if (slice < 8) slice = 8;
+    if (slice > batch) slice = batch;
+    const long long nslices = (batch + slice - 1) / slice;
+    slice = (batch + nslices - 1) / nslices;
+    if ((slice << cs.rows_log) > 0x7fffffffLL * 4 || (slice << (nr - cs.contig_log)) > 0x7fffffffLL) return SPINNER_ERR_BAD_BATCH;
+    TileParams p;
+    memset(&p, 0, sizeof(p));
+    p.xcd_group_log = -1;
+    p.in_stride = n; p.out_stride = n; p.m = n;
+    for (long long b0 = 0; b0 < batch; b0 += slice) {
+        const long long nb = batch - b0 < slice ? batch - b0 : slice;
+        hipError_t e;
+        p.batch = nb;
+        p.x = in + b0 * (long long)n; p.out = out + b0 * (long long)n; p.d[0] = diag;
+        p.tiles_per_vec_log = cs.rows_log; p.tb = nr; p.sl = 0; p.factor = 1.0f;
+        e = diag ? launch_row_first(nr, false, p, nb << cs.rows_log, s) : launch_row_plain(nr, p, nb << cs.rows_log, s);
+        if (e != hipSuccess) return hip_fail(e);
+        p.x = p.out; p.d[0] = nullptr;
+        p.tiles_per_vec_log = nr - cs.contig_log; p.tb = cs.contig_log; p.sl = nr; p.factor = (float)factor;
+        if ((e = launch_col_last(cs.rows_log, cs.contig_log, EPI_STORE_NONE, p, nb << (nr - cs.contig_log), s)) != hipSuccess)
+            return hip_fail(e);
+    }
     return SPINNER_OK;
 }
 
@@ -486,6 +523,17 @@ int spinner_layer_forward(const float* x, int n, long batch, const float* d1, co
     if (!x || !d1 || !d2 || !d3 || !y || !saved) return SPINNER_ERR_NULL_PTR;
     if (!aligned16(x) || !aligned16(d1) || !aligned16(d2) || !aligned16(d3) || !aligned16(y) || !aligned16(saved))
         return SPINNER_ERR_ALIGNMENT;
+    if (log2n > spinner::kLayerMaxLog) {
+        // three single transforms; the activations entering D2 and D3 are kept normalised
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        float* a2 = static_cast<float*>(saved);
+        float* a3 = a2 + (size_t)batch * n;
+        const double h = 1.0 / sqrt((double)n);
+        int r = large_round(x, d1, a2, n, log2n, batch, h, s);
+        if (r == SPINNER_OK) r = large_round(a2, d2, a3, n, log2n, batch, h, s);
+        if (r == SPINNER_OK) r = large_round(a3, d3, y, n, log2n, batch, h * (double)scale, s);
+        return r;
+    }
     spinner::LayerForwardParams p;
     p.x = x; p.d[0] = d1; p.d[1] = d2; p.d[2] = d3; p.y = y;
     p.saved1 = static_cast<float*>(saved);
@@ -510,6 +558,26 @@ int spinner_layer_backward(const float* dy, const float* x, const void* saved, i
         !aligned16(dx) || !aligned16(dd) || !aligned16(workspace))
         return SPINNER_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (log2n > spinner::kLayerMaxLog) {
+        // the signal arriving at D3, D2, D1 from the output side is materialised in turn (g3 = scale H dy, g2 = H D3 g3,
+        // g1 = H D2 g2); each diagonal's gradient is the batch sum of signal times saved activation; dx = D1 g1
+        const float* a2 = static_cast<const float*>(saved);
+        const float* a3 = a2 + (size_t)batch * n;
+        float* w0 = static_cast<float*>(workspace);
+        float* w1 = w0 + (size_t)batch * n;
+        float* partial = w1 + (size_t)batch * n;
+        const double h = 1.0 / sqrt((double)n);
+        int r = large_round(dy, nullptr, w0, n, log2n, batch, h * (double)scale, s);
+        if (r != SPINNER_OK) return r;
+        hipError_t e = spinner::launch_layer_large_dd(w0, a3, log2n, batch, partial, dd + 2 * (size_t)n, nullptr, nullptr, s);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((r = large_round(w0, d3, w1, n, log2n, batch, h, s)) != SPINNER_OK) return r;
+        if ((e = spinner::launch_layer_large_dd(w1, a2, log2n, batch, partial, dd + (size_t)n, nullptr, nullptr, s)) != hipSuccess)
+            return hip_fail(e);
+        if ((r = large_round(w1, d2, w0, n, log2n, batch, h, s)) != SPINNER_OK) return r;
+        e = spinner::launch_layer_large_dd(w0, x, log2n, batch, partial, dd, d1, dx, s);
+        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+    }
     const double factor = (double)scale / ((double)n * sqrt((double)n));
     spinner::LayerBackwardParams p;
     p.dy = dy; p.x = x;

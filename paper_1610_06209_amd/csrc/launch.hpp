@@ -113,6 +113,7 @@ hipError_t launch_fused_cossin(int log2n, bool signs, const TileParams& p, long 
 // signs: the diagonal of the pass comes as packed words p.sw[] (rows of at least 2^kRowSignsMinLog elements), not as p.d[]
 hipError_t launch_row_first(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s);    // D1 then rows
 hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // rows, D3, rows
+hipError_t launch_row_plain(int nt, const TileParams& p, long long tiles, hipStream_t s);                 // rows
 // signs: the pass flips by the lane masks p.sw[1] that launch_pack_col_words prepared for its tiles
 hipError_t launch_col_middle(int rows_log, int contig_log, bool signs, const TileParams& p, long long tiles, hipStream_t s);   // cols, D2, cols
 hipError_t launch_col_last(int rows_log, int contig_log, int epi, const TileParams& p, long long tiles, hipStream_t s);   // cols, epilogue
@@ -188,6 +189,11 @@ hipError_t launch_layer_forward(int log2n, const LayerForwardParams& p, hipStrea
 long long layer_backward_slots(int log2n, long long batch);      // partial-sum rows the backward kernel writes
 hipError_t launch_layer_backward(int log2n, const LayerBackwardParams& p, hipStream_t s);
 hipError_t launch_layer_reduce(const float* partial, long long slots, long long len, double factor, float* dd, hipStream_t s);
+// n > 2^14: dd[i] = sum over the batch of g[b][i] a[b][i] (partial: layer_large_slabs(log2n, batch) rows of n floats);
+// with d1 != null the same sweep writes dx = d1 .* g
+long long layer_large_slabs(int log2n, long long batch);
+hipError_t launch_layer_large_dd(const float* g, const float* a, int log2n, long long batch, float* partial, float* dd,
+                                 const float* d1, float* dx, hipStream_t s);
 
 // Newton sketch: transposition with optional row weights, Gram matrix on the matrix pipe
 hipError_t launch_transpose_scale(const float* src, long long rows, long long cols, const float* row_scale, float* dst,

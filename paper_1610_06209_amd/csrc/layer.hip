@@ -1,4 +1,4 @@
-// Adaptive-layer kernels: forward with saved activations, backward, n = 2^4 .. 2^14.
+// Adaptive-layer kernels: forward with saved activations, backward, n = 2^4 .. 2^14; batch sums of the backward pass above that.
 #include "launch.hpp"
 #include "layer_kernels.hpp"
 namespace spinner {
@@ -34,6 +34,53 @@ __global__ void __launch_bounds__(256) layer_reduce_kernel(const float* __restri
         for (int r = 0; r < 16; ++r) t += sh[r][tx];
         dd[i] = (float)(factor * t);
     }
+}
+
+// Above the fused range the backward pass materialises the signal that arrives at each diagonal; the gradient of
+// that diagonal is then a sum over the batch of (signal x activation), per coordinate.  Block (bx, by) owns four
+// coordinates per thread and the vectors by, by + S, by + 2S, ... (S = gridDim.y) and writes row `by` of `partial`
+// (fp64 sums, rounded once); layer_reduce_kernel adds the S rows in fp64 in a fixed order.  With d1 != null the same
+// sweep also writes dx = d1 .* g (the last step of the backward pass).
+__global__ void __launch_bounds__(256) layer_large_dd_kernel(const float* __restrict__ g, const float* __restrict__ a, long long n,
+                                                             long long batch, float* __restrict__ partial,
+                                                             const float* __restrict__ d1, float* __restrict__ dx)
+{
+    const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n) return;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    float4 dv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (d1) dv = *reinterpret_cast<const float4*>(d1 + i);
+    for (long long b = blockIdx.y; b < batch; b += gridDim.y) {
+        const float4 gv = *reinterpret_cast<const float4*>(g + b * n + i);
+        const float4 av = *reinterpret_cast<const float4*>(a + b * n + i);
+        s0 += (double)gv.x * (double)av.x; s1 += (double)gv.y * (double)av.y;
+        s2 += (double)gv.z * (double)av.z; s3 += (double)gv.w * (double)av.w;
+        if (d1) *reinterpret_cast<float4*>(dx + b * n + i) = make_float4(dv.x * gv.x, dv.y * gv.y, dv.z * gv.z, dv.w * gv.w);
+    }
+    *reinterpret_cast<float4*>(partial + (long long)blockIdx.y * n + i) = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+}
+
+// rows of `partial` the large-n backward pass uses: enough blocks to fill the chip, never more than the batch
+long long layer_large_slabs(int log2n, long long batch)
+{
+    const long long per_row = ((1LL << log2n) / 4 + 255) / 256;       // blocks along the coordinates
+    long long slabs = (2048 + per_row - 1) / per_row;
+    if (slabs > batch) slabs = batch;
+    if (slabs > 1024) slabs = 1024;
+    return slabs < 1 ? 1 : slabs;
+}
+
+hipError_t launch_layer_large_dd(const float* g, const float* a, int log2n, long long batch, float* partial, float* dd,
+                                 const float* d1, float* dx, hipStream_t s)
+{
+    const long long n = 1LL << log2n;
+    const long long per_row = (n / 4 + 255) / 256;
+    const long long slabs = layer_large_slabs(log2n, batch);
+    if (per_row > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(layer_large_dd_kernel, dim3((unsigned)per_row, (unsigned)slabs), dim3(256), 0, s, g, a, n, batch, partial, d1, dx);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_layer_reduce(partial, slabs, n, 1.0, dd, s);
 }
 
 template <int NT>

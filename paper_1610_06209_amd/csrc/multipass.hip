@@ -27,6 +27,16 @@ hipError_t launch_row_middle(int nt, bool signs, const TileParams& p, long long 
     default: return hipErrorInvalidValue;
     }
 }
+// rows only, no diagonal (single transforms of the adaptive layer above its fused range)
+#define ROWPLAIN(NT) case NT: return launch_tile<float, NT, NT, 1, false, EPI_STORE_NONE>(p, tiles, s);
+hipError_t launch_row_plain(int nt, const TileParams& p, long long tiles, hipStream_t s)
+{
+    switch (nt) {
+        ROWPLAIN(5) ROWPLAIN(6) ROWPLAIN(7) ROWPLAIN(8) ROWPLAIN(9) ROWPLAIN(10) ROWPLAIN(11) ROWPLAIN(12) ROWPLAIN(13) ROWPLAIN(14)
+    default: return hipErrorInvalidValue;
+    }
+}
+#undef ROWPLAIN
 #undef ROWCASE
 #define COLCASE(NT, C, STEPS, EPI) if (rows_log + contig_log == NT && contig_log == C) return launch_tile<float, NT, C, STEPS, false, EPI>(p, tiles, s);
 #define COLMID(NT, C)                                                                                     \

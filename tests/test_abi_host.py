@@ -161,7 +161,7 @@ def test_sign_code_entry_points_host_side(b):
 
 def test_layer_entry_points_host_side(b):
     assert b.spinner_layer_saved_bytes(1024, 10) == 2 * 10 * 1024 * 4
-    assert b.spinner_layer_saved_bytes(1 << 15, 10) == 0 and b.spinner_layer_saved_bytes(1000, 10) == 0
+    assert b.spinner_layer_saved_bytes(1 << 15, 10) == 2 * 10 * (1 << 15) * 4 and b.spinner_layer_saved_bytes(1000, 10) == 0
     # one partial row of 3 n floats per tile slot: small batches take one slot per vector (rounded up to whole workgroups)
     assert b.spinner_layer_workspace_bytes(4096, 8) == 8 * 3 * 4096 * 4
     # large batches: as many slots as tiles are resident on the chip (four workgroups per compute unit, or what the
@@ -171,11 +171,15 @@ def test_layer_entry_points_host_side(b):
     assert b.spinner_layer_workspace_bytes(4096, 1 << 20) == 768 * 3 * 4096 * 4
     assert b.spinner_layer_workspace_bytes(8192, 1 << 20) == 512 * 3 * 8192 * 4
     assert b.spinner_layer_workspace_bytes(16, 1 << 20) == 8192 * 3 * 16 * 4          # bounded number of partial rows
-    assert b.spinner_layer_workspace_bytes(1 << 15, 8) == 0
+    # above 2^14: two signal buffers and one partial row per slab of the batch sums (never more slabs than vectors)
+    assert b.spinner_layer_workspace_bytes(1 << 15, 8) == (2 * 8 + 8) * (1 << 15) * 4
+    assert b.spinner_layer_workspace_bytes(1 << 15, 1000) == (2 * 1000 + 64) * (1 << 15) * 4
+    assert b.spinner_layer_workspace_bytes(1 << 24, 3) == (2 * 3 + 1) * (1 << 24) * 4
     f = b.lib.spinner_layer_forward
     one = ctypes.c_float(1.0)
     assert f(64, 1000, 4, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_BAD_N
-    assert f(64, 1 << 15, 4, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
+    assert f(64, 1 << 25, 4, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_BAD_N
+    assert f(64, 1 << 15, 4, 64, 64, 64, one, 64, None, None) == b.SPINNER_ERR_NULL_PTR
     assert f(64, 1024, -1, 64, 64, 64, one, 64, 64, None) == b.SPINNER_ERR_BAD_BATCH
     assert f(64, 1024, 4, 64, None, 64, one, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
     assert f(64, 1024, 4, 64, 64, 64, one, 64, None, None) == b.SPINNER_ERR_NULL_PTR
@@ -184,6 +188,7 @@ def test_layer_entry_points_host_side(b):
     g = b.lib.spinner_layer_backward
     assert g(64, 64, 64, 1000, 4, 64, 64, 64, one, 64, 64, 64, None) == b.SPINNER_ERR_BAD_N
     assert g(64, 64, 64, 1024, 4, 64, 64, 64, one, 64, 64, None, None) == b.SPINNER_ERR_WORKSPACE
+    assert g(64, 64, 64, 1 << 17, 4, 64, 64, 64, one, 64, 64, None, None) == b.SPINNER_ERR_WORKSPACE
     assert g(64, None, 64, 1024, 4, 64, 64, 64, one, 64, 64, 64, None) == b.SPINNER_ERR_NULL_PTR
     assert g(64, 64, 64, 1024, 4, 64, 64, 64, one, 64, 68, 64, None) == b.SPINNER_ERR_ALIGNMENT
     assert g(None, None, None, 1024, 0, None, None, None, one, None, None, None, None) == b.SPINNER_OK

@@ -76,6 +76,26 @@ def test_layer_forward_backward_every_size(gpu, oracle, log2n):
     _check(oracle, x, d, dy, scale, y, dx, dd)
 
 
+@pytest.mark.parametrize("log2n,batch", [(15, 5), (16, 3), (17, 70), (19, 2), (20, 2)])
+def test_layer_above_the_fused_range(gpu, oracle, log2n, batch):
+    # single transforms as a pass over rows and a pass over columns, the signals of the backward pass materialised,
+    # the diagonal gradients as batch sums; (17, 70): more vectors than slabs of the batch sum
+    n = 1 << log2n
+    x, d, dy = _case(n, batch, 6300 + log2n)
+    scale = 1.0 if log2n % 2 else 1.7
+    y, dx, dd = _run(gpu, x, d, dy, scale)
+    _check(oracle, x, d, dy, scale, y, dx, dd)
+    # dx written over dy; the forward pass agrees with the projection entry point
+    xt, dt, dyt = _to(gpu, x), _to(gpu, d), _to(gpu, dy)
+    y1, saved = gpu.b.spinner_layer_forward(xt, dt[0], dt[1], dt[2], scale)
+    dx2, dd2 = gpu.b.spinner_layer_backward(dyt, xt, saved, dt[0], dt[1], dt[2], scale, dx=dyt)
+    y3 = gpu.b.spinner_apply(xt, dt[0], dt[1], dt[2], n, "none", scale)
+    gpu.torch.cuda.synchronize()
+    assert dx2.data_ptr() == dyt.data_ptr()
+    assert np.array_equal(dx2.cpu().numpy(), dx) and np.array_equal(dd2.cpu().numpy(), dd)
+    assert rel_l2_per_vector(y1.cpu().numpy(), y3.cpu().numpy().astype(np.float64)).max() <= 2e-6
+
+
 @pytest.mark.parametrize("n,batch", [(64, 70000), (256, 20000), (2048, 2300), (4096, 1100), (8192, 700), (16384, 600)])
 def test_layer_backward_many_vectors_per_slot(gpu, oracle, n, batch):
     # more vectors than resident tile slots: every slot accumulates several vectors, the last round is ragged
