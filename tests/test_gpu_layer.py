@@ -96,6 +96,30 @@ def test_layer_above_the_fused_range(gpu, oracle, log2n, batch):
     assert rel_l2_per_vector(y1.cpu().numpy(), y3.cpu().numpy().astype(np.float64)).max() <= 2e-6
 
 
+def test_layer_above_the_fused_range_in_several_slices(gpu):
+    # n = 2^17: the passes walk the batch in slices of 512 vectors; 513 vectors leave a second, shorter slice (257 + 256).
+    # Vectors are independent, so y and dx of any row must have the bits of a run on that row alone; each diagonal
+    # gradient satisfies sum_i d_k[i] dd_k[i] = <dy, y> (the layer is linear in each diagonal).
+    t = gpu.torch
+    n, batch = 1 << 17, 513
+    g = t.Generator(device=gpu.dev)
+    g.manual_seed(6400)
+    x = t.randn((batch, n), generator=g, device=gpu.dev, dtype=t.float32)
+    dy = t.randn((batch, n), generator=g, device=gpu.dev, dtype=t.float32)
+    d = t.randn((3, n), generator=g, device=gpu.dev, dtype=t.float32) * 0.5 + 1.0
+    y, saved = gpu.b.spinner_layer_forward(x, d[0], d[1], d[2], 1.3)
+    dx, dd = gpu.b.spinner_layer_backward(dy, x, saved, d[0], d[1], d[2], 1.3)
+    rows = [0, 255, 256, 257, 511, 512]
+    xs, dys = x[rows].contiguous(), dy[rows].contiguous()
+    ys, saved_s = gpu.b.spinner_layer_forward(xs, d[0], d[1], d[2], 1.3)
+    dxs, _ = gpu.b.spinner_layer_backward(dys, xs, saved_s, d[0], d[1], d[2], 1.3)
+    t.cuda.synchronize()
+    assert t.equal(y[rows], ys) and t.equal(dx[rows], dxs)
+    inner = float((dy.double() * y.double()).sum())
+    for k in range(3):
+        assert abs(float((d[k].double() * dd[k].double()).sum()) - inner) <= 1e-5 * abs(inner)
+
+
 @pytest.mark.parametrize("n,batch", [(64, 70000), (256, 20000), (2048, 2300), (4096, 1100), (8192, 700), (16384, 600)])
 def test_layer_backward_many_vectors_per_slot(gpu, oracle, n, batch):
     # more vectors than resident tile slots: every slot accumulates several vectors, the last round is ragged
@@ -138,11 +162,11 @@ def test_layer_empty_batch_and_errors(gpu):
     x = t.zeros((0, 256), dtype=t.float32, device=gpu.dev)
     y, saved = b.spinner_layer_forward(x, d, d, d)
     assert tuple(y.shape) == (0, 256)
-    big = t.zeros((2, 1 << 15), dtype=t.float32, device=gpu.dev)
-    dbig = t.ones(1 << 15, dtype=t.float32, device=gpu.dev)
+    bad = t.zeros((2, 1000), dtype=t.float32, device=gpu.dev)
+    dbad = t.ones(1000, dtype=t.float32, device=gpu.dev)
     with pytest.raises(b.SpinnerError) as e:
-        b.spinner_layer_forward(big, dbig, dbig, dbig)
-    assert e.value.status == b.SPINNER_ERR_UNSUPPORTED
+        b.spinner_layer_forward(bad, dbad, dbad, dbad)
+    assert e.value.status == b.SPINNER_ERR_BAD_N
 
 
 def test_layer_step_as_a_captured_graph(gpu):
