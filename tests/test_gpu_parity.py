@@ -226,6 +226,23 @@ def test_hash_above_the_fused_range(gpu, oracle, log2n, batch, L):
         gpu.b.spinner_hash(_to(gpu, x), _to(gpu, ds))      # the call without a workspace stops at 2^16
 
 
+def test_hash_above_the_fused_range_in_several_slices(gpu):
+    # n = 2^17, 513 vectors: the passes walk the batch in two slices (257 + 256).  The bucket must be the argmax of the
+    # projection that spinner_apply writes for the same triple (same passes, so the same bits; random data has no ties)
+    t = gpu.torch
+    n, batch, L = 1 << 17, 513, 2
+    g = t.Generator(device=gpu.dev)
+    g.manual_seed(77)
+    x = t.randn((batch, n), generator=g, device=gpu.dev, dtype=t.float32)
+    ds = (1.0 - 2.0 * t.randint(0, 2, (L, 3, n), generator=g, device=gpu.dev)).float()
+    idx = gpu.b.spinner_hash_ws(x, ds)
+    for l in range(L):
+        y = gpu.b.spinner_apply(x, ds[l, 0], ds[l, 1], ds[l, 2])
+        i = y.abs().argmax(dim=1)
+        want = i + n * (y[t.arange(batch, device=gpu.dev), i] < 0).long()
+        assert bool((idx[:, l].long() == want).all()), l
+
+
 def test_hash_above_the_fused_range_on_constructed_inputs(gpu):
     # D = I: x = +-(column j of normalised H) gives y = +-e_j exactly (entries are +-2^-9 at n = 2^18); a tie between
     # two coordinates that fall into different chunks of the scan goes to the lower index; zero vector -> bucket 0
