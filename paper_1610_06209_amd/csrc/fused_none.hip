@@ -8,8 +8,6 @@ namespace spinner {
                                                 : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true>(p, tiles, s))            \
                                        : (whole ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false, 0, false>(p, tiles, s) \
                                                 : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false>(p, tiles, s));
-#define RCASE(NT) case NT: return signs ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true>(p, tiles, s) \
-                                        : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false>(p, tiles, s);
 #define PCASE(NT) case NT: return signs ? launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, true, kPruneBits>(p, tiles, s) \
                                         : launch_tile<float, NT, NT, 3, true, EPI_STORE_NONE, false, kPruneBits>(p, tiles, s);
 hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams& p, long long tiles, hipStream_t s)
@@ -23,13 +21,15 @@ hipError_t launch_fused_none(int log2n, bool signs, int prune, const TileParams&
     }
     switch (log2n) {
         CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14)
-        // 2^15, 2^16: the kernels without row-limit tests measured no faster with sign words and 2-6 % slower with fp32 diagonals
-        RCASE(15) RCASE(16)
+        // 2^15: the kernel without row-limit tests measured 1 % faster with sign words and 4 % slower with fp32 diagonals
+        case 15: return signs ? (whole ? launch_tile<float, 15, 15, 3, true, EPI_STORE_NONE, true, 0, false>(p, tiles, s)
+                                       : launch_tile<float, 15, 15, 3, true, EPI_STORE_NONE, true>(p, tiles, s))
+                              : launch_tile<float, 15, 15, 3, true, EPI_STORE_NONE, false>(p, tiles, s);
+        CASE(16)
     default: return hipErrorInvalidValue;
     }
 }
 #undef CASE
-#undef RCASE
 #undef PCASE
 
 // Lane masks of the sign flips in layout 1 of the wide geometries (n = 2^12 .. 2^14), behind the other words of
