@@ -233,8 +233,10 @@ def measure_layer(torch, b, dev, n, batch, steps, warmup, graph=False):
     return res
 
 
-def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup):
-    """Newton sketch: B = S diag(w) A (transposes + projection) and the d x d Gram matrix on the matrix pipe."""
+def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup, form):
+    """Newton sketch: B = S diag(w) A and the d x d Gram matrix on the matrix pipe.  `form` names the path the library
+    takes for this shape: the columns loaded as they lie (n <= 2^12, wide or small matrices), or transposition +
+    projection + transposition."""
     import math as _m
 
     g = torch.Generator(device=dev)
@@ -253,7 +255,7 @@ def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup):
     torch.cuda.synchronize()
     _, s_ms = time_calls(torch, sk, steps, warmup)
     _, g_ms = time_calls(torch, gr, steps, warmup)
-    res = {"workload": "newton_sketch_n%d_d%d_m%d" % (n, d, m), "sketch_ms": round(s_ms, 4), "gram_ms": round(g_ms, 4),
+    res = {"workload": "newton_sketch_n%d_d%d_m%d" % (n, d, m), "form": form, "sketch_ms": round(s_ms, 4), "gram_ms": round(g_ms, 4),
            # the method's own bytes: A read once, B written once
            "sketch_GBs": round((4.0 * n * d + 4.0 * m * d) / (s_ms * 1e-3) / 1e9, 1),
            "gram_TFLOPs": round(2.0 * m * d * d / (g_ms * 1e-3) / 1e12, 2), "gram_mfma_frac": round(2.0 * m * d * d / (g_ms * 1e-3) / 157.3e12, 4)}
@@ -363,10 +365,12 @@ def measure_next_rows(torch, b, W, dev, args):
     log("[bench] %s: forward %.4f ms (%.0f GB/s), backward %.4f ms (%.0f GB/s)" % (
         lay["workload"], lay["forward_ms"], lay["forward_GBs"], lay["backward_ms"], lay["backward_GBs"]))
     nxt.append(lay)
-    skt = measure_sketch(torch, b, W, dev, 1 << 16, 512, 2048, 10, 3)
-    log("[bench] %s: sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
-        skt["workload"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
-    nxt.append(skt)
+    for shape in ((1 << 16, 512, 2048, "transposition + projection + transposition"),
+                  (1 << 12, 4096, 2048, "columns loaded as they lie")):
+        skt = measure_sketch(torch, b, W, dev, shape[0], shape[1], shape[2], 10, 3, shape[3])
+        log("[bench] %s (%s): sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
+            skt["workload"], skt["form"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
+        nxt.append(skt)
     for kind in ("circulant", "toeplitz"):
         st = measure_struct(torch, b, dev, kind, 4096, 16384, 5, 2)
         log("[bench] %s: %.4f ms  %.3e vec/s  (%.0f GB/s counting 8 B per element)" % (

@@ -293,9 +293,15 @@ int spinner_layer_backward(const float *dy, const float *x, const void *saved,
  *   d1..d3     in   device fp32 [n]
  *   m, scale   in   rows of the sketch, extra factor (sqrt(n/m) makes E[S^T S] = I)
  *   B          out  device fp32 [m][d] row-major
- *   workspace  in   device scratch of spinner_sketch_workspace_bytes(n, d, m) bytes:
- *                   the matrix is transposed (weights applied on the way) so that each
- *                   column becomes one contiguous vector, projected with the same
+ *   workspace  in   device scratch of spinner_sketch_workspace_bytes(n, d, m) bytes.
+ *                   Two forms, picked by shape.  For n <= 2^12 with d a multiple of 4
+ *                   (matrices wide enough to fill the chip with column groups, and small
+ *                   ones) one kernel loads the columns as they lie in the row-major
+ *                   matrix - a tile is all n rows by 16 or 32 contiguous columns - and A
+ *                   is moved once; the workspace is then not touched.  Otherwise (n >> d,
+ *                   a column does not fit on chip beside enough neighbours for coalesced
+ *                   loads) the matrix is transposed (weights applied on the way) so that
+ *                   each column becomes one contiguous vector, projected with the same
  *                   kernels as spinner_apply, and the result transposed back
  * spinner_sketch_gram computes G = B^T B (device fp32 [d][d], all of it, symmetric)
  * on the fp32 matrix pipe; the sum over the m rows is split into slabs that are added

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspinner.so")
-UNITS = ["api", "fused_none", "fused_cossin", "fused_signbits", "multipass", "hash", "layer", "sketch", "structured", "blocks", "fused_shared"]
+UNITS = ["api", "fused_none", "fused_cossin", "fused_signbits", "multipass", "hash", "layer", "sketch", "structured", "blocks", "fused_shared", "sketch_cols"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          # packed fp32 VALU forms are not used on this target

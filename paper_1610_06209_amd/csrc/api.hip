@@ -619,6 +619,12 @@ int spinner_sketch(const float* A, int n, int d, const float* w, const float* d1
         !aligned16(workspace))
         return SPINNER_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (spinner::sketch_cols_pays(log2n, d)) {
+        // the columns as they lie: one pass over A
+        const double factor_d = (double)scale / ((double)n * sqrt((double)n));
+        const hipError_t e = spinner::launch_sketch_cols(A, log2n, d, w, d1, d2, d3, m, (float)factor_d, B, s);
+        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+    }
     char* base = static_cast<char*>(workspace);
     float* At = reinterpret_cast<float*>(base);                                             // [d][n]
     float* Ut = reinterpret_cast<float*>(base + align256((size_t)d * n * sizeof(float)));   // [d][m]

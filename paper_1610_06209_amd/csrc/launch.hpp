@@ -198,6 +198,18 @@ hipError_t launch_layer_large_dd(const float* g, const float* a, int log2n, long
 // Newton sketch: transposition with optional row weights, Gram matrix on the matrix pipe
 hipError_t launch_transpose_scale(const float* src, long long rows, long long cols, const float* row_scale, float* dst,
                                   hipStream_t s);
+// the sketch on the columns as they lie (sketch_cols.hip): n = 2^4 .. 2^kSketchColsMaxLog, d a multiple of 4; factor = n^{-3/2} scale
+constexpr int kSketchColsMaxLog = 12;
+// Shapes for which that form is the faster one.  Measured against transposition + projection + transposition (ms):
+// n = 4096: d = 512 0.035 / 0.017, 1024 0.037 / 0.023, 2048 0.040 / 0.036, 4096 0.044 / 0.062, 16384 0.184 / 0.252;
+// n = 2048: d = 2048 0.022 / 0.024, 8192 0.039 / 0.058; n = 1024: d = 256 0.012 / 0.013, 4096 0.016 / 0.022,
+// 65536 0.125 / 0.239; n = 256, d = 65536: 0.026 / 0.050.
+inline bool sketch_cols_pays(int log2n, long long d)
+{
+    return log2n <= kSketchColsMaxLog && (d & 3) == 0 && d >= (log2n == 12 ? 4096 : (log2n == 11 ? 1024 : 64));
+}
+hipError_t launch_sketch_cols(const float* A, int log2n, long long d, const float* w, const float* d1, const float* d2, const float* d3,
+                              int m, float factor, float* B, hipStream_t s);
 int sketch_gram_slabs(int m, int d);      // d x d slabs of scratch the Gram kernel needs (1: none)
 hipError_t launch_sketch_gram(const float* B, int m, int d, float* G, float* slabs, hipStream_t s);
 // scratch of spinner_sketch_gram_static: a file-scope device array in sketch.hip; gram_static_scratch_ptr gives its

@@ -60,6 +60,40 @@ def test_sketch_matches_oracle(gpu, oracle, n, d, m, weights):
     assert err.max() <= REL_L2_TOL, err.max()
 
 
+@pytest.mark.parametrize("log2n", list(range(4, 13)))
+def test_sketch_on_the_columns_as_they_lie(gpu, oracle, log2n):
+    # Shapes that take the kernel which loads the columns of the row-major matrix directly (n <= 2^12, d a multiple
+    # of 4 and wide enough for its size): a last column group of 4 columns, several workgroups, the 32-column tiles
+    # (d >= 8192, n <= 2^11); general (non +-1) diagonals, so that a swapped or dropped diagonal would show; m ragged,
+    # m = n and m = 1.  Columns are independent, so wide matrices are compared on sampled columns.
+    n = 1 << log2n
+    rng = np.random.default_rng(8300 + log2n)
+    dmin = 4096 if log2n == 12 else (1024 if log2n == 11 else 64)
+    shapes = [(dmin + 4, max(1, n // 2 - 3), True), (dmin + 256, n, False), (dmin, 1, True)]
+    if log2n in (4, 8, 11):
+        shapes.append((8192 + 4, max(1, n // 4 + 1), True))
+    for d, m, weights in shapes:
+        assert gpu.b.spinner_sketch_workspace_bytes(n, d, m) > 0
+        A, w = W.newton_sketch_problem(n, d, 8400 + log2n + d)
+        dg = (rng.standard_normal((3, n)) * 0.5 + 1.0).astype(np.float32)
+        scale = math.sqrt(n / m)
+        B = gpu.b.spinner_sketch(_to(gpu, A), _to(gpu, w) if weights else None, _to(gpu, dg[0]), _to(gpu, dg[1]),
+                                 _to(gpu, dg[2]), m, scale)
+        gpu.torch.cuda.synchronize()
+        assert B.shape == (m, d)
+        B = B.cpu().numpy().astype(np.float64)
+        cols = np.arange(d) if d <= 400 else np.unique(np.concatenate([np.arange(0, 40), np.arange(d - 40, d), rng.integers(0, d, 60)]))
+        want = oracle.sketch(A[:, cols], w if weights else None, dg[0], dg[1], dg[2], m, scale)
+        got = B[:, cols]
+        if m > 8:
+            err = rel_l2_per_vector(got.T, want.T)
+        else:      # a single kept coordinate can cancel to nothing: measure against the column's expected size
+            WA = A[:, cols].astype(np.float64) * (w.astype(np.float64)[:, None] if weights else 1.0)
+            ref = scale * math.sqrt(m / n) * np.linalg.norm(WA, axis=0)
+            err = np.linalg.norm(got - want, axis=0) / np.maximum(ref, np.linalg.norm(want, axis=0))
+        assert err.max() <= REL_L2_TOL, (d, m, err.max())
+
+
 @pytest.mark.parametrize("m,d", [(1, 1), (7, 5), (64, 128), (1000, 129), (4096, 300), (513, 1024)])
 def test_gram_matches_oracle(gpu, oracle, m, d):
     rng = np.random.default_rng(m * 7 + d)
