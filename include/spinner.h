@@ -348,10 +348,17 @@ int spinner_sketch_gram_static(const float *B, int m, int d, float *G, void *str
  * spinner_struct_spectrum_bytes(kind, n) bytes) once, off the clock, as the paper
  * prepares all parameters in advance.  spinner_struct_apply computes
  *     out[batch][m] = scale * (first m rows of G_struct D2 H D1 x)
- * with H the normalised Hadamard matrix, in one kernel that needs no scratch
- * memory.  The product with G_struct is an O(n log n) FFT convolution.
- * n = 2^5 .. 2^14 for the circulant, .. 2^13 for the others (SPINNER_ERR_UNSUPPORTED
- * outside); an unknown kind gives SPINNER_ERR_BAD_EPILOGUE.
+ * with H the normalised Hadamard matrix.  The product with G_struct is an O(n log n)
+ * FFT convolution of length P = n (circulant) or 2n (the others).  While the transform
+ * fits the LDS (P <= 2^14: n = 2^5 .. 2^14 for the circulant, .. 2^13 for the others)
+ * the call is one kernel that needs no scratch memory; spinner_struct_apply returns
+ * SPINNER_ERR_UNSUPPORTED above that.  spinner_struct_apply_ws takes a workspace of
+ * spinner_struct_workspace_bytes(kind, n, batch) bytes (0 for the sizes above) and also
+ * serves P = 2^15 .. 2^22 (n up to 2^22 / 2^21): H D1 x by a pass over rows and a pass
+ * over columns, then the transform in three passes through global memory (its top
+ * stages over column tiles, blocks of 2^12 points with the spectrum product, the top
+ * stages back).  spinner_struct_prepare serves all of these sizes.  An unknown kind
+ * gives SPINNER_ERR_BAD_EPILOGUE.
  */
 enum { SPINNER_STRUCT_CIRCULANT = 0, SPINNER_STRUCT_SKEW_CIRCULANT = 1, SPINNER_STRUCT_TOEPLITZ = 2, SPINNER_STRUCT_HANKEL = 3 };
 size_t spinner_struct_params(int kind, int n);
@@ -360,6 +367,10 @@ int spinner_struct_prepare(int kind, const float *params, int n, void *spectrum,
 int spinner_struct_apply(const float *x, int n, long batch, int kind, const void *spectrum,
                          const float *d1, const float *d2, int m, float scale,
                          float *out, void *stream);
+size_t spinner_struct_workspace_bytes(int kind, int n, long batch);
+int spinner_struct_apply_ws(const float *x, int n, long batch, int kind, const void *spectrum,
+                            const float *d1, const float *d2, int m, float scale,
+                            float *out, void *workspace, void *stream);
 
 /*
  * Bytes of device scratch spinner_apply needs for these arguments: 0 up to the

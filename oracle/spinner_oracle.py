@@ -31,6 +31,8 @@ What each function follows:
 * ``struct_matrix`` / ``struct_apply`` - the members G_struct D2 H D1 of the family (Lemma 1 and the remark after
   it; Theorem 3; Section 5 experiments): G_struct a Gaussian circulant, skew-circulant, Toeplitz or Hankel matrix,
   written out densely from its generating vector.
+* ``struct_rows`` / ``struct_apply_rows`` - the same members for n too large for the dense matrix: selected rows of
+  G_struct written out from the generating vector, and the matching outputs.
 * ``apply_blocks``       - Section 3.2: independently constructed m x n blocks stacked vertically.
 * ``sketch`` / ``sketched_gram`` - the Newton-sketch use of the Supplement ("Additional experiments"):
   an m x n sketching matrix S (the first m rows of a spinner, scaled) applied to the columns of a
@@ -324,6 +326,36 @@ def struct_apply(x, kind: str, params, d1, d2, m: int, scale: float) -> np.ndarr
     t = hadamard_apply(x * np.asarray(d1, dtype=np.float64)) * np.asarray(d2, dtype=np.float64)
     G = struct_matrix(kind, params, n)
     return float(scale) * (t @ G[:m].T)
+
+
+def struct_rows(kind: str, params, n: int, rows) -> np.ndarray:
+    """The listed rows of the n x n structured matrix, fp64 [len(rows)][n], written out from the generating vector by
+    the definitions in ``struct_matrix`` (for n where the whole matrix would not fit in memory)."""
+    p = np.asarray(params, dtype=np.float64)
+    i = np.asarray(rows, dtype=np.int64)[:, None]
+    j = np.arange(n, dtype=np.int64)[None, :]
+    if kind == "circulant":
+        assert p.shape == (n,)
+        return p[(j - i) % n]
+    if kind == "skew_circulant":
+        assert p.shape == (n,)
+        return np.where(j >= i, 1.0, -1.0) * p[(j - i) % n]
+    if kind == "toeplitz":
+        assert p.shape == (2 * n - 1,)
+        return p[j - i + n - 1]
+    if kind == "hankel":
+        assert p.shape == (2 * n - 1,)
+        return p[i + j]
+    raise ValueError("unknown structured matrix %r" % (kind,))
+
+
+def struct_apply_rows(x, kind: str, params, d1, d2, rows, scale: float) -> np.ndarray:
+    """scale * (the listed rows of G_struct D2 H D1 x), fp64 [batch][len(rows)]; H through its two Kronecker factors
+    above DENSE_MAX_N."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    n = x.shape[-1]
+    t = hadamard_apply(x * np.asarray(d1, dtype=np.float64), default_kron_a(n)) * np.asarray(d2, dtype=np.float64)
+    return float(scale) * (t @ struct_rows(kind, params, n, rows).T)
 
 
 def apply_blocks(x, diag_sets: np.ndarray, m: int, epilogue: str, scale: float, nthreads: int = 0) -> np.ndarray:

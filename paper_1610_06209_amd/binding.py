@@ -38,7 +38,8 @@ EXPORTS = ["spinner_apply", "spinner_hash", "spinner_workspace_bytes", "spinner_
            "spinner_layer_backward", "spinner_sketch_workspace_bytes", "spinner_sketch", "spinner_sketch_gram",
            "spinner_sketch_gram_workspace_bytes", "spinner_sketch_gram_static", "spinner_sketch_gram_static_limit",
            "spinner_blocks_workspace_bytes", "spinner_apply_blocks",
-           "spinner_struct_params", "spinner_struct_spectrum_bytes", "spinner_struct_prepare", "spinner_struct_apply"]
+           "spinner_struct_params", "spinner_struct_spectrum_bytes", "spinner_struct_prepare", "spinner_struct_apply",
+           "spinner_struct_workspace_bytes", "spinner_struct_apply_ws"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -124,6 +125,11 @@ lib.spinner_struct_spectrum_bytes.restype = ctypes.c_size_t
 lib.spinner_struct_spectrum_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
 lib.spinner_struct_prepare.restype = ctypes.c_int
 lib.spinner_struct_prepare.argtypes = [ctypes.c_int, _vp, ctypes.c_int, _vp, _vp]
+lib.spinner_struct_workspace_bytes.restype = ctypes.c_size_t
+lib.spinner_struct_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_long]
+lib.spinner_struct_apply_ws.restype = ctypes.c_int
+lib.spinner_struct_apply_ws.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp, ctypes.c_int, ctypes.c_float,
+                                        _vp, _vp, _vp]
 lib.spinner_struct_apply.restype = ctypes.c_int
 lib.spinner_struct_apply.argtypes = [_vp, ctypes.c_int, ctypes.c_long, ctypes.c_int, _vp, _vp, _vp, ctypes.c_int, ctypes.c_float,
                                      _vp, _vp]
@@ -688,6 +694,39 @@ def spinner_struct_apply(x, kind, spectrum, d1, d2, m=None, scale=1.0, out=None,
             raise ValueError("out has the wrong size")
     rc = lib.spinner_struct_apply(x.data_ptr(), n, batch, k, spectrum.data_ptr(), d1.data_ptr(), d2.data_ptr(), m,
                                   ctypes.c_float(scale), out.data_ptr(), _stream_handle(stream))
+    if rc != SPINNER_OK:
+        raise SpinnerError(rc)
+    return out
+
+
+def spinner_struct_workspace_bytes(kind, n: int, batch: int) -> int:
+    k = STRUCT_KINDS[kind] if isinstance(kind, str) else int(kind)
+    return int(lib.spinner_struct_workspace_bytes(k, int(n), int(batch)))
+
+
+def spinner_struct_apply_ws(x, kind, spectrum, d1, d2, m=None, scale=1.0, out=None, workspace=None, stream=None):
+    """spinner_struct_apply for every supported n (a workspace tensor is made when none is given and one is needed)."""
+    import torch
+
+    k = STRUCT_KINDS[kind] if isinstance(kind, str) else int(kind)
+    for name, t in (("x", x), ("d1", d1), ("d2", d2)):
+        _check_tensor(t, name, torch.float32)
+    batch, n = x.shape
+    m = n if m is None else int(m)
+    if out is None:
+        out = torch.empty((batch, m), dtype=torch.float32, device=x.device)
+    else:
+        _check_tensor(out, "out", torch.float32)
+        if out.numel() != batch * m:
+            raise ValueError("out has the wrong size")
+    need = spinner_struct_workspace_bytes(k, n, batch)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    rc = lib.spinner_struct_apply_ws(x.data_ptr(), n, batch, k, spectrum.data_ptr(), d1.data_ptr(), d2.data_ptr(), m,
+                                     ctypes.c_float(scale), out.data_ptr(),
+                                     workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
     if rc != SPINNER_OK:
         raise SpinnerError(rc)
     return out

@@ -726,12 +726,16 @@ int spinner_apply_blocks(const float* x, int n, long batch, int L, const float* 
 // ------------------------------------------------------------------ G_struct D2 H D1 members
 static int struct_log2p(int kind, int log2n) { return kind == SPINNER_STRUCT_CIRCULANT ? log2n : log2n + 1; }
 
-static int check_struct(int kind, int n, int* log2n)
+constexpr int kStructLdsMaxLog2p = 14;      // longest transform one workgroup holds in LDS
+
+// with_workspace: the call can take the path through global memory (transforms of 2^15 .. 2^22 points)
+static int check_struct(int kind, int n, int* log2n, bool with_workspace = true)
 {
     if (kind < SPINNER_STRUCT_CIRCULANT || kind > SPINNER_STRUCT_HANKEL) return SPINNER_ERR_BAD_EPILOGUE;
     if (!pow2_in_range(n, log2n)) return SPINNER_ERR_BAD_N;
-    // H D1 x comes from the one-step tile kernels (n >= 32); the transform of length P must fit the LDS (P <= 2^14)
-    if (*log2n < 5 || struct_log2p(kind, *log2n) > 14) return SPINNER_ERR_UNSUPPORTED;
+    // H D1 x comes from the one-step tile kernels (n >= 32)
+    const int lp = struct_log2p(kind, *log2n);
+    if (*log2n < 5 || lp > (with_workspace ? spinner::kStructLargeMaxLog2pHost : kStructLdsMaxLog2p)) return SPINNER_ERR_UNSUPPORTED;
     return SPINNER_OK;
 }
 
@@ -746,8 +750,20 @@ size_t spinner_struct_spectrum_bytes(int kind, int n)
 {
     int log2n;
     if (check_struct(kind, n, &log2n) != SPINNER_OK) return 0;
-    const size_t P = (size_t)1 << struct_log2p(kind, log2n);
-    return P * 8 + (P / 2) * 8;                       // spectrum, then the twiddle table
+    const int lp = struct_log2p(kind, log2n);
+    const size_t P = (size_t)1 << lp;
+    // spectrum, then the twiddle table; long transforms also carry the table of their blocks of 2^12 points
+    return P * 8 + (P / 2) * 8 + (lp > kStructLdsMaxLog2p ? 2048 * 8 : 0);
+}
+
+size_t spinner_struct_workspace_bytes(int kind, int n, long batch)
+{
+    int log2n;
+    if (check_struct(kind, n, &log2n) != SPINNER_OK || batch <= 0) return 0;
+    const int lp = struct_log2p(kind, log2n);
+    if (lp <= kStructLdsMaxLog2p) return 0;
+    // H D1 x of every vector, then one complex work buffer of P points per pair of vectors
+    return align256((size_t)batch * (size_t)n * sizeof(float)) + (size_t)((batch + 1) / 2) * ((size_t)8 << lp);
 }
 
 int spinner_struct_prepare(int kind, const float* params, int n, void* spectrum, void* stream)
@@ -759,16 +775,19 @@ int spinner_struct_prepare(int kind, const float* params, int n, void* spectrum,
     if (!aligned16(params) || !aligned16(spectrum)) return SPINNER_ERR_ALIGNMENT;
     const int lp = struct_log2p(kind, log2n);
     float2* spec = static_cast<float2*>(spectrum);
-    const hipError_t e = spinner::launch_struct_prepare(params, kind, n, lp, spec, spec + ((size_t)1 << lp),
-                                                        static_cast<hipStream_t>(stream));
+    float2* tw = spec + ((size_t)1 << lp);
+    const hipError_t e = lp > kStructLdsMaxLog2p
+                             ? spinner::launch_struct_prepare_large(params, kind, n, lp, spec, tw, tw + ((size_t)1 << (lp - 1)),
+                                                                    static_cast<hipStream_t>(stream))
+                             : spinner::launch_struct_prepare(params, kind, n, lp, spec, tw, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
 }
 
-int spinner_struct_apply(const float* x, int n, long batch, int kind, const void* spectrum, const float* d1, const float* d2,
-                         int m, float scale, float* out, void* stream)
+static int struct_apply_impl(const float* x, int n, long batch, int kind, const void* spectrum, const float* d1, const float* d2,
+                             int m, float scale, float* out, bool with_workspace, void* workspace, void* stream)
 {
     int log2n;
-    const int rc = check_struct(kind, n, &log2n);
+    const int rc = check_struct(kind, n, &log2n, with_workspace);
     if (rc != SPINNER_OK) return rc;
     if (m < 1 || m > n) return SPINNER_ERR_BAD_M;
     if (batch < 0 || batch > 0x7fffffffL || (double)batch * (double)n > 9.0e15) return SPINNER_ERR_BAD_BATCH;
@@ -779,10 +798,37 @@ int spinner_struct_apply(const float* x, int n, long batch, int kind, const void
     const float2* spec = static_cast<const float2*>(spectrum);
     // the Hadamard stages and both transforms of the convolution run unnormalised: 1 / sqrt(n) and 1 / P go into the last scale
     const double factor = (double)scale / ((double)((size_t)1 << lp) * sqrt((double)n));
+    if (lp > kStructLdsMaxLog2p) {
+        // H D1 x (unnormalised) of every vector by a pass over rows and a pass over columns, then the convolution
+        // through global memory: column stages, blocks of 2^12 points (with the spectrum product), column stages back
+        if (!workspace) return SPINNER_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return SPINNER_ERR_ALIGNMENT;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        float* t = static_cast<float*>(workspace);
+        float2* z = reinterpret_cast<float2*>(static_cast<char*>(workspace) + align256((size_t)batch * (size_t)n * sizeof(float)));
+        const int r = large_round(x, d1, t, n, log2n, batch, 1.0, s);
+        if (r != SPINNER_OK) return r;
+        const float2* tw = spec + ((size_t)1 << lp);
+        const hipError_t e = spinner::launch_struct_conv_large(t, d2, spec, tw, tw + ((size_t)1 << (lp - 1)), z, out, batch, n, lp, m,
+                                                               kind == SPINNER_STRUCT_HANKEL ? 1 : 0, (float)factor, s);
+        return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+    }
     const hipError_t e = spinner::launch_struct_conv(x, d1, d2, spec, spec + ((size_t)1 << lp), out, batch, n, log2n, lp, m,
                                                      kind == SPINNER_STRUCT_HANKEL ? 1 : 0, (float)factor,
                                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SPINNER_OK : hip_fail(e);
+}
+
+int spinner_struct_apply(const float* x, int n, long batch, int kind, const void* spectrum, const float* d1, const float* d2,
+                         int m, float scale, float* out, void* stream)
+{
+    return struct_apply_impl(x, n, batch, kind, spectrum, d1, d2, m, scale, out, false, nullptr, stream);
+}
+
+int spinner_struct_apply_ws(const float* x, int n, long batch, int kind, const void* spectrum, const float* d1, const float* d2,
+                            int m, float scale, float* out, void* workspace, void* stream)
+{
+    return struct_apply_impl(x, n, batch, kind, spectrum, d1, d2, m, scale, out, true, workspace, stream);
 }
 
 int spinner_stream_copy(const float* src, float* dst, size_t count, void* stream)

@@ -222,4 +222,11 @@ hipError_t launch_struct_prepare(const float* params, int kind, int n, int log2p
 hipError_t launch_struct_conv(const float* x, const float* d1, const float* d2, const float2* spec, const float2* tw, float* out,
                               long long batch, int n, int log2n, int log2p, int m, int reverse, float factor, hipStream_t s);
 
+// transforms of length P = 2^15 .. 2^kStructLargeMaxLog2pHost through global memory (structured.hip)
+constexpr int kStructLargeMaxLog2pHost = 22;
+hipError_t launch_struct_prepare_large(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, float2* tw_b,
+                                       hipStream_t s);
+hipError_t launch_struct_conv_large(const float* t, const float* d2, const float2* spec, const float2* tw, const float2* tw_b, float2* z,
+                                    float* out, long long batch, int n, int log2p, int m, int reverse, float factor, hipStream_t s);
+
 }  // namespace spinner

@@ -297,30 +297,150 @@ __global__ void __launch_bounds__(256) struct_twiddle_kernel(float2* tw, int hal
 //   kind 1 skew-circulant  wrapped entries negated:               c[0] = g[0], c[k] = -g[n - k], c[2n - q] = g[q]
 //   kind 2 Toeplitz        G[i][j] = t[j - i + n - 1]:            c[k] = t[n - 1 - k], c[2n - q] = t[n - 1 + q]
 //   kind 3 Hankel          G[i][j] = h[i + j], v reversed:        Toeplitz with t'[e] = h[2n - 2 - e]
+__device__ __forceinline__ float conv_kernel_entry(const float* __restrict__ params, int kind, int n, int k)
+{
+    float v = 0.f;
+    if (kind == 0) {
+        v = params[(n - k) & (n - 1)];
+    } else if (k < n) {                       // k = i - j >= 0
+        if (kind == 1) v = k == 0 ? params[0] : -params[n - k];
+        else if (kind == 2) v = params[n - 1 - k];
+        else v = params[2 * n - 2 - (n - 1 - k)];
+    } else if (k > n) {                       // k = 2n - q, q = j - i > 0
+        const int q = 2 * n - k;
+        if (kind == 1) v = params[q];
+        else if (kind == 2) v = params[n - 1 + q];
+        else v = params[2 * n - 2 - (n - 1 + q)];
+    }
+    return v;
+}
+
 __global__ void __launch_bounds__(512) struct_spectrum_kernel(const float* __restrict__ params, int kind, int n, int log2p,
                                                               const float2* __restrict__ tw, float2* __restrict__ spec)
 {
     extern __shared__ float2 X[];
     const int P = 1 << log2p;
     for (int k = threadIdx.x; k < P; k += blockDim.x) {
-        float v = 0.f;
-        if (kind == 0) {
-            v = params[(n - k) & (n - 1)];
-        } else if (k < n) {                       // k = i - j >= 0
-            if (kind == 1) v = k == 0 ? params[0] : -params[n - k];
-            else if (kind == 2) v = params[n - 1 - k];
-            else v = params[2 * n - 2 - (n - 1 - k)];
-        } else if (k > n) {                       // k = 2n - q, q = j - i > 0
-            const int q = 2 * n - k;
-            if (kind == 1) v = params[q];
-            else if (kind == 2) v = params[n - 1 + q];
-            else v = params[2 * n - 2 - (n - 1 + q)];
-        }
+        const float v = conv_kernel_entry(params, kind, n, k);
         X[pad(k)] = make_float2(v, 0.f);
     }
     __syncthreads();
     fft_forward(X, tw, log2p);
     for (int k = threadIdx.x; k < P; k += blockDim.x) spec[k] = X[pad(k)];
+}
+
+
+// ------------------------------------------------------------------ transforms longer than the LDS holds (P = 2^15 .. 2^22)
+// The decimation-in-frequency transform of length P = 2^L is split after its top La = L - 12 stages.  Those stages
+// pair points 2^12 and more apart: for every offset b below 2^12 they are a transform over the 2^La points
+// a 2^12 + b, with twiddles exp(-2 pi i o / 2^(s+1)), o = the point's offset in its group of 2^s.  A workgroup of
+// struct_col_kernel takes all a for sixteen consecutive b (128-byte runs) through LDS, one stage per pass.  The
+// twelve stages below act inside each contiguous block of 2^12 points and are the in-LDS transform of that length
+// with its own twiddle table (struct_block_kernel), which multiplies by the block's part of the spectrum and runs
+// the inverse stages on the way back; the inverse (decimation in time) column stages then mirror the forward ones,
+// so the points return to natural order without any reordering pass.  Two real vectors travel as one complex one.
+constexpr int kBlockLog = 12, kColLog = 4;
+constexpr int kStructLargeMaxLog2p = kBlockLog + 10;      // a column tile of 2^(La + 4) points must fit the LDS
+
+struct StructLargeParams {
+    const float* t;        // [batch][n]: H D1 x (unnormalised), input of the forward column stages
+    const float* d2;       // [n]
+    float2* z;             // [pairs][P] complex work buffer
+    const float2* tw;      // [P/2] exp(-2 pi i k / P)
+    const float2* tw_b;    // [2^11] exp(-2 pi i k / 2^12)
+    const float2* spec;    // [P] spectrum in the order the forward transform leaves it
+    float* out;            // [batch][m]
+    long long batch;
+    int n, log2p, m, reverse;
+    float factor;
+};
+
+enum { COL_FWD_REAL = 0, COL_FWD_COMPLEX = 1, COL_INV_OUT = 2 };
+
+template <int MODE>
+__global__ void __launch_bounds__(256) struct_col_kernel(StructLargeParams p)
+{
+    extern __shared__ float2 X[];
+    constexpr bool INVERSE = MODE == COL_INV_OUT;
+    const int L = p.log2p, T = L - kBlockLog + kColLog;              // index bits of a tile: a above, sixteen b below
+    const long long pair = blockIdx.x >> (kBlockLog - kColLog);
+    const int b0 = (int)(blockIdx.x & ((1 << (kBlockLog - kColLog)) - 1)) << kColLog;
+    const long long v0 = 2 * pair, v1 = v0 + 1;
+    const bool two = v1 < p.batch;
+    float2* z = p.z + (pair << L);
+    auto true_index = [&](int i) { return ((i >> kColLog) << kBlockLog) | (b0 + (i & ((1 << kColLog) - 1))); };
+
+    for (int i = threadIdx.x; i < (1 << T); i += 256) {
+        const int pt = true_index(i);
+        float2 v;
+        if constexpr (MODE == COL_FWD_REAL) {
+            const int pc = pt < p.n ? pt : p.n - 1;                  // clamped: no load under a condition
+            const int q = p.reverse ? p.n - 1 - pc : pc;             // Hankel: G acts on the reversed vector
+            const float dd = p.d2[q];
+            const float a = p.t[v0 * p.n + q], c = p.t[(two ? v1 : v0) * p.n + q];
+            v = pt < p.n ? make_float2(a * dd, c * dd) : make_float2(0.f, 0.f);
+        } else {
+            v = z[pt];
+        }
+        X[pad(i)] = v;
+    }
+    __syncthreads();
+    for (int step = 0; step < T - kColLog; ++step) {
+        const int t = INVERSE ? kColLog + step : T - 1 - step;       // tile bit of this stage
+        const int s = t - kColLog + kBlockLog;                        // its bit in the transform
+        for (int bf = threadIdx.x; bf < (1 << (T - 1)); bf += 256) {
+            const int o = bf & ((1 << t) - 1);
+            const int lo = ((bf >> t) << (t + 1)) | o;
+            const int ot = ((o >> kColLog) << kBlockLog) | (b0 + (o & ((1 << kColLog) - 1)));      // offset in the group of 2^s
+            float2 a = X[pad(lo)], c = X[pad(lo + (1 << t))];
+            butterfly<INVERSE>(a, c, p.tw[(long long)ot << (L - 1 - s)]);
+            X[pad(lo)] = a;
+            X[pad(lo + (1 << t))] = c;
+        }
+        __syncthreads();
+    }
+    for (int i = threadIdx.x; i < (1 << T); i += 256) {
+        const int pt = true_index(i);
+        const float2 v = X[pad(i)];
+        if constexpr (MODE == COL_INV_OUT) {
+            if (pt < p.m) {
+                p.out[v0 * p.m + pt] = v.x * p.factor;
+                if (two) p.out[v1 * p.m + pt] = v.y * p.factor;
+            }
+        } else {
+            z[pt] = v;
+        }
+    }
+}
+
+// The twelve low stages of one block of 2^12 points: forward, product with the spectrum, inverse, in place
+// (FORWARD_ONLY: forward alone, for the spectrum of the generator).
+template <bool FORWARD_ONLY>
+__global__ void __launch_bounds__(256) struct_block_kernel(StructLargeParams p)
+{
+    extern __shared__ float2 X[];
+    constexpr int L = kBlockLog;
+    float2* z = p.z + ((long long)blockIdx.x << L);                  // block (pair, a): blocks of a pair are consecutive
+    const float2* spec = p.spec + (((long long)blockIdx.x & ((1LL << (p.log2p - L)) - 1)) << L);
+    auto from_lds = [&](int i) { return X[pad(i)]; };
+    auto to_lds = [&](int i, float2 v) { X[pad(i)] = v; };
+    fft_trip16<false>(p.tw_b, 11, L, [&](int i) { return z[i]; }, to_lds);
+    fft_trip16<false>(X, p.tw_b, 7, L);
+    if constexpr (FORWARD_ONLY) {
+        fft_trip16<false>(p.tw_b, 3, L, from_lds, [&](int i, float2 v) { z[i] = v; });
+    } else {
+        fft_trip16<false>(p.tw_b, 3, L, from_lds, [&](int i, float2 v) { X[pad(i)] = cmul(v, spec[i]); });
+        fft_trip16<true>(X, p.tw_b, 3, L);
+        fft_trip16<true>(X, p.tw_b, 7, L);
+        fft_trip16<true>(p.tw_b, 11, L, from_lds, [&](int i, float2 v) { z[i] = v; });
+    }
+}
+
+// c[k] of the structured matrix as complex points in global memory (the generator of a long transform)
+__global__ void __launch_bounds__(256) struct_fill_kernel(const float* __restrict__ params, int kind, int n, int log2p, float2* __restrict__ c)
+{
+    const long long k = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (k < (1LL << log2p)) c[k] = make_float2(conv_kernel_entry(params, kind, n, (int)k), 0.f);
 }
 
 static hipError_t allow_lds(const void* kernel, size_t bytes)
@@ -353,6 +473,49 @@ hipError_t launch_struct_conv(const float* x, const float* d1, const float* d2, 
     // one thread per sixteen points of the transform
     const int threads = (1 << log2p) / 16 < 64 ? 64 : ((1 << log2p) / 16 > 512 ? 512 : (1 << log2p) / 16);
     hipLaunchKernelGGL(struct_conv_kernel, dim3((unsigned)blocks), dim3(threads), lds, s, p);
+    return hipGetLastError();
+}
+
+// spectrum of a generator whose transform does not fit the LDS: [P] spectrum, [P/2] twiddles, [2^11] twiddles of the blocks
+hipError_t launch_struct_prepare_large(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, float2* tw_b,
+                                       hipStream_t s)
+{
+    if (log2p <= kBlockLog + 2 || log2p > kStructLargeMaxLog2p) return hipErrorInvalidValue;
+    const long long P = 1LL << log2p;
+    hipLaunchKernelGGL(struct_twiddle_kernel, dim3((unsigned)((P / 2 + 255) / 256)), dim3(256), 0, s, tw, (int)(P / 2));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_twiddle_kernel, dim3((1 << (kBlockLog - 1)) / 256), dim3(256), 0, s, tw_b, 1 << (kBlockLog - 1));
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_fill_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, params, kind, n, log2p, spec);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    StructLargeParams p{nullptr, nullptr, spec, tw, tw_b, nullptr, nullptr, 1, n, log2p, 0, 0, 1.0f};
+    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + kColLog), lds_blk = fft_lds_bytes(kBlockLog);
+    if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_FWD_COMPLEX>), lds_col)) != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_COMPLEX>, dim3(1 << (kBlockLog - kColLog)), dim3(256), lds_col, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_block_kernel<true>, dim3(1 << (log2p - kBlockLog)), dim3(256), lds_blk, s, p);
+    return hipGetLastError();
+}
+
+// t: H D1 x (unnormalised) [batch][n]; z: ceil(batch / 2) * P complex points of scratch
+hipError_t launch_struct_conv_large(const float* t, const float* d2, const float2* spec, const float2* tw, const float2* tw_b, float2* z,
+                                    float* out, long long batch, int n, int log2p, int m, int reverse, float factor, hipStream_t s)
+{
+    if (batch <= 0) return hipSuccess;
+    if (log2p <= kBlockLog + 2 || log2p > kStructLargeMaxLog2p) return hipErrorInvalidValue;
+    const long long pairs = (batch + 1) / 2;
+    if ((pairs << (log2p - kBlockLog)) > 0x7fffffffLL || (pairs << (kBlockLog - kColLog)) > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    StructLargeParams p{t, d2, z, tw, tw_b, spec, out, batch, n, log2p, m, reverse, factor};
+    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + kColLog), lds_blk = fft_lds_bytes(kBlockLog);
+    hipError_t e;
+    if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_FWD_REAL>), lds_col)) != hipSuccess) return e;
+    if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_INV_OUT>), lds_col)) != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_REAL>, dim3((unsigned)(pairs << (kBlockLog - kColLog))), dim3(256), lds_col, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_block_kernel<false>, dim3((unsigned)(pairs << (log2p - kBlockLog))), dim3(256), lds_blk, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_col_kernel<COL_INV_OUT>, dim3((unsigned)(pairs << (kBlockLog - kColLog))), dim3(256), lds_col, s, p);
     return hipGetLastError();
 }
 }  // namespace spinner

@@ -68,6 +68,30 @@ def test_struct_members_match_oracle(gpu, oracle, kind, log2n):
     assert rel_l2_per_vector(got, want).max() <= REL_L2_TOL
 
 
+@pytest.mark.parametrize("kind,log2n,batch", [("circulant", 15, 3), ("toeplitz", 14, 5), ("skew_circulant", 15, 2), ("hankel", 15, 3),
+                                               ("circulant", 17, 4), ("toeplitz", 17, 1), ("hankel", 18, 2), ("circulant", 20, 2),
+                                               ("toeplitz", 21, 1), ("circulant", 22, 1)])
+def test_struct_members_with_transforms_through_global_memory(gpu, oracle, kind, log2n, batch):
+    # transforms of 2^15 .. 2^22 points (spinner_struct_apply_ws): the dense matrix does not fit, so the oracle writes out
+    # sampled rows of G_struct from the generating vector; first / last rows, rows around the block boundaries of the
+    # transform and random ones; full width and a ragged row limit
+    n = 1 << log2n
+    x, d, params = _case(kind, n, batch, 10300 + log2n)
+    rng = np.random.default_rng(log2n)
+    rows = np.unique(np.concatenate([np.arange(0, 6), np.arange(n - 6, n), np.arange(4090, 4102), rng.integers(0, n, 60)]))
+    spec = gpu.b.spinner_struct_prepare(kind, _to(gpu, params), n)
+    assert gpu.b.spinner_struct_workspace_bytes(kind, n, batch) > 0
+    got = gpu.b.spinner_struct_apply_ws(_to(gpu, x), kind, spec, _to(gpu, d[0]), _to(gpu, d[1]), n, 1.25).cpu().numpy()
+    want = oracle.struct_apply_rows(x, kind, params, d[0], d[1], rows, 1.25)
+    assert got.shape == (batch, n)
+    assert rel_l2_per_vector(got[:, rows], want).max() <= REL_L2_TOL
+    m = n // 2 + 5
+    got_m = gpu.b.spinner_struct_apply_ws(_to(gpu, x), kind, spec, _to(gpu, d[0]), _to(gpu, d[1]), m, 1.25).cpu().numpy()
+    assert got_m.shape == (batch, m) and np.array_equal(got_m, got[:, :m])
+    with pytest.raises(gpu.b.SpinnerError):
+        gpu.b.spinner_struct_apply(_to(gpu, x), kind, spec, _to(gpu, d[0]), _to(gpu, d[1]), n, 1.0)      # no workspace: stops at 2^14 points
+
+
 def test_circulant_at_the_largest_size_and_special_generators(gpu, oracle):
     n, batch = 1 << 14, 3
     x, d, params = _case("circulant", n, batch, 10100)
@@ -91,13 +115,21 @@ def test_circulant_at_the_largest_size_and_special_generators(gpu, oracle):
 
 
 def test_struct_argument_errors(gpu):
+    import ctypes
     b = gpu.b
     assert b.lib.spinner_struct_params(0, 1024) == 1024 and b.lib.spinner_struct_params(2, 1024) == 2047
     assert b.lib.spinner_struct_spectrum_bytes(0, 1024) == 1024 * 8 + 512 * 8
     assert b.lib.spinner_struct_spectrum_bytes(2, 1024) == 2048 * 8 + 1024 * 8
-    assert b.lib.spinner_struct_spectrum_bytes(2, 1 << 14) == 0 and b.lib.spinner_struct_spectrum_bytes(0, 16) == 0
+    # transforms beyond the LDS (2^15 .. 2^22 points) also carry the twiddle table of their blocks of 2^12 points
+    assert b.lib.spinner_struct_spectrum_bytes(2, 1 << 14) == (1 << 15) * 8 + (1 << 14) * 8 + 2048 * 8
+    assert b.lib.spinner_struct_spectrum_bytes(0, 1 << 23) == 0 and b.lib.spinner_struct_spectrum_bytes(2, 1 << 22) == 0
+    assert b.lib.spinner_struct_spectrum_bytes(0, 16) == 0
+    assert b.spinner_struct_workspace_bytes(0, 1 << 14, 5) == 0 and b.spinner_struct_workspace_bytes(2, 1 << 13, 5) == 0
+    assert b.spinner_struct_workspace_bytes(2, 1 << 14, 5) == 5 * (1 << 14) * 4 + 3 * (1 << 15) * 8
+    g = b.lib.spinner_struct_apply_ws
+    assert g(64, 1 << 14, 4, 2, 64, 64, 64, 16, ctypes.c_float(1.0), 64, None, None) == b.SPINNER_ERR_WORKSPACE
+    assert g(64, 1 << 23, 4, 0, 64, 64, 64, 16, ctypes.c_float(1.0), 64, 64, None) == b.SPINNER_ERR_UNSUPPORTED
     assert b.lib.spinner_struct_spectrum_bytes(7, 1024) == 0
-    import ctypes
     one = ctypes.c_float(1.0)
     f = b.lib.spinner_struct_apply
     assert f(64, 1024, 4, 9, 64, 64, 64, 1024, one, 64, None) == b.SPINNER_ERR_BAD_EPILOGUE

@@ -67,3 +67,38 @@ def test_gaussian_circulant_member_behaves_like_a_gaussian_projection(oracle):
     y = np.concatenate(acc)
     assert abs(y.var() / float((x.astype(np.float64) ** 2).sum()) - 1.0) < 0.05
     assert abs(y.mean()) < 0.05 * y.std()
+
+
+@pytest.mark.parametrize("kind", ["circulant", "skew_circulant", "toeplitz", "hankel"])
+def test_selected_rows_are_rows_of_the_dense_matrix(oracle, kind):
+    # the route for n too large for the dense matrix: rows written out one by one, checked against the dense matrix
+    # (itself pinned against library constructions above) and against the FFT identity at a size the dense one
+    # cannot reach
+    n = 64
+    rng = np.random.default_rng(5)
+    params = rng.standard_normal(n if "circ" in kind else 2 * n - 1)
+    rows = [0, 1, 17, 63]
+    assert np.array_equal(oracle.struct_rows(kind, params, n, rows), oracle.struct_matrix(kind, params, n)[rows])
+    x = rng.standard_normal((3, n)).astype(np.float32)
+    d = rng.standard_normal((2, n)).astype(np.float32)
+    want = oracle.struct_apply(x, kind, params, d[0], d[1], n, 0.7)[:, rows]
+    assert np.allclose(oracle.struct_apply_rows(x, kind, params, d[0], d[1], rows, 0.7), want, atol=1e-12)
+
+
+def test_selected_rows_at_a_large_size_against_the_fft_identity(oracle):
+    n = 1 << 16
+    rng = np.random.default_rng(6)
+    g = rng.standard_normal(n)
+    v = rng.standard_normal(n)
+    rows = [0, 5, 40000, n - 1]
+    want = np.fft.ifft(np.conj(np.fft.fft(g)) * np.fft.fft(v)).real[rows]
+    assert np.allclose(oracle.struct_rows("circulant", g, n, rows) @ v, want, atol=1e-8)
+    # Toeplitz rows are windows of the generating vector: row i is t[n - 1 - i : 2 n - 1 - i]
+    t = rng.standard_normal(2 * n - 1)
+    R = oracle.struct_rows("toeplitz", t, n, rows)
+    for k, i in enumerate(rows):
+        assert np.array_equal(R[k], t[n - 1 - i: 2 * n - 1 - i])
+    # Hankel rows likewise: row i is h[i : i + n]
+    R = oracle.struct_rows("hankel", t, n, rows)
+    for k, i in enumerate(rows):
+        assert np.array_equal(R[k], t[i: i + n])
