@@ -265,7 +265,8 @@ def measure_sketch(torch, b, W, dev, n, d, m, steps, warmup, form):
 
 
 def measure_struct(torch, b, dev, kind, n, batch, steps, warmup):
-    """G_struct D2 H D1 member: Hadamard stages and FFT convolution of two vectors in LDS, one kernel."""
+    """G_struct D2 H D1 member: Hadamard stages and FFT convolution of two vectors in LDS, one kernel; transforms beyond
+    the LDS (n = 2^15, the largest size of the paper's timing table) through global memory with a workspace."""
     g = torch.Generator(device=dev)
     g.manual_seed(1610 + n)
     x = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
@@ -273,14 +274,15 @@ def measure_struct(torch, b, dev, kind, n, batch, steps, warmup):
     params = torch.randn(int(b.lib.spinner_struct_params(b.STRUCT_KINDS[kind], n)), generator=g, device=dev, dtype=torch.float32)
     spec = b.spinner_struct_prepare(kind, params, n)
     out = torch.empty((batch, n), dtype=torch.float32, device=dev)
-    fn = lambda: b.spinner_struct_apply(x, kind, spec, d[0], d[1], n, 1.0, out=out)
+    ws = torch.empty(max(16, b.spinner_struct_workspace_bytes(kind, n, batch)), dtype=torch.uint8, device=dev)
+    fn = lambda: b.spinner_struct_apply_ws(x, kind, spec, d[0], d[1], n, 1.0, out=out, workspace=ws)
     for _ in range(5):
         fn()
     torch.cuda.synchronize()
     _, ms = time_calls(torch, fn, steps, warmup)
     res = {"workload": "struct_%s_n%d_b%d" % (kind, n, batch), "ms": round(ms, 4), "vectors_per_s": batch / (ms * 1e-3),
            "GBs_of_8B_per_element": round(8.0 * batch * n / (ms * 1e-3) / 1e9, 1)}
-    del x, d, params, spec, out
+    del x, d, params, spec, out, ws
     torch.cuda.empty_cache()
     return res
 
@@ -371,8 +373,8 @@ def measure_next_rows(torch, b, W, dev, args):
         log("[bench] %s (%s): sketch %.4f ms (%.0f GB/s of its own bytes), Gram %.4f ms (%.1f TFLOP/s fp32 MFMA)" % (
             skt["workload"], skt["form"], skt["sketch_ms"], skt["sketch_GBs"], skt["gram_ms"], skt["gram_TFLOPs"]))
         nxt.append(skt)
-    for kind in ("circulant", "toeplitz"):
-        st = measure_struct(torch, b, dev, kind, 4096, 16384, 5, 2)
+    for kind, sn, sbatch in (("circulant", 4096, 16384), ("toeplitz", 4096, 16384), ("circulant", 1 << 15, 2048), ("toeplitz", 1 << 15, 2048)):
+        st = measure_struct(torch, b, dev, kind, sn, sbatch, 5, 2)
         log("[bench] %s: %.4f ms  %.3e vec/s  (%.0f GB/s counting 8 B per element)" % (
             st["workload"], st["ms"], st["vectors_per_s"], st["GBs_of_8B_per_element"]))
         nxt.append(st)

@@ -334,13 +334,16 @@ __global__ void __launch_bounds__(512) struct_spectrum_kernel(const float* __res
 // The decimation-in-frequency transform of length P = 2^L is split after its top La = L - 12 stages.  Those stages
 // pair points 2^12 and more apart: for every offset b below 2^12 they are a transform over the 2^La points
 // a 2^12 + b, with twiddles exp(-2 pi i o / 2^(s+1)), o = the point's offset in its group of 2^s.  A workgroup of
-// struct_col_kernel takes all a for sixteen consecutive b (128-byte runs) through LDS, one stage per pass.  The
+// struct_col_kernel takes all a for sixteen or more consecutive b (runs of 128 bytes and up) through LDS, one stage per pass.  The
 // twelve stages below act inside each contiguous block of 2^12 points and are the in-LDS transform of that length
 // with its own twiddle table (struct_block_kernel), which multiplies by the block's part of the spectrum and runs
 // the inverse stages on the way back; the inverse (decimation in time) column stages then mirror the forward ones,
 // so the points return to natural order without any reordering pass.  Two real vectors travel as one complex one.
-constexpr int kBlockLog = 12, kColLog = 4;
+constexpr int kBlockLog = 12;
 constexpr int kStructLargeMaxLog2p = kBlockLog + 10;      // a column tile of 2^(La + 4) points must fit the LDS
+// consecutive b per column tile (log2): sixteen (128-byte runs) for long columns, more for short ones so that a
+// workgroup still has 2^11 points to work on
+constexpr int struct_col_log(int log2p) { return 11 - (log2p - kBlockLog) > 4 ? 11 - (log2p - kBlockLog) : 4; }
 
 struct StructLargeParams {
     const float* t;        // [batch][n]: H D1 x (unnormalised), input of the forward column stages
@@ -353,6 +356,7 @@ struct StructLargeParams {
     long long batch;
     int n, log2p, m, reverse;
     float factor;
+    int col_log;
 };
 
 enum { COL_FWD_REAL = 0, COL_FWD_COMPLEX = 1, COL_INV_OUT = 2 };
@@ -362,13 +366,14 @@ __global__ void __launch_bounds__(256) struct_col_kernel(StructLargeParams p)
 {
     extern __shared__ float2 X[];
     constexpr bool INVERSE = MODE == COL_INV_OUT;
-    const int L = p.log2p, T = L - kBlockLog + kColLog;              // index bits of a tile: a above, sixteen b below
-    const long long pair = blockIdx.x >> (kBlockLog - kColLog);
-    const int b0 = (int)(blockIdx.x & ((1 << (kBlockLog - kColLog)) - 1)) << kColLog;
+    const int cl = p.col_log;                                         // log2 of the consecutive b of a tile
+    const int L = p.log2p, T = L - kBlockLog + cl;              // index bits of a tile: a above, sixteen b below
+    const long long pair = blockIdx.x >> (kBlockLog - cl);
+    const int b0 = (int)(blockIdx.x & ((1 << (kBlockLog - cl)) - 1)) << cl;
     const long long v0 = 2 * pair, v1 = v0 + 1;
     const bool two = v1 < p.batch;
     float2* z = p.z + (pair << L);
-    auto true_index = [&](int i) { return ((i >> kColLog) << kBlockLog) | (b0 + (i & ((1 << kColLog) - 1))); };
+    auto true_index = [&](int i) { return ((i >> cl) << kBlockLog) | (b0 + (i & ((1 << cl) - 1))); };
 
     for (int i = threadIdx.x; i < (1 << T); i += 256) {
         const int pt = true_index(i);
@@ -385,13 +390,13 @@ __global__ void __launch_bounds__(256) struct_col_kernel(StructLargeParams p)
         X[pad(i)] = v;
     }
     __syncthreads();
-    for (int step = 0; step < T - kColLog; ++step) {
-        const int t = INVERSE ? kColLog + step : T - 1 - step;       // tile bit of this stage
-        const int s = t - kColLog + kBlockLog;                        // its bit in the transform
+    for (int step = 0; step < T - cl; ++step) {
+        const int t = INVERSE ? cl + step : T - 1 - step;       // tile bit of this stage
+        const int s = t - cl + kBlockLog;                        // its bit in the transform
         for (int bf = threadIdx.x; bf < (1 << (T - 1)); bf += 256) {
             const int o = bf & ((1 << t) - 1);
             const int lo = ((bf >> t) << (t + 1)) | o;
-            const int ot = ((o >> kColLog) << kBlockLog) | (b0 + (o & ((1 << kColLog) - 1)));      // offset in the group of 2^s
+            const int ot = ((o >> cl) << kBlockLog) | (b0 + (o & ((1 << cl) - 1)));      // offset in the group of 2^s
             float2 a = X[pad(lo)], c = X[pad(lo + (1 << t))];
             butterfly<INVERSE>(a, c, p.tw[(long long)ot << (L - 1 - s)]);
             X[pad(lo)] = a;
@@ -489,10 +494,11 @@ hipError_t launch_struct_prepare_large(const float* params, int kind, int n, int
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(struct_fill_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, params, kind, n, log2p, spec);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    StructLargeParams p{nullptr, nullptr, spec, tw, tw_b, nullptr, nullptr, 1, n, log2p, 0, 0, 1.0f};
-    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + kColLog), lds_blk = fft_lds_bytes(kBlockLog);
+    const int cl = struct_col_log(log2p);
+    StructLargeParams p{nullptr, nullptr, spec, tw, tw_b, nullptr, nullptr, 1, n, log2p, 0, 0, 1.0f, cl};
+    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + cl), lds_blk = fft_lds_bytes(kBlockLog);
     if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_FWD_COMPLEX>), lds_col)) != hipSuccess) return e;
-    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_COMPLEX>, dim3(1 << (kBlockLog - kColLog)), dim3(256), lds_col, s, p);
+    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_COMPLEX>, dim3(1 << (kBlockLog - cl)), dim3(256), lds_col, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(struct_block_kernel<true>, dim3(1 << (log2p - kBlockLog)), dim3(256), lds_blk, s, p);
     return hipGetLastError();
@@ -505,17 +511,18 @@ hipError_t launch_struct_conv_large(const float* t, const float* d2, const float
     if (batch <= 0) return hipSuccess;
     if (log2p <= kBlockLog + 2 || log2p > kStructLargeMaxLog2p) return hipErrorInvalidValue;
     const long long pairs = (batch + 1) / 2;
-    if ((pairs << (log2p - kBlockLog)) > 0x7fffffffLL || (pairs << (kBlockLog - kColLog)) > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    StructLargeParams p{t, d2, z, tw, tw_b, spec, out, batch, n, log2p, m, reverse, factor};
-    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + kColLog), lds_blk = fft_lds_bytes(kBlockLog);
+    const int cl = struct_col_log(log2p);
+    if ((pairs << (log2p - kBlockLog)) > 0x7fffffffLL || (pairs << (kBlockLog - cl)) > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    StructLargeParams p{t, d2, z, tw, tw_b, spec, out, batch, n, log2p, m, reverse, factor, cl};
+    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + cl), lds_blk = fft_lds_bytes(kBlockLog);
     hipError_t e;
     if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_FWD_REAL>), lds_col)) != hipSuccess) return e;
     if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_INV_OUT>), lds_col)) != hipSuccess) return e;
-    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_REAL>, dim3((unsigned)(pairs << (kBlockLog - kColLog))), dim3(256), lds_col, s, p);
+    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_REAL>, dim3((unsigned)(pairs << (kBlockLog - cl))), dim3(256), lds_col, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(struct_block_kernel<false>, dim3((unsigned)(pairs << (log2p - kBlockLog))), dim3(256), lds_blk, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(struct_col_kernel<COL_INV_OUT>, dim3((unsigned)(pairs << (kBlockLog - kColLog))), dim3(256), lds_col, s, p);
+    hipLaunchKernelGGL(struct_col_kernel<COL_INV_OUT>, dim3((unsigned)(pairs << (kBlockLog - cl))), dim3(256), lds_col, s, p);
     return hipGetLastError();
 }
 }  // namespace spinner
