@@ -226,6 +226,18 @@ def test_hash_above_the_fused_range(gpu, oracle, log2n, batch, L):
         gpu.b.spinner_hash(_to(gpu, x), _to(gpu, ds))      # the call without a workspace stops at 2^16
 
 
+def test_hash_with_workspace_is_the_plain_call_up_to_the_fused_range(gpu):
+    # up to 2^16 the variant with a workspace argument is spinner_hash itself: no workspace needed, same buckets
+    t = gpu.torch
+    for n, batch in ((1024, 300), (1 << 15, 5)):
+        w = W.Workload("h", "hash", n, batch, n, "hash", 1.0, 3, "unit_normal", 640 + n, batch)
+        x, ds = _to(gpu, W.make_x_numpy(w)), _to(gpu, W.diag_sets(w))
+        assert gpu.b.spinner_hash_workspace_bytes(n, batch) == 0
+        assert t.equal(gpu.b.spinner_hash_ws(x, ds), gpu.b.spinner_hash(x, ds))
+        signs = gpu.b.spinner_pack_signs(ds)
+        assert t.equal(gpu.b.spinner_hash_signs_ws(x, signs, 3), gpu.b.spinner_hash_signs(x, signs, 3))
+
+
 def test_hash_above_the_fused_range_in_several_slices(gpu):
     # n = 2^17, 513 vectors: the passes walk the batch in two slices (257 + 256).  The bucket must be the argmax of the
     # projection that spinner_apply writes for the same triple (same passes, so the same bits; random data has no ties)

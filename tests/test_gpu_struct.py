@@ -92,6 +92,16 @@ def test_struct_members_with_transforms_through_global_memory(gpu, oracle, kind,
         gpu.b.spinner_struct_apply(_to(gpu, x), kind, spec, _to(gpu, d[0]), _to(gpu, d[1]), n, 1.0)      # no workspace: stops at 2^14 points
 
 
+def test_struct_apply_with_workspace_is_the_plain_call_while_the_transform_fits_the_lds(gpu):
+    for kind, n in (("circulant", 1 << 14), ("toeplitz", 2048), ("hankel", 64)):
+        x, d, params = _case(kind, n, 5, 10400 + n)
+        spec = gpu.b.spinner_struct_prepare(kind, _to(gpu, params), n)
+        assert gpu.b.spinner_struct_workspace_bytes(kind, n, 5) == 0
+        a = gpu.b.spinner_struct_apply(_to(gpu, x), kind, spec, _to(gpu, d[0]), _to(gpu, d[1]), n // 2, 0.5)
+        b = gpu.b.spinner_struct_apply_ws(_to(gpu, x), kind, spec, _to(gpu, d[0]), _to(gpu, d[1]), n // 2, 0.5)
+        assert gpu.torch.equal(a, b)
+
+
 def test_circulant_at_the_largest_size_and_special_generators(gpu, oracle):
     n, batch = 1 << 14, 3
     x, d, params = _case("circulant", n, batch, 10100)
