@@ -418,6 +418,58 @@ __global__ void __launch_bounds__(256) struct_col_kernel(StructLargeParams p)
     }
 }
 
+// The same column stages for short columns (LA = 3 or 4 stages, transforms of 2^15 and 2^16 points): a thread holds the
+// 2^LA points a 2^12 + b of one b in registers and runs all stages there; consecutive threads take consecutive b.
+template <int MODE, int LA>
+__global__ void __launch_bounds__(256) struct_col_reg_kernel(StructLargeParams p)
+{
+    constexpr bool INVERSE = MODE == COL_INV_OUT;
+    constexpr int M = 1 << LA, L = kBlockLog + LA;
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long pair = gid >> kBlockLog;
+    const int b = (int)(gid & ((1 << kBlockLog) - 1));
+    const long long v0 = 2 * pair, v1 = v0 + 1;
+    const bool two = v1 < p.batch;
+    float2* z = p.z + (pair << L);
+    float2 v[M];
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+        const int pt = (a << kBlockLog) | b;
+        if constexpr (MODE == COL_FWD_REAL) {
+            const int pc = pt < p.n ? pt : p.n - 1;
+            const int q = p.reverse ? p.n - 1 - pc : pc;
+            const float dd = p.d2[q];
+            const float x0 = p.t[v0 * p.n + q], x1 = p.t[(two ? v1 : v0) * p.n + q];
+            v[a] = pt < p.n ? make_float2(x0 * dd, x1 * dd) : make_float2(0.f, 0.f);
+        } else {
+            v[a] = z[pt];
+        }
+    }
+#pragma unroll
+    for (int step = 0; step < LA; ++step) {
+        const int t = INVERSE ? step : LA - 1 - step;             // bit of a
+        const int s = t + kBlockLog;
+#pragma unroll
+        for (int a = 0; a < M; ++a)
+            if (!(a & (1 << t))) {
+                const int ot = ((a & ((1 << t) - 1)) << kBlockLog) | b;      // offset in the group of 2^s
+                butterfly<INVERSE>(v[a], v[a | (1 << t)], p.tw[ot << (L - 1 - s)]);
+            }
+    }
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+        const int pt = (a << kBlockLog) | b;
+        if constexpr (MODE == COL_INV_OUT) {
+            if (pt < p.m) {
+                p.out[v0 * p.m + pt] = v[a].x * p.factor;
+                if (two) p.out[v1 * p.m + pt] = v[a].y * p.factor;
+            }
+        } else {
+            z[pt] = v[a];
+        }
+    }
+}
+
 // The twelve low stages of one block of 2^12 points: forward, product with the spectrum, inverse, in place
 // (FORWARD_ONLY: forward alone, for the spectrum of the generator).
 template <bool FORWARD_ONLY>
@@ -481,6 +533,23 @@ hipError_t launch_struct_conv(const float* x, const float* d1, const float* d2, 
     return hipGetLastError();
 }
 
+template <int MODE>
+static hipError_t launch_struct_col(const StructLargeParams& p, long long pairs, hipStream_t s)
+{
+    const int la = p.log2p - kBlockLog;
+    if (la == 3 || la == 4) {
+        const unsigned blocks = (unsigned)((pairs << kBlockLog) / 256);
+        if (la == 3) hipLaunchKernelGGL((struct_col_reg_kernel<MODE, 3>), dim3(blocks), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((struct_col_reg_kernel<MODE, 4>), dim3(blocks), dim3(256), 0, s, p);
+        return hipGetLastError();
+    }
+    const size_t lds_col = fft_lds_bytes(la + p.col_log);
+    const hipError_t e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<MODE>), lds_col);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(struct_col_kernel<MODE>, dim3((unsigned)(pairs << (kBlockLog - p.col_log))), dim3(256), lds_col, s, p);
+    return hipGetLastError();
+}
+
 // spectrum of a generator whose transform does not fit the LDS: [P] spectrum, [P/2] twiddles, [2^11] twiddles of the blocks
 hipError_t launch_struct_prepare_large(const float* params, int kind, int n, int log2p, float2* spec, float2* tw, float2* tw_b,
                                        hipStream_t s)
@@ -496,10 +565,8 @@ hipError_t launch_struct_prepare_large(const float* params, int kind, int n, int
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const int cl = struct_col_log(log2p);
     StructLargeParams p{nullptr, nullptr, spec, tw, tw_b, nullptr, nullptr, 1, n, log2p, 0, 0, 1.0f, cl};
-    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + cl), lds_blk = fft_lds_bytes(kBlockLog);
-    if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_FWD_COMPLEX>), lds_col)) != hipSuccess) return e;
-    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_COMPLEX>, dim3(1 << (kBlockLog - cl)), dim3(256), lds_col, s, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t lds_blk = fft_lds_bytes(kBlockLog);
+    if ((e = launch_struct_col<COL_FWD_COMPLEX>(p, 1, s)) != hipSuccess) return e;
     hipLaunchKernelGGL(struct_block_kernel<true>, dim3(1 << (log2p - kBlockLog)), dim3(256), lds_blk, s, p);
     return hipGetLastError();
 }
@@ -514,15 +581,11 @@ hipError_t launch_struct_conv_large(const float* t, const float* d2, const float
     const int cl = struct_col_log(log2p);
     if ((pairs << (log2p - kBlockLog)) > 0x7fffffffLL || (pairs << (kBlockLog - cl)) > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     StructLargeParams p{t, d2, z, tw, tw_b, spec, out, batch, n, log2p, m, reverse, factor, cl};
-    const size_t lds_col = fft_lds_bytes(log2p - kBlockLog + cl), lds_blk = fft_lds_bytes(kBlockLog);
+    const size_t lds_blk = fft_lds_bytes(kBlockLog);
     hipError_t e;
-    if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_FWD_REAL>), lds_col)) != hipSuccess) return e;
-    if ((e = allow_lds(reinterpret_cast<const void*>(struct_col_kernel<COL_INV_OUT>), lds_col)) != hipSuccess) return e;
-    hipLaunchKernelGGL(struct_col_kernel<COL_FWD_REAL>, dim3((unsigned)(pairs << (kBlockLog - cl))), dim3(256), lds_col, s, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_struct_col<COL_FWD_REAL>(p, pairs, s)) != hipSuccess) return e;
     hipLaunchKernelGGL(struct_block_kernel<false>, dim3((unsigned)(pairs << (log2p - kBlockLog))), dim3(256), lds_blk, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(struct_col_kernel<COL_INV_OUT>, dim3((unsigned)(pairs << (kBlockLog - cl))), dim3(256), lds_col, s, p);
-    return hipGetLastError();
+    return launch_struct_col<COL_INV_OUT>(p, pairs, s);
 }
 }  // namespace spinner
