@@ -287,6 +287,42 @@ def measure_struct(torch, b, dev, kind, n, batch, steps, warmup):
     return res
 
 
+def measure_feature_sizes(torch, b, W, dev):
+    """Time per projected vector at the dimensions of the paper's feature-map timing table (2^9 .. 2^15) for the family
+    members it lists: H D3 H D2 H D1 with the cos / sin feature map, and the G_struct D2 H D1 members (projection alone).
+    2^24 input elements per call.  Context for that table, whose entries are CPU speed-ups over a dense product."""
+    import math as _m
+
+    rows = []
+    for k in range(9, 16):
+        n = 1 << k
+        batch = (1 << 24) // n
+        g = torch.Generator(device=dev)
+        g.manual_seed(1610 + k)
+        x = torch.randn((batch, n), generator=g, device=dev, dtype=torch.float32)
+        ds = torch.from_numpy(W.rademacher_diagonals(n, 3, 90 + k)).to(dev)
+        signs = b.spinner_pack_signs(ds[None].contiguous())
+        out = torch.empty((batch, 2 * n), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(16, b.spinner_workspace_bytes(n, batch, n, "cossin")), dtype=torch.uint8, device=dev)
+        fn = lambda: b.spinner_apply_signs(x, signs, n, "cossin", _m.sqrt(n), out=out, workspace=ws)
+        _, ms = time_calls(torch, fn, 10, 5)
+        row = {"n": n, "batch": batch, "hd3hd2hd1_features_ns_per_vector": round(ms * 1e6 / batch, 2)}
+        outp = out[:, :n]
+        for kind in ("circulant", "toeplitz", "skew_circulant"):
+            params = torch.randn(int(b.lib.spinner_struct_params(b.STRUCT_KINDS[kind], n)), generator=g, device=dev, dtype=torch.float32)
+            spec = b.spinner_struct_prepare(kind, params, n)
+            so = torch.empty((batch, n), dtype=torch.float32, device=dev)
+            sws = torch.empty(max(16, b.spinner_struct_workspace_bytes(kind, n, batch)), dtype=torch.uint8, device=dev)
+            sfn = lambda: b.spinner_struct_apply_ws(x, kind, spec, ds[0], ds[1], n, 1.0, out=so, workspace=sws)
+            _, sms = time_calls(torch, sfn, 10, 5)
+            row["g_%s_ns_per_vector" % kind] = round(sms * 1e6 / batch, 2)
+            del params, spec, so, sws
+        rows.append(row)
+        del x, ds, signs, out, outp, ws
+        torch.cuda.empty_cache()
+    return {"workload": "feature_table_sizes_2p9_2p15", "rows": rows}
+
+
 def copy_ceiling(torch, b, dev, steps, warmup):
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
@@ -378,6 +414,11 @@ def measure_next_rows(torch, b, W, dev, args):
         log("[bench] %s: %.4f ms  %.3e vec/s  (%.0f GB/s counting 8 B per element)" % (
             st["workload"], st["ms"], st["vectors_per_s"], st["GBs_of_8B_per_element"]))
         nxt.append(st)
+    ft = measure_feature_sizes(torch, b, W, dev)
+    log("[bench] ns per vector at n = 2^9..2^15, HD3HD2HD1 features / G_circ / G_Toeplitz / G_skew-circ: " + "  ".join(
+        "%d: %.1f/%.1f/%.1f/%.1f" % (r["n"], r["hd3hd2hd1_features_ns_per_vector"], r["g_circulant_ns_per_vector"],
+                                     r["g_toeplitz_ns_per_vector"], r["g_skew_circulant_ns_per_vector"]) for r in ft["rows"]))
+    nxt.append(ft)
     # hidden sizes of the paper's MLP timing table (Table 2), one layer, batch 1024: forward + backward per step
     tbl = []
     for k in range(4, 13):
